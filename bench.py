@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the fp32 GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others]
+
+A step is one call of the whole hot path (tg_sgemm / tg_sgemm_batched: configuration
+lookup, grid mapping, tile loads, LDS staging, MFMA loop, epilogue) on one synthetic
+problem whose operands already sit in device memory.  The headline workload is the
+4096^3 product, the shape the roofline target of the benchmark definition is quoted on;
+the other four workloads are timed the same way and reported under "workloads".
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import pathlib
+import sys
+import time
+
+import numpy as np
+
+ROOT = pathlib.Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
+ELEM_TOL, FRO_TOL = 1e-5, 1e-6
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_flops(batch, m, n, k):
+    return 2.0 * batch * m * n * k
+
+
+def algorithmic_bytes(batch, m, n, k):
+    """A and B read once, C written once."""
+    return 4.0 * batch * (m * k + k * n + m * n)
+
+
+def time_workload(tg, torch, name, steps, warmup, reps_tune):
+    """Tune, warm up, then time `steps` back-to-back calls.  Returns a dict of measurements."""
+    from paper_1904_03383_amd import inputgen as ig
+    batch, m, n, k, dist = ig.CONFIGS[name]
+    a, b = ig.make_config(name)
+    if batch == 1:
+        a, b = a[0], b[0]
+    da = torch.from_numpy(a).to("cuda")
+    db = torch.from_numpy(b).to("cuda")
+    call = tg.sgemm if batch == 1 else tg.sgemm_batched
+    out = tg.tune(da, db, reps=reps_tune)
+    cfg = tg.last_config()
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        call(da, db, out=out)
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        call(da, db, out=out)          # launched on torch's current stream, where the events sit
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / steps
+    dev_ms = ev0.elapsed_time(ev1) / steps
+    flops, nbytes = algorithmic_flops(batch, m, n, k), algorithmic_bytes(batch, m, n, k)
+    res = {
+        "workload": name, "batch": batch, "m": m, "n": n, "k": k, "dist": dist, "tile_config": cfg,
+        "ms_per_step": wall_ms, "device_ms_per_step": dev_ms,
+        "tflops": flops / (wall_ms * 1e-3) / 1e12,
+        "device_tflops": flops / (dev_ms * 1e-3) / 1e12,
+        "frac_mfma_peak": flops / (dev_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
+        "algorithmic_gbs": nbytes / (dev_ms * 1e-3) / 1e9,
+        "frac_hbm_peak": nbytes / (dev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "flops": flops, "bytes": nbytes,
+    }
+    ideal_compute = flops / (PEAK_MFMA_F32_TFLOPS * 1e12)
+    ideal_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
+    res["bound"] = "mfma" if ideal_compute >= ideal_hbm else "hbm"
+    return res, (a, b, out)
+
+
+def parity_on_rows(a, b, out, rows):
+    """Compare sampled rows of the device result with the oracle (element-wise and Frobenius)."""
+    from oracle import oracle
+    c_ref, s_abs = oracle.sgemm_f64(a, b, rows=rows, want_abs=True)
+    host = out.cpu().numpy()
+    got = host[..., rows, :]
+    return oracle.parity_metrics(got, c_ref, s_abs)
+
+
+def cpu_baseline(a, b, target_seconds=15.0):
+    """The oracle as it stands, timed on the host cores, on a bounded number of rows of C."""
+    from oracle import oracle
+    cores = oracle.host_cores()
+    squeeze = a.ndim == 2
+    a3 = a[None] if squeeze else a
+    b3 = b[None] if squeeze else b
+    batch, m, k = a3.shape
+    n = b3.shape[2]
+    probe_rows = list(range(min(m, max(1, cores))))
+    t0 = time.perf_counter()
+    oracle.sgemm_f64(a3, b3, rows=probe_rows)
+    probe = max(time.perf_counter() - t0, 1e-6)
+    rows_per_s = len(probe_rows) / probe
+    nrows = int(min(m, max(len(probe_rows), rows_per_s * target_seconds)))
+    rows = list(range(nrows))
+    t0 = time.perf_counter()
+    oracle.sgemm_f64(a3, b3, rows=rows)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * batch * nrows * n * k
+    sample = (f"rows 0..{nrows - 1} of {m} of every problem ({batch} x {nrows}x{n}x{k}), "
+              f"{dt:.2f} s wall, fp64 triple loop")
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": sample, "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c5_4096")
+    ap.add_argument("--no-others", action="store_true", help="time only the headline workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune-reps", type=int, default=5)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import paper_1904_03383_amd as tg
+    from paper_1904_03383_amd import inputgen as ig
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    tg.load_library()
+    if args.workload not in ig.CONFIGS:
+        sys.exit(f"bench.py: unknown workload {args.workload}; choose from {list(ig.CONFIGS)}")
+
+    ws_bytes = max(tg.workspace_bytes(*ig.CONFIGS[w][:4]) for w in ig.CONFIGS)
+    ws = torch.empty(max(ws_bytes // 4, 4), dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+
+    log(f"headline workload {args.workload}")
+    head, (a, b, out) = time_workload(tg, torch, args.workload, args.steps, args.warmup, args.tune_reps)
+    log(f"  {head['tile_config']}  {head['device_ms_per_step'] * 1e3:.1f} us  {head['device_tflops']:.1f} TFLOP/s")
+
+    rows = sorted(set(int(r) for r in np.linspace(0, head["m"] - 1, num=min(head["m"], 128))))
+    par = parity_on_rows(a, b, out, rows)
+    parity_ok = bool(par["finite"] and par["zero_ok"] and par["max_ratio"] <= ELEM_TOL and par["rel_fro"] <= FRO_TOL)
+    log(f"  parity on {len(rows)} sampled rows: max_ratio {par['max_ratio']:.2e} rel_fro {par['rel_fro']:.2e} ok={parity_ok}")
+
+    base = None
+    if not args.no_cpu_baseline:
+        log("cpu baseline (oracle) ...")
+        base = cpu_baseline(a, b)
+        log(f"  {base['value'] * 1e3:.2f} GFLOP/s on {base['cores']} cores")
+    del a, b, out
+
+    others = []
+    if not args.no_others:
+        for name in ig.CONFIGS:
+            if name == args.workload:
+                continue
+            steps = args.steps if ig.CONFIGS[name][3] >= 1024 else max(args.steps, 500)
+            r, bufs = time_workload(tg, torch, name, steps, args.warmup, args.tune_reps)
+            del bufs
+            log(f"  {name}: {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.2f} us  {r['device_tflops']:.2f} TFLOP/s")
+            others.append(r)
+
+    traffic = None
+    tfile = ROOT / "profiles" / "hbm_traffic.json"
+    if tfile.exists():
+        traffic = json.loads(tfile.read_text()).get(args.workload, {}).get("bytes_per_launch")
+
+    if head["bound"] == "mfma":
+        roof = {"bound": "mfma", "achieved": head["device_tflops"], "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                "frac": head["frac_mfma_peak"], "traffic": traffic}
+    else:
+        roof = {"bound": "hbm", "achieved": head["algorithmic_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": head["frac_hbm_peak"], "traffic": traffic}
+    roof["kernel"] = head["tile_config"]
+    roof["avg_launch_ms"] = head["device_ms_per_step"]
+
+    line = {
+        "metric": "fp32 GEMM TFLOP/s (2mnk/t)", "value": head["tflops"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": head["batch"], "m": head["m"], "n": head["n"], "k": head["k"],
+                   "layout": "row-major", "distribution": head["dist"], "tile_config": head["tile_config"]},
+        "roofline": roof,
+        "cpu_baseline": base,
+        "parity": {"rows_checked": len(rows), "max_ratio": par["max_ratio"], "rel_fro": par["rel_fro"], "ok": parity_ok},
+        "workloads": [head] + others,
+    }
+    print(json.dumps(line), flush=True)
+    if not parity_ok:
+        sys.exit("bench.py: the timed result does not match the oracle")
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,137 @@
+/*
+ * tgemm -- single-precision dense matrix multiplication for AMD MI355X (gfx950).
+ *
+ * The operation is "matmul" of Sec. 5.2 of the paper (arXiv 1904.03383): C = A.B with
+ * A of size m x k and B of size k x n, i.e. C[i][j] = sum_{p<k} A[i][p] * B[p][j].
+ * There is no alpha/beta and no transpose flag, exactly as in that problem statement;
+ * C is overwritten and never read.  The batched entry point applies the same
+ * definition independently to `batch` problems (benchmark workload; not in the paper).
+ *
+ * Layout.  Row-major with leading dimensions in ELEMENTS: A[i*lda + p], B[p*ldb + j],
+ * C[i*ldc + j]; lda >= k, ldb >= n, ldc >= n.  Elements of C between n and ldc are
+ * never written.  The paper stores matrices column-major (Sec. 5.2); a column-major
+ * product C = A.B is obtained from this library by swapping the operands:
+ * tg_sgemm(n, m, k, B, ldb, A, lda, C, ldc, stream).
+ *
+ * Pointers.  A, B, C and the workspace are DEVICE pointers owned by the caller; the
+ * library never allocates, frees or keeps them (the workspace pointer is kept until
+ * replaced).  C must not overlap A or B (not checked).  `stream` is a hipStream_t
+ * passed as void* (NULL = the default stream).
+ *
+ * Execution.  Calls validate their arguments on the host, enqueue kernels on `stream`
+ * and return without synchronising; C is valid once the stream has been synchronised.
+ * tg_tune is the only blocking call.
+ *
+ * Errors.  Nothing is thrown across this boundary; every function returns a tg_status
+ * (or a plain value where stated).  Argument errors are detected before any GPU call,
+ * so they are reported even on a machine without a GPU.  tg_last_error() returns a
+ * thread-local, human-readable description of the most recent failure on this thread.
+ *
+ * Accuracy.  fp32 multiply-add on the matrix cores, fp32 accumulation; for k > 1024 the
+ * running sums are folded into a second accumulator every 512 terms so that the
+ * relative Frobenius error stays below 1e-6 at k = 4096.
+ */
+#ifndef TGEMM_H
+#define TGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TG_OK = 0,
+    TG_ERR_INVALID_ARG = 1, /* null pointer with non-empty extent, negative size, ld or stride too small, overflow */
+    TG_ERR_UNSUPPORTED = 2, /* current device is not gfx950, or size beyond 2^31-1 per dimension */
+    TG_ERR_WORKSPACE = 3,   /* a forced split-K configuration needs more workspace than was set */
+    TG_ERR_HIP = 4,         /* a HIP runtime call failed; text in tg_last_error() */
+    TG_ERR_INTERNAL = 5
+} tg_status;
+
+/*
+ * C = A.B (Sec. 5.2 "matmul").  m, n, k >= 0.  m == 0 or n == 0: nothing is done.
+ * k == 0: the m x n region of C is set to +0.0.
+ */
+tg_status tg_sgemm(int64_t m, int64_t n, int64_t k,
+                   const float *A, int64_t lda,
+                   const float *B, int64_t ldb,
+                   float *C, int64_t ldc,
+                   void *stream);
+
+/*
+ * `batch` independent products of the same shape (Sec. 5.2 definition per problem).
+ * Problem b uses A + b*strideA, B + b*strideB, C + b*strideC (strides in elements).
+ * "Packed contiguously" means lda = k, ldb = n, ldc = n, strideA = m*k, strideB = k*n,
+ * strideC = m*n.  For batch > 1: strideC >= (m-1)*ldc + n (outputs must not overlap);
+ * strideA and strideB may be any non-negative value (0 broadcasts one operand).
+ */
+tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
+                           const float *A, int64_t lda, int64_t strideA,
+                           const float *B, int64_t ldb, int64_t strideB,
+                           float *C, int64_t ldc, int64_t strideC,
+                           void *stream);
+
+/*
+ * Host-side tile-configuration tuner (the counterpart of the decisions -- block/thread
+ * mapping, tile sizes, unrolling, memory space -- that the paper's search fixes per
+ * kernel and input size, Secs. 4 and 5.1; here a small fixed candidate set is timed).
+ * Runs every candidate configuration that is valid for this problem on the caller's
+ * buffers (`reps` timed launches each after a warm-up, reps <= 0 selects 5), remembers
+ * the fastest for this (batch, m, n, k, alignment class) and leaves a valid product in C.
+ * Candidates whose roofline lower bound already exceeds the best time seen are skipped.
+ * Blocking: synchronises `stream`.  tg_sgemm / tg_sgemm_batched never time anything;
+ * without a tuned entry they use a static heuristic.
+ */
+tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
+                  const float *A, int64_t lda, int64_t strideA,
+                  const float *B, int64_t ldb, int64_t strideB,
+                  float *C, int64_t ldc, int64_t strideC,
+                  void *stream, int reps);
+
+/*
+ * Split-K workspace (device memory, caller-owned, 16-byte aligned).  Split-K
+ * configurations are considered only while a workspace of at least
+ * tg_workspace_bytes(...) is set; otherwise a non-split configuration is used.
+ * Pass (NULL, 0) to remove it.  Calls that use the workspace concurrently on different
+ * streams race; give concurrent streams separate processes or no workspace.
+ */
+tg_status tg_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Largest workspace any split-K candidate for this problem can need (bytes). 0 on invalid sizes. */
+size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k);
+
+/*
+ * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>]", e.g.
+ * "t128x128x16_w64x64:s1:g8"; kernel names are listed by tg_config_name.
+ * tg_force_config(spec) makes every later call use that configuration when it is valid
+ * for the problem (otherwise the call fails with TG_ERR_INVALID_ARG, or TG_ERR_WORKSPACE
+ * for split-K without room); tg_force_config(NULL) returns to tuned/heuristic choice.
+ * The environment variable TG_FORCE_CONFIG is read once, at the first call, the same way.
+ */
+tg_status tg_force_config(const char *spec);
+
+/* Writes the spec that a call with these sizes (packed, aligned operands) would use now. */
+tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *buf, size_t len);
+
+/* Spec the most recent successful tg_sgemm/tg_sgemm_batched/tg_tune call on this thread ran (or "" ). */
+const char *tg_last_config(void);
+
+/* Number of compiled kernel variants, and the name of variant idx (0 <= idx < count). */
+int tg_num_kernels(void);
+tg_status tg_kernel_name(int idx, char *buf, size_t len);
+
+/* Tuned-entry cache: plain text, one entry per line.  Loading merges into the live cache. */
+tg_status tg_load_tune_cache(const char *path);
+tg_status tg_save_tune_cache(const char *path);
+void tg_clear_tune_cache(void);
+
+const char *tg_status_string(tg_status s);
+const char *tg_last_error(void);
+int tg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TGEMM_H */

@@ -1,0 +1,25 @@
+"""MI355X-native fp32 GEMM (C = A.B, single and batched) behind a C-ABI library.
+
+``binding`` marshals torch device tensors into ``libtgemm.so``; every arithmetic step
+runs in the HIP kernels.  ``inputgen`` holds the seeded synthetic operands (numpy only).
+Nothing is loaded at import time; the shared library is opened on first use and its
+absence is an error (there is no fallback path).
+"""
+from .binding import (  # noqa: F401
+    TgemmError,
+    clear_tune_cache,
+    force_config,
+    get_config,
+    kernel_names,
+    last_config,
+    library_path,
+    load_library,
+    load_tune_cache,
+    save_tune_cache,
+    set_workspace,
+    sgemm,
+    sgemm_batched,
+    tune,
+    version,
+    workspace_bytes,
+)

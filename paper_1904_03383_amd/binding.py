@@ -1,0 +1,214 @@
+"""ctypes binding of the tgemm C-ABI (include/tgemm.h).  Argument marshalling only.
+
+Functions mirror the C entry points: ``sgemm`` -> tg_sgemm, ``sgemm_batched`` ->
+tg_sgemm_batched, ``tune`` -> tg_tune, and so on.  torch is used for device memory and
+the current stream; it performs no arithmetic here.
+"""
+from __future__ import annotations
+
+import ctypes
+import pathlib
+
+_LIB_PATH = pathlib.Path(__file__).resolve().parent / "libtgemm.so"
+_lib = None
+_workspace = None  # keeps the workspace tensor alive while the library points at it
+
+TG_OK = 0
+STATUS_NAMES = {0: "TG_OK", 1: "TG_ERR_INVALID_ARG", 2: "TG_ERR_UNSUPPORTED", 3: "TG_ERR_WORKSPACE",
+                4: "TG_ERR_HIP", 5: "TG_ERR_INTERNAL"}
+
+# Every symbol declared in include/tgemm.h: name -> (restype, argtypes)
+_i64, _p, _sz, _int, _cstr = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_char_p
+SIGNATURES = {
+    "tg_sgemm": (_int, [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _i64, _p]),
+    "tg_sgemm_batched": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p]),
+    "tg_tune": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _int]),
+    "tg_set_workspace": (_int, [_p, _sz]),
+    "tg_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
+    "tg_force_config": (_int, [_cstr]),
+    "tg_get_config": (_int, [_i64, _i64, _i64, _i64, _p, _sz]),
+    "tg_last_config": (_cstr, []),
+    "tg_num_kernels": (_int, []),
+    "tg_kernel_name": (_int, [_int, _p, _sz]),
+    "tg_load_tune_cache": (_int, [_cstr]),
+    "tg_save_tune_cache": (_int, [_cstr]),
+    "tg_clear_tune_cache": (None, []),
+    "tg_status_string": (_cstr, [_int]),
+    "tg_last_error": (_cstr, []),
+    "tg_version": (_int, []),
+}
+
+
+class TgemmError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        self.status = status
+        self.status_name = STATUS_NAMES.get(status, f"status {status}")
+        super().__init__(f"{self.status_name}: {detail}")
+
+
+def library_path() -> pathlib.Path:
+    return _LIB_PATH
+
+
+def load_library():
+    """Open libtgemm.so (built by ``python -m paper_1904_03383_amd.build``); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_1904_03383_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(str(_LIB_PATH))
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int):
+    if status != TG_OK:
+        raise TgemmError(status, load_library().tg_last_error().decode())
+
+
+def _stream_handle(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _require_f32_cuda(name, t):
+    import torch
+    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or not t.is_cuda:
+        raise ValueError(f"{name} must be a float32 tensor in device memory")
+
+
+def _ld(t, rows_dim, cols) -> int:
+    """Leading dimension of a row-major matrix view; unit stride along columns required."""
+    if t.shape[rows_dim + 1] > 1 and t.stride(rows_dim + 1) != 1:
+        raise ValueError("matrices must have unit stride along their rows (row-major)")
+    ld = t.stride(rows_dim) if t.shape[rows_dim] > 1 else max(cols, 1)
+    return max(int(ld), 1)
+
+
+def sgemm(a, b, out=None, stream=None):
+    """C = A.B for 2-D float32 device tensors a (m,k), b (k,n); returns out (m,n).  -> tg_sgemm"""
+    import torch
+    _require_f32_cuda("a", a)
+    _require_f32_cuda("b", b)
+    if a.dim() != 2 or b.dim() != 2 or a.shape[1] != b.shape[0]:
+        raise ValueError(f"shape mismatch: {tuple(a.shape)} x {tuple(b.shape)}")
+    m, k = a.shape
+    n = b.shape[1]
+    if out is None:
+        out = torch.empty((m, n), dtype=torch.float32, device=a.device)
+    _require_f32_cuda("out", out)
+    if tuple(out.shape) != (m, n):
+        raise ValueError("out has the wrong shape")
+    st = load_library().tg_sgemm(m, n, k, a.data_ptr(), _ld(a, 0, k), b.data_ptr(), _ld(b, 0, n),
+                                 out.data_ptr(), _ld(out, 0, n), _stream_handle(stream))
+    _check(st)
+    return out
+
+
+def _batched_args(a, b, out):
+    import torch
+    _require_f32_cuda("a", a)
+    _require_f32_cuda("b", b)
+    if a.dim() != 3 or b.dim() != 3 or a.shape[0] != b.shape[0] or a.shape[2] != b.shape[1]:
+        raise ValueError(f"shape mismatch: {tuple(a.shape)} x {tuple(b.shape)}")
+    batch, m, k = a.shape
+    n = b.shape[2]
+    if out is None:
+        out = torch.empty((batch, m, n), dtype=torch.float32, device=a.device)
+    _require_f32_cuda("out", out)
+    if tuple(out.shape) != (batch, m, n):
+        raise ValueError("out has the wrong shape")
+
+    def bstride(t, one):
+        return int(t.stride(0)) if batch > 1 else one
+    args = (batch, m, n, k,
+            a.data_ptr(), _ld(a, 1, k), bstride(a, m * k),
+            b.data_ptr(), _ld(b, 1, n), bstride(b, k * n),
+            out.data_ptr(), _ld(out, 1, n), bstride(out, m * n))
+    return args, out
+
+
+def sgemm_batched(a, b, out=None, stream=None):
+    """out[i] = a[i].b[i] for 3-D float32 device tensors (batch,m,k), (batch,k,n).  -> tg_sgemm_batched"""
+    args, out = _batched_args(a, b, out)
+    _check(load_library().tg_sgemm_batched(*args, _stream_handle(stream)))
+    return out
+
+
+def tune(a, b, out=None, reps: int = 5, stream=None):
+    """Time the candidate configurations on these operands and cache the winner.  -> tg_tune
+
+    Accepts 2-D or 3-D operands; returns out holding the product.  Blocking.
+    """
+    squeeze = a.dim() == 2
+    if squeeze:
+        a, b = a.unsqueeze(0), b.unsqueeze(0)
+        out = out.unsqueeze(0) if out is not None else None
+    args, out = _batched_args(a, b, out)
+    _check(load_library().tg_tune(*args, _stream_handle(stream), int(reps)))
+    return out[0] if squeeze else out
+
+
+def set_workspace(tensor):
+    """Give the library a device buffer for split-K partial sums (None removes it).  -> tg_set_workspace"""
+    global _workspace
+    lib = load_library()
+    if tensor is None:
+        _check(lib.tg_set_workspace(None, 0))
+        _workspace = None
+        return
+    if not tensor.is_cuda or not tensor.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    _check(lib.tg_set_workspace(tensor.data_ptr(), tensor.numel() * tensor.element_size()))
+    _workspace = tensor
+
+
+def workspace_bytes(batch: int, m: int, n: int, k: int) -> int:
+    return int(load_library().tg_workspace_bytes(batch, m, n, k))
+
+
+def force_config(spec):
+    _check(load_library().tg_force_config(spec.encode() if spec else None))
+
+
+def get_config(batch: int, m: int, n: int, k: int) -> str:
+    buf = ctypes.create_string_buffer(256)
+    _check(load_library().tg_get_config(batch, m, n, k, ctypes.cast(buf, ctypes.c_void_p), 256))
+    return buf.value.decode()
+
+
+def last_config() -> str:
+    return load_library().tg_last_config().decode()
+
+
+def kernel_names():
+    lib = load_library()
+    out = []
+    buf = ctypes.create_string_buffer(128)
+    for i in range(lib.tg_num_kernels()):
+        _check(lib.tg_kernel_name(i, ctypes.cast(buf, ctypes.c_void_p), 128))
+        out.append(buf.value.decode())
+    return out
+
+
+def load_tune_cache(path):
+    _check(load_library().tg_load_tune_cache(str(path).encode()))
+
+
+def save_tune_cache(path):
+    _check(load_library().tg_save_tune_cache(str(path).encode()))
+
+
+def clear_tune_cache():
+    load_library().tg_clear_tune_cache()
+
+
+def version() -> int:
+    return int(load_library().tg_version())

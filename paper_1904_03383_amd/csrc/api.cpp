@@ -1,0 +1,639 @@
+// Host side of the tgemm C-ABI (include/tgemm.h): argument validation, choice of a
+// tile configuration (forced > tuned > static heuristic), the timing tuner with its
+// lower-bound pruning, the tune cache, and kernel dispatch.  No device memory is
+// allocated or freed here.
+#include "tg_internal.h"
+
+#include "../../include/tgemm.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <tuple>
+#include <vector>
+
+namespace {
+
+using tg::GemmParams;
+using tg::KernelInfo;
+
+constexpr int kVersion = 100;               // 0.1.0
+constexpr int kNumCUs = 256;                // MI355X: 8 XCDs x 32 CUs
+constexpr double kPeakFlops = 157.3e12;     // fp32 MFMA: 256 CU x 256 flop/clk x 2.4 GHz
+constexpr double kPeakHbm = 8.0e12;         // bytes/s
+constexpr double kSimdFlops = 64 * 2.4e9;   // one SIMD: 64 flop/clk
+constexpr int kLongK = 1024;                // K range above which second-level accumulators are required
+constexpr int kFlushK = 512;                // K terms between folds of the first-level accumulators
+constexpr int kWaveMaxK = 2048;             // longest K the single-accumulator wave kernel may take
+constexpr int kDefaultGroup = 8;
+constexpr int kLdsPerCU = 160 * 1024;
+
+thread_local std::string t_error;
+thread_local std::string t_last_config;
+
+struct Config {
+    int kernel = -1;
+    int splits = 1;
+    int group = kDefaultGroup;
+};
+
+struct Problem {
+    int64_t batch, m, n, k;
+    const float *A; int64_t lda, strideA;
+    const float *B; int64_t ldb, strideB;
+    float *C; int64_t ldc, strideC;
+    bool aligned;   // every row of A, B, C (and every problem) starts on a 16-byte boundary
+};
+
+typedef std::tuple<int64_t, int64_t, int64_t, int64_t, int> ShapeKey;
+
+struct TunedEntry {
+    Config cfg;
+    double usec;
+};
+
+std::mutex g_mutex;
+std::map<ShapeKey, TunedEntry> g_cache;
+void *g_ws = nullptr;
+size_t g_ws_bytes = 0;
+bool g_forced = false;
+bool g_env_read = false;
+Config g_force_cfg;
+int g_device_ok[64] = {0};  // 0 unknown, 1 gfx950, -1 other
+
+tg_status fail(tg_status s, const std::string &msg) {
+    t_error = msg;
+    return s;
+}
+
+std::string spec_of(const Config &c) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "%s:s%d:g%d", tg::kernel(c.kernel).name, c.splits, c.group);
+    return buf;
+}
+
+int find_kernel(const std::string &name) {
+    for (int i = 0; i < tg::num_kernels(); ++i)
+        if (name == tg::kernel(i).name) return i;
+    return -1;
+}
+
+// "<kernel>[:s<splits>][:g<group>]"
+bool parse_spec(const char *spec, Config &out, std::string &why) {
+    std::string s(spec);
+    size_t pos = s.find(':');
+    std::string name = s.substr(0, pos);
+    Config c;
+    c.kernel = find_kernel(name);
+    if (c.kernel < 0) { why = "unknown kernel '" + name + "'"; return false; }
+    while (pos != std::string::npos) {
+        size_t next = s.find(':', pos + 1);
+        std::string tok = s.substr(pos + 1, next == std::string::npos ? std::string::npos : next - pos - 1);
+        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g')) { why = "bad token '" + tok + "'"; return false; }
+        char *end = nullptr;
+        long v = strtol(tok.c_str() + 1, &end, 10);
+        if (*end != '\0' || v < 1 || v > 4096) { why = "bad value in '" + tok + "'"; return false; }
+        if (tok[0] == 's') c.splits = (int)v; else c.group = (int)v;
+        pos = next;
+    }
+    out = c;
+    return true;
+}
+
+void read_env_once() {
+    if (g_env_read) return;
+    g_env_read = true;
+    const char *e = getenv("TG_FORCE_CONFIG");
+    if (e && *e) {
+        Config c;
+        std::string why;
+        if (parse_spec(e, c, why)) { g_forced = true; g_force_cfg = c; }
+        else fprintf(stderr, "tgemm: ignoring TG_FORCE_CONFIG: %s\n", why.c_str());
+    }
+}
+
+bool mul_ovf(int64_t a, int64_t b, int64_t *r) { return __builtin_mul_overflow(a, b, r); }
+bool add_ovf(int64_t a, int64_t b, int64_t *r) { return __builtin_add_overflow(a, b, r); }
+
+// extent of a strided matrix: (rows-1)*ld + cols, false on overflow
+bool extent(int64_t rows, int64_t cols, int64_t ld, int64_t *out) {
+    if (rows == 0 || cols == 0) { *out = 0; return true; }
+    int64_t t;
+    if (mul_ovf(rows - 1, ld, &t)) return false;
+    return !add_ovf(t, cols, out);
+}
+
+tg_status validate(Problem &p) {
+    if (p.batch < 0 || p.m < 0 || p.n < 0 || p.k < 0)
+        return fail(TG_ERR_INVALID_ARG, "negative size");
+    if (p.lda < std::max<int64_t>(p.k, 1) || p.ldb < std::max<int64_t>(p.n, 1) || p.ldc < std::max<int64_t>(p.n, 1))
+        return fail(TG_ERR_INVALID_ARG, "leading dimension too small: need lda >= max(k,1), ldb >= max(n,1), ldc >= max(n,1)");
+    if (p.strideA < 0 || p.strideB < 0 || p.strideC < 0)
+        return fail(TG_ERR_INVALID_ARG, "negative batch stride");
+    int64_t ea, eb, ec, t;
+    if (!extent(p.m, p.k, p.lda, &ea) || !extent(p.k, p.n, p.ldb, &eb) || !extent(p.m, p.n, p.ldc, &ec))
+        return fail(TG_ERR_INVALID_ARG, "matrix extent overflows int64");
+    if (p.batch > 1) {
+        if (p.strideC < ec) return fail(TG_ERR_INVALID_ARG, "strideC smaller than one output matrix");
+        if (mul_ovf(p.batch - 1, p.strideA, &t) || add_ovf(t, ea, &t) || t > INT64_MAX / 4 ||
+            mul_ovf(p.batch - 1, p.strideB, &t) || add_ovf(t, eb, &t) || t > INT64_MAX / 4 ||
+            mul_ovf(p.batch - 1, p.strideC, &t) || add_ovf(t, ec, &t) || t > INT64_MAX / 4)
+            return fail(TG_ERR_INVALID_ARG, "batch extent overflows int64");
+    } else if (ea > INT64_MAX / 4 || eb > INT64_MAX / 4 || ec > INT64_MAX / 4) {
+        return fail(TG_ERR_INVALID_ARG, "matrix extent overflows int64");
+    }
+    const bool out_nonempty = p.batch > 0 && p.m > 0 && p.n > 0;
+    if (out_nonempty) {
+        if (!p.C) return fail(TG_ERR_INVALID_ARG, "C is null");
+        if (p.k > 0 && (!p.A || !p.B)) return fail(TG_ERR_INVALID_ARG, "A or B is null");
+    }
+    if (p.m > INT32_MAX || p.n > INT32_MAX || p.k > INT32_MAX || p.batch > INT32_MAX)
+        return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
+    auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    p.aligned = a16(p.A) && a16(p.B) && a16(p.C) && p.lda % 4 == 0 && p.ldb % 4 == 0 && p.ldc % 4 == 0 &&
+                (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0 && p.strideC % 4 == 0));
+    return TG_OK;
+}
+
+tg_status check_device() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= 64) return fail(TG_ERR_UNSUPPORTED, "device index out of range");
+    std::lock_guard<std::mutex> lk(g_mutex);
+    if (g_device_ok[dev] == 0) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("hipGetDeviceProperties: ") + hipGetErrorString(e));
+        g_device_ok[dev] = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+    }
+    if (g_device_ok[dev] < 0) return fail(TG_ERR_UNSUPPORTED, "the current device is not gfx950 (MI355X)");
+    return TG_OK;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Number of K ranges actually used when `want` are asked for, and K tiles per range.
+void split_plan(const KernelInfo &ki, int64_t k, int want, int *splits, int *per) {
+    const int64_t kt = std::max<int64_t>(ceil_div(k, ki.BK), 1);
+    const int64_t pp = ceil_div(kt, std::max(want, 1));
+    *per = (int)pp;
+    *splits = (int)ceil_div(kt, pp);
+}
+
+size_t ws_need(const Problem &p, int splits) {
+    return splits > 1 ? (size_t)p.batch * splits * p.m * p.n * sizeof(float) : 0;
+}
+
+// Is this configuration usable for this problem?  (static validity filter of the tuner:
+// divisibility, alignment, accumulation depth, LDS capacity, workspace)
+bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::string *why = nullptr) {
+    auto no = [&](const char *w) { if (why) *why = w; return false; };
+    if (c.kernel < 0 || c.kernel >= tg::num_kernels()) return no("no such kernel");
+    const KernelInfo &ki = tg::kernel(c.kernel);
+    if (c.group < 1) return no("group must be >= 1");
+    if (ki.kind == tg::KIND_WAVE) {
+        if (c.splits != 1) return no("the wave kernel has no split-K");
+        if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
+        if (ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch > (int64_t)4 * INT32_MAX) return no("too many tiles");
+        return true;
+    }
+    if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
+    if (!ki.edge) {
+        if (!p.aligned) return no("operands are not 16-byte aligned");
+        if (p.m % ki.BM || p.n % ki.BN || p.k % ki.BK) return no("sizes are not multiples of the tile");
+    }
+    int splits, per;
+    split_plan(ki, p.k, c.splits, &splits, &per);
+    if (splits != c.splits) return no("split count leaves an empty K range");
+    const int64_t k_range = std::min<int64_t>((int64_t)per * ki.BK, p.k);
+    if (k_range > kLongK && !ki.two_level) return no("K range too long for a single accumulator level");
+    if (k_range <= kLongK && ki.two_level) return no("second accumulator level not needed");
+    if (c.splits > 1) {
+        if (per < 2) return no("K range shorter than two tiles");
+        if (ws_need(p, c.splits) > ws_bytes) return no("workspace too small for this split");
+    }
+    const int64_t blocks = ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * c.splits * p.batch;
+    if (blocks > INT32_MAX) return no("too many workgroups");
+    return true;
+}
+
+// Lower bound on the run time of a configuration (seconds): no kernel can beat the chip's
+// MFMA peak, a wave cannot beat the one SIMD it runs on, workgroups cannot use more CUs
+// than exist, and operands/results cross HBM at least once (Sec. 5.1 of the paper prunes
+// candidates with such a bound; this is the flat-set version of that cut).
+double lower_bound_seconds(const Problem &p, const Config &c) {
+    const KernelInfo &ki = tg::kernel(c.kernel);
+    const double flops = 2.0 * p.batch * p.m * p.n * p.k;
+    double t = flops / kPeakFlops;
+    int splits = 1, per = 1;
+    int waves_per_block = ki.threads / 64;
+    double wave_flops;
+    int64_t blocks;
+    if (ki.kind == tg::KIND_WAVE) {
+        wave_flops = 2.0 * 32 * 32 * p.k;
+        blocks = ceil_div(ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch, 4);
+    } else {
+        split_plan(ki, p.k, c.splits, &splits, &per);
+        wave_flops = 2.0 * ki.WM * ki.WN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
+        blocks = ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * splits * p.batch;
+    }
+    t = std::max(t, wave_flops / kSimdFlops);
+    // workgroups are spread over at most kNumCUs CUs; each CU has 4 SIMDs
+    const double rounds = (double)ceil_div(blocks * std::min(waves_per_block, 4), (int64_t)kNumCUs * 4);
+    t = std::max(t, rounds * wave_flops / kSimdFlops);
+    double bytes = 4.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n + (double)p.m * p.n);
+    if (splits > 1) bytes += 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n;
+    t = std::max(t, bytes / kPeakHbm);
+    return t;
+}
+
+// Rough cost model used only to rank candidates and as the fallback when nothing is tuned.
+// A CU delivers its MFMA rate once it holds four waves; workgroups beyond one per CU queue up.
+double heuristic_seconds(const Problem &p, const Config &c) {
+    const KernelInfo &ki = tg::kernel(c.kernel);
+    const double launch = 4e-6;
+    if (ki.kind == tg::KIND_WAVE) {
+        const double waves = (double)ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch;
+        const double per_simd = std::ceil(waves / (kNumCUs * 4.0));
+        const double wave_flops = 2.0 * 32 * 32 * p.k;
+        // a lone wave reads its operands with the latency exposed (~1/6 of the SIMD rate);
+        // several waves on one SIMD overlap, up to about half the rate
+        const double t = std::max(wave_flops / (kSimdFlops / 6.0), per_simd * wave_flops / (kSimdFlops * 0.5));
+        return launch + t;
+    }
+    int splits, per;
+    split_plan(ki, p.k, c.splits, &splits, &per);
+    const double blocks = (double)ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * splits * p.batch;
+    const double per_cu = std::ceil(blocks / kNumCUs);
+    // operand traffic per flop falls with the wave tile; predication and the second
+    // accumulator level cost a little
+    const double eff = 1.0 / (1.0 + 12.0 / ki.WM + 12.0 / ki.WN) * (ki.edge ? 0.5 : 1.0) * (ki.two_level ? 0.97 : 1.0);
+    const double block_flops = 2.0 * ki.BM * ki.BN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
+    const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
+    double t = launch + per_cu * block_flops / cu_rate;
+    if (splits > 1) t += 3e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
+    return t;
+}
+
+std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
+    std::vector<Config> out;
+    static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    for (int ki = 0; ki < tg::num_kernels(); ++ki) {
+        for (int s : kSplits) {
+            Config c;
+            c.kernel = ki;
+            c.splits = s;
+            c.group = kDefaultGroup;
+            if (!config_valid(p, c, ws_bytes)) continue;
+            // splitting only pays while the chip is under-filled
+            if (s > 1) {
+                const KernelInfo &k = tg::kernel(ki);
+                const int64_t base = ceil_div(p.m, k.BM) * ceil_div(p.n, k.BN) * p.batch;
+                if (base >= 2 * kNumCUs || base * s > 4 * kNumCUs) continue;
+            }
+            out.push_back(c);
+        }
+    }
+    // an edge kernel is only interesting when no exact-fit kernel exists
+    bool have_exact = false;
+    for (const Config &c : out)
+        if (tg::kernel(c.kernel).kind == tg::KIND_TILE && !tg::kernel(c.kernel).edge) have_exact = true;
+    if (have_exact) {
+        out.erase(std::remove_if(out.begin(), out.end(), [](const Config &c) {
+                      return tg::kernel(c.kernel).kind == tg::KIND_TILE && tg::kernel(c.kernel).edge; }),
+                  out.end());
+    }
+    std::sort(out.begin(), out.end(), [&](const Config &a, const Config &b) {
+        return heuristic_seconds(p, a) < heuristic_seconds(p, b);
+    });
+    return out;
+}
+
+ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, p.aligned ? 1 : 0); }
+
+// forced > tuned > heuristic.  Caller holds g_mutex.
+tg_status choose(const Problem &p, Config *out) {
+    read_env_once();
+    if (g_forced) {
+        std::string why;
+        if (!config_valid(p, g_force_cfg, g_ws_bytes, &why)) {
+            const bool ws_issue = g_force_cfg.splits > 1 && ws_need(p, g_force_cfg.splits) > g_ws_bytes;
+            return fail(ws_issue ? TG_ERR_WORKSPACE : TG_ERR_INVALID_ARG,
+                        "forced configuration " + spec_of(g_force_cfg) + " is not valid here: " + why);
+        }
+        *out = g_force_cfg;
+        return TG_OK;
+    }
+    auto it = g_cache.find(key_of(p));
+    if (it != g_cache.end() && config_valid(p, it->second.cfg, g_ws_bytes)) {
+        *out = it->second.cfg;
+        return TG_OK;
+    }
+    std::vector<Config> cands = candidates(p, g_ws_bytes);
+    if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
+    *out = cands.front();
+    return TG_OK;
+}
+
+tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream) {
+    const KernelInfo &ki = tg::kernel(c.kernel);
+    GemmParams g;
+    memset(&g, 0, sizeof g);
+    g.A = p.A; g.B = p.B; g.C = p.C;
+    g.lda = p.lda; g.ldb = p.ldb; g.ldc = p.ldc;
+    g.strideA = p.strideA; g.strideB = p.strideB; g.strideC = p.strideC;
+    g.m = (int)p.m; g.n = (int)p.n; g.k = (int)p.k; g.batch = (int)p.batch;
+    g.tiles_m = (int)ceil_div(p.m, ki.BM);
+    g.tiles_n = (int)ceil_div(p.n, ki.BN);
+    g.group = std::min(c.group, g.tiles_m);
+    g.splits = 1;
+    g.ktiles_per_split = (int)std::max<int64_t>(ceil_div(p.k, ki.BK), 1);
+    g.flush_tiles = ki.two_level ? std::max(1, kFlushK / ki.BK) : 0;
+    g.flags = 0;
+    if (p.aligned) g.flags |= tg::kFlagVecA | tg::kFlagVecC;
+    if (ki.kind == tg::KIND_TILE && c.splits > 1) {
+        split_plan(ki, p.k, c.splits, &g.splits, &g.ktiles_per_split);
+        g.ws = static_cast<float *>(ws);
+    }
+    hipError_t e = ki.launch(g, stream);
+    if (e == hipSuccess && g.splits > 1) {
+        if (p.n % 4 != 0) g.flags &= ~tg::kFlagVecC;
+        e = tg::launch_splitk_reduce(g, stream);
+    }
+    if (e != hipSuccess)
+        return fail(TG_ERR_HIP, std::string("launch of ") + ki.name + " failed: " + hipGetErrorString(e));
+    return TG_OK;
+}
+
+tg_status zero_fill(const Problem &p, hipStream_t stream) {
+    GemmParams g;
+    memset(&g, 0, sizeof g);
+    g.C = p.C; g.ldc = p.ldc; g.strideC = p.strideC;
+    g.m = (int)p.m; g.n = (int)p.n; g.batch = (int)p.batch;
+    hipError_t e = tg::launch_zero_fill(g, stream);
+    if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("zero fill failed: ") + hipGetErrorString(e));
+    return TG_OK;
+}
+
+tg_status run(Problem &p, void *stream) {
+    tg_status st = validate(p);
+    if (st != TG_OK) return st;
+    if (p.batch == 0 || p.m == 0 || p.n == 0) { t_last_config.clear(); return TG_OK; }
+    st = check_device();
+    if (st != TG_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (p.k == 0) { t_last_config = "zero_fill"; return zero_fill(p, s); }
+    Config c;
+    void *ws;
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        st = choose(p, &c);
+        ws = g_ws;
+    }
+    if (st != TG_OK) return st;
+    st = launch(p, c, ws, s);
+    if (st == TG_OK) t_last_config = spec_of(c);
+    return st;
+}
+
+}  // namespace
+
+extern "C" {
+
+tg_status tg_sgemm(int64_t m, int64_t n, int64_t k, const float *A, int64_t lda, const float *B, int64_t ldb,
+                   float *C, int64_t ldc, void *stream) {
+    Problem p{1, m, n, k, A, lda, 0, B, ldb, 0, C, ldc, 0, false};
+    return run(p, stream);
+}
+
+tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A, int64_t lda,
+                           int64_t strideA, const float *B, int64_t ldb, int64_t strideB, float *C, int64_t ldc,
+                           int64_t strideC, void *stream) {
+    Problem p{batch, m, n, k, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, false};
+    return run(p, stream);
+}
+
+tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A, int64_t lda, int64_t strideA,
+                  const float *B, int64_t ldb, int64_t strideB, float *C, int64_t ldc, int64_t strideC,
+                  void *stream, int reps) {
+    Problem p{batch, m, n, k, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, false};
+    tg_status st = validate(p);
+    if (st != TG_OK) return st;
+    if (p.batch == 0 || p.m == 0 || p.n == 0 || p.k == 0) return run(p, stream);
+    st = check_device();
+    if (st != TG_OK) return st;
+    if (reps <= 0) reps = 5;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    void *ws;
+    size_t ws_bytes;
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        ws = g_ws;
+        ws_bytes = g_ws_bytes;
+    }
+    std::vector<Config> cands = candidates(p, ws_bytes);
+    if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
+
+    hipEvent_t ev0, ev1;
+    if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess)
+        return fail(TG_ERR_HIP, "hipEventCreate failed");
+
+    auto time_config = [&](const Config &c, double *usec) -> tg_status {
+        tg_status r = launch(p, c, ws, s);   // warm-up (also loads the code object)
+        if (r != TG_OK) return r;
+        hipEventRecord(ev0, s);
+        for (int i = 0; i < reps && r == TG_OK; ++i) r = launch(p, c, ws, s);
+        hipEventRecord(ev1, s);
+        hipError_t e = hipEventSynchronize(ev1);
+        if (r != TG_OK) return r;
+        if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
+        float ms = 0.f;
+        hipEventElapsedTime(&ms, ev0, ev1);
+        *usec = 1e3 * ms / reps;
+        return TG_OK;
+    };
+
+    Config best;
+    double best_us = 1e300;
+    std::string last_err;
+    const bool log = getenv("TG_LOG") != nullptr;
+    for (const Config &c : cands) {
+        const double lb_us = 1e6 * lower_bound_seconds(p, c);
+        if (lb_us >= best_us) {
+            if (log) fprintf(stderr, "tgemm tune: %-44s pruned (bound %.1f us >= best %.1f us)\n", spec_of(c).c_str(), lb_us, best_us);
+            continue;
+        }
+        double us = 0;
+        tg_status r = time_config(c, &us);
+        if (r != TG_OK) {
+            last_err = t_error;
+            (void)hipGetLastError();   // clear the error so the next candidate starts clean
+            continue;
+        }
+        if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us (bound %.1f)\n", spec_of(c).c_str(), us, lb_us);
+        if (us < best_us) { best_us = us; best = c; }
+    }
+    if (best.kernel >= 0 && tg::kernel(best.kernel).kind == tg::KIND_TILE) {
+        // refine the tile-order group of the winner
+        static const int kGroups[] = {1, 2, 4, 16, 32};
+        const int tiles_m = (int)ceil_div(p.m, tg::kernel(best.kernel).BM);
+        Config base = best;
+        for (int g : kGroups) {
+            if (g >= 2 * tiles_m && g != 1) continue;
+            Config c = base;
+            c.group = g;
+            double us = 0;
+            if (time_config(c, &us) != TG_OK) continue;
+            if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+            if (us < best_us) { best_us = us; best = c; }
+        }
+    }
+    hipEventDestroy(ev0);
+    hipEventDestroy(ev1);
+    if (best.kernel < 0) return fail(TG_ERR_HIP, "every candidate failed to run: " + last_err);
+
+    st = launch(p, best, ws, s);   // leave C holding the product computed by the winner
+    hipError_t e = hipStreamSynchronize(s);
+    if (st != TG_OK) return st;
+    if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        g_cache[key_of(p)] = TunedEntry{best, best_us};
+    }
+    t_last_config = spec_of(best);
+    return TG_OK;
+}
+
+tg_status tg_set_workspace(void *dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0)) return fail(TG_ERR_INVALID_ARG, "workspace pointer and size must both be set or both be empty");
+    if (reinterpret_cast<uintptr_t>(dev_ptr) & 15u) return fail(TG_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    std::lock_guard<std::mutex> lk(g_mutex);
+    g_ws = dev_ptr;
+    g_ws_bytes = bytes;
+    return TG_OK;
+}
+
+size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k) {
+    if (batch <= 0 || m <= 0 || n <= 0 || k <= 0) return 0;
+    if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return 0;
+    Problem p{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, true};
+    size_t need = 0;
+    for (const Config &c : candidates(p, SIZE_MAX)) need = std::max(need, ws_need(p, c.splits));
+    return need;
+}
+
+tg_status tg_force_config(const char *spec) {
+    std::lock_guard<std::mutex> lk(g_mutex);
+    g_env_read = true;   // an explicit call overrides the environment
+    if (!spec || !*spec) { g_forced = false; return TG_OK; }
+    Config c;
+    std::string why;
+    if (!parse_spec(spec, c, why)) return fail(TG_ERR_INVALID_ARG, "bad configuration spec: " + why);
+    g_forced = true;
+    g_force_cfg = c;
+    return TG_OK;
+}
+
+tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *buf, size_t len) {
+    if (!buf || len == 0) return fail(TG_ERR_INVALID_ARG, "no output buffer");
+    if (batch <= 0 || m <= 0 || n <= 0 || k <= 0) return fail(TG_ERR_INVALID_ARG, "sizes must be positive");
+    if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
+    Problem p{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, false};
+    p.aligned = k % 4 == 0 && n % 4 == 0;
+    Config c;
+    tg_status st;
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        st = choose(p, &c);
+    }
+    if (st != TG_OK) return st;
+    const std::string s = spec_of(c);
+    if (s.size() + 1 > len) return fail(TG_ERR_INVALID_ARG, "output buffer too small");
+    memcpy(buf, s.c_str(), s.size() + 1);
+    return TG_OK;
+}
+
+const char *tg_last_config(void) { return t_last_config.c_str(); }
+
+int tg_num_kernels(void) { return tg::num_kernels(); }
+
+tg_status tg_kernel_name(int idx, char *buf, size_t len) {
+    if (idx < 0 || idx >= tg::num_kernels() || !buf) return fail(TG_ERR_INVALID_ARG, "kernel index out of range");
+    const char *n = tg::kernel(idx).name;
+    if (strlen(n) + 1 > len) return fail(TG_ERR_INVALID_ARG, "output buffer too small");
+    memcpy(buf, n, strlen(n) + 1);
+    return TG_OK;
+}
+
+tg_status tg_save_tune_cache(const char *path) {
+    if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
+    FILE *f = fopen(path, "w");
+    if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
+    fprintf(f, "tgemm-tune-cache 1 gfx950\n");
+    std::lock_guard<std::mutex> lk(g_mutex);
+    for (const auto &kv : g_cache) {
+        const ShapeKey &k = kv.first;
+        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
+                (long long)std::get<2>(k), (long long)std::get<3>(k), std::get<4>(k),
+                tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.usec);
+    }
+    fclose(f);
+    return TG_OK;
+}
+
+tg_status tg_load_tune_cache(const char *path) {
+    if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
+    FILE *f = fopen(path, "r");
+    if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
+    char head[64] = {0}, arch[32] = {0};
+    int ver = 0;
+    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || ver != 1 ||
+        strcmp(arch, "gfx950") != 0) {
+        fclose(f);
+        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 1)");
+    }
+    std::lock_guard<std::mutex> lk(g_mutex);
+    long long b, m, n, k;
+    int al, splits, group;
+    char name[128];
+    double us;
+    while (fscanf(f, "%lld %lld %lld %lld %d %127s %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &us) == 9) {
+        Config c;
+        c.kernel = find_kernel(name);
+        c.splits = splits;
+        c.group = group;
+        if (c.kernel < 0 || splits < 1 || group < 1) continue;   // entry from another build: ignore
+        g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
+    }
+    fclose(f);
+    return TG_OK;
+}
+
+void tg_clear_tune_cache(void) {
+    std::lock_guard<std::mutex> lk(g_mutex);
+    g_cache.clear();
+}
+
+const char *tg_status_string(tg_status s) {
+    switch (s) {
+        case TG_OK: return "TG_OK";
+        case TG_ERR_INVALID_ARG: return "TG_ERR_INVALID_ARG";
+        case TG_ERR_UNSUPPORTED: return "TG_ERR_UNSUPPORTED";
+        case TG_ERR_WORKSPACE: return "TG_ERR_WORKSPACE";
+        case TG_ERR_HIP: return "TG_ERR_HIP";
+        case TG_ERR_INTERNAL: return "TG_ERR_INTERNAL";
+    }
+    return "TG_ERR_UNKNOWN";
+}
+
+const char *tg_last_error(void) { return t_error.c_str(); }
+
+int tg_version(void) { return kVersion; }
+
+}  // extern "C"

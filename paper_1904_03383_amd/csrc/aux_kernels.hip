@@ -1,0 +1,127 @@
+// Kernels around the workgroup-tile SGEMM: the one-wave-per-tile kernel for small and
+// batched problems, the deterministic split-K reduction and the k == 0 zero fill.
+#include "tile_kernel.hpp"
+
+namespace tg {
+
+// One wave computes one 32x32 tile of C over the whole of K (matmul of Sec. 5.2 of the
+// paper, per problem of a batch), reading its operands straight from global memory: with
+// a single wave per tile nothing is shared between waves, so LDS staging and barriers
+// would only add latency.  Four independent waves share a 256-thread workgroup.
+// Lane l (i = l % 32, h = l / 32) reads A[row i][8o+4h .. 8o+4h+3] and B[8o+4h+t][col i]
+// (t = 0..3) and issues four v_mfma_f32_32x32x2_f32, so MFMA t multiplies the k pair
+// (8o+t, 8o+4+t); every access is predicated, any m, n, k and leading dimension works.
+__global__ void __launch_bounds__(256) sgemm_wave32_kernel(const GemmParams p) {
+    const int lane = threadIdx.x & 63;
+    const int li = lane & 31, h = lane >> 5;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= tiles * p.batch) return;   // whole wave leaves; the kernel has no barrier
+    const int prob = (int)(wid / tiles);
+    const int t_in = (int)(wid - (int64_t)prob * tiles);
+    const int tm = t_in / p.tiles_n, tn = t_in - tm * p.tiles_n;
+
+    const int row = tm * 32 + li, col = tn * 32 + li;
+    const bool row_ok = row < p.m, col_ok = col < p.n;
+    const float *a_row = p.A + (int64_t)prob * p.strideA + (int64_t)row * p.lda;
+    const float *b_col = p.B + (int64_t)prob * p.strideB + col;
+    const bool vec_a = (p.flags & kFlagVecA) != 0;
+
+    f32x16 acc = (f32x16)(0.0f);
+#pragma unroll 2
+    for (int k0 = 0; k0 < p.k; k0 += 8) {
+        const int kk = k0 + 4 * h;
+        f32x4 a;
+        if (vec_a && row_ok && kk + 3 < p.k) {
+            a = *reinterpret_cast<const f32x4 *>(a_row + kk);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[e] = (row_ok && kk + e < p.k) ? a_row[kk + e] : 0.0f;
+        }
+        float b[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) b[t] = (col_ok && kk + t < p.k) ? b_col[(int64_t)(kk + t) * p.ldb] : 0.0f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
+    }
+
+    float *c = p.C + (int64_t)prob * p.strideC;
+    if (col_ok) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = tm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            if (r < p.m) c[(int64_t)r * p.ldc + col] = acc[v];
+        }
+    }
+}
+
+hipError_t launch_wave32(const GemmParams &p, hipStream_t s) {
+    const int64_t waves = (int64_t)p.tiles_m * p.tiles_n * p.batch;
+    const int64_t blocks = (waves + 3) / 4;
+    hipLaunchKernelGGL(sgemm_wave32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// C[b][i][j] = sum over s = 0..splits-1 of ws[b][s][i][j], added in that fixed order, so
+// the result does not depend on scheduling (no floating-point atomics anywhere).
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p) {
+    const int64_t mn = (int64_t)p.m * p.n;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p.flags & kFlagVecC) {
+        const int64_t n4 = p.n / 4;
+        const int64_t total = (int64_t)p.batch * p.m * n4;
+        for (int64_t idx = first; idx < total; idx += stride) {
+            const int64_t b = idx / (p.m * n4);
+            const int64_t rem = idx - b * p.m * n4;
+            const int64_t i = rem / n4, j = (rem - i * n4) * 4;
+            const float *src = p.ws + b * p.splits * mn + i * p.n + j;
+            f32x4 sum = *reinterpret_cast<const f32x4 *>(src);
+            for (int s = 1; s < p.splits; ++s) sum += *reinterpret_cast<const f32x4 *>(src + s * mn);
+            *reinterpret_cast<f32x4 *>(p.C + b * p.strideC + i * p.ldc + j) = sum;
+        }
+    } else {
+        const int64_t total = (int64_t)p.batch * mn;
+        for (int64_t idx = first; idx < total; idx += stride) {
+            const int64_t b = idx / mn;
+            const int64_t rem = idx - b * mn;
+            const int64_t i = rem / p.n, j = rem - i * p.n;
+            const float *src = p.ws + b * p.splits * mn + rem;
+            float sum = src[0];
+            for (int s = 1; s < p.splits; ++s) sum += src[s * mn];
+            p.C[b * p.strideC + i * p.ldc + j] = sum;
+        }
+    }
+}
+
+hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s) {
+    const int64_t items = (p.flags & kFlagVecC) ? (int64_t)p.batch * p.m * (p.n / 4) : (int64_t)p.batch * p.m * p.n;
+    int64_t blocks = (items + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) zero_fill_kernel(const GemmParams p) {
+    const int64_t mn = (int64_t)p.m * p.n;
+    const int64_t total = (int64_t)p.batch * mn;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const int64_t b = idx / mn;
+        const int64_t rem = idx - b * mn;
+        const int64_t i = rem / p.n, j = rem - i * p.n;
+        p.C[b * p.strideC + i * p.ldc + j] = 0.0f;
+    }
+}
+
+hipError_t launch_zero_fill(const GemmParams &p, hipStream_t s) {
+    const int64_t items = (int64_t)p.batch * p.m * p.n;
+    int64_t blocks = (items + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace tg

@@ -1,0 +1,43 @@
+// Table of compiled kernel variants.  The template instantiations live in the
+// tile_inst_*.hip units; this file only declares and lists them.
+#include "tg_internal.h"
+
+namespace tg {
+
+#define TG_DECL(BM, BN, BK, WM, WN, L2, EDGE) \
+    extern template hipError_t launch_tile<BM, BN, BK, WM, WN, L2, EDGE>(const GemmParams &, hipStream_t);
+#define TG_ROW(BM, BN, BK, WM, WN, L2, EDGE, NAME)                                              \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, EDGE, (BM / WM) * (BN / WN) * 64,                 \
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE>},
+
+// (BM, BN, BK, WM, WN, two_level, edge, name)
+#define TG_TILE_LIST(X)                                                     \
+    X(128, 128, 16, 64, 64, false, false, "t128x128x16_w64x64")             \
+    X(128, 128, 16, 64, 64, true, false, "t128x128x16_w64x64_acc2")         \
+    X(128, 128, 32, 64, 64, false, false, "t128x128x32_w64x64")             \
+    X(128, 128, 32, 64, 64, true, false, "t128x128x32_w64x64_acc2")         \
+    X(256, 128, 16, 128, 64, false, false, "t256x128x16_w128x64")           \
+    X(256, 128, 16, 128, 64, true, false, "t256x128x16_w128x64_acc2")       \
+    X(128, 256, 16, 64, 128, false, false, "t128x256x16_w64x128")           \
+    X(128, 256, 16, 64, 128, true, false, "t128x256x16_w64x128_acc2")       \
+    X(64, 64, 32, 32, 32, false, false, "t64x64x32_w32x32")                 \
+    X(64, 64, 32, 32, 32, true, false, "t64x64x32_w32x32_acc2")             \
+    X(128, 64, 32, 64, 32, false, false, "t128x64x32_w64x32")               \
+    X(64, 128, 32, 32, 64, false, false, "t64x128x32_w32x64")               \
+    X(128, 128, 16, 64, 64, false, true, "t128x128x16_w64x64_edge")         \
+    X(128, 128, 16, 64, 64, true, true, "t128x128x16_w64x64_acc2_edge")     \
+    X(64, 64, 16, 32, 32, false, true, "t64x64x16_w32x32_edge")             \
+    X(64, 64, 16, 32, 32, true, true, "t64x64x16_w32x32_acc2_edge")
+
+#define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE)
+TG_TILE_LIST(TG_DECL_X)
+
+static const KernelInfo kTable[] = {
+    TG_TILE_LIST(TG_ROW)
+    {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, 256, 0, &launch_wave32},
+};
+
+int num_kernels() { return (int)(sizeof(kTable) / sizeof(kTable[0])); }
+const KernelInfo &kernel(int idx) { return kTable[idx]; }
+
+}  // namespace tg

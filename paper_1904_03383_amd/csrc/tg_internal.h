@@ -1,0 +1,76 @@
+// Internal interface between the host side (API, dispatcher, tuner) and the HIP kernels.
+// Not part of the public boundary (include/tgemm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tg {
+
+// Everything a GEMM kernel launch needs.  Sizes are validated to fit in int32 by the
+// API layer; element offsets are formed in 64 bits.
+struct GemmParams {
+    const float *A;
+    const float *B;
+    float *C;             // final output
+    float *ws;            // split-K partial sums: [batch][splits][m][n], ld = n (nullptr if splits == 1)
+    int64_t lda, ldb, ldc;
+    int64_t strideA, strideB, strideC;
+    int m, n, k;
+    int batch;
+    int splits;           // number of K ranges; each writes its own partial product
+    int ktiles_per_split; // K tiles (of the kernel's BK) per range
+    int tiles_m, tiles_n; // C tiles per problem
+    int group;            // tile rows per swizzle group (tile order inside one problem)
+    int flush_tiles;      // two-level accumulation: fold the MFMA accumulators into the
+                          // second-level sums every this many K tiles (0 = never)
+    int flags;            // kFlag* bits, computed on the host from pointers and strides
+};
+
+constexpr int kFlagVecA = 1;  // rows of A may be read as aligned 16-byte vectors (wave kernel)
+constexpr int kFlagVecC = 2;  // rows of C may be written as aligned 16-byte vectors (reduce kernel)
+
+typedef hipError_t (*launch_fn)(const GemmParams &, hipStream_t);
+
+enum KernelKind { KIND_TILE = 0, KIND_WAVE = 1 };
+
+struct KernelInfo {
+    const char *name;
+    KernelKind kind;
+    int BM, BN, BK;      // workgroup tile (KIND_WAVE: tile of one wave, BK = k step)
+    int WM, WN;          // wave tile
+    bool two_level;      // has second-level accumulators (needed for long K)
+    bool edge;           // predicated variant: any m, n, k, leading dimension and alignment
+    int threads;
+    int lds_bytes;
+    launch_fn launch;
+};
+
+// Kernel table (registry.cpp).
+int num_kernels();
+const KernelInfo &kernel(int idx);
+
+// Workgroup-tile kernels: LDS-staged, double-buffered, MFMA 32x32x2 register blocks.
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
+hipError_t launch_tile(const GemmParams &p, hipStream_t s);
+template <int BM, int BN, int BK, int WM, int WN>
+constexpr int tile_lds_bytes();
+
+// One wave per 32x32 C tile, operands straight from global memory (small / batched problems).
+hipError_t launch_wave32(const GemmParams &p, hipStream_t s);
+
+// C[b][i][j] = sum_s ws[b][s][i][j], fixed order s = 0..splits-1 (deterministic).
+hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s);
+
+// C[b][i][j] = +0.0 on the m x n region (k == 0).
+hipError_t launch_zero_fill(const GemmParams &p, hipStream_t s);
+
+constexpr int kLdsPadA = 4;  // floats added to each A row in LDS (conflict-free b128 reads)
+constexpr int kLdsPadB = 8;  // floats added to each B row in LDS
+
+template <int BM, int BN, int BK, int WM, int WN>
+constexpr int tile_lds_bytes() {
+    return 2 * (BM * (BK + kLdsPadA) + BK * (BN + kLdsPadB)) * (int)sizeof(float);
+}
+
+}  // namespace tg

@@ -1,0 +1,319 @@
+"""GPU parity: the HIP path (through the C-ABI) against the CPU oracle, element by element.
+
+Cases: the five benchmark workloads at full size with their distributions, the integer
+variant of every workload (bit exact), every compiled kernel variant forced in turn on a
+shape spanning several tiles, ragged sizes, padded leading dimensions, split-K, batch
+strides, k = 0, and run-to-run bit identity.
+"""
+import numpy as np
+import pytest
+
+import paper_1904_03383_amd as tg
+from paper_1904_03383_amd import inputgen as ig
+
+from gpu_common import check_against_oracle, run_hip, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _clean_library_state():
+    tg.force_config(None)
+    tg.set_workspace(None)
+    yield
+    tg.force_config(None)
+    tg.set_workspace(None)
+
+
+def _squeeze(a, b):
+    return (a[0], b[0]) if a.shape[0] == 1 else (a, b)
+
+
+# ---- the five workloads, at full size, in the configuration the library picks itself ----
+
+@pytest.mark.parametrize("name", list(ig.CONFIGS))
+def test_workload_matches_oracle(name):
+    say(f"workload {name} ({ig.CONFIGS[name]})")
+    a, b = _squeeze(*ig.make_config(name))
+    c = run_hip(a, b)
+    m = check_against_oracle(c, a, b, what=name)
+    say(f"  config {tg.last_config()}  max_ratio {m['max_ratio']:.2e}  rel_fro {m['rel_fro']:.2e}")
+
+
+@pytest.mark.parametrize("name", list(ig.CONFIGS))
+def test_workload_integer_variant_is_bit_exact(name):
+    """Entries in {-4..4}: every partial sum is an integer below 2^24, so any summation order is exact."""
+    say(f"integer variant of {name}")
+    a, b = _squeeze(*ig.make_config(name, dist="int"))
+    c = run_hip(a, b)
+    check_against_oracle(c, a, b, exact=True, what=name + "/int")
+
+
+def test_workload_c5_tuned_configuration_matches_oracle():
+    """4096^3 in the launch configuration the benchmark times (after tg_tune)."""
+    import torch
+    say("c5_4096 after tune")
+    a, b = _squeeze(*ig.make_config("c5_4096"))
+    da, db = to_dev(a), to_dev(b)
+    tg.clear_tune_cache()
+    try:
+        c = tg.tune(da, db, reps=2)
+        torch.cuda.synchronize()
+        tuned = tg.last_config()
+        c2 = tg.sgemm(da, db)
+        torch.cuda.synchronize()
+        assert tg.last_config() == tuned
+        assert torch.equal(c, c2)
+        m = check_against_oracle(c2.cpu().numpy(), a, b, what="c5 tuned " + tuned)
+        say(f"  tuned {tuned}  rel_fro {m['rel_fro']:.2e}")
+    finally:
+        tg.clear_tune_cache()
+
+
+# ---- every kernel variant, forced -----------------------------------------------------------
+
+def _shape_for(name: str):
+    """A shape valid for the named variant that spans several tiles (ragged for predicated ones)."""
+    if name == "wave32":
+        return 1, 70, 45, 61
+    body = name.split("_")[0][1:]
+    bm, bn, bk = (int(x) for x in body.split("x"))
+    k = 1536 if "acc2" in name else 320      # acc2 variants need a K range above 1024
+    if name.endswith("_edge"):
+        return 1, 2 * bm + 37, bn + 21, k + 13
+    return 1, 2 * bm, 3 * bn, k
+
+
+@pytest.mark.parametrize("dist", ["uniform", "int"])
+def test_each_kernel_variant(dist):
+    for name in tg.kernel_names():
+        batch, m, n, k = _shape_for(name)
+        say(f"forced {name} on {m}x{n}x{k} ({dist})")
+        a, b = ig.make_operands(batch, m, n, k, dist, 301, 302)
+        tg.force_config(name + ":s1:g2")
+        c = run_hip(a[0], b[0])
+        assert tg.last_config() == name + ":s1:g2"
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=name)
+
+
+@pytest.mark.parametrize("group", [1, 3, 8, 64])
+def test_tile_order_groups(group):
+    say(f"tile order group {group}")
+    a, b = ig.make_operands(1, 5 * 128, 3 * 128, 64, "int", 311, 312)
+    tg.force_config(f"t128x128x16_w64x64:s1:g{group}")
+    check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what=f"group {group}")
+
+
+# ---- ragged shapes, padded leading dimensions, batches ---------------------------------------
+
+RAGGED = [(1, 1, 1), (1, 7, 3), (7, 1, 5), (31, 33, 65), (33, 31, 7), (65, 100, 257), (100, 257, 31),
+          (257, 65, 100), (129, 127, 1030), (300, 200, 2100), (2, 3000, 9), (3000, 2, 40)]
+
+
+@pytest.mark.parametrize("shape", RAGGED, ids=lambda s: "x".join(map(str, s)))
+def test_ragged_shapes(shape):
+    m, n, k = shape
+    say(f"ragged {m}x{n}x{k}")
+    for dist in ("normal", "int"):
+        a, b = ig.make_operands(1, m, n, k, dist, 321, 322)
+        c = run_hip(a[0], b[0])
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"ragged {shape} {dist}")
+
+
+@pytest.mark.parametrize("forced", [None, "t128x128x16_w64x64_edge", "t64x64x16_w32x32_edge", "wave32"])
+def test_ragged_through_each_predicated_kernel(forced):
+    m, n, k = 150, 139, 77
+    say(f"ragged {m}x{n}x{k} forced={forced}")
+    a, b = ig.make_operands(1, m, n, k, "int", 331, 332)
+    if forced:
+        tg.force_config(forced)
+    check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what=str(forced))
+
+
+@pytest.mark.parametrize("pads", [(0, 0, 0), (4, 8, 12), (1, 3, 5)], ids=str)
+@pytest.mark.parametrize("shape", [(256, 256, 64), (130, 70, 50)], ids=str)
+def test_leading_dimensions_and_untouched_padding(shape, pads):
+    """lda > k, ldb > n, ldc > n; elements of C beyond column n must keep their sentinel."""
+    import torch
+    m, n, k = shape
+    pa, pb, pc = pads
+    say(f"leading dimensions {shape} pads {pads}")
+    a_full = ig.small_int(341, (m, k + pa))
+    b_full = ig.small_int(342, (k, n + pb))
+    da, db = to_dev(a_full)[:, :k], to_dev(b_full)[:, :n]
+    c_full = torch.full((m, n + pc), -777.0, device="cuda")
+    out = c_full[:, :n]
+    tg.sgemm(da, db, out=out)
+    torch.cuda.synchronize()
+    host = c_full.cpu().numpy()
+    assert np.all(host[:, n:] == -777.0)
+    check_against_oracle(host[:, :n], np.ascontiguousarray(a_full[:, :k]), np.ascontiguousarray(b_full[:, :n]),
+                         exact=True, what=f"ld {shape} {pads}")
+
+
+def test_unaligned_base_pointers():
+    """Operands that start 4 bytes off a 16-byte boundary take the predicated path."""
+    import torch
+    say("unaligned base pointers")
+    m, n, k = 128, 128, 64
+    a = ig.small_int(351, (m * k + 1,))
+    b = ig.small_int(352, (k * n + 1,))
+    da = to_dev(a)[1:].view(m, k)
+    db = to_dev(b)[1:].view(k, n)
+    buf = torch.empty(m * n + 1, device="cuda")
+    out = buf[1:].view(m, n)
+    assert da.data_ptr() % 16 == 4
+    tg.sgemm(da, db, out=out)
+    torch.cuda.synchronize()
+    assert "_edge" in tg.last_config() or tg.last_config().startswith("wave32")
+    check_against_oracle(out.cpu().numpy(), a[1:].reshape(m, k), b[1:].reshape(k, n), exact=True, what="unaligned")
+
+
+@pytest.mark.parametrize("case", [(3, 32, 32, 64), (5, 70, 33, 20), (2, 256, 128, 96), (1, 64, 64, 64), (130, 16, 16, 16)], ids=str)
+def test_batched_shapes(case):
+    batch, m, n, k = case
+    say(f"batched {case}")
+    a, b = ig.make_operands(batch, m, n, k, "int", 361, 362)
+    check_against_oracle(run_hip(a, b), a, b, exact=True, what=f"batched {case}")
+    a, b = ig.make_operands(batch, m, n, k, "uniform", 363, 364)
+    check_against_oracle(run_hip(a, b), a, b, what=f"batched {case}")
+
+
+def test_batched_strides_and_broadcast():
+    """Batch strides larger than a matrix, and strideB = 0 (one B shared by all problems)."""
+    import torch
+    say("batched strides / broadcast")
+    batch, m, n, k = 4, 64, 64, 32
+    a_big = ig.small_int(371, (batch, m + 3, k))
+    da = to_dev(a_big)[:, :m, :]                      # strideA = (m+3)*k
+    b_one = ig.small_int(372, (1, k, n))
+    db = to_dev(b_one).expand(batch, k, n)            # strideB = 0
+    out = tg.sgemm_batched(da, db)
+    torch.cuda.synchronize()
+    a = np.ascontiguousarray(a_big[:, :m, :])
+    b = np.ascontiguousarray(np.broadcast_to(b_one, (batch, k, n)))
+    check_against_oracle(out.cpu().numpy(), a, b, exact=True, what="batched strides")
+
+
+# ---- split-K ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("spec,shape", [
+    ("t128x128x16_w64x64:s4", (256, 384, 1024)),
+    ("t128x128x16_w64x64:s3", (256, 128, 1008)),
+    ("t128x128x16_w64x64_acc2:s2", (256, 256, 4096)),
+    ("t64x64x32_w32x32:s8", (128, 192, 2048)),
+    ("t64x64x16_w32x32_edge:s5", (100, 77, 1000)),
+    ("t128x128x16_w64x64_edge:s2", (130, 250, 333)),
+], ids=str)
+def test_split_k(spec, shape):
+    import torch
+    m, n, k = shape
+    say(f"split-K {spec} on {shape}")
+    ws = torch.empty(16 * m * n, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config(spec)
+    for dist in ("int", "uniform"):
+        a, b = ig.make_operands(1, m, n, k, dist, 381, 382)
+        c = run_hip(a[0], b[0])
+        assert tg.last_config().startswith(spec)
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=spec)
+
+
+def test_split_k_batched_and_workspace_too_small():
+    import torch
+    say("split-K batched / workspace checks")
+    batch, m, n, k = 3, 128, 128, 512
+    a, b = ig.make_operands(batch, m, n, k, "int", 391, 392)
+    tg.force_config("t128x128x16_w64x64:s4")
+    with pytest.raises(tg.TgemmError) as ei:
+        run_hip(a, b)
+    assert ei.value.status_name == "TG_ERR_WORKSPACE"
+    ws = torch.empty(batch * 4 * m * n - 4, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    with pytest.raises(tg.TgemmError):
+        run_hip(a, b)
+    ws = torch.empty(batch * 4 * m * n, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    check_against_oracle(run_hip(a, b), a, b, exact=True, what="split-K batched")
+
+
+# ---- degenerate sizes -------------------------------------------------------------------------
+
+def test_k_zero_gives_zeros_and_empty_outputs_are_noops():
+    import torch
+    say("k == 0 and empty outputs")
+    a = torch.empty((5, 0), device="cuda")
+    b = torch.empty((0, 7), device="cuda")
+    out = torch.full((5, 9), 3.0, device="cuda")
+    tg.sgemm(a, b, out=out[:, :7])
+    torch.cuda.synchronize()
+    host = out.cpu().numpy()
+    assert np.all(host[:, :7] == 0.0) and np.all(host[:, 7:] == 3.0)
+    assert tg.sgemm(torch.empty((0, 4), device="cuda"), torch.empty((4, 6), device="cuda")).shape == (0, 6)
+    assert tg.sgemm(torch.empty((3, 4), device="cuda"), torch.empty((4, 0), device="cuda")).shape == (3, 0)
+    assert tg.sgemm_batched(torch.empty((0, 3, 4), device="cuda"), torch.empty((0, 4, 5), device="cuda")).shape == (0, 3, 5)
+    ab = torch.empty((2, 3, 0), device="cuda")
+    bb = torch.empty((2, 0, 4), device="cuda")
+    assert torch.all(tg.sgemm_batched(ab, bb) == 0)
+
+
+def test_output_may_start_as_nan():
+    """C is overwritten, never read: NaNs already in the output buffer do not leak."""
+    import torch
+    say("NaN-initialised output")
+    a, b = ig.make_operands(1, 256, 256, 128, "int", 401, 402)
+    out = torch.full((256, 256), float("nan"), device="cuda")
+    tg.sgemm(to_dev(a[0]), to_dev(b[0]), out=out)
+    torch.cuda.synchronize()
+    check_against_oracle(out.cpu().numpy(), a[0], b[0], exact=True, what="nan out")
+
+
+# ---- determinism --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("spec,shape", [("t128x128x16_w64x64", (512, 512, 512)),
+                                        ("t128x128x16_w64x64:s4", (256, 256, 2048)),
+                                        ("wave32", (96, 96, 200))], ids=str)
+def test_repeated_launches_are_bit_identical(spec, shape):
+    """No atomics and a barrier between LDS stages: 50 launches must agree bit for bit."""
+    import torch
+    m, n, k = shape
+    say(f"determinism {spec} {shape}")
+    ws = torch.empty(4 * m * n, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config(spec)
+    a, b = ig.make_operands(1, m, n, k, "normal", 411, 412)
+    da, db = to_dev(a[0]), to_dev(b[0])
+    first = tg.sgemm(da, db).clone()
+    for _ in range(50):
+        again = tg.sgemm(da, db)
+        assert torch.equal(first, again)
+    torch.cuda.synchronize()
+
+
+# ---- tuner ------------------------------------------------------------------------------------------
+
+def test_tune_picks_a_valid_configuration_and_is_used_afterwards():
+    import torch
+    say("tuner on 1024^3 with workspace")
+    a, b = _squeeze(*ig.make_config("c2_1024"))
+    da, db = to_dev(a), to_dev(b)
+    ws = torch.empty(tg.workspace_bytes(1, 1024, 1024, 1024) // 4, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    tg.clear_tune_cache()
+    try:
+        c = tg.tune(da, db, reps=3)
+        tuned = tg.last_config()
+        assert tuned.split(":")[0] in tg.kernel_names()
+        assert tg.get_config(1, 1024, 1024, 1024) == tuned
+        check_against_oracle(c.cpu().numpy(), a, b, what="tuned c2 " + tuned)
+        c2 = tg.sgemm(da, db)
+        torch.cuda.synchronize()
+        assert tg.last_config() == tuned and torch.equal(c, c2)
+        # the tuned split-K entry is not used once the workspace is gone; the call still succeeds
+        tg.set_workspace(None)
+        c3 = tg.sgemm(da, db)
+        torch.cuda.synchronize()
+        assert ":s1:" in tg.last_config()
+        check_against_oracle(c3.cpu().numpy(), a, b, what="c2 without workspace")
+    finally:
+        tg.clear_tune_cache()
