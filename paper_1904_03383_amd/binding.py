@@ -58,6 +58,9 @@ def load_library():
             raise FileNotFoundError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_1904_03383_amd.build` "
                 "(there is no fallback implementation)")
+        # torch is imported first so that libtgemm.so binds to the HIP runtime torch has
+        # already loaded (same soname); a second runtime in the process would not see the GPU.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(str(_LIB_PATH))
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)

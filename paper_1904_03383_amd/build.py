@@ -58,6 +58,9 @@ def build(force: bool = False, jobs: int | None = None) -> pathlib.Path:
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force, hdr_mtime), srcs))
     if force or not LIB.exists() or LIB.stat().st_mtime < max(o.stat().st_mtime for o in objs):
+        # The library needs libamdhip64.so.7 by soname: inside a PyTorch process it binds to the
+        # runtime torch has already loaded (the binding imports torch first; two HIP runtimes in
+        # one process do not both see the GPU), stand-alone it finds ROCm's through the run path.
         cmd = [_hipcc(), f"--offload-arch={ARCH}", "-shared", "-fPIC", "-o", str(LIB)] + [str(o) for o in objs]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
