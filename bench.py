@@ -129,6 +129,8 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune-reps", type=int, default=5)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -172,6 +174,15 @@ def main():
             del bufs
             log(f"  {name}: {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.2f} us  {r['device_tflops']:.2f} TFLOP/s")
             others.append(r)
+
+    if args.copy_calibration:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copy calibration: one 256 MiB device-to-device copy done")
+        del src, dst
 
     traffic = None
     tfile = ROOT / "profiles" / "hbm_traffic.json"

@@ -30,7 +30,7 @@ constexpr int kLongK = 1024;                // K range above which second-level 
 constexpr int kFlushK = 512;                // K terms between folds of the first-level accumulators
 constexpr int kWaveMaxK = 2048;             // longest K the single-accumulator wave kernel may take
 constexpr int kDefaultGroup = 8;
-constexpr int kLdsPerCU = 160 * 1024;
+using tg::kLdsPerCU;
 
 thread_local std::string t_error;
 thread_local std::string t_last_config;
@@ -39,6 +39,7 @@ struct Config {
     int kernel = -1;
     int splits = 1;
     int group = kDefaultGroup;
+    int occ = 0;   // cap on workgroups per CU (0 = whatever fits)
 };
 
 struct Problem {
@@ -72,7 +73,8 @@ tg_status fail(tg_status s, const std::string &msg) {
 
 std::string spec_of(const Config &c) {
     char buf[160];
-    snprintf(buf, sizeof buf, "%s:s%d:g%d", tg::kernel(c.kernel).name, c.splits, c.group);
+    if (c.occ > 0) snprintf(buf, sizeof buf, "%s:s%d:g%d:o%d", tg::kernel(c.kernel).name, c.splits, c.group, c.occ);
+    else snprintf(buf, sizeof buf, "%s:s%d:g%d", tg::kernel(c.kernel).name, c.splits, c.group);
     return buf;
 }
 
@@ -82,7 +84,7 @@ int find_kernel(const std::string &name) {
     return -1;
 }
 
-// "<kernel>[:s<splits>][:g<group>]"
+// "<kernel>[:s<splits>][:g<group>][:o<workgroups per CU>]"
 bool parse_spec(const char *spec, Config &out, std::string &why) {
     std::string s(spec);
     size_t pos = s.find(':');
@@ -93,11 +95,13 @@ bool parse_spec(const char *spec, Config &out, std::string &why) {
     while (pos != std::string::npos) {
         size_t next = s.find(':', pos + 1);
         std::string tok = s.substr(pos + 1, next == std::string::npos ? std::string::npos : next - pos - 1);
-        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g')) { why = "bad token '" + tok + "'"; return false; }
+        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g' && tok[0] != 'o')) { why = "bad token '" + tok + "'"; return false; }
         char *end = nullptr;
         long v = strtol(tok.c_str() + 1, &end, 10);
         if (*end != '\0' || v < 1 || v > 4096) { why = "bad value in '" + tok + "'"; return false; }
-        if (tok[0] == 's') c.splits = (int)v; else c.group = (int)v;
+        if (tok[0] == 's') c.splits = (int)v;
+        else if (tok[0] == 'g') c.group = (int)v;
+        else c.occ = (int)v;
         pos = next;
     }
     out = c;
@@ -196,6 +200,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     if (c.kernel < 0 || c.kernel >= tg::num_kernels()) return no("no such kernel");
     const KernelInfo &ki = tg::kernel(c.kernel);
     if (c.group < 1) return no("group must be >= 1");
+    if (c.occ < 0 || c.occ > 16) return no("occupancy cap must be 0..16");
     if (ki.kind == tg::KIND_WAVE) {
         if (c.splits != 1) return no("the wave kernel has no split-K");
         if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
@@ -206,13 +211,15 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     if (!ki.edge) {
         if (!p.aligned) return no("operands are not 16-byte aligned");
         if (p.m % ki.BM || p.n % ki.BN || p.k % ki.BK) return no("sizes are not multiples of the tile");
+        // the fast variants address inside a tile with 32-bit element offsets
+        if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
+            return no("leading dimension too large for the exact-fit kernels");
     }
     int splits, per;
     split_plan(ki, p.k, c.splits, &splits, &per);
     if (splits != c.splits) return no("split count leaves an empty K range");
     const int64_t k_range = std::min<int64_t>((int64_t)per * ki.BK, p.k);
     if (k_range > kLongK && !ki.two_level) return no("K range too long for a single accumulator level");
-    if (k_range <= kLongK && ki.two_level) return no("second accumulator level not needed");
     if (c.splits > 1) {
         if (per < 2) return no("K range shorter than two tiles");
         if (ws_need(p, c.splits) > ws_bytes) return no("workspace too small for this split");
@@ -290,6 +297,13 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             c.splits = s;
             c.group = kDefaultGroup;
             if (!config_valid(p, c, ws_bytes)) continue;
+            const KernelInfo &kinfo = tg::kernel(ki);
+            if (kinfo.kind == tg::KIND_TILE && kinfo.two_level) {
+                // second-level accumulators only cost registers when the K range is short
+                int sp, per;
+                split_plan(kinfo, p.k, s, &sp, &per);
+                if (std::min<int64_t>((int64_t)per * kinfo.BK, p.k) <= kLongK) continue;
+            }
             // splitting only pays while the chip is under-filled
             if (s > 1) {
                 const KernelInfo &k = tg::kernel(ki);
@@ -340,6 +354,22 @@ tg_status choose(const Problem &p, Config *out) {
     return TG_OK;
 }
 
+// 2-D split of the tile grid over the 8 XCDs: among the factorisations xm * xn == 8 that
+// divide the grid, take the one whose regions touch the fewest operand elements
+// (region rows + region columns); none fits -> linear ranges (xcd_m = xcd_n = 0).
+void choose_xcd_split(const KernelInfo &ki, const Problem &p, GemmParams &g) {
+    g.xcd_m = g.xcd_n = 0;
+    if (ki.kind != tg::KIND_TILE) return;
+    int64_t best = INT64_MAX;
+    for (int xm = 1; xm <= 8; xm *= 2) {
+        const int xn = 8 / xm;
+        if (g.tiles_m % xm || g.tiles_n % xn) continue;
+        const int64_t cost = (int64_t)(g.tiles_m / xm) * ki.BM + (int64_t)(g.tiles_n / xn) * ki.BN;
+        if (cost < best) { best = cost; g.xcd_m = xm; g.xcd_n = xn; }
+    }
+    (void)p;
+}
+
 tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream) {
     const KernelInfo &ki = tg::kernel(c.kernel);
     GemmParams g;
@@ -351,9 +381,11 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     g.tiles_m = (int)ceil_div(p.m, ki.BM);
     g.tiles_n = (int)ceil_div(p.n, ki.BN);
     g.group = std::min(c.group, g.tiles_m);
+    choose_xcd_split(ki, p, g);
     g.splits = 1;
     g.ktiles_per_split = (int)std::max<int64_t>(ceil_div(p.k, ki.BK), 1);
     g.flush_tiles = ki.two_level ? std::max(1, kFlushK / ki.BK) : 0;
+    g.max_blocks_per_cu = c.occ;
     g.flags = 0;
     if (p.aligned) g.flags |= tg::kFlagVecA | tg::kFlagVecC;
     if (ki.kind == tg::KIND_TILE && c.splits > 1) {
@@ -494,6 +526,18 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             if (us < best_us) { best_us = us; best = c; }
         }
     }
+    if (best.kernel >= 0 && tg::kernel(best.kernel).kind == tg::KIND_TILE) {
+        // refine the cap on workgroups per CU of the winner
+        Config base = best;
+        for (int occ = 1; occ <= 4; ++occ) {
+            Config c = base;
+            c.occ = occ;
+            double us = 0;
+            if (time_config(c, &us) != TG_OK) continue;
+            if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+            if (us < best_us * 0.995) { best_us = us; best = c; }
+        }
+    }
     hipEventDestroy(ev0);
     hipEventDestroy(ev1);
     if (best.kernel < 0) return fail(TG_ERR_HIP, "every candidate failed to run: " + last_err);
@@ -575,13 +619,14 @@ tg_status tg_save_tune_cache(const char *path) {
     if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
     FILE *f = fopen(path, "w");
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
-    fprintf(f, "tgemm-tune-cache 1 gfx950\n");
+    fprintf(f, "tgemm-tune-cache 2 gfx950\n");
     std::lock_guard<std::mutex> lk(g_mutex);
     for (const auto &kv : g_cache) {
         const ShapeKey &k = kv.first;
-        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
+        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
                 (long long)std::get<2>(k), (long long)std::get<3>(k), std::get<4>(k),
-                tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.usec);
+                tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.cfg.occ,
+                kv.second.usec);
     }
     fclose(f);
     return TG_OK;
@@ -593,22 +638,23 @@ tg_status tg_load_tune_cache(const char *path) {
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
     char head[64] = {0}, arch[32] = {0};
     int ver = 0;
-    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || ver != 1 ||
+    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || ver != 2 ||
         strcmp(arch, "gfx950") != 0) {
         fclose(f);
-        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 1)");
+        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 2)");
     }
     std::lock_guard<std::mutex> lk(g_mutex);
     long long b, m, n, k;
-    int al, splits, group;
+    int al, splits, group, occ;
     char name[128];
     double us;
-    while (fscanf(f, "%lld %lld %lld %lld %d %127s %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &us) == 9) {
+    while (fscanf(f, "%lld %lld %lld %lld %d %127s %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ, &us) == 10) {
         Config c;
         c.kernel = find_kernel(name);
         c.splits = splits;
         c.group = group;
-        if (c.kernel < 0 || splits < 1 || group < 1) continue;   // entry from another build: ignore
+        c.occ = occ;
+        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0) continue;   // entry from another build: ignore
         g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
     }
     fclose(f);

@@ -20,6 +20,10 @@ namespace tg {
     X(256, 128, 16, 128, 64, true, false, "t256x128x16_w128x64_acc2")       \
     X(128, 256, 16, 64, 128, false, false, "t128x256x16_w64x128")           \
     X(128, 256, 16, 64, 128, true, false, "t128x256x16_w64x128_acc2")       \
+    X(256, 128, 32, 128, 64, false, false, "t256x128x32_w128x64")           \
+    X(256, 128, 32, 128, 64, true, false, "t256x128x32_w128x64_acc2")       \
+    X(128, 256, 32, 64, 128, false, false, "t128x256x32_w64x128")           \
+    X(128, 256, 32, 64, 128, true, false, "t128x256x32_w64x128_acc2")       \
     X(64, 64, 32, 32, 32, false, false, "t64x64x32_w32x32")                 \
     X(64, 64, 32, 32, 32, true, false, "t64x64x32_w32x32_acc2")             \
     X(128, 64, 32, 64, 32, false, false, "t128x64x32_w64x32")               \

@@ -21,9 +21,12 @@ struct GemmParams {
     int splits;           // number of K ranges; each writes its own partial product
     int ktiles_per_split; // K tiles (of the kernel's BK) per range
     int tiles_m, tiles_n; // C tiles per problem
-    int group;            // tile rows per swizzle group (tile order inside one problem)
+    int group;            // tile rows per swizzle group (tile order inside one XCD's region)
+    int xcd_m, xcd_n;     // 2-D split of one problem's tile grid over the 8 XCDs (xcd_m * xcd_n == 8),
+                          // or 0, 0: XCDs take contiguous ranges of the linear tile order
     int flush_tiles;      // two-level accumulation: fold the MFMA accumulators into the
                           // second-level sums every this many K tiles (0 = never)
+    int max_blocks_per_cu; // occupancy cap enforced through the LDS request (0 = none)
     int flags;            // kFlag* bits, computed on the host from pointers and strides
 };
 
@@ -65,6 +68,7 @@ hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s);
 // C[b][i][j] = +0.0 on the m x n region (k == 0).
 hipError_t launch_zero_fill(const GemmParams &p, hipStream_t s);
 
+constexpr int kLdsPerCU = 160 * 1024;  // gfx950
 constexpr int kLdsPadA = 4;  // floats added to each A row in LDS (conflict-free b128 reads)
 constexpr int kLdsPadB = 8;  // floats added to each B row in LDS
 

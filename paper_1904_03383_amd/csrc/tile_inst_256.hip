@@ -5,4 +5,8 @@ template hipError_t launch_tile<256, 128, 16, 128, 64, false, false>(const GemmP
 template hipError_t launch_tile<256, 128, 16, 128, 64, true, false>(const GemmParams &, hipStream_t);
 template hipError_t launch_tile<128, 256, 16, 64, 128, false, false>(const GemmParams &, hipStream_t);
 template hipError_t launch_tile<128, 256, 16, 64, 128, true, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<256, 128, 32, 128, 64, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<256, 128, 32, 128, 64, true, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 256, 32, 64, 128, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 256, 32, 64, 128, true, false>(const GemmParams &, hipStream_t);
 }  // namespace tg

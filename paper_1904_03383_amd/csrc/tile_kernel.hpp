@@ -23,6 +23,8 @@
 
 #include "tg_internal.h"
 
+#include <type_traits>
+
 namespace tg {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -38,32 +40,67 @@ __device__ __forceinline__ float vec_get(float v, int) { return v; }
 __device__ __forceinline__ float vec_get(f32x2 v, int i) { return v[i]; }
 __device__ __forceinline__ float vec_get(f32x4 v, int i) { return v[i]; }
 
-// Workgroup id -> (slice, tile row, tile column).
-// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, each XCD having its own
-// L2.  The first step gives XCD x one contiguous range of logical ids, so the workgroups
-// resident on one XCD at a time work on neighbouring tiles; the second step orders tiles
-// inside a problem in groups of `group` tile rows walked column by column, which keeps the
-// set of A and B panels in flight small.  slice = problem * splits + split.
+// Workgroup id -> (slice, tile row, tile column);  slice = problem * splits + split.
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, and each XCD has its own
+// 4 MB L2.  So that the workgroups resident on one XCD share operand panels:
+//  * 2-D mode (xcd_m * xcd_n == 8, both dividing the tile grid): XCD x owns the
+//    rectangular region (x / xcd_n, x % xcd_n) of every slice's tile grid, which minimises
+//    the A rows plus B columns an XCD ever touches;
+//  * otherwise XCD x takes one contiguous range of the linear order (slice-major).
+// Inside a region (or a problem) tiles are walked in groups of `group` tile rows, column by
+// column, which keeps the set of panels in flight small.
+__device__ __forceinline__ void grouped_order(unsigned t, unsigned rows, unsigned cols, unsigned group,
+                                              unsigned &r, unsigned &c) {
+    const unsigned gw = group * cols;
+    const unsigned g = t / gw;
+    const unsigned first = g * group;
+    const unsigned rest = rows - first;
+    const unsigned gsz = rest < group ? rest : group;
+    const unsigned in = t - g * gw;
+    r = first + in % gsz;
+    c = in / gsz;
+}
+
 __device__ __forceinline__ void map_workgroup(const GemmParams &p, int &slice, int &tm, int &tn) {
     const unsigned W = gridDim.x, w = blockIdx.x;
-    const unsigned q = W >> 3, r = W & 7u, x = w & 7u, s = w >> 3;
-    const unsigned logical = x * q + (x < r ? x : r) + s;
+    const unsigned x = w & 7u, s = w >> 3;
     const unsigned T = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
+    unsigned r, c;
+    if (p.xcd_m != 0) {
+        const unsigned per = T >> 3;                 // tiles of one slice owned by one XCD
+        const unsigned sl = s / per, t = s - sl * per;
+        const unsigned rm = (unsigned)p.tiles_m / (unsigned)p.xcd_m, rn = (unsigned)p.tiles_n / (unsigned)p.xcd_n;
+        grouped_order(t, rm, rn, (unsigned)p.group < rm ? (unsigned)p.group : rm, r, c);
+        slice = (int)sl;
+        tm = (int)((x / (unsigned)p.xcd_n) * rm + r);
+        tn = (int)((x % (unsigned)p.xcd_n) * rn + c);
+        return;
+    }
+    const unsigned q = W >> 3, rem = W & 7u;
+    const unsigned logical = x * q + (x < rem ? x : rem) + s;
     const unsigned sl = logical / T;
-    const unsigned t = logical - sl * T;
-    const unsigned gw = (unsigned)p.group * (unsigned)p.tiles_n;
-    const unsigned g = t / gw;
-    const unsigned first = g * (unsigned)p.group;
-    const unsigned rest = (unsigned)p.tiles_m - first;
-    const unsigned gsz = rest < (unsigned)p.group ? rest : (unsigned)p.group;
-    const unsigned in = t - g * gw;
+    grouped_order(logical - sl * T, (unsigned)p.tiles_m, (unsigned)p.tiles_n, (unsigned)p.group, r, c);
     slice = (int)sl;
-    tm = (int)(first + in % gsz);
-    tn = (int)(in / gsz);
+    tm = (int)r;
+    tn = (int)c;
+}
+
+// Registers: a wave tile keeps WM*WN/64 accumulator registers per lane (twice that with the
+// second accumulation level), plus the staging registers of one K tile and two fragment
+// sets.  When that budget fits, the kernel is compiled for two waves per SIMD (256
+// registers per lane): two waves from different workgroups cover each other's barrier and
+// memory waits.
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+constexpr int min_waves_per_simd() {
+    constexpr int nt = (BM / WM) * (BN / WN) * 64;
+    constexpr int acc = (WM * WN / 64) * (TWO_LEVEL ? 2 : 1);
+    constexpr int staging = (BM * BK + BK * BN) / nt;
+    constexpr int frags = 2 * (4 * (WM / 32) + 4 * (WN / 32));
+    return acc + staging + frags + 64 <= 256 ? 2 : 1;
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
-__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64)
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (min_waves_per_simd<BM, BN, BK, WM, WN, TWO_LEVEL>()))
 sgemm_tile_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -97,58 +134,68 @@ sgemm_tile_kernel(const GemmParams p) {
     const int kt_stop = kt_begin + p.ktiles_per_split;
     const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
+    // Tile origins are wave-uniform (kept in scalar registers and advanced per K tile); each
+    // thread adds fixed offsets for its slots.  Fast variants use 32-bit offsets (the host
+    // checks that a tile spans fewer than 2^31 elements), predicated ones 64-bit.
     const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
     const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+    typedef typename std::conditional<EDGE, int64_t, unsigned>::type off_t;
 
     // Per-thread slots of the tile loads: slot f = tid + i*NT is one 16-byte vector.
     int a_row[A_LD], a_k[A_LD], b_row[B_LD], b_col[B_LD];
-    const float *a_ptr[A_LD], *b_ptr[B_LD];
+    off_t a_off[A_LD], b_off[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         const int f = tid + i * NT;
         a_row[i] = f / (BK / 4);
         a_k[i] = (f % (BK / 4)) * 4;
-        a_ptr[i] = Ag + (int64_t)a_row[i] * p.lda + a_k[i];
+        a_off[i] = (off_t)a_row[i] * (off_t)p.lda + (off_t)a_k[i];
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
         const int f = tid + i * NT;
         b_row[i] = f / (BN / 4);
         b_col[i] = (f % (BN / 4)) * 4;
-        b_ptr[i] = Bg + (int64_t)b_row[i] * p.ldb + b_col[i];
+        b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)b_col[i];
     }
 
     f32x4 a_reg[A_LD], b_reg[B_LD];
 
-    auto load_global = [&](int kt) {
-        // kt is the absolute K-tile index of the tile being fetched.
+    // Fetch K tile `kt` (absolute index) into the staging registers.  The pointers then move
+    // on to the next tile only if `advance` is set, so that asking again for the last tile of
+    // the range (when nothing is left to prefetch) stays inside the matrices.
+    auto load_global = [&](int kt, bool advance) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
+            const float *src = Ag + a_off[i];
             if constexpr (!EDGE) {
-                a_reg[i] = *reinterpret_cast<const f32x4 *>(a_ptr[i]);
+                a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
             } else {
                 const bool row_ok = m0 + a_row[i] < p.m;
                 const int kk = kt * BK + a_k[i];
                 f32x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (row_ok && kk + e < p.k) ? a_ptr[i][e] : 0.0f;
+                for (int e = 0; e < 4; ++e) v[e] = (row_ok && kk + e < p.k) ? src[e] : 0.0f;
                 a_reg[i] = v;
             }
-            a_ptr[i] += BK;
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
+            const float *src = Bg + b_off[i];
             if constexpr (!EDGE) {
-                b_reg[i] = *reinterpret_cast<const f32x4 *>(b_ptr[i]);
+                b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
             } else {
                 const bool row_ok = kt * BK + b_row[i] < p.k;
                 const int cc = n0 + b_col[i];
                 f32x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (row_ok && cc + e < p.n) ? b_ptr[i][e] : 0.0f;
+                for (int e = 0; e < 4; ++e) v[e] = (row_ok && cc + e < p.n) ? src[e] : 0.0f;
                 b_reg[i] = v;
             }
-            b_ptr[i] += (int64_t)BK * p.ldb;
+        }
+        if (advance) {
+            Ag += BK;
+            Bg += (int64_t)BK * p.ldb;
         }
     };
 
@@ -176,34 +223,41 @@ sgemm_tile_kernel(const GemmParams p) {
     const int a_frag_off = (wm * WM + li) * LDA_S + h * 4;
     const int b_frag_off = (h * 4) * LDB_S + wn * WN + li * CB;
 
-    auto compute = [&](int stage) {
-        const float *as = As + stage * A_STAGE + a_frag_off;
-        const float *bs = Bs + stage * B_STAGE + b_frag_off;
+    // Operand fragments of two consecutive k-octets: while the MFMAs of octet o run from
+    // one set, the LDS reads of octet o+1 fill the other.
+    constexpr int NO = BK / 8;
+    static_assert(NO % 2 == 0, "BK must be a multiple of 16 (fragment sets alternate per octet)");
+    f32x4 a_frag[2][RB];
+    bvec b_frag[2][4];
+
+    auto read_frags = [&](int stage, int o, int set) {
+        const float *as = As + stage * A_STAGE + a_frag_off + o * 8;
+        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * LDB_S;
 #pragma unroll
-        for (int o = 0; o < BK / 8; ++o) {
-            f32x4 a_frag[RB];
-            bvec b_frag[4];
+        for (int rb = 0; rb < RB; ++rb)
+            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-                a_frag[rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S + o * 8);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                b_frag[t] = *reinterpret_cast<const bvec *>(bs + (o * 8 + t) * LDB_S);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                            a_frag[rb][t], vec_get(b_frag[t], cb), acc[rb][cb], 0, 0, 0);
-        }
+        for (int t = 0; t < 4; ++t)
+            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * LDB_S);
     };
 
+    auto mfma_octet = [&](int set) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+    };
+
+    // Second accumulation level: after every flush_tiles K tiles the MFMA accumulators are
+    // added into `total` and cleared, which bounds the length of any single fp32 running sum.
     int since_flush = 0;
     auto maybe_flush = [&]() {
         if constexpr (TWO_LEVEL) {
-            if (++since_flush == p.flush_tiles) {
+            if (since_flush == p.flush_tiles) {
                 since_flush = 0;
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
@@ -211,28 +265,85 @@ sgemm_tile_kernel(const GemmParams p) {
                     for (int cb = 0; cb < CB; ++cb) {
                         total[rb][cb] += acc[rb][cb];
                         acc[rb][cb] = (f32x16)(0.0f);
+                        // one block at a time keeps the temporaries of this rare path small
+                        __builtin_amdgcn_sched_barrier(0);
                     }
             }
+            ++since_flush;
         }
     };
 
+    // K loop.  LDS holds two stages; the staging registers hold the tile after the one in LDS.
+    // Per K tile kt (multiplied out of stage s):
+    //   octets 0 .. NO-3 : fetch the fragments of the next octet, multiply the current one;
+    //   octet NO-2       : the same, with the LDS writes of tile kt+1 (stage s^1) spread between
+    //                      its MFMAs, so the matrix pipe keeps running while they issue;
+    //   one barrier      : stage s^1 is complete, nobody reads stage s any more;
+    //   octet NO-1       : fetch the first fragments of tile kt+1, start the global loads of
+    //                      tile kt+2 into the (now free) staging registers, multiply.
+    // A wave can have only one MFMA in flight, so every instruction that is not an MFMA is
+    // placed in the shadow of one; the fences and group hints below pin that order, which the
+    // scheduler would otherwise undo to save registers.
+    // One barrier per K tile is enough: stage s^1 was last read before the previous barrier,
+    // and stage s is not overwritten before the next one.
+    constexpr int N_MFMA = 4 * RB * CB;          // MFMAs of one octet
+    constexpr int N_ST = A_LD + B_LD;            // LDS writes / global loads of one tile
+    constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
     if (kt_begin < kt_end) {
-        load_global(kt_begin);
+        const int last = kt_end - 1;
+        load_global(kt_begin, kt_begin < last);
         store_lds(0);
         __syncthreads();
+        read_frags(0, 0, 0);
+        {
+            const int nl = kt_begin + 1 < last ? kt_begin + 1 : last;
+            load_global(nl, nl < last);
+        }
         int stage = 0;
-        for (int kt = kt_begin; kt < kt_end - 1; ++kt) {
-            load_global(kt + 1);          // next tile travels while this one is multiplied
-            // Keep the loads issued here: without this fence the scheduler sinks them below
-            // the MFMA block to save registers and their latency is no longer hidden.
+        for (int kt = kt_begin; kt < last; ++kt) {
+            maybe_flush();                // (at the top, so the loop body below stays one block)
             __builtin_amdgcn_sched_barrier(0);
-            compute(stage);
-            maybe_flush();
+#pragma unroll
+            for (int o = 0; o < NO - 2; ++o) {
+                read_frags(stage, o + 1, (o + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_octet(o & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            read_frags(stage, NO - 1, (NO - 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_octet((NO - 2) & 1);
             store_lds(stage ^ 1);
-            __syncthreads();              // one barrier per K tile (see header comment of the loop)
+#pragma unroll
+            for (int i = 0; i < N_ST; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // LDS write
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            read_frags(stage ^ 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                const int nl = kt + 2 < last ? kt + 2 : last;
+                load_global(nl, nl < last);
+            }
+            mfma_octet((NO - 1) & 1);
+#pragma unroll
+            for (int i = 0; i < N_ST; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global load
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+            }
+            __builtin_amdgcn_sched_barrier(0);
             stage ^= 1;
         }
-        compute(stage);
+#pragma unroll
+        for (int o = 0; o < NO - 1; ++o) {
+            read_frags(stage, o + 1, (o + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_octet(o & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mfma_octet((NO - 1) & 1);
     }
     if constexpr (TWO_LEVEL) {
 #pragma unroll
@@ -281,13 +392,18 @@ sgemm_tile_kernel(const GemmParams p) {
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
 hipError_t launch_tile(const GemmParams &p, hipStream_t s) {
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
-    constexpr int lds = tile_lds_bytes<BM, BN, BK, WM, WN>();
+    constexpr int lds_used = tile_lds_bytes<BM, BN, BK, WM, WN>();
     auto kern = sgemm_tile_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, EDGE>;
-    if (lds > 48 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (attr != hipSuccess) return attr;
+    // Occupancy cap: asking for a larger LDS allocation than the tile uses limits how many
+    // workgroups share a CU (max_blocks_per_cu == 0: no cap).
+    int lds = lds_used;
+    if (p.max_blocks_per_cu > 0) {
+        const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
+        if (share > lds) lds = share;
     }
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
+    if (attr != hipSuccess) return attr;
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
     return hipGetLastError();

@@ -30,7 +30,10 @@ def run_hip(a: np.ndarray, b: np.ndarray, fn=None):
     da, db = to_dev(a), to_dev(b)
     if fn is None:
         fn = tg.sgemm if a.ndim == 2 else tg.sgemm_batched
-    c = fn(da, db)
+    # NaN-filled output: a tile the kernel fails to write cannot pass as stale data
+    shape = (a.shape[0], b.shape[1]) if a.ndim == 2 else (a.shape[0], a.shape[1], b.shape[2])
+    out = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+    c = fn(da, db, out=out)
     torch.cuda.synchronize()
     return c.cpu().numpy()
 
