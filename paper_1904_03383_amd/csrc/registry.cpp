@@ -36,8 +36,25 @@ namespace tg {
 #define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE)
 TG_TILE_LIST(TG_DECL_X)
 
+// direct-to-LDS variants: (BM, BN, BK, WM, WN, two_level, name)
+#define TG_DIRECT_LIST(X)                                                   \
+    X(128, 128, 32, 64, 64, false, "d128x128x32_w64x64")                    \
+    X(128, 128, 32, 64, 64, true, "d128x128x32_w64x64_acc2")                \
+    X(128, 256, 32, 64, 128, false, "d128x256x32_w64x128")                  \
+    X(128, 256, 32, 64, 128, true, "d128x256x32_w64x128_acc2")              \
+    X(256, 128, 32, 128, 64, false, "d256x128x32_w128x64")                  \
+    X(256, 128, 32, 128, 64, true, "d256x128x32_w128x64_acc2")              \
+    X(64, 64, 32, 32, 32, false, "d64x64x32_w32x32")
+#define TG_DDECL(BM, BN, BK, WM, WN, L2, NAME) \
+    extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2>(const GemmParams &, hipStream_t);
+#define TG_DROW(BM, BN, BK, WM, WN, L2, NAME)                                                   \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, (BM / WM) * (BN / WN) * 64,                \
+     2 * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2>},
+TG_DIRECT_LIST(TG_DDECL)
+
 static const KernelInfo kTable[] = {
     TG_TILE_LIST(TG_ROW)
+    TG_DIRECT_LIST(TG_DROW)
     {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, 256, 0, &launch_wave32},
 };
 

@@ -59,6 +59,10 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();
 
+// Same, with operand tiles loaded global -> LDS directly (exact-fit shapes, BK = 32).
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s);
+
 // One wave per 32x32 C tile, operands straight from global memory (small / batched problems).
 hipError_t launch_wave32(const GemmParams &p, hipStream_t s);
 

@@ -1,0 +1,294 @@
+// Workgroup-tile SGEMM kernel for gfx950 whose operand tiles travel global -> LDS directly
+// (global_load_lds_dwordx4), without passing through registers.  Same decomposition as
+// tile_kernel.hpp (matmul of Sec. 5.2 of the paper; BLOCK / THREAD / UNROLL / VECTOR
+// mapping and SHARED staging of Sec. 4); exact-fit shapes only.
+//
+// What differs from the register-staged kernel:
+//  * A direct load writes the 64 lanes' 16-byte pieces to 1 KB of consecutive LDS, so rows
+//    cannot be padded.  The A tile (rows of BK floats = BK/4 chunks of 16 bytes) is instead
+//    stored with its chunks permuted inside each row: chunk c of row r sits at position
+//    c ^ swz(r).  The lane that fills LDS position (r, q) therefore fetches chunk
+//    q ^ swz(r) from global memory, and a fragment read of chunk c goes to c ^ swz(r); the
+//    16 lanes of one LDS access then hit distinct bank groups.
+//  * The B tile is stored row by row (k-major, BN floats per row); its fragment reads are
+//    runs of consecutive floats and need no permutation.
+//  * There are no staging registers and no LDS write instructions: the loads of tile kt+1
+//    are issued right after the barrier that frees their stage, between the MFMAs of the
+//    first octet, and are waited for (vmcnt) just before the next barrier, a whole K tile
+//    later.
+#pragma once
+
+#include "tile_kernel.hpp"
+
+namespace tg {
+
+typedef __attribute__((address_space(3))) float lds_float;
+typedef __attribute__((address_space(1))) const float glb_float;
+
+// Chunk permutation of A rows.  For BK = 32 (8 chunks per row) it is a bijection of the
+// chunk index for every row, and distinct over each aligned group of 8 rows as well as over
+// the even and the odd rows of each aligned group of 16, which covers both ways 16-byte LDS
+// accesses may be grouped over banks.
+template <int BK>
+__device__ __forceinline__ int a_swizzle(int row) {
+    static_assert(BK == 32, "the chunk permutation is laid out for rows of 8 chunks");
+    return (row & 6) | ((row ^ (row >> 3)) & 1);
+}
+
+template <int BM, int BN, int BK>
+constexpr int direct_lds_bytes() {
+    return 2 * (BM * BK + BK * BN) * (int)sizeof(float);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+constexpr int direct_min_waves() {
+    constexpr int acc = (WM * WN / 64) * (TWO_LEVEL ? 2 : 1);
+    constexpr int frags = 2 * (4 * (WM / 32) + 4 * (WN / 32));
+    return acc + frags + 56 <= 256 ? 2 : 1;
+}
+
+// One K tile on its way: instruction i of a wave fills LDS floats [slot*256, slot*256+256) of
+// the stage, slot = i * NWAVES + wave.  a_stage / b_stage are float offsets into the
+// __shared__ array.  The builtin wants address-space-qualified pointers, hence the explicit
+// casts (without them the host pass drops the kernel without a diagnostic).
+#define TG_ISSUE_DIRECT_LOADS(a_stage, b_stage)                                                          \
+    do {                                                                                                 \
+        _Pragma("unroll") for (int i_ = 0; i_ < A_LD; ++i_)                                              \
+            __builtin_amdgcn_global_load_lds((glb_float *)(Ag + a_off[i_]), (lds_float *)(smem + (a_stage) + (i_ * NWAVES + wave) * 256), 16, 0, 0); \
+        _Pragma("unroll") for (int i_ = 0; i_ < B_LD; ++i_)                                              \
+            __builtin_amdgcn_global_load_lds((glb_float *)(Bg + b_off[i_]), (lds_float *)(smem + (b_stage) + (i_ * NWAVES + wave) * 256), 16, 0, 0); \
+    } while (0)
+
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (direct_min_waves<BM, BN, BK, WM, WN, TWO_LEVEL>()))
+sgemm_tile_direct_kernel(const GemmParams p) {
+    constexpr int WAVES_N = BN / WN;
+    constexpr int NWAVES = (BM / WM) * (BN / WN);
+    constexpr int NT = NWAVES * 64;
+    constexpr int RB = WM / 32, CB = WN / 32;
+    constexpr int A_STAGE = BM * BK, B_STAGE = BK * BN;      // floats, unpadded
+    constexpr int A_LD = BM * BK / 4 / NT, B_LD = BK * BN / 4 / NT;
+    constexpr int NO = BK / 8;
+    static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
+    static_assert(BK == 32, "BK must be 32");
+    static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0 && A_LD >= 1 && B_LD >= 1,
+                  "tile loads must divide evenly over the workgroup");
+    static_assert(BN % 4 == 0 && (256 % BK) == 0, "one load instruction covers whole chunks and rows");
+    typedef typename vec_of<CB>::type bvec;
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float *As = smem;
+    float *Bs = smem + 2 * A_STAGE;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, h = lane >> 5;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    int slice, tm, tn;
+    map_workgroup(p, slice, tm, tn);
+    const int prob = slice / p.splits, split = slice - prob * p.splits;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int kt_total = p.k / BK;
+    const int kt_begin = split * p.ktiles_per_split;
+    const int kt_stop = kt_begin + p.ktiles_per_split;
+    const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
+
+    // Tile origins are wave-uniform and advance per K tile; per-lane offsets are fixed.
+    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
+    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+
+    // Load instruction i of this wave fills LDS floats [slot*256, slot*256 + 256) of a stage,
+    // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3.
+    unsigned a_off[A_LD], b_off[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
+        const int row = pos / BK;
+        const int q = (pos % BK) / 4;                          // chunk position inside the row
+        a_off[i] = (unsigned)row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
+        b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)(pos % BN);
+    }
+
+    const int64_t b_step = (int64_t)BK * p.ldb;
+
+    f32x16 acc[RB][CB];
+    f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            acc[rb][cb] = (f32x16)(0.0f);
+            if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
+        }
+
+    // Fragment addressing.  A: row r = wm*WM + rb*32 + li, chunk 2*o + h at position
+    // (2*o + h) ^ swz(r); rb*32 does not change swz (it only looks at the low four row bits).
+    const int a_row = wm * WM + li;
+    const int a_swz = a_swizzle<BK>(a_row);
+    const int b_frag_off = (h * 4) * BN + wn * WN + li * CB;
+
+    f32x4 a_frag[2][RB];
+    bvec b_frag[2][4];
+
+    auto read_frags = [&](int stage, int o, int set) {
+        const float *as = As + stage * A_STAGE + a_row * BK + (((2 * o + h) ^ a_swz) * 4);
+        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * BN;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
+    };
+
+    auto mfma_octet = [&](int set) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+    };
+
+    int since_flush = 0;
+    auto maybe_flush = [&]() {
+        if constexpr (TWO_LEVEL) {
+            if (since_flush == p.flush_tiles) {
+                since_flush = 0;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        total[rb][cb] += acc[rb][cb];
+                        acc[rb][cb] = (f32x16)(0.0f);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+            ++since_flush;
+        }
+    };
+
+    // s_waitcnt with vmcnt = 0 and the other counters left alone (gfx9 encoding: vmcnt in
+    // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+    constexpr int kWaitVm0 = 0x0F70;
+    constexpr int N_MFMA = 4 * RB * CB;
+    constexpr int N_LD = A_LD + B_LD;
+    constexpr int MFMA_PER_LD = N_MFMA / N_LD > 0 ? N_MFMA / N_LD : 1;
+
+    if (kt_begin < kt_end) {
+        const int last = kt_end - 1;
+        TG_ISSUE_DIRECT_LOADS(0, 2 * A_STAGE);
+        if (kt_begin < last) {
+            Ag += BK;
+            Bg += b_step;
+        }
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __syncthreads();
+        read_frags(0, 0, 0);
+        int stage = 0;
+        for (int kt = kt_begin; kt < last; ++kt) {
+            maybe_flush();
+            __builtin_amdgcn_sched_barrier(0);
+            // octet 0: fetch octet 1, start tile kt+1 on its way into the other stage
+            read_frags(stage, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            TG_ISSUE_DIRECT_LOADS((stage ^ 1) * A_STAGE, 2 * A_STAGE + (stage ^ 1) * B_STAGE);
+            if (kt + 1 < last) {
+                Ag += BK;
+                Bg += b_step;
+            }
+            mfma_octet(0);
+#pragma unroll
+            for (int i = 0; i < N_LD; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_LD, 0);   // MFMA
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int o = 1; o < NO - 1; ++o) {
+                read_frags(stage, o + 1, (o + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_octet(o & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);    // this wave's share of tile kt+1 is in LDS
+            __syncthreads();                         // everyone's is; stage `stage` is free
+            read_frags(stage ^ 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_octet((NO - 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            stage ^= 1;
+        }
+#pragma unroll
+        for (int o = 0; o < NO - 1; ++o) {
+            read_frags(stage, o + 1, (o + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_octet(o & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mfma_octet((NO - 1) & 1);
+    }
+    if constexpr (TWO_LEVEL) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
+    }
+
+    // Epilogue: registers -> C (or the split-K partial).
+    float *out;
+    int64_t ldo;
+    if (p.splits > 1) {
+        out = p.ws + (int64_t)slice * p.m * p.n;
+        ldo = p.n;
+    } else {
+        out = p.C + (int64_t)prob * p.strideC;
+        ldo = p.ldc;
+    }
+    const int col = n0 + wn * WN + li * CB;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            float *dst = out + (int64_t)row * ldo + col;
+            bvec o;
+            if constexpr (CB == 1) {
+                o = acc[rb][0][v];
+            } else {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+            }
+            *reinterpret_cast<bvec *>(dst) = o;
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s) {
+    constexpr int threads = (BM / WM) * (BN / WN) * 64;
+    constexpr int lds_used = direct_lds_bytes<BM, BN, BK>();
+    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL>;
+    int lds = lds_used;
+    if (p.max_blocks_per_cu > 0) {
+        const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
+        if (share > lds) lds = share;
+    }
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
+    if (attr != hipSuccess) return attr;
+    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace tg
