@@ -103,9 +103,10 @@ tg_status tg_set_workspace(void *dev_ptr, size_t bytes);
 size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k);
 
 /*
- * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>]", e.g.
- * "t128x128x16_w64x64:s1:g8" (split-K factor, tile rows per ordering group, cap on
- * workgroups per CU); kernel names are listed by tg_kernel_name.
+ * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>][:p<n>]", e.g.
+ * "t128x128x16_w64x64:s1:g8" (split-K factor; tile rows per ordering group; cap on
+ * workgroups per CU; persistent launch with n workgroups per CU that loop over the tiles);
+ * kernel names are listed by tg_kernel_name.
  * tg_force_config(spec) makes every later call use that configuration when it is valid
  * for the problem (otherwise the call fails with TG_ERR_INVALID_ARG, or TG_ERR_WORKSPACE
  * for split-K without room); tg_force_config(NULL) returns to tuned/heuristic choice.

@@ -40,6 +40,7 @@ struct Config {
     int splits = 1;
     int group = kDefaultGroup;
     int occ = 0;   // cap on workgroups per CU (0 = whatever fits)
+    int persist = 0;   // > 0: persistent launch with this many workgroups per CU
 };
 
 struct Problem {
@@ -73,8 +74,9 @@ tg_status fail(tg_status s, const std::string &msg) {
 
 std::string spec_of(const Config &c) {
     char buf[160];
-    if (c.occ > 0) snprintf(buf, sizeof buf, "%s:s%d:g%d:o%d", tg::kernel(c.kernel).name, c.splits, c.group, c.occ);
-    else snprintf(buf, sizeof buf, "%s:s%d:g%d", tg::kernel(c.kernel).name, c.splits, c.group);
+    int n = snprintf(buf, sizeof buf, "%s:s%d:g%d", tg::kernel(c.kernel).name, c.splits, c.group);
+    if (c.occ > 0) n += snprintf(buf + n, sizeof buf - n, ":o%d", c.occ);
+    if (c.persist > 0) n += snprintf(buf + n, sizeof buf - n, ":p%d", c.persist);
     return buf;
 }
 
@@ -84,7 +86,7 @@ int find_kernel(const std::string &name) {
     return -1;
 }
 
-// "<kernel>[:s<splits>][:g<group>][:o<workgroups per CU>]"
+// "<kernel>[:s<splits>][:g<group>][:o<cap on workgroups per CU>][:p<persistent workgroups per CU>]"
 bool parse_spec(const char *spec, Config &out, std::string &why) {
     std::string s(spec);
     size_t pos = s.find(':');
@@ -95,13 +97,14 @@ bool parse_spec(const char *spec, Config &out, std::string &why) {
     while (pos != std::string::npos) {
         size_t next = s.find(':', pos + 1);
         std::string tok = s.substr(pos + 1, next == std::string::npos ? std::string::npos : next - pos - 1);
-        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g' && tok[0] != 'o')) { why = "bad token '" + tok + "'"; return false; }
+        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g' && tok[0] != 'o' && tok[0] != 'p')) { why = "bad token '" + tok + "'"; return false; }
         char *end = nullptr;
         long v = strtol(tok.c_str() + 1, &end, 10);
         if (*end != '\0' || v < 1 || v > 4096) { why = "bad value in '" + tok + "'"; return false; }
         if (tok[0] == 's') c.splits = (int)v;
         else if (tok[0] == 'g') c.group = (int)v;
-        else c.occ = (int)v;
+        else if (tok[0] == 'o') c.occ = (int)v;
+        else c.persist = (int)v;
         pos = next;
     }
     out = c;
@@ -201,6 +204,8 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     const KernelInfo &ki = tg::kernel(c.kernel);
     if (c.group < 1) return no("group must be >= 1");
     if (c.occ < 0 || c.occ > 16) return no("occupancy cap must be 0..16");
+    if (c.persist < 0 || c.persist > 16) return no("persistent workgroups per CU must be 0..16");
+    if ((c.persist > 0) != ki.persistent) return no("p<n> goes with the persistent kernel variants (names starting with p), and only with them");
     if (ki.kind == tg::KIND_WAVE) {
         if (c.splits != 1) return no("the wave kernel has no split-K");
         if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
@@ -296,6 +301,7 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             c.kernel = ki;
             c.splits = s;
             c.group = kDefaultGroup;
+            c.persist = tg::kernel(ki).persistent ? 2 : 0;
             if (!config_valid(p, c, ws_bytes)) continue;
             const KernelInfo &kinfo = tg::kernel(ki);
             if (kinfo.kind == tg::KIND_TILE && kinfo.two_level) {
@@ -386,6 +392,7 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     g.ktiles_per_split = (int)std::max<int64_t>(ceil_div(p.k, ki.BK), 1);
     g.flush_tiles = ki.two_level ? std::max(1, kFlushK / ki.BK) : 0;
     g.max_blocks_per_cu = c.occ;
+    g.persistent_blocks = c.persist > 0 ? c.persist * kNumCUs : 0;   // a multiple of 8
     g.flags = 0;
     if (p.aligned) g.flags |= tg::kFlagVecA | tg::kFlagVecC;
     if (ki.kind == tg::KIND_TILE && c.splits > 1) {
@@ -537,6 +544,16 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
             if (us < best_us * 0.995) { best_us = us; best = c; }
         }
+        // ... and, for a persistent variant, the number of workgroups per CU
+        base = best;
+        for (int per_cu = 1; per_cu <= 4 && tg::kernel(base.kernel).persistent; ++per_cu) {
+            Config c = base;
+            c.persist = per_cu;
+            double us = 0;
+            if (time_config(c, &us) != TG_OK) continue;
+            if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+            if (us < best_us * 0.995) { best_us = us; best = c; }
+        }
     }
     hipEventDestroy(ev0);
     hipEventDestroy(ev1);
@@ -619,14 +636,14 @@ tg_status tg_save_tune_cache(const char *path) {
     if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
     FILE *f = fopen(path, "w");
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
-    fprintf(f, "tgemm-tune-cache 2 gfx950\n");
+    fprintf(f, "tgemm-tune-cache 3 gfx950\n");
     std::lock_guard<std::mutex> lk(g_mutex);
     for (const auto &kv : g_cache) {
         const ShapeKey &k = kv.first;
-        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
+        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
                 (long long)std::get<2>(k), (long long)std::get<3>(k), std::get<4>(k),
                 tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.cfg.occ,
-                kv.second.usec);
+                kv.second.cfg.persist, kv.second.usec);
     }
     fclose(f);
     return TG_OK;
@@ -638,23 +655,25 @@ tg_status tg_load_tune_cache(const char *path) {
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
     char head[64] = {0}, arch[32] = {0};
     int ver = 0;
-    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || ver != 2 ||
+    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || ver != 3 ||
         strcmp(arch, "gfx950") != 0) {
         fclose(f);
-        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 2)");
+        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3)");
     }
     std::lock_guard<std::mutex> lk(g_mutex);
     long long b, m, n, k;
-    int al, splits, group, occ;
+    int al, splits, group, occ, persist;
     char name[128];
     double us;
-    while (fscanf(f, "%lld %lld %lld %lld %d %127s %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ, &us) == 10) {
+    while (fscanf(f, "%lld %lld %lld %lld %d %127s %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ,
+                  &persist, &us) == 11) {
         Config c;
         c.kernel = find_kernel(name);
         c.splits = splits;
         c.group = group;
         c.occ = occ;
-        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0) continue;   // entry from another build: ignore
+        c.persist = persist;
+        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0 || persist < 0) continue;   // entry from another build: ignore
         g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
     }
     fclose(f);

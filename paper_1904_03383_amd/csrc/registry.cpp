@@ -4,11 +4,14 @@
 
 namespace tg {
 
-#define TG_DECL(BM, BN, BK, WM, WN, L2, EDGE) \
-    extern template hipError_t launch_tile<BM, BN, BK, WM, WN, L2, EDGE>(const GemmParams &, hipStream_t);
+#define TG_DECL(BM, BN, BK, WM, WN, L2, EDGE, PERS) \
+    extern template hipError_t launch_tile<BM, BN, BK, WM, WN, L2, EDGE, PERS>(const GemmParams &, hipStream_t);
 #define TG_ROW(BM, BN, BK, WM, WN, L2, EDGE, NAME)                                              \
-    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, EDGE, (BM / WM) * (BN / WN) * 64,                 \
-     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE>},
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, EDGE, false, (BM / WM) * (BN / WN) * 64,          \
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE, false>},
+#define TG_PROW(BM, BN, BK, WM, WN, NAME)                                                       \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, true, (BM / WM) * (BN / WN) * 64,       \
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, false, false, true>},
 
 // (BM, BN, BK, WM, WN, two_level, edge, name)
 #define TG_TILE_LIST(X)                                                     \
@@ -33,8 +36,10 @@ namespace tg {
     X(64, 64, 16, 32, 32, false, true, "t64x64x16_w32x32_edge")             \
     X(64, 64, 16, 32, 32, true, true, "t64x64x16_w32x32_acc2_edge")
 
-#define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE)
+#define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE, false)
 TG_TILE_LIST(TG_DECL_X)
+TG_DECL(128, 128, 16, 64, 64, false, false, true)
+TG_DECL(128, 128, 32, 64, 64, false, false, true)
 
 // direct-to-LDS variants: (BM, BN, BK, WM, WN, two_level, name)
 #define TG_DIRECT_LIST(X)                                                   \
@@ -48,14 +53,16 @@ TG_TILE_LIST(TG_DECL_X)
 #define TG_DDECL(BM, BN, BK, WM, WN, L2, NAME) \
     extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2>(const GemmParams &, hipStream_t);
 #define TG_DROW(BM, BN, BK, WM, WN, L2, NAME)                                                   \
-    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, (BM / WM) * (BN / WN) * 64,                \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, (BM / WM) * (BN / WN) * 64,         \
      2 * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2>},
 TG_DIRECT_LIST(TG_DDECL)
 
 static const KernelInfo kTable[] = {
     TG_TILE_LIST(TG_ROW)
     TG_DIRECT_LIST(TG_DROW)
-    {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, 256, 0, &launch_wave32},
+    TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")
+    TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
+    {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, 256, 0, &launch_wave32},
 };
 
 int num_kernels() { return (int)(sizeof(kTable) / sizeof(kTable[0])); }

@@ -26,6 +26,7 @@ struct GemmParams {
                           // or 0, 0: XCDs take contiguous ranges of the linear tile order
     int flush_tiles;      // two-level accumulation: fold the MFMA accumulators into the
                           // second-level sums every this many K tiles (0 = never)
+    int persistent_blocks; // > 0: launch this many workgroups (a multiple of 8) that loop over the work items
     int max_blocks_per_cu; // occupancy cap enforced through the LDS request (0 = none)
     int flags;            // kFlag* bits, computed on the host from pointers and strides
 };
@@ -44,6 +45,7 @@ struct KernelInfo {
     int WM, WN;          // wave tile
     bool two_level;      // has second-level accumulators (needed for long K)
     bool edge;           // predicated variant: any m, n, k, leading dimension and alignment
+    bool persistent;     // workgroups loop over tiles (launch with a fixed number of workgroups per CU)
     int threads;
     int lds_bytes;
     launch_fn launch;
@@ -54,7 +56,7 @@ int num_kernels();
 const KernelInfo &kernel(int idx);
 
 // Workgroup-tile kernels: LDS-staged, double-buffered, MFMA 32x32x2 register blocks.
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE, bool PERSIST>
 hipError_t launch_tile(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();

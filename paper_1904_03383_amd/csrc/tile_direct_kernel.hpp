@@ -86,190 +86,195 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     const int li = lane & 31, h = lane >> 5;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-    int slice, tm, tn;
-    map_workgroup(p, slice, tm, tn);
-    const int prob = slice / p.splits, split = slice - prob * p.splits;
-    const int m0 = tm * BM, n0 = tn * BN;
+    // One workgroup per work item (tile x slice); the loop below runs once.
+    const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
+    for (unsigned work = blockIdx.x; work < total_work; work += gridDim.x) {
+        int slice, tm, tn;
+        map_workgroup(p, total_work, work, slice, tm, tn);
+        const int prob = slice / p.splits, split = slice - prob * p.splits;
+        const int m0 = tm * BM, n0 = tn * BN;
 
-    const int kt_total = p.k / BK;
-    const int kt_begin = split * p.ktiles_per_split;
-    const int kt_stop = kt_begin + p.ktiles_per_split;
-    const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
+        const int kt_total = p.k / BK;
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_stop = kt_begin + p.ktiles_per_split;
+        const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
-    // Tile origins are wave-uniform and advance per K tile; per-lane offsets are fixed.
-    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+        // Tile origins are wave-uniform and advance per K tile; per-lane offsets are fixed.
+        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
+        const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
 
-    // Load instruction i of this wave fills LDS floats [slot*256, slot*256 + 256) of a stage,
-    // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3.
-    unsigned a_off[A_LD], b_off[B_LD];
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
-        const int row = pos / BK;
-        const int q = (pos % BK) / 4;                          // chunk position inside the row
-        a_off[i] = (unsigned)row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
-    }
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) {
-        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
-        b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)(pos % BN);
-    }
-
-    const int64_t b_step = (int64_t)BK * p.ldb;
-
-    f32x16 acc[RB][CB];
-    f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            acc[rb][cb] = (f32x16)(0.0f);
-            if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
+        // Load instruction i of this wave fills LDS floats [slot*256, slot*256 + 256) of a stage,
+        // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3.
+        unsigned a_off[A_LD], b_off[B_LD];
+    #pragma unroll
+        for (int i = 0; i < A_LD; ++i) {
+            const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
+            const int row = pos / BK;
+            const int q = (pos % BK) / 4;                          // chunk position inside the row
+            a_off[i] = (unsigned)row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+        }
+    #pragma unroll
+        for (int i = 0; i < B_LD; ++i) {
+            const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
+            b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)(pos % BN);
         }
 
-    // Fragment addressing.  A: row r = wm*WM + rb*32 + li, chunk 2*o + h at position
-    // (2*o + h) ^ swz(r); rb*32 does not change swz (it only looks at the low four row bits).
-    const int a_row = wm * WM + li;
-    const int a_swz = a_swizzle<BK>(a_row);
-    const int b_frag_off = (h * 4) * BN + wn * WN + li * CB;
+        const int64_t b_step = (int64_t)BK * p.ldb;
 
-    f32x4 a_frag[2][RB];
-    bvec b_frag[2][4];
-
-    auto read_frags = [&](int stage, int o, int set) {
-        const float *as = As + stage * A_STAGE + a_row * BK + (((2 * o + h) ^ a_swz) * 4);
-        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * BN;
-#pragma unroll
+        f32x16 acc[RB][CB];
+        f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
+    #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
-    };
-
-    auto mfma_octet = [&](int set) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
-    };
-
-    int since_flush = 0;
-    auto maybe_flush = [&]() {
-        if constexpr (TWO_LEVEL) {
-            if (since_flush == p.flush_tiles) {
-                since_flush = 0;
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) {
-                        total[rb][cb] += acc[rb][cb];
-                        acc[rb][cb] = (f32x16)(0.0f);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+    #pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                acc[rb][cb] = (f32x16)(0.0f);
+                if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
             }
-            ++since_flush;
-        }
-    };
 
-    // s_waitcnt with vmcnt = 0 and the other counters left alone (gfx9 encoding: vmcnt in
-    // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
-    constexpr int kWaitVm0 = 0x0F70;
-    constexpr int N_MFMA = 4 * RB * CB;
-    constexpr int N_LD = A_LD + B_LD;
-    constexpr int MFMA_PER_LD = N_MFMA / N_LD > 0 ? N_MFMA / N_LD : 1;
+        // Fragment addressing.  A: row r = wm*WM + rb*32 + li, chunk 2*o + h at position
+        // (2*o + h) ^ swz(r); rb*32 does not change swz (it only looks at the low four row bits).
+        const int a_row = wm * WM + li;
+        const int a_swz = a_swizzle<BK>(a_row);
+        const int b_frag_off = (h * 4) * BN + wn * WN + li * CB;
 
-    if (kt_begin < kt_end) {
-        const int last = kt_end - 1;
-        TG_ISSUE_DIRECT_LOADS(0, 2 * A_STAGE);
-        if (kt_begin < last) {
-            Ag += BK;
-            Bg += b_step;
-        }
-        __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        __syncthreads();
-        read_frags(0, 0, 0);
-        int stage = 0;
-        for (int kt = kt_begin; kt < last; ++kt) {
-            maybe_flush();
-            __builtin_amdgcn_sched_barrier(0);
-            // octet 0: fetch octet 1, start tile kt+1 on its way into the other stage
-            read_frags(stage, 1, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            TG_ISSUE_DIRECT_LOADS((stage ^ 1) * A_STAGE, 2 * A_STAGE + (stage ^ 1) * B_STAGE);
-            if (kt + 1 < last) {
+        f32x4 a_frag[2][RB];
+        bvec b_frag[2][4];
+
+        auto read_frags = [&](int stage, int o, int set) {
+            const float *as = As + stage * A_STAGE + a_row * BK + (((2 * o + h) ^ a_swz) * 4);
+            const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * BN;
+    #pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
+    #pragma unroll
+            for (int t = 0; t < 4; ++t)
+                b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
+        };
+
+        auto mfma_octet = [&](int set) {
+    #pragma unroll
+            for (int t = 0; t < 4; ++t)
+    #pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+    #pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                            a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+        };
+
+        int since_flush = 0;
+        auto maybe_flush = [&]() {
+            if constexpr (TWO_LEVEL) {
+                if (since_flush == p.flush_tiles) {
+                    since_flush = 0;
+    #pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+    #pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) {
+                            total[rb][cb] += acc[rb][cb];
+                            acc[rb][cb] = (f32x16)(0.0f);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                }
+                ++since_flush;
+            }
+        };
+
+        // s_waitcnt with vmcnt = 0 and the other counters left alone (gfx9 encoding: vmcnt in
+        // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+        constexpr int kWaitVm0 = 0x0F70;
+        constexpr int N_MFMA = 4 * RB * CB;
+        constexpr int N_LD = A_LD + B_LD;
+        constexpr int MFMA_PER_LD = N_MFMA / N_LD > 0 ? N_MFMA / N_LD : 1;
+
+        if (kt_begin < kt_end) {
+            const int last = kt_end - 1;
+            TG_ISSUE_DIRECT_LOADS(0, 2 * A_STAGE);
+            if (kt_begin < last) {
                 Ag += BK;
                 Bg += b_step;
             }
-            mfma_octet(0);
-#pragma unroll
-            for (int i = 0; i < N_LD; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
-                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_LD, 0);   // MFMA
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            __syncthreads();
+            read_frags(0, 0, 0);
+            int stage = 0;
+            for (int kt = kt_begin; kt < last; ++kt) {
+                maybe_flush();
+                __builtin_amdgcn_sched_barrier(0);
+                // octet 0: fetch octet 1, start tile kt+1 on its way into the other stage
+                read_frags(stage, 1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                TG_ISSUE_DIRECT_LOADS((stage ^ 1) * A_STAGE, 2 * A_STAGE + (stage ^ 1) * B_STAGE);
+                if (kt + 1 < last) {
+                    Ag += BK;
+                    Bg += b_step;
+                }
+                mfma_octet(0);
+    #pragma unroll
+                for (int i = 0; i < N_LD; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
+                    __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_LD, 0);   // MFMA
+                }
+                __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                for (int o = 1; o < NO - 1; ++o) {
+                    read_frags(stage, o + 1, (o + 1) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_octet(o & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __builtin_amdgcn_s_waitcnt(kWaitVm0);    // this wave's share of tile kt+1 is in LDS
+                __syncthreads();                         // everyone's is; stage `stage` is free
+                read_frags(stage ^ 1, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_octet((NO - 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                stage ^= 1;
             }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int o = 1; o < NO - 1; ++o) {
+    #pragma unroll
+            for (int o = 0; o < NO - 1; ++o) {
                 read_frags(stage, o + 1, (o + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_octet(o & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_s_waitcnt(kWaitVm0);    // this wave's share of tile kt+1 is in LDS
-            __syncthreads();                         // everyone's is; stage `stage` is free
-            read_frags(stage ^ 1, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
             mfma_octet((NO - 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            stage ^= 1;
         }
-#pragma unroll
-        for (int o = 0; o < NO - 1; ++o) {
-            read_frags(stage, o + 1, (o + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_octet(o & 1);
-            __builtin_amdgcn_sched_barrier(0);
+        if constexpr (TWO_LEVEL) {
+    #pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+    #pragma unroll
+                for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
         }
-        mfma_octet((NO - 1) & 1);
-    }
-    if constexpr (TWO_LEVEL) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
-    }
 
-    // Epilogue: registers -> C (or the split-K partial).
-    float *out;
-    int64_t ldo;
-    if (p.splits > 1) {
-        out = p.ws + (int64_t)slice * p.m * p.n;
-        ldo = p.n;
-    } else {
-        out = p.C + (int64_t)prob * p.strideC;
-        ldo = p.ldc;
-    }
-    const int col = n0 + wn * WN + li * CB;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-            float *dst = out + (int64_t)row * ldo + col;
-            bvec o;
-            if constexpr (CB == 1) {
-                o = acc[rb][0][v];
-            } else {
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
-            }
-            *reinterpret_cast<bvec *>(dst) = o;
+        // Epilogue: registers -> C (or the split-K partial).
+        float *out;
+        int64_t ldo;
+        if (p.splits > 1) {
+            out = p.ws + (int64_t)slice * p.m * p.n;
+            ldo = p.n;
+        } else {
+            out = p.C + (int64_t)prob * p.strideC;
+            ldo = p.ldc;
         }
+        const int col = n0 + wn * WN + li * CB;
+    #pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+    #pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                float *dst = out + (int64_t)row * ldo + col;
+                bvec o;
+                if constexpr (CB == 1) {
+                    o = acc[rb][0][v];
+                } else {
+    #pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+                }
+                *reinterpret_cast<bvec *>(dst) = o;
+            }
+        }
+        break;
     }
 }
 
@@ -286,7 +291,7 @@ hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
     if (attr != hipSuccess) return attr;
-    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
     return hipGetLastError();
 }

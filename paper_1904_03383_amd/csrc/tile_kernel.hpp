@@ -61,8 +61,9 @@ __device__ __forceinline__ void grouped_order(unsigned t, unsigned rows, unsigne
     c = in / gsz;
 }
 
-__device__ __forceinline__ void map_workgroup(const GemmParams &p, int &slice, int &tm, int &tn) {
-    const unsigned W = gridDim.x, w = blockIdx.x;
+// W = number of work items (tiles x slices) of the launch, w = this work item.
+__device__ __forceinline__ void map_workgroup(const GemmParams &p, unsigned W, unsigned w, int &slice, int &tm,
+                                              int &tn) {
     const unsigned x = w & 7u, s = w >> 3;
     const unsigned T = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
     unsigned r, c;
@@ -99,7 +100,7 @@ constexpr int min_waves_per_simd() {
     return acc + staging + frags + 64 <= 256 ? 2 : 1;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE, bool PERSIST>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (min_waves_per_simd<BM, BN, BK, WM, WN, TWO_LEVEL>()))
 sgemm_tile_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
@@ -124,276 +125,286 @@ sgemm_tile_kernel(const GemmParams p) {
     const int li = lane & 31, h = lane >> 5;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-    int slice, tm, tn;
-    map_workgroup(p, slice, tm, tn);
-    const int prob = slice / p.splits, split = slice - prob * p.splits;
-    const int m0 = tm * BM, n0 = tn * BN;
+    // Work loop.  PERSIST variants: a workgroup takes work items blockIdx.x, blockIdx.x +
+    // gridDim.x, ... (the host launches a multiple of 8 workgroups, so an item's XCD, work % 8,
+    // is the workgroup's own); the stores of one tile drain while the next tile is being
+    // loaded and multiplied.  Other variants: one workgroup per item, the loop runs once.
+    const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
+    for (unsigned work = blockIdx.x; work < total_work; work += gridDim.x) {
+        int slice, tm, tn;
+        map_workgroup(p, total_work, work, slice, tm, tn);
+        const int prob = slice / p.splits, split = slice - prob * p.splits;
+        const int m0 = tm * BM, n0 = tn * BN;
 
-    const int kt_total = (p.k + BK - 1) / BK;
-    const int kt_begin = split * p.ktiles_per_split;
-    const int kt_stop = kt_begin + p.ktiles_per_split;
-    const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
+        const int kt_total = (p.k + BK - 1) / BK;
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_stop = kt_begin + p.ktiles_per_split;
+        const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
-    // Tile origins are wave-uniform (kept in scalar registers and advanced per K tile); each
-    // thread adds fixed offsets for its slots.  Fast variants use 32-bit offsets (the host
-    // checks that a tile spans fewer than 2^31 elements), predicated ones 64-bit.
-    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
-    typedef typename std::conditional<EDGE, int64_t, unsigned>::type off_t;
+        // Tile origins are wave-uniform (kept in scalar registers and advanced per K tile); each
+        // thread adds fixed offsets for its slots.  Fast variants use 32-bit offsets (the host
+        // checks that a tile spans fewer than 2^31 elements), predicated ones 64-bit.
+        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
+        const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+        typedef typename std::conditional<EDGE, int64_t, unsigned>::type off_t;
 
-    // Per-thread slots of the tile loads: slot f = tid + i*NT is one 16-byte vector.
-    int a_row[A_LD], a_k[A_LD], b_row[B_LD], b_col[B_LD];
-    off_t a_off[A_LD], b_off[B_LD];
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-        const int f = tid + i * NT;
-        a_row[i] = f / (BK / 4);
-        a_k[i] = (f % (BK / 4)) * 4;
-        a_off[i] = (off_t)a_row[i] * (off_t)p.lda + (off_t)a_k[i];
-    }
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) {
-        const int f = tid + i * NT;
-        b_row[i] = f / (BN / 4);
-        b_col[i] = (f % (BN / 4)) * 4;
-        b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)b_col[i];
-    }
-
-    f32x4 a_reg[A_LD], b_reg[B_LD];
-
-    // Fetch K tile `kt` (absolute index) into the staging registers.  The pointers then move
-    // on to the next tile only if `advance` is set, so that asking again for the last tile of
-    // the range (when nothing is left to prefetch) stays inside the matrices.
-    auto load_global = [&](int kt, bool advance) {
-#pragma unroll
+        // Per-thread slots of the tile loads: slot f = tid + i*NT is one 16-byte vector.
+        int a_row[A_LD], a_k[A_LD], b_row[B_LD], b_col[B_LD];
+        off_t a_off[A_LD], b_off[B_LD];
+    #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            const float *src = Ag + a_off[i];
-            if constexpr (!EDGE) {
-                a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
-            } else {
-                const bool row_ok = m0 + a_row[i] < p.m;
-                const int kk = kt * BK + a_k[i];
-                f32x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (row_ok && kk + e < p.k) ? src[e] : 0.0f;
-                a_reg[i] = v;
-            }
+            const int f = tid + i * NT;
+            a_row[i] = f / (BK / 4);
+            a_k[i] = (f % (BK / 4)) * 4;
+            a_off[i] = (off_t)a_row[i] * (off_t)p.lda + (off_t)a_k[i];
         }
-#pragma unroll
+    #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
-            const float *src = Bg + b_off[i];
-            if constexpr (!EDGE) {
-                b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
-            } else {
-                const bool row_ok = kt * BK + b_row[i] < p.k;
-                const int cc = n0 + b_col[i];
-                f32x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (row_ok && cc + e < p.n) ? src[e] : 0.0f;
-                b_reg[i] = v;
+            const int f = tid + i * NT;
+            b_row[i] = f / (BN / 4);
+            b_col[i] = (f % (BN / 4)) * 4;
+            b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)b_col[i];
+        }
+
+        f32x4 a_reg[A_LD], b_reg[B_LD];
+
+        // Fetch K tile `kt` (absolute index) into the staging registers.  The pointers then move
+        // on to the next tile only if `advance` is set, so that asking again for the last tile of
+        // the range (when nothing is left to prefetch) stays inside the matrices.
+        auto load_global = [&](int kt, bool advance) {
+    #pragma unroll
+            for (int i = 0; i < A_LD; ++i) {
+                const float *src = Ag + a_off[i];
+                if constexpr (!EDGE) {
+                    a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                } else {
+                    const bool row_ok = m0 + a_row[i] < p.m;
+                    const int kk = kt * BK + a_k[i];
+                    f32x4 v;
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (row_ok && kk + e < p.k) ? src[e] : 0.0f;
+                    a_reg[i] = v;
+                }
             }
-        }
-        if (advance) {
-            Ag += BK;
-            Bg += (int64_t)BK * p.ldb;
-        }
-    };
+    #pragma unroll
+            for (int i = 0; i < B_LD; ++i) {
+                const float *src = Bg + b_off[i];
+                if constexpr (!EDGE) {
+                    b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                } else {
+                    const bool row_ok = kt * BK + b_row[i] < p.k;
+                    const int cc = n0 + b_col[i];
+                    f32x4 v;
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (row_ok && cc + e < p.n) ? src[e] : 0.0f;
+                    b_reg[i] = v;
+                }
+            }
+            if (advance) {
+                Ag += BK;
+                Bg += (int64_t)BK * p.ldb;
+            }
+        };
 
-    auto store_lds = [&](int stage) {
-        float *as = As + stage * A_STAGE;
-        float *bs = Bs + stage * B_STAGE;
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i)
-            *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i)
-            *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = b_reg[i];
-    };
+        auto store_lds = [&](int stage) {
+            float *as = As + stage * A_STAGE;
+            float *bs = Bs + stage * B_STAGE;
+    #pragma unroll
+            for (int i = 0; i < A_LD; ++i)
+                *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
+    #pragma unroll
+            for (int i = 0; i < B_LD; ++i)
+                *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = b_reg[i];
+        };
 
-    f32x16 acc[RB][CB];
-    f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            acc[rb][cb] = (f32x16)(0.0f);
-            if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
-        }
-
-    const int a_frag_off = (wm * WM + li) * LDA_S + h * 4;
-    const int b_frag_off = (h * 4) * LDB_S + wn * WN + li * CB;
-
-    // Operand fragments of two consecutive k-octets: while the MFMAs of octet o run from
-    // one set, the LDS reads of octet o+1 fill the other.
-    constexpr int NO = BK / 8;
-    static_assert(NO % 2 == 0, "BK must be a multiple of 16 (fragment sets alternate per octet)");
-    f32x4 a_frag[2][RB];
-    bvec b_frag[2][4];
-
-    auto read_frags = [&](int stage, int o, int set) {
-        const float *as = As + stage * A_STAGE + a_frag_off + o * 8;
-        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * LDB_S;
-#pragma unroll
+        f32x16 acc[RB][CB];
+        f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
+    #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S);
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * LDB_S);
-    };
-
-    auto mfma_octet = [&](int set) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
-    };
-
-    // Second accumulation level: after every flush_tiles K tiles the MFMA accumulators are
-    // added into `total` and cleared, which bounds the length of any single fp32 running sum.
-    int since_flush = 0;
-    auto maybe_flush = [&]() {
-        if constexpr (TWO_LEVEL) {
-            if (since_flush == p.flush_tiles) {
-                since_flush = 0;
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) {
-                        total[rb][cb] += acc[rb][cb];
-                        acc[rb][cb] = (f32x16)(0.0f);
-                        // one block at a time keeps the temporaries of this rare path small
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+    #pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                acc[rb][cb] = (f32x16)(0.0f);
+                if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
             }
-            ++since_flush;
-        }
-    };
 
-    // K loop.  LDS holds two stages; the staging registers hold the tile after the one in LDS.
-    // Per K tile kt (multiplied out of stage s):
-    //   octets 0 .. NO-3 : fetch the fragments of the next octet, multiply the current one;
-    //   octet NO-2       : the same, with the LDS writes of tile kt+1 (stage s^1) spread between
-    //                      its MFMAs, so the matrix pipe keeps running while they issue;
-    //   one barrier      : stage s^1 is complete, nobody reads stage s any more;
-    //   octet NO-1       : fetch the first fragments of tile kt+1, start the global loads of
-    //                      tile kt+2 into the (now free) staging registers, multiply.
-    // A wave can have only one MFMA in flight, so every instruction that is not an MFMA is
-    // placed in the shadow of one; the fences and group hints below pin that order, which the
-    // scheduler would otherwise undo to save registers.
-    // One barrier per K tile is enough: stage s^1 was last read before the previous barrier,
-    // and stage s is not overwritten before the next one.
-    constexpr int N_MFMA = 4 * RB * CB;          // MFMAs of one octet
-    constexpr int N_ST = A_LD + B_LD;            // LDS writes / global loads of one tile
-    constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
-    if (kt_begin < kt_end) {
-        const int last = kt_end - 1;
-        load_global(kt_begin, kt_begin < last);
-        store_lds(0);
-        __syncthreads();
-        read_frags(0, 0, 0);
-        {
-            const int nl = kt_begin + 1 < last ? kt_begin + 1 : last;
-            load_global(nl, nl < last);
-        }
-        int stage = 0;
-        for (int kt = kt_begin; kt < last; ++kt) {
-            maybe_flush();                // (at the top, so the loop body below stays one block)
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int o = 0; o < NO - 2; ++o) {
+        const int a_frag_off = (wm * WM + li) * LDA_S + h * 4;
+        const int b_frag_off = (h * 4) * LDB_S + wn * WN + li * CB;
+
+        // Operand fragments of two consecutive k-octets: while the MFMAs of octet o run from
+        // one set, the LDS reads of octet o+1 fill the other.
+        constexpr int NO = BK / 8;
+        static_assert(NO % 2 == 0, "BK must be a multiple of 16 (fragment sets alternate per octet)");
+        f32x4 a_frag[2][RB];
+        bvec b_frag[2][4];
+
+        auto read_frags = [&](int stage, int o, int set) {
+            const float *as = As + stage * A_STAGE + a_frag_off + o * 8;
+            const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * LDB_S;
+    #pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S);
+    #pragma unroll
+            for (int t = 0; t < 4; ++t)
+                b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * LDB_S);
+        };
+
+        auto mfma_octet = [&](int set) {
+    #pragma unroll
+            for (int t = 0; t < 4; ++t)
+    #pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+    #pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                            a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+        };
+
+        // Second accumulation level: after every flush_tiles K tiles the MFMA accumulators are
+        // added into `total` and cleared, which bounds the length of any single fp32 running sum.
+        int since_flush = 0;
+        auto maybe_flush = [&]() {
+            if constexpr (TWO_LEVEL) {
+                if (since_flush == p.flush_tiles) {
+                    since_flush = 0;
+    #pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+    #pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) {
+                            total[rb][cb] += acc[rb][cb];
+                            acc[rb][cb] = (f32x16)(0.0f);
+                            // one block at a time keeps the temporaries of this rare path small
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                }
+                ++since_flush;
+            }
+        };
+
+        // K loop.  LDS holds two stages; the staging registers hold the tile after the one in LDS.
+        // Per K tile kt (multiplied out of stage s):
+        //   octets 0 .. NO-3 : fetch the fragments of the next octet, multiply the current one;
+        //   octet NO-2       : the same, with the LDS writes of tile kt+1 (stage s^1) spread between
+        //                      its MFMAs, so the matrix pipe keeps running while they issue;
+        //   one barrier      : stage s^1 is complete, nobody reads stage s any more;
+        //   octet NO-1       : fetch the first fragments of tile kt+1, start the global loads of
+        //                      tile kt+2 into the (now free) staging registers, multiply.
+        // A wave can have only one MFMA in flight, so every instruction that is not an MFMA is
+        // placed in the shadow of one; the fences and group hints below pin that order, which the
+        // scheduler would otherwise undo to save registers.
+        // One barrier per K tile is enough: stage s^1 was last read before the previous barrier,
+        // and stage s is not overwritten before the next one.
+        constexpr int N_MFMA = 4 * RB * CB;          // MFMAs of one octet
+        constexpr int N_ST = A_LD + B_LD;            // LDS writes / global loads of one tile
+        constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
+        if (kt_begin < kt_end) {
+            const int last = kt_end - 1;
+            load_global(kt_begin, kt_begin < last);
+            store_lds(0);
+            __syncthreads();
+            read_frags(0, 0, 0);
+            {
+                const int nl = kt_begin + 1 < last ? kt_begin + 1 : last;
+                load_global(nl, nl < last);
+            }
+            int stage = 0;
+            for (int kt = kt_begin; kt < last; ++kt) {
+                maybe_flush();                // (at the top, so the loop body below stays one block)
+                __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                for (int o = 0; o < NO - 2; ++o) {
+                    read_frags(stage, o + 1, (o + 1) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_octet(o & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                read_frags(stage, NO - 1, (NO - 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_octet((NO - 2) & 1);
+                store_lds(stage ^ 1);
+    #pragma unroll
+                for (int i = 0; i < N_ST; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // LDS write
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();
+                read_frags(stage ^ 1, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                {
+                    const int nl = kt + 2 < last ? kt + 2 : last;
+                    load_global(nl, nl < last);
+                }
+                mfma_octet((NO - 1) & 1);
+    #pragma unroll
+                for (int i = 0; i < N_ST; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global load
+                    __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                stage ^= 1;
+            }
+    #pragma unroll
+            for (int o = 0; o < NO - 1; ++o) {
                 read_frags(stage, o + 1, (o + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_octet(o & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            read_frags(stage, NO - 1, (NO - 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_octet((NO - 2) & 1);
-            store_lds(stage ^ 1);
-#pragma unroll
-            for (int i = 0; i < N_ST; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // LDS write
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            read_frags(stage ^ 1, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            {
-                const int nl = kt + 2 < last ? kt + 2 : last;
-                load_global(nl, nl < last);
-            }
             mfma_octet((NO - 1) & 1);
-#pragma unroll
-            for (int i = 0; i < N_ST; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global load
-                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            stage ^= 1;
         }
-#pragma unroll
-        for (int o = 0; o < NO - 1; ++o) {
-            read_frags(stage, o + 1, (o + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_octet(o & 1);
-            __builtin_amdgcn_sched_barrier(0);
+        if constexpr (TWO_LEVEL) {
+    #pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+    #pragma unroll
+                for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
         }
-        mfma_octet((NO - 1) & 1);
-    }
-    if constexpr (TWO_LEVEL) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
-    }
 
-    // Epilogue: registers -> C (or the split-K partial).
-    float *out;
-    int64_t ldo;
-    if (p.splits > 1) {
-        out = p.ws + (int64_t)slice * p.m * p.n;
-        ldo = p.n;
-    } else {
-        out = p.C + (int64_t)prob * p.strideC;
-        ldo = p.ldc;
-    }
-    const int col = n0 + wn * WN + li * CB;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-            float *dst = out + (int64_t)row * ldo + col;
-            if constexpr (!EDGE) {
-                bvec o;
-                if constexpr (CB == 1) {
-                    o = acc[rb][0][v];
+        // Epilogue: registers -> C (or the split-K partial).
+        float *out;
+        int64_t ldo;
+        if (p.splits > 1) {
+            out = p.ws + (int64_t)slice * p.m * p.n;
+            ldo = p.n;
+        } else {
+            out = p.C + (int64_t)prob * p.strideC;
+            ldo = p.ldc;
+        }
+        const int col = n0 + wn * WN + li * CB;
+    #pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+    #pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                float *dst = out + (int64_t)row * ldo + col;
+                if constexpr (!EDGE) {
+                    bvec o;
+                    if constexpr (CB == 1) {
+                        o = acc[rb][0][v];
+                    } else {
+    #pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+                    }
+                    *reinterpret_cast<bvec *>(dst) = o;
                 } else {
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
-                }
-                *reinterpret_cast<bvec *>(dst) = o;
-            } else {
-                if (row < p.m) {
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-                        if (col + cb < p.n) dst[cb] = acc[rb][cb][v];
+                    if (row < p.m) {
+    #pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            if (col + cb < p.n) dst[cb] = acc[rb][cb][v];
+                    }
                 }
             }
         }
+        if constexpr (!PERSIST) break;
+        // the next item's first tile overwrites LDS stage 0: wait until every wave has read its last fragments
+        if (work + gridDim.x < total_work) __syncthreads();
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE, bool PERSIST>
 hipError_t launch_tile(const GemmParams &p, hipStream_t s) {
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     constexpr int lds_used = tile_lds_bytes<BM, BN, BK, WM, WN>();
-    auto kern = sgemm_tile_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, EDGE>;
+    auto kern = sgemm_tile_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, EDGE, PERSIST>;
     // Occupancy cap: asking for a larger LDS allocation than the tile uses limits how many
     // workgroups share a CU (max_blocks_per_cu == 0: no cap).
     int lds = lds_used;
@@ -404,7 +415,8 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t s) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
     if (attr != hipSuccess) return attr;
-    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    if (PERSIST && p.persistent_blocks > 0 && p.persistent_blocks < blocks) blocks = p.persistent_blocks;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
     return hipGetLastError();
 }

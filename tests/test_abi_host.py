@@ -142,10 +142,10 @@ def test_force_config_grammar_and_get_config(lib):
 
 def test_tune_cache_file_round_trip(tmp_path, lib):
     path = tmp_path / "cache.txt"
-    path.write_text("tgemm-tune-cache 2 gfx950\n"
-                    "1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 20.5\n"
-                    "1 512 512 512 1 t64x64x32_w32x32 1 2 2 7.5\n"
-                    "1 2048 2048 2048 1 some_kernel_of_another_build 1 4 0 99.0\n")
+    path.write_text("tgemm-tune-cache 3 gfx950\n"
+                    "1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 0 20.5\n"
+                    "1 512 512 512 1 p128x128x32_w64x64 1 2 2 3 7.5\n"
+                    "1 2048 2048 2048 1 some_kernel_of_another_build 1 4 0 0 99.0\n")
     try:
         tg.clear_tune_cache()
         tg.load_tune_cache(path)
@@ -153,10 +153,10 @@ def test_tune_cache_file_round_trip(tmp_path, lib):
         out = tmp_path / "saved.txt"
         tg.save_tune_cache(out)
         text = out.read_text().splitlines()
-        assert tg.get_config(1, 512, 512, 512) == "t64x64x32_w32x32:s1:g2:o2"
-        assert text[0] == "tgemm-tune-cache 2 gfx950" and len(text) == 3
-        assert text[1].startswith("1 512 512 512 1 t64x64x32_w32x32 1 2 2")
-        assert text[2].startswith("1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0")
+        assert tg.get_config(1, 512, 512, 512) == "p128x128x32_w64x64:s1:g2:o2:p3"
+        assert text[0] == "tgemm-tune-cache 3 gfx950" and len(text) == 3
+        assert text[1].startswith("1 512 512 512 1 p128x128x32_w64x64 1 2 2 3")
+        assert text[2].startswith("1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 0")
         bad = tmp_path / "bad.txt"
         bad.write_text("something else\n")
         with pytest.raises(tg.TgemmError):

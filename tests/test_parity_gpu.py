@@ -90,10 +90,25 @@ def test_each_kernel_variant(dist):
         batch, m, n, k = _shape_for(name)
         say(f"forced {name} on {m}x{n}x{k} ({dist})")
         a, b = ig.make_operands(batch, m, n, k, dist, 301, 302)
-        tg.force_config(name + ":s1:g2")
+        spec = name + ":s1:g2" + (":p1" if name.startswith("p") else "")
+        tg.force_config(spec)
         c = run_hip(a[0], b[0])
-        assert tg.last_config() == name + ":s1:g2"
+        assert tg.last_config() == spec
         check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=name)
+
+
+@pytest.mark.parametrize("spec", ["p128x128x16_w64x64:p1", "p128x128x32_w64x64:p2:o2", "p128x128x32_w64x64:p3:g3",
+                                  "p128x128x16_w64x64:s2:p1"])
+def test_persistent_launch(spec):
+    """Fewer workgroups than tiles: every workgroup loops over several tiles."""
+    import torch
+    say(f"persistent {spec}")
+    m, n, k = 40 * 128, 26 * 128, 192        # 1040 tiles of 128x128 on 256 x p workgroups
+    ws = torch.empty(2 * m * n, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    a, b = ig.make_operands(1, m, n, k, "int", 313, 314)
+    tg.force_config(spec)
+    check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what=spec)
 
 
 @pytest.mark.parametrize("group", [1, 3, 8, 64])
