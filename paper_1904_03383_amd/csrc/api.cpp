@@ -483,18 +483,29 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
     if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess)
         return fail(TG_ERR_HIP, "hipEventCreate failed");
 
+    // One timing: warm-up launch, then `n` back-to-back launches between two events.  Short
+    // kernels are repeated more often (until about 0.3 ms is covered) so that launch jitter
+    // does not decide between candidates.
     auto time_config = [&](const Config &c, double *usec) -> tg_status {
         tg_status r = launch(p, c, ws, s);   // warm-up (also loads the code object)
         if (r != TG_OK) return r;
-        hipEventRecord(ev0, s);
-        for (int i = 0; i < reps && r == TG_OK; ++i) r = launch(p, c, ws, s);
-        hipEventRecord(ev1, s);
-        hipError_t e = hipEventSynchronize(ev1);
-        if (r != TG_OK) return r;
-        if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
-        float ms = 0.f;
-        hipEventElapsedTime(&ms, ev0, ev1);
-        *usec = 1e3 * ms / reps;
+        int n = reps;
+        double best_of = 1e300;
+        for (int round = 0; round < 3; ++round) {
+            hipEventRecord(ev0, s);
+            for (int i = 0; i < n && r == TG_OK; ++i) r = launch(p, c, ws, s);
+            hipEventRecord(ev1, s);
+            hipError_t e = hipEventSynchronize(ev1);
+            if (r != TG_OK) return r;
+            if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
+            float ms = 0.f;
+            hipEventElapsedTime(&ms, ev0, ev1);
+            const double us = 1e3 * ms / n;
+            best_of = std::min(best_of, us);
+            if (us * n >= 300.0 || n >= 64) break;          // long enough
+            n = std::min<int>(64, std::max<int>(n * 2, (int)(300.0 / std::max(us, 1.0)) + 1));
+        }
+        *usec = best_of;
         return TG_OK;
     };
 

@@ -72,6 +72,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
     static_assert(BK == 32, "BK must be 32");
+    static_assert(BK / 8 >= 3, "the K loop below is written for at least three octets per tile");
     static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0 && A_LD >= 1 && B_LD >= 1,
                   "tile loads must divide evenly over the workgroup");
     static_assert(BN % 4 == 0 && (256 % BK) == 0, "one load instruction covers whole chunks and rows");
@@ -185,7 +186,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
         constexpr int kWaitVm0 = 0x0F70;
         constexpr int N_MFMA = 4 * RB * CB;
         constexpr int N_LD = A_LD + B_LD;
-        constexpr int MFMA_PER_LD = N_MFMA / N_LD > 0 ? N_MFMA / N_LD : 1;
+        constexpr int MFMA_PER_LD = (N_MFMA - 2) / N_LD > 0 ? (N_MFMA - 2) / N_LD : 1;
 
         if (kt_begin < kt_end) {
             const int last = kt_end - 1;
@@ -201,33 +202,44 @@ sgemm_tile_direct_kernel(const GemmParams p) {
             for (int kt = kt_begin; kt < last; ++kt) {
                 maybe_flush();
                 __builtin_amdgcn_sched_barrier(0);
-                // octet 0: fetch octet 1, start tile kt+1 on its way into the other stage
+                // Every octet: two MFMAs, then the fetch of the next octet's fragments, then the
+                // rest of the MFMAs.  The compiler counts direct loads as pending LDS traffic of
+                // another kind, which turns every LDS wait into a full one (lgkmcnt(0)) while
+                // they are in flight; with this order the full wait always falls before the
+                // next fetch is issued and after the previous one had 14+ MFMAs to finish.
+                // octet 0 also starts tile kt+1 on its way into the other stage.
+                mfma_octet(0);
                 read_frags(stage, 1, 1);
-                __builtin_amdgcn_sched_barrier(0);
                 TG_ISSUE_DIRECT_LOADS((stage ^ 1) * A_STAGE, 2 * A_STAGE + (stage ^ 1) * B_STAGE);
                 if (kt + 1 < last) {
                     Ag += BK;
                     Bg += b_step;
                 }
-                mfma_octet(0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);         // LDS reads
     #pragma unroll
                 for (int i = 0; i < N_LD; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
                     __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_LD, 0);   // MFMA
                 }
+                __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);         // remaining MFMAs
                 __builtin_amdgcn_sched_barrier(0);
     #pragma unroll
                 for (int o = 1; o < NO - 1; ++o) {
-                    read_frags(stage, o + 1, (o + 1) & 1);
-                    __builtin_amdgcn_sched_barrier(0);
                     mfma_octet(o & 1);
+                    read_frags(stage, o + 1, (o + 1) & 1);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 __builtin_amdgcn_s_waitcnt(kWaitVm0);    // this wave's share of tile kt+1 is in LDS
                 __syncthreads();                         // everyone's is; stage `stage` is free
-                read_frags(stage ^ 1, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
                 mfma_octet((NO - 1) & 1);
+                read_frags(stage ^ 1, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 stage ^= 1;
             }
