@@ -109,6 +109,39 @@ def time_workload(tg, torch, name, steps, warmup, reps_tune):
     return res, (a, b, out)
 
 
+def time_axpy(tg, torch, steps, warmup):
+    """axpy of Sec. 5.2 (z = alpha.x + y, n = 2^26): the paper's bandwidth-bound kernel.  HBM roofline."""
+    from paper_1904_03383_amd import inputgen as ig
+    from oracle import oracle
+    n, alpha = 1 << 26, 0.37
+    x, y = ig.uniform(3001, (n,)), ig.normal(3002, (n,))
+    dx, dy = torch.from_numpy(x).to("cuda"), torch.from_numpy(y).to("cuda")
+    dz = torch.empty_like(dx)
+    for _ in range(warmup):
+        tg.saxpy(alpha, dx, dy, out=dz)
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record(torch.cuda.current_stream())
+    for _ in range(steps):
+        tg.saxpy(alpha, dx, dy, out=dz)
+    ev1.record(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    dev_ms = ev0.elapsed_time(ev1) / steps
+    nbytes = 12.0 * n
+    # parity on a sample (every 1024th element plus the tail)
+    idx = np.unique(np.concatenate([np.arange(0, n, 1024), np.arange(n - 64, n)]))
+    ref = oracle.saxpy_f64(alpha, x[idx], y[idx])
+    got = dz.cpu().numpy()[idx].astype(np.float64)
+    ok = bool(np.all(np.abs(got - ref) <= 2.0 ** -24 * np.abs(ref) * (1 + 1e-9) + 2.0 ** -149))
+    t0 = time.perf_counter()
+    oracle.saxpy_f64(alpha, x, y)
+    cpu_s = time.perf_counter() - t0
+    return {"workload": "axpy_2p26", "n": n, "alpha": alpha, "device_ms_per_step": dev_ms, "bytes": nbytes, "flops": 2.0 * n,
+            "algorithmic_gbs": nbytes / (dev_ms * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (dev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "bound": "hbm", "parity_ok": ok, "cpu_oracle_seconds": cpu_s, "cpu_oracle_gbs": nbytes / cpu_s / 1e9, "cpu_cores": 1}
+
+
 def parity_on_rows(a, b, out, rows):
     """Compare sampled rows of the device result with the oracle (element-wise and Frobenius)."""
     from oracle import oracle
@@ -210,6 +243,12 @@ def main():
 
     if cache and not cache.exists():
         tg.save_tune_cache(cache)
+
+    if not args.no_others:
+        r = time_axpy(tg, torch, min(args.steps, 100), min(args.warmup, 10))
+        log(f"  axpy n=2^26: {r['device_ms_per_step'] * 1e3:.1f} us  {r['algorithmic_gbs']:.0f} GB/s  "
+            f"({r['frac_hbm_peak'] * 100:.1f}% of HBM peak)  parity_ok={r['parity_ok']}")
+        others.append(r)
 
     if args.copy_calibration:
         # a plain streaming kernel of known size: reads 256 MiB, writes 256 MiB

@@ -74,6 +74,15 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
                            void *stream);
 
 /*
+ * z[i] = alpha * x[i] + y[i] for 0 <= i < n (Sec. 5.2 "axpy": z = alpha.x + y, the paper's
+ * bandwidth-bound kernel, n = 2^26 there).  x, y, z are device pointers to n contiguous
+ * floats; z may be the same pointer as y or x (in-place), partial overlap is undefined.
+ * Each element is one fused multiply-add (a single rounding).  n == 0: nothing is done.
+ * Errors: negative n, or a null pointer with n > 0 -> TG_ERR_INVALID_ARG.
+ */
+tg_status tg_saxpy(int64_t n, float alpha, const float *x, const float *y, float *z, void *stream);
+
+/*
  * Host-side tile-configuration tuner (the counterpart of the decisions -- block/thread
  * mapping, tile sizes, unrolling, memory space -- that the paper's search fixes per
  * kernel and input size, Secs. 4 and 5.1; here a small fixed candidate set is timed).

@@ -120,6 +120,18 @@ int oracle_sgemm_f64(int64_t batch, int64_t m, int64_t n, int64_t k,
     return 0;
 }
 
+/*
+ * axpy of Sec. 5.2 of the paper: z = alpha.x + y on vectors of n elements, written as the
+ * definition.  alpha and x[i] are fp32, their product is exact in fp64; the sum with y[i] is
+ * one fp64 addition (relative error <= 2^-53).  Returns 0, or 1 on an invalid argument.
+ */
+int oracle_saxpy_f64(int64_t n, float alpha, const float *x, const float *y, double *z)
+{
+    if (n < 0) return 1;
+    for (int64_t i = 0; i < n; ++i) z[i] = (double)alpha * (double)x[i] + (double)y[i];
+    return 0;
+}
+
 /* Number of online host cores (used as the default thread count by the Python side). */
 int oracle_host_cores(void)
 {

@@ -27,6 +27,8 @@ def _load():
                                          p, i64, i64, p, p, i64, ctypes.c_int]
         lib.oracle_sgemm_f64.restype = ctypes.c_int
         lib.oracle_host_cores.restype = ctypes.c_int
+        lib.oracle_saxpy_f64.argtypes = [i64, ctypes.c_float, p, p, p]
+        lib.oracle_saxpy_f64.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -87,6 +89,19 @@ def sgemm_f64(a: np.ndarray, b: np.ndarray, rows=None, want_abs: bool = False, t
         c = c[0]
         s = s[0] if want_abs else None
     return (c, s) if want_abs else c
+
+
+def saxpy_f64(alpha: float, x: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """fp64 value of alpha * x + y for fp32 vectors (axpy of Sec. 5.2 of the paper)."""
+    if x.dtype != np.float32 or y.dtype != np.float32 or x.ndim != 1 or x.shape != y.shape:
+        raise TypeError("x and y must be float32 vectors of equal length")
+    x = np.ascontiguousarray(x)
+    y = np.ascontiguousarray(y)
+    z = np.empty(x.shape, dtype=np.float64)
+    rc = _load().oracle_saxpy_f64(x.size, float(np.float32(alpha)), x.ctypes.data, y.ctypes.data, z.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_saxpy_f64 failed with code {rc}")
+    return z
 
 
 def parity_metrics(c_test: np.ndarray, c_ref: np.ndarray, s_abs: np.ndarray) -> dict:

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     load_library,
     load_tune_cache,
     save_tune_cache,
+    saxpy,
     set_workspace,
     sgemm,
     sgemm_batched,

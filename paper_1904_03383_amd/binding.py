@@ -22,6 +22,7 @@ _i64, _p, _sz, _int, _cstr = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, c
 SIGNATURES = {
     "tg_sgemm": (_int, [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _i64, _p]),
     "tg_sgemm_batched": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p]),
+    "tg_saxpy": (_int, [_i64, ctypes.c_float, _p, _p, _p, _p]),
     "tg_tune": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _int]),
     "tg_set_workspace": (_int, [_p, _sz]),
     "tg_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
@@ -112,6 +113,23 @@ def sgemm(a, b, out=None, stream=None):
     st = load_library().tg_sgemm(m, n, k, a.data_ptr(), _ld(a, 0, k), b.data_ptr(), _ld(b, 0, n),
                                  out.data_ptr(), _ld(out, 0, n), _stream_handle(stream))
     _check(st)
+    return out
+
+
+def saxpy(alpha: float, x, y, out=None, stream=None):
+    """out = alpha * x + y for 1-D contiguous float32 device tensors; out may be y or x.  -> tg_saxpy"""
+    import torch
+    _require_f32_cuda("x", x)
+    _require_f32_cuda("y", y)
+    if x.dim() != 1 or y.dim() != 1 or x.numel() != y.numel() or not x.is_contiguous() or not y.is_contiguous():
+        raise ValueError("x and y must be contiguous 1-D tensors of equal length")
+    if out is None:
+        out = torch.empty_like(y)
+    _require_f32_cuda("out", out)
+    if out.dim() != 1 or out.numel() != x.numel() or not out.is_contiguous():
+        raise ValueError("out has the wrong shape")
+    _check(load_library().tg_saxpy(x.numel(), float(alpha), x.data_ptr(), y.data_ptr(), out.data_ptr(),
+                                   _stream_handle(stream)))
     return out
 
 

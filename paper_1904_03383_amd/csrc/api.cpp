@@ -457,6 +457,18 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k, const
     return run(p, stream);
 }
 
+tg_status tg_saxpy(int64_t n, float alpha, const float *x, const float *y, float *z, void *stream) {
+    if (n < 0) return fail(TG_ERR_INVALID_ARG, "negative size");
+    if (n == 0) return TG_OK;
+    if (!x || !y || !z) return fail(TG_ERR_INVALID_ARG, "x, y or z is null");
+    if (n > INT64_MAX / 4) return fail(TG_ERR_INVALID_ARG, "vector extent overflows int64");
+    tg_status st = check_device();
+    if (st != TG_OK) return st;
+    hipError_t e = tg::launch_saxpy(n, alpha, x, y, z, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("saxpy launch failed: ") + hipGetErrorString(e));
+    return TG_OK;
+}
+
 tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A, int64_t lda, int64_t strideA,
                   const float *B, int64_t ldb, int64_t strideB, float *C, int64_t ldc, int64_t strideC,
                   void *stream, int reps) {

@@ -124,4 +124,45 @@ hipError_t launch_zero_fill(const GemmParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// z = alpha * x + y (axpy of Sec. 5.2 of the paper): 12 bytes of HBM traffic per element and
+// one FMA, so the only thing that matters is keeping many 16-byte loads in flight.  Each
+// thread handles four consecutive floats per step (dwordx4 when the three pointers are
+// 16-byte aligned), the grid strides over the vector; the tail and unaligned vectors take
+// the scalar path.  In the paper's terms: n strip-mined into BLOCK x THREAD x VECTOR(4).
+template <bool VEC>
+__global__ void __launch_bounds__(256) saxpy_kernel(int64_t n, float alpha, const float *x, const float *y, float *z) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if constexpr (VEC) {
+        const int64_t n4 = n >> 2;
+        const f32x4 *x4 = reinterpret_cast<const f32x4 *>(x);
+        const f32x4 *y4 = reinterpret_cast<const f32x4 *>(y);
+        f32x4 *z4 = reinterpret_cast<f32x4 *>(z);
+        for (int64_t i = tid; i < n4; i += stride) {
+            const f32x4 a = x4[i], b = y4[i];
+            f32x4 r;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = __builtin_fmaf(alpha, a[e], b[e]);
+            z4[i] = r;
+        }
+        for (int64_t i = (n4 << 2) + tid; i < n; i += stride) z[i] = __builtin_fmaf(alpha, x[i], y[i]);
+    } else {
+        for (int64_t i = tid; i < n; i += stride) z[i] = __builtin_fmaf(alpha, x[i], y[i]);
+    }
+}
+
+// In-place use (z == y or z == x) is allowed (hence no __restrict__): a thread reads an element
+// before it writes the same element and no other thread touches it.
+hipError_t launch_saxpy(int64_t n, float alpha, const float *x, const float *y, float *z, hipStream_t s) {
+    const bool vec = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(z)) & 15u) == 0;
+    const int64_t items = vec ? (n + 3) / 4 : n;
+    int64_t blocks = (items + 255) / 256;
+    const int64_t cap = 256 * 16;     // 16 workgroups per CU keep enough loads in flight
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    if (vec) hipLaunchKernelGGL(saxpy_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, n, alpha, x, y, z);
+    else hipLaunchKernelGGL(saxpy_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, n, alpha, x, y, z);
+    return hipGetLastError();
+}
+
 }  // namespace tg

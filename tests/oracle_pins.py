@@ -140,3 +140,46 @@ def pin_freivalds(gemm, m=300, n=280, k=520, reps=4):
 
 ALL_PINS = [pin_identity, pin_all_ones, pin_empty_k, pin_exact_bruteforce, pin_closed_forms,
             pin_invariants, pin_library_dgemm, pin_freivalds]
+
+
+# ---- axpy (Sec. 5.2: z = alpha.x + y) ------------------------------------------------------------
+
+def axpy_pin_special_values(axpy):
+    x = ig.uniform(81, (1000,))
+    y = ig.uniform(82, (1000,))
+    assert np.array_equal(axpy(0.0, x, y), y.astype(np.float64))                    # alpha = 0
+    assert np.array_equal(axpy(1.0, x, np.zeros_like(x)), x.astype(np.float64))     # y = 0, alpha = 1
+    assert np.all(axpy(-1.0, x, x) == 0.0)                                          # x - x
+    assert np.array_equal(axpy(1.0, x, y), axpy(1.0, y, x))                         # commutes at alpha = 1
+    assert axpy(3.0, np.array([2.0], np.float32), np.array([-1.0], np.float32))[0] == 5.0
+    assert axpy(-0.5, np.array([4.0], np.float32), np.array([1.0], np.float32))[0] == -1.0
+
+
+def axpy_pin_exact_cases(axpy):
+    xi = ig.small_int(83, (5000,), -100, 100)
+    yi = ig.small_int(84, (5000,), -1000, 1000)
+    got = axpy(7.0, xi, yi)
+    want = [7 * int(a) + int(b) for a, b in zip(xi.tolist(), yi.tolist())]          # integer arithmetic
+    assert got.tolist() == [float(v) for v in want]
+    # power-of-two alpha: alpha*x is an exact scaling, and on the 2^-23 grid the sum is exact in fp64
+    x = ig.uniform(85, (4096,))
+    y = ig.uniform(86, (4096,))
+    from fractions import Fraction
+    got = axpy(0.25, x, y)
+    for i in (0, 1, 17, 4095):
+        assert Fraction(got[i]) == Fraction(1, 4) * Fraction(float(x[i])) + Fraction(float(y[i]))
+
+
+def axpy_pin_elementwise_and_empty(axpy):
+    x = ig.normal(87, (257,))
+    y = ig.normal(88, (257,))
+    z = axpy(1.5, x, y)
+    x2 = x.copy()
+    x2[100] = 0.0
+    z2 = axpy(1.5, x2, y)
+    assert z2[100] == float(y[100]) and np.array_equal(np.delete(z, 100), np.delete(z2, 100))
+    assert axpy(2.0, x[:0], y[:0]).shape == (0,)
+    assert np.array_equal(axpy(2.0, x, y)[::-1], axpy(2.0, x[::-1].copy(), y[::-1].copy()))   # order free
+
+
+AXPY_PINS = [axpy_pin_special_values, axpy_pin_exact_cases, axpy_pin_elementwise_and_empty]

@@ -93,6 +93,14 @@ def test_empty_problems_return_ok_without_a_launch(lib):
     assert lib.tg_tune(0, 5, 5, 5, None, 5, 25, None, 5, 25, None, 5, 25, None, 3) == 0
 
 
+def test_saxpy_argument_checks(lib):
+    assert lib.tg_saxpy(-1, 1.0, FAKE, FAKE, FAKE, None) == 1 and b"negative" in lib.tg_last_error()
+    assert lib.tg_saxpy(8, 1.0, None, FAKE, FAKE, None) == 1 and b"null" in lib.tg_last_error()
+    assert lib.tg_saxpy(8, 1.0, FAKE, None, FAKE, None) == 1
+    assert lib.tg_saxpy(8, 1.0, FAKE, FAKE, None, None) == 1
+    assert lib.tg_saxpy(0, 1.0, None, None, None, None) == 0          # empty: no launch
+
+
 def test_tune_validates_like_sgemm(lib):
     st = lib.tg_tune(1, 4, 4, 8, FAKE, 7, 0, FAKE, 4, 0, FAKE, 4, 0, None, 3)
     assert st == 1 and b"leading dimension" in lib.tg_last_error()

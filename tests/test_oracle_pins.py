@@ -162,3 +162,34 @@ def test_pins_reject_planted_mistake(mutant):
         except (AssertionError, ValueError, IndexError):
             caught.append(pin.__name__)
     assert caught, f"no pin noticed {mutant.__name__}"
+
+
+# ---- axpy ---------------------------------------------------------------------------------------
+
+from oracle_pins import AXPY_PINS  # noqa: E402
+
+
+@pytest.mark.parametrize("pin", AXPY_PINS, ids=lambda p: p.__name__)
+def test_axpy_oracle_passes_pin(pin):
+    pin(oracle.saxpy_f64)
+
+
+AXPY_MUTANTS = [
+    lambda al, x, y: al * x.astype(np.float64),                                  # y dropped
+    lambda al, x, y: al * x.astype(np.float64) - y,                              # wrong sign
+    lambda al, x, y: x + al * y.astype(np.float64),                              # alpha on the wrong vector
+    lambda al, x, y: al * (x.astype(np.float64) + y),                            # alpha on both
+    lambda al, x, y: (np.float32(al) * x + y).astype(np.float64) + 1e-7,         # off by a constant
+    lambda al, x, y: np.roll(al * x.astype(np.float64) + y, 1),                  # shifted by one element
+]
+
+
+@pytest.mark.parametrize("idx", range(len(AXPY_MUTANTS)))
+def test_axpy_pins_reject_planted_mistake(idx):
+    caught = []
+    for pin in AXPY_PINS:
+        try:
+            pin(AXPY_MUTANTS[idx])
+        except (AssertionError, ValueError, IndexError):
+            caught.append(pin.__name__)
+    assert caught, f"no axpy pin noticed mutant {idx}"
