@@ -74,6 +74,23 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
                            void *stream);
 
 /*
+ * C = A.B with arbitrary element strides on the operands:
+ *     C[i*ldc + j] = sum_{p<k} A[i*rsa + p*csa] * B[p*rsb + j*csb].
+ * Covers the paper's "strided matmul" (Sec. 5.2: matmul 1024^3 whose consecutive elements of
+ * A sit 32 elements apart: csa = 32), and transposed / column-major operands ("transposed
+ * layouts", Sec. 5.2): a column-major A with leading dimension lda is rsa = 1, csa = lda.
+ * A column-major C is obtained by computing C^T = B^T.A^T: swap the operands and exchange
+ * each one's two strides.  All strides are in elements and must be >= 1 (ldc >= n); the
+ * operands may not overlap C.  With csa == csb == 1 this is tg_sgemm(lda = rsa, ldb = rsb);
+ * otherwise the predicated kernels gather the operands element by element.
+ */
+tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k,
+                           const float *A, int64_t rsa, int64_t csa,
+                           const float *B, int64_t rsb, int64_t csb,
+                           float *C, int64_t ldc,
+                           void *stream);
+
+/*
  * z[i] = alpha * x[i] + y[i] for 0 <= i < n (Sec. 5.2 "axpy": z = alpha.x + y, the paper's
  * bandwidth-bound kernel, n = 2^26 there).  x, y, z are device pointers to n contiguous
  * floats; z may be the same pointer as y or x (in-place), partial overlap is undefined.

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     set_workspace,
     sgemm,
     sgemm_batched,
+    sgemm_strided,
     tune,
     version,
     workspace_bytes,

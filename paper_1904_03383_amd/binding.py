@@ -22,6 +22,7 @@ _i64, _p, _sz, _int, _cstr = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, c
 SIGNATURES = {
     "tg_sgemm": (_int, [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _i64, _p]),
     "tg_sgemm_batched": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p]),
+    "tg_sgemm_strided": (_int, [_i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _p]),
     "tg_saxpy": (_int, [_i64, ctypes.c_float, _p, _p, _p, _p]),
     "tg_tune": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _int]),
     "tg_set_workspace": (_int, [_p, _sz]),
@@ -113,6 +114,39 @@ def sgemm(a, b, out=None, stream=None):
     st = load_library().tg_sgemm(m, n, k, a.data_ptr(), _ld(a, 0, k), b.data_ptr(), _ld(b, 0, n),
                                  out.data_ptr(), _ld(out, 0, n), _stream_handle(stream))
     _check(st)
+    return out
+
+
+def sgemm_strided(a, b, out=None, stream=None):
+    """C = A.B for 2-D float32 device tensors with any positive strides (views such as a[:, ::32] or a.T).
+
+    out, if given, must be row-major (unit stride along its rows).  -> tg_sgemm_strided
+    """
+    import torch
+    _require_f32_cuda("a", a)
+    _require_f32_cuda("b", b)
+    if a.dim() != 2 or b.dim() != 2 or a.shape[1] != b.shape[0]:
+        raise ValueError(f"shape mismatch: {tuple(a.shape)} x {tuple(b.shape)}")
+    m, k = a.shape
+    n = b.shape[1]
+    if out is None:
+        out = torch.empty((m, n), dtype=torch.float32, device=a.device)
+    _require_f32_cuda("out", out)
+    if tuple(out.shape) != (m, n):
+        raise ValueError("out has the wrong shape")
+
+    def strides(t):
+        rs = int(t.stride(0)) if t.shape[0] > 1 else 1
+        cs = int(t.stride(1)) if t.shape[1] > 1 else 1
+        return max(rs, 1), max(cs, 1)
+    rsa, csa = strides(a)
+    rsb, csb = strides(b)
+    if csa == 1:
+        rsa = max(rsa, k, 1)
+    if csb == 1:
+        rsb = max(rsb, n, 1)
+    _check(load_library().tg_sgemm_strided(m, n, k, a.data_ptr(), rsa, csa, b.data_ptr(), rsb, csb,
+                                           out.data_ptr(), _ld(out, 0, n), _stream_handle(stream)))
     return out
 
 

@@ -49,6 +49,8 @@ struct Problem {
     const float *B; int64_t ldb, strideB;
     float *C; int64_t ldc, strideC;
     bool aligned;   // every row of A, B, C (and every problem) starts on a 16-byte boundary
+    int64_t csa = 1, csb = 1;   // element strides along k of A / along n of B (strided entry point)
+    bool unit() const { return csa == 1 && csb == 1; }
 };
 
 typedef std::tuple<int64_t, int64_t, int64_t, int64_t, int> ShapeKey;
@@ -137,13 +139,26 @@ bool extent(int64_t rows, int64_t cols, int64_t ld, int64_t *out) {
 tg_status validate(Problem &p) {
     if (p.batch < 0 || p.m < 0 || p.n < 0 || p.k < 0)
         return fail(TG_ERR_INVALID_ARG, "negative size");
-    if (p.lda < std::max<int64_t>(p.k, 1) || p.ldb < std::max<int64_t>(p.n, 1) || p.ldc < std::max<int64_t>(p.n, 1))
+    if (p.unit()) {
+        if (p.lda < std::max<int64_t>(p.k, 1) || p.ldb < std::max<int64_t>(p.n, 1))
+            return fail(TG_ERR_INVALID_ARG, "leading dimension too small: need lda >= max(k,1), ldb >= max(n,1), ldc >= max(n,1)");
+    } else if (p.lda < 1 || p.ldb < 1 || p.csa < 1 || p.csb < 1) {
+        return fail(TG_ERR_INVALID_ARG, "element strides of A and B must be positive");
+    }
+    if (p.ldc < std::max<int64_t>(p.n, 1))
         return fail(TG_ERR_INVALID_ARG, "leading dimension too small: need lda >= max(k,1), ldb >= max(n,1), ldc >= max(n,1)");
     if (p.strideA < 0 || p.strideB < 0 || p.strideC < 0)
         return fail(TG_ERR_INVALID_ARG, "negative batch stride");
     int64_t ea, eb, ec, t;
     if (!extent(p.m, p.k, p.lda, &ea) || !extent(p.k, p.n, p.ldb, &eb) || !extent(p.m, p.n, p.ldc, &ec))
         return fail(TG_ERR_INVALID_ARG, "matrix extent overflows int64");
+    if (!p.unit()) {   // (rows-1)*rs + (cols-1)*cs + 1
+        int64_t t1, t2;
+        if (p.m > 0 && p.k > 0 && (mul_ovf(p.m - 1, p.lda, &t1) || mul_ovf(p.k - 1, p.csa, &t2) || add_ovf(t1, t2, &ea) || add_ovf(ea, 1, &ea)))
+            return fail(TG_ERR_INVALID_ARG, "matrix extent overflows int64");
+        if (p.k > 0 && p.n > 0 && (mul_ovf(p.k - 1, p.ldb, &t1) || mul_ovf(p.n - 1, p.csb, &t2) || add_ovf(t1, t2, &eb) || add_ovf(eb, 1, &eb)))
+            return fail(TG_ERR_INVALID_ARG, "matrix extent overflows int64");
+    }
     if (p.batch > 1) {
         if (p.strideC < ec) return fail(TG_ERR_INVALID_ARG, "strideC smaller than one output matrix");
         if (mul_ovf(p.batch - 1, p.strideA, &t) || add_ovf(t, ea, &t) || t > INT64_MAX / 4 ||
@@ -162,7 +177,7 @@ tg_status validate(Problem &p) {
         return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
     p.aligned = a16(p.A) && a16(p.B) && a16(p.C) && p.lda % 4 == 0 && p.ldb % 4 == 0 && p.ldc % 4 == 0 &&
-                (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0 && p.strideC % 4 == 0));
+                (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0 && p.strideC % 4 == 0)) && p.unit();
     return TG_OK;
 }
 
@@ -207,6 +222,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     if (c.persist < 0 || c.persist > 16) return no("persistent workgroups per CU must be 0..16");
     if ((c.persist > 0) != ki.persistent) return no("p<n> goes with the persistent kernel variants (names starting with p), and only with them");
     if (ki.kind == tg::KIND_WAVE) {
+        if (!p.unit()) return no("the wave kernel needs unit element strides");
         if (c.splits != 1) return no("the wave kernel has no split-K");
         if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
         if (ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch > (int64_t)4 * INT32_MAX) return no("too many tiles");
@@ -334,7 +350,7 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
     return out;
 }
 
-ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, p.aligned ? 1 : 0); }
+ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, p.aligned ? 1 : (p.unit() ? 0 : 2)); }
 
 // forced > tuned > heuristic.  Caller holds g_mutex.
 tg_status choose(const Problem &p, Config *out) {
@@ -382,6 +398,7 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     memset(&g, 0, sizeof g);
     g.A = p.A; g.B = p.B; g.C = p.C;
     g.lda = p.lda; g.ldb = p.ldb; g.ldc = p.ldc;
+    g.csa = p.csa; g.csb = p.csb;
     g.strideA = p.strideA; g.strideB = p.strideB; g.strideC = p.strideC;
     g.m = (int)p.m; g.n = (int)p.n; g.k = (int)p.k; g.batch = (int)p.batch;
     g.tiles_m = (int)ceil_div(p.m, ki.BM);
@@ -454,6 +471,14 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k, const
                            int64_t strideA, const float *B, int64_t ldb, int64_t strideB, float *C, int64_t ldc,
                            int64_t strideC, void *stream) {
     Problem p{batch, m, n, k, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, false};
+    return run(p, stream);
+}
+
+tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k, const float *A, int64_t rsa, int64_t csa, const float *B,
+                           int64_t rsb, int64_t csb, float *C, int64_t ldc, void *stream) {
+    Problem p{1, m, n, k, A, rsa, 0, B, rsb, 0, C, ldc, 0, false};
+    p.csa = csa;
+    p.csb = csb;
     return run(p, stream);
 }
 

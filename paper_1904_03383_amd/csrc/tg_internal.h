@@ -15,6 +15,8 @@ struct GemmParams {
     float *C;             // final output
     float *ws;            // split-K partial sums: [batch][splits][m][n], ld = n (nullptr if splits == 1)
     int64_t lda, ldb, ldc;
+    int64_t csa, csb;     // element strides along k of A and along n of B (1 except for the strided entry point;
+                          // only the predicated kernels honour values other than 1)
     int64_t strideA, strideB, strideC;
     int m, n, k;
     int batch;

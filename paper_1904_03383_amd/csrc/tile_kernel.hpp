@@ -144,8 +144,10 @@ sgemm_tile_kernel(const GemmParams p) {
         // Tile origins are wave-uniform (kept in scalar registers and advanced per K tile); each
         // thread adds fixed offsets for its slots.  Fast variants use 32-bit offsets (the host
         // checks that a tile spans fewer than 2^31 elements), predicated ones 64-bit.
-        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-        const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+        // (csa, csb: element strides along k of A / along n of B, honoured by the predicated variants)
+        const int64_t csa = EDGE ? p.csa : 1, csb = EDGE ? p.csb : 1;
+        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK * csa;
+        const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + (int64_t)n0 * csb;
         typedef typename std::conditional<EDGE, int64_t, unsigned>::type off_t;
 
         // Per-thread slots of the tile loads: slot f = tid + i*NT is one 16-byte vector.
@@ -156,14 +158,14 @@ sgemm_tile_kernel(const GemmParams p) {
             const int f = tid + i * NT;
             a_row[i] = f / (BK / 4);
             a_k[i] = (f % (BK / 4)) * 4;
-            a_off[i] = (off_t)a_row[i] * (off_t)p.lda + (off_t)a_k[i];
+            a_off[i] = (off_t)a_row[i] * (off_t)p.lda + (off_t)a_k[i] * (off_t)csa;
         }
     #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             const int f = tid + i * NT;
             b_row[i] = f / (BN / 4);
             b_col[i] = (f % (BN / 4)) * 4;
-            b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)b_col[i];
+            b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)b_col[i] * (off_t)csb;
         }
 
         f32x4 a_reg[A_LD], b_reg[B_LD];
@@ -182,7 +184,7 @@ sgemm_tile_kernel(const GemmParams p) {
                     const int kk = kt * BK + a_k[i];
                     f32x4 v;
     #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (row_ok && kk + e < p.k) ? src[e] : 0.0f;
+                    for (int e = 0; e < 4; ++e) v[e] = (row_ok && kk + e < p.k) ? src[e * csa] : 0.0f;
                     a_reg[i] = v;
                 }
             }
@@ -196,12 +198,12 @@ sgemm_tile_kernel(const GemmParams p) {
                     const int cc = n0 + b_col[i];
                     f32x4 v;
     #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (row_ok && cc + e < p.n) ? src[e] : 0.0f;
+                    for (int e = 0; e < 4; ++e) v[e] = (row_ok && cc + e < p.n) ? src[e * csb] : 0.0f;
                     b_reg[i] = v;
                 }
             }
             if (advance) {
-                Ag += BK;
+                Ag += BK * csa;
                 Bg += (int64_t)BK * p.ldb;
             }
         };

@@ -93,6 +93,18 @@ def test_empty_problems_return_ok_without_a_launch(lib):
     assert lib.tg_tune(0, 5, 5, 5, None, 5, 25, None, 5, 25, None, 5, 25, None, 3) == 0
 
 
+def test_strided_argument_checks(lib):
+    ok = lib.tg_sgemm_strided
+    assert ok(4, 4, 4, FAKE, 4, 0, FAKE, 4, 1, FAKE, 4, None) == 1 and b"positive" in lib.tg_last_error()
+    assert ok(4, 4, 4, FAKE, 4, 2, FAKE, 4, -1, FAKE, 4, None) == 1
+    assert ok(4, 4, 4, FAKE, 0, 2, FAKE, 4, 1, FAKE, 4, None) == 1
+    assert ok(4, 4, 4, FAKE, 8, 2, FAKE, 4, 1, FAKE, 3, None) == 1 and b"leading dimension" in lib.tg_last_error()
+    assert ok(4, 4, 4, None, 8, 2, FAKE, 4, 1, FAKE, 4, None) == 1 and b"null" in lib.tg_last_error()
+    assert ok(1 << 30, 4, 1 << 30, FAKE, 1 << 40, 1 << 40, FAKE, 4, 1, FAKE, 4, None) == 1 and b"overflow" in lib.tg_last_error()
+    assert ok(4, 4, 4, FAKE, 3, 1, FAKE, 4, 1, FAKE, 4, None) == 1          # unit strides: lda >= k as in tg_sgemm
+    assert ok(0, 4, 4, None, 1, 7, None, 1, 9, None, 4, None) == 0          # empty: no launch
+
+
 def test_saxpy_argument_checks(lib):
     assert lib.tg_saxpy(-1, 1.0, FAKE, FAKE, FAKE, None) == 1 and b"negative" in lib.tg_last_error()
     assert lib.tg_saxpy(8, 1.0, None, FAKE, FAKE, None) == 1 and b"null" in lib.tg_last_error()
