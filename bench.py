@@ -142,6 +142,39 @@ def time_axpy(tg, torch, steps, warmup):
             "bound": "hbm", "parity_ok": ok, "cpu_oracle_seconds": cpu_s, "cpu_oracle_gbs": nbytes / cpu_s / 1e9, "cpu_cores": 1}
 
 
+def time_strided(tg, torch, steps, warmup):
+    """Strided matmul of Sec. 5.2: 1024^3 with consecutive elements of A stored 32 apart (tg_sgemm_strided)."""
+    from paper_1904_03383_amd import inputgen as ig
+    from oracle import oracle
+    m = n = k = 1024
+    a_store = ig.uniform(3003, (m, k * 32))
+    b = ig.uniform(3004, (k, n))
+    da = torch.from_numpy(a_store).to("cuda")[:, ::32]
+    db = torch.from_numpy(b).to("cuda")
+    out = torch.empty((m, n), device="cuda")
+    for _ in range(warmup):
+        tg.sgemm_strided(da, db, out=out)
+    cfg = tg.last_config()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record(torch.cuda.current_stream())
+    for _ in range(steps):
+        tg.sgemm_strided(da, db, out=out)
+    ev1.record(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    dev_ms = ev0.elapsed_time(ev1) / steps
+    rows = list(range(0, m, 16))
+    a = np.ascontiguousarray(a_store[:, ::32])
+    c_ref, s_abs = oracle.sgemm_f64(a, b, rows=rows, want_abs=True)
+    par = oracle.parity_metrics(out.cpu().numpy()[rows], c_ref, s_abs)
+    flops = 2.0 * m * n * k
+    return {"workload": "strided_1024_csa32", "m": m, "n": n, "k": k, "tile_config": cfg, "device_ms_per_step": dev_ms,
+            "flops": flops, "device_tflops": flops / (dev_ms * 1e-3) / 1e12,
+            "frac_mfma_peak": flops / (dev_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, "bound": "mfma",
+            "parity_ok": bool(par["max_ratio"] <= ELEM_TOL and par["rel_fro"] <= FRO_TOL and par["finite"])}
+
+
 def parity_on_rows(a, b, out, rows):
     """Compare sampled rows of the device result with the oracle (element-wise and Frobenius)."""
     from oracle import oracle
@@ -248,6 +281,10 @@ def main():
         r = time_axpy(tg, torch, min(args.steps, 100), min(args.warmup, 10))
         log(f"  axpy n=2^26: {r['device_ms_per_step'] * 1e3:.1f} us  {r['algorithmic_gbs']:.0f} GB/s  "
             f"({r['frac_hbm_peak'] * 100:.1f}% of HBM peak)  parity_ok={r['parity_ok']}")
+        others.append(r)
+        r = time_strided(tg, torch, min(args.steps, 100), min(args.warmup, 10))
+        log(f"  strided matmul 1024^3 (A element stride 32): {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.1f} us  "
+            f"{r['device_tflops']:.2f} TFLOP/s  parity_ok={r['parity_ok']}")
         others.append(r)
 
     if args.copy_calibration:

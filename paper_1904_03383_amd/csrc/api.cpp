@@ -290,8 +290,8 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double per_simd = std::ceil(waves / (kNumCUs * 4.0));
         const double wave_flops = 2.0 * 32 * 32 * p.k;
         // a lone wave reads its operands with the latency exposed (~1/6 of the SIMD rate);
-        // several waves on one SIMD overlap, up to about half the rate
-        const double t = std::max(wave_flops / (kSimdFlops / 6.0), per_simd * wave_flops / (kSimdFlops * 0.5));
+        // several waves on one SIMD overlap, up to about a third of the rate (measured)
+        const double t = std::max(wave_flops / (kSimdFlops / 6.0), per_simd * wave_flops / (kSimdFlops * 0.3));
         return launch + t;
     }
     int splits, per;
@@ -300,7 +300,14 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     const double per_cu = std::ceil(blocks / kNumCUs);
     // operand traffic per flop falls with the wave tile; predication and the second
     // accumulator level cost a little
-    const double eff = 1.0 / (1.0 + 12.0 / ki.WM + 12.0 / ki.WN) * (ki.edge ? 0.5 : 1.0) * (ki.two_level ? 0.97 : 1.0);
+    // (measured on MI355X: K tiles of 32 beat 16 by ~1 %, direct-to-LDS loads win by ~1 % on
+    // the large tiles, persistent variants only pay for short K; element-strided operands
+    // cost the predicated kernels another factor of about two)
+    double eff = 1.0 / (1.0 + 12.0 / ki.WM + 12.0 / ki.WN) * (ki.edge ? 0.75 : 1.0) * (ki.two_level ? 0.97 : 1.0);
+    eff *= ki.BK >= 32 ? 1.0 : 0.985;
+    if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? 1.01 : 0.97;
+    if (ki.persistent) eff *= p.k <= 256 ? 1.0 : 0.95;
+    if (!p.unit()) eff *= 0.5;
     const double block_flops = 2.0 * ki.BM * ki.BN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
     double t = launch + per_cu * block_flops / cu_rate;
@@ -411,7 +418,13 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     g.max_blocks_per_cu = c.occ;
     g.persistent_blocks = c.persist > 0 ? c.persist * kNumCUs : 0;   // a multiple of 8
     g.flags = 0;
-    if (p.aligned) g.flags |= tg::kFlagVecA | tg::kFlagVecC;
+    {
+        auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+        const bool multi = p.batch > 1;
+        if (p.csa == 1 && a16(p.A) && p.lda % 4 == 0 && (!multi || p.strideA % 4 == 0)) g.flags |= tg::kFlagVecA;
+        if (p.csb == 1 && a16(p.B) && p.ldb % 4 == 0 && (!multi || p.strideB % 4 == 0)) g.flags |= tg::kFlagVecB;
+        if (a16(p.C) && p.ldc % 4 == 0 && (!multi || p.strideC % 4 == 0)) g.flags |= tg::kFlagVecC;
+    }
     if (ki.kind == tg::KIND_TILE && c.splits > 1) {
         split_plan(ki, p.k, c.splits, &g.splits, &g.ktiles_per_split);
         g.ws = static_cast<float *>(ws);

@@ -4,14 +4,14 @@
 
 namespace tg {
 
-#define TG_DECL(BM, BN, BK, WM, WN, L2, EDGE, PERS) \
-    extern template hipError_t launch_tile<BM, BN, BK, WM, WN, L2, EDGE, PERS>(const GemmParams &, hipStream_t);
+#define TG_DECL(BM, BN, BK, WM, WN, L2, EDGE) \
+    extern template hipError_t launch_tile<BM, BN, BK, WM, WN, L2, EDGE>(const GemmParams &, hipStream_t);
 #define TG_ROW(BM, BN, BK, WM, WN, L2, EDGE, NAME)                                              \
     {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, EDGE, false, (BM / WM) * (BN / WN) * 64,          \
-     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE, false>},
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE>},
 #define TG_PROW(BM, BN, BK, WM, WN, NAME)                                                       \
     {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, true, (BM / WM) * (BN / WN) * 64,       \
-     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, false, false, true>},
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile_stream<BM, BN, BK, WM, WN, false>},
 
 // (BM, BN, BK, WM, WN, two_level, edge, name)
 #define TG_TILE_LIST(X)                                                     \
@@ -36,10 +36,11 @@ namespace tg {
     X(64, 64, 16, 32, 32, false, true, "t64x64x16_w32x32_edge")             \
     X(64, 64, 16, 32, 32, true, true, "t64x64x16_w32x32_acc2_edge")
 
-#define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE, false)
+#define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE)
 TG_TILE_LIST(TG_DECL_X)
-TG_DECL(128, 128, 16, 64, 64, false, false, true)
-TG_DECL(128, 128, 32, 64, 64, false, false, true)
+extern template hipError_t launch_tile_stream<128, 128, 16, 64, 64, false>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_tile_stream<128, 128, 32, 64, 64, false>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(const GemmParams &, hipStream_t);
 
 // direct-to-LDS variants: (BM, BN, BK, WM, WN, two_level, name)
 #define TG_DIRECT_LIST(X)                                                   \
@@ -62,6 +63,7 @@ static const KernelInfo kTable[] = {
     TG_DIRECT_LIST(TG_DROW)
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")
     TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
+    TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")
     {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, 256, 0, &launch_wave32},
 };
 

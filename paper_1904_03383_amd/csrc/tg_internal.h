@@ -33,8 +33,9 @@ struct GemmParams {
     int flags;            // kFlag* bits, computed on the host from pointers and strides
 };
 
-constexpr int kFlagVecA = 1;  // rows of A may be read as aligned 16-byte vectors (wave kernel)
-constexpr int kFlagVecC = 2;  // rows of C may be written as aligned 16-byte vectors (reduce kernel)
+constexpr int kFlagVecA = 1;  // rows of A: unit element stride, 16-byte aligned (base, leading dimension, batch stride)
+constexpr int kFlagVecC = 2;  // rows of C: 16-byte aligned
+constexpr int kFlagVecB = 4;  // rows of B: unit element stride, 16-byte aligned
 
 typedef hipError_t (*launch_fn)(const GemmParams &, hipStream_t);
 
@@ -58,8 +59,13 @@ int num_kernels();
 const KernelInfo &kernel(int idx);
 
 // Workgroup-tile kernels: LDS-staged, double-buffered, MFMA 32x32x2 register blocks.
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE, bool PERSIST>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
 hipError_t launch_tile(const GemmParams &p, hipStream_t s);
+
+// Persistent form of the tile kernel: a fixed number of workgroups walk the K tiles of
+// several output tiles as one stream (exact-fit shapes).
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();
 

@@ -1,11 +1,8 @@
 // Explicit instantiations: 128x128 workgroup tiles (four waves of 64x64).
 #include "tile_kernel.hpp"
 namespace tg {
-template hipError_t launch_tile<128, 128, 16, 64, 64, false, false, false>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<128, 128, 16, 64, 64, true, false, false>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<128, 128, 32, 64, 64, false, false, false>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<128, 128, 32, 64, 64, true, false, false>(const GemmParams &, hipStream_t);
-// persistent variants (short-K problems: the epilogue of one tile overlaps the next tile)
-template hipError_t launch_tile<128, 128, 16, 64, 64, false, false, true>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<128, 128, 32, 64, 64, false, false, true>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 128, 16, 64, 64, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 128, 16, 64, 64, true, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 128, 32, 64, 64, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 128, 32, 64, 64, true, false>(const GemmParams &, hipStream_t);
 }  // namespace tg

@@ -2,8 +2,8 @@
 // small to fill the chip with larger tiles.
 #include "tile_kernel.hpp"
 namespace tg {
-template hipError_t launch_tile<64, 64, 32, 32, 32, false, false, false>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<64, 64, 32, 32, 32, true, false, false>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<128, 64, 32, 64, 32, false, false, false>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile<64, 128, 32, 32, 64, false, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<64, 64, 32, 32, 32, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<64, 64, 32, 32, 32, true, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<128, 64, 32, 64, 32, false, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile<64, 128, 32, 32, 64, false, false>(const GemmParams &, hipStream_t);
 }  // namespace tg

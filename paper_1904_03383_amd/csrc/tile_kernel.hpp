@@ -100,7 +100,7 @@ constexpr int min_waves_per_simd() {
     return acc + staging + frags + 64 <= 256 ? 2 : 1;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE, bool PERSIST>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (min_waves_per_simd<BM, BN, BK, WM, WN, TWO_LEVEL>()))
 sgemm_tile_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
@@ -125,12 +125,10 @@ sgemm_tile_kernel(const GemmParams p) {
     const int li = lane & 31, h = lane >> 5;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-    // Work loop.  PERSIST variants: a workgroup takes work items blockIdx.x, blockIdx.x +
-    // gridDim.x, ... (the host launches a multiple of 8 workgroups, so an item's XCD, work % 8,
-    // is the workgroup's own); the stores of one tile drain while the next tile is being
-    // loaded and multiplied.  Other variants: one workgroup per item, the loop runs once.
+    // One workgroup per work item (tile x slice).
     const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
-    for (unsigned work = blockIdx.x; work < total_work; work += gridDim.x) {
+    const unsigned work = blockIdx.x;
+    {
         int slice, tm, tn;
         map_workgroup(p, total_work, work, slice, tm, tn);
         const int prob = slice / p.splits, split = slice - prob * p.splits;
@@ -173,12 +171,28 @@ sgemm_tile_kernel(const GemmParams p) {
         // Fetch K tile `kt` (absolute index) into the staging registers.  The pointers then move
         // on to the next tile only if `advance` is set, so that asking again for the last tile of
         // the range (when nothing is left to prefetch) stays inside the matrices.
+        // Predicated variants: a tile that lies wholly inside the matrices (the common case even
+        // for ragged sizes) is fetched without per-element tests, with 16-byte loads when the
+        // operand's rows allow it (unit element stride, 16-byte aligned rows: host flags), else
+        // with four plain loads per slot; only tiles that cross an edge take the tested path.
+        const bool full_m = m0 + BM <= p.m, full_n = n0 + BN <= p.n;      // workgroup-uniform
+        const bool vec_a = (p.flags & kFlagVecA) != 0, vec_b = (p.flags & kFlagVecB) != 0;
         auto load_global = [&](int kt, bool advance) {
+            const bool full_k = EDGE && (kt + 1) * BK <= p.k;
     #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
                 const float *src = Ag + a_off[i];
                 if constexpr (!EDGE) {
                     a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                } else if (full_m && full_k) {
+                    if (vec_a) {
+                        a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                    } else {
+                        f32x4 v;
+    #pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = src[e * csa];
+                        a_reg[i] = v;
+                    }
                 } else {
                     const bool row_ok = m0 + a_row[i] < p.m;
                     const int kk = kt * BK + a_k[i];
@@ -193,6 +207,15 @@ sgemm_tile_kernel(const GemmParams p) {
                 const float *src = Bg + b_off[i];
                 if constexpr (!EDGE) {
                     b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                } else if (full_n && full_k) {
+                    if (vec_b) {
+                        b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                    } else {
+                        f32x4 v;
+    #pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = src[e * csb];
+                        b_reg[i] = v;
+                    }
                 } else {
                     const bool row_ok = kt * BK + b_row[i] < p.k;
                     const int cc = n0 + b_col[i];
@@ -372,6 +395,8 @@ sgemm_tile_kernel(const GemmParams p) {
             ldo = p.ldc;
         }
         const int col = n0 + wn * WN + li * CB;
+        // CB-float stores need aligned destination rows: C by host flag, a split-K partial (ld = n) when CB divides n
+        const bool vec_c = p.splits > 1 ? (p.n % CB == 0) : (p.flags & kFlagVecC) != 0;
     #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
     #pragma unroll
@@ -379,6 +404,16 @@ sgemm_tile_kernel(const GemmParams p) {
                 const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
                 float *dst = out + (int64_t)row * ldo + col;
                 if constexpr (!EDGE) {
+                    bvec o;
+                    if constexpr (CB == 1) {
+                        o = acc[rb][0][v];
+                    } else {
+    #pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+                    }
+                    *reinterpret_cast<bvec *>(dst) = o;
+                } else if (full_m && full_n && vec_c) {
+                    // interior tile, rows of the destination aligned for CB-float stores
                     bvec o;
                     if constexpr (CB == 1) {
                         o = acc[rb][0][v];
@@ -396,17 +431,14 @@ sgemm_tile_kernel(const GemmParams p) {
                 }
             }
         }
-        if constexpr (!PERSIST) break;
-        // the next item's first tile overwrites LDS stage 0: wait until every wave has read its last fragments
-        if (work + gridDim.x < total_work) __syncthreads();
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE, bool PERSIST>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool EDGE>
 hipError_t launch_tile(const GemmParams &p, hipStream_t s) {
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     constexpr int lds_used = tile_lds_bytes<BM, BN, BK, WM, WN>();
-    auto kern = sgemm_tile_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, EDGE, PERSIST>;
+    auto kern = sgemm_tile_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, EDGE>;
     // Occupancy cap: asking for a larger LDS allocation than the tile uses limits how many
     // workgroups share a CU (max_blocks_per_cu == 0: no cap).
     int lds = lds_used;
@@ -417,8 +449,7 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t s) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
     if (attr != hipSuccess) return attr;
-    int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
-    if (PERSIST && p.persistent_blocks > 0 && p.persistent_blocks < blocks) blocks = p.persistent_blocks;
+    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
     return hipGetLastError();
 }

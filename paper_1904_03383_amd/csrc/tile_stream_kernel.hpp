@@ -1,0 +1,282 @@
+// Persistent ("stream") form of the workgroup-tile SGEMM kernel for gfx950.
+//
+// Same tile, LDS layout, fragment mapping and MFMA blocks as tile_kernel.hpp (matmul of
+// Sec. 5.2 of the paper), exact-fit shapes only.  The difference is the outer structure: a
+// fixed number of workgroups (a multiple of 8, so a work item's XCD, item % 8, is the
+// workgroup's own) each take work items blockIdx.x, blockIdx.x + gridDim.x, ... and treat
+// the K tiles of all their items as ONE stream.  The load side runs ahead of the compute side
+// across item boundaries: while the last K tiles of one output tile are multiplied, the first
+// K tiles of the next one are already being fetched and staged, so there is no per-tile
+// prologue, and the C stores of one output tile drain while the next is being computed.  This
+// is what short-K problems need (k = 128: only 4..8 K tiles per output tile), where a
+// workgroup-per-tile launch leaves the matrix pipe idle during every prologue and epilogue.
+#pragma once
+
+#include "tile_kernel.hpp"
+
+namespace tg {
+
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (min_waves_per_simd<BM, BN, BK, WM, WN, TWO_LEVEL>()))
+sgemm_tile_stream_kernel(const GemmParams p) {
+    constexpr int WAVES_N = BN / WN;
+    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    constexpr int RB = WM / 32, CB = WN / 32;
+    constexpr int LDA_S = BK + kLdsPadA, LDB_S = BN + kLdsPadB;
+    constexpr int A_STAGE = BM * LDA_S, B_STAGE = BK * LDB_S;
+    constexpr int A_LD = BM * BK / 4 / NT, B_LD = BK * BN / 4 / NT;
+    constexpr int NO = BK / 8;
+    static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
+    static_assert(NO % 2 == 0, "BK must be a multiple of 16 (fragment sets alternate per octet)");
+    static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0 && A_LD >= 1 && B_LD >= 1,
+                  "tile loads must divide evenly over the workgroup");
+    typedef typename vec_of<CB>::type bvec;
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float *As = smem;
+    float *Bs = smem + 2 * A_STAGE;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, h = lane >> 5;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
+    const unsigned step = gridDim.x;
+    const int kt_total = p.k / BK;
+
+    // Per-thread slots of the tile loads: slot f = tid + i*NT is one 16-byte vector.
+    int a_row[A_LD], a_k[A_LD], b_row[B_LD], b_col[B_LD];
+    unsigned a_off[A_LD], b_off[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int f = tid + i * NT;
+        a_row[i] = f / (BK / 4);
+        a_k[i] = (f % (BK / 4)) * 4;
+        a_off[i] = (unsigned)a_row[i] * (unsigned)p.lda + (unsigned)a_k[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int f = tid + i * NT;
+        b_row[i] = f / (BN / 4);
+        b_col[i] = (f % (BN / 4)) * 4;
+        b_off[i] = (unsigned)b_row[i] * (unsigned)p.ldb + (unsigned)b_col[i];
+    }
+
+    // K range of a work item (slice = problem * splits + split).
+    auto k_range = [&](int slice, int &prob, int &kt_begin, int &kt_end) {
+        prob = slice / p.splits;
+        const int split = slice - prob * p.splits;
+        kt_begin = split * p.ktiles_per_split;
+        const int kt_stop = kt_begin + p.ktiles_per_split;
+        kt_end = kt_stop < kt_total ? kt_stop : kt_total;
+    };
+
+    // ---- load side: a cursor over (work item, K tile), wave-uniform --------------------------
+    unsigned ld_work = blockIdx.x;
+    const float *Ag = nullptr, *Bg = nullptr;   // origin of the tile under the cursor
+    int ld_left = 0;                            // K tiles of the cursor's item not fetched yet
+    auto seek = [&](unsigned w) {
+        int slice, tm, tn, prob, kb, ke;
+        map_workgroup(p, total_work, w, slice, tm, tn);
+        k_range(slice, prob, kb, ke);
+        Ag = p.A + (int64_t)prob * p.strideA + (int64_t)tm * BM * p.lda + (int64_t)kb * BK;
+        Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kb * BK * p.ldb + (int64_t)tn * BN;
+        ld_left = ke - kb;
+    };
+
+    f32x4 a_reg[A_LD], b_reg[B_LD];
+    // Fetch the tile under the cursor into the staging registers and move the cursor on.  Past
+    // the end of the stream the cursor stays on its last tile (fetching it again is harmless
+    // and keeps the loop body uniform).
+    auto load_next = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) a_reg[i] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i]);
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) b_reg[i] = *reinterpret_cast<const f32x4 *>(Bg + b_off[i]);
+        if (ld_left > 1) {
+            --ld_left;
+            Ag += BK;
+            Bg += (int64_t)BK * p.ldb;
+        } else if (ld_work + step < total_work) {
+            ld_work += step;
+            seek(ld_work);
+        }
+    };
+
+    auto store_lds = [&](int stage) {
+        float *as = As + stage * A_STAGE;
+        float *bs = Bs + stage * B_STAGE;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+            *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = b_reg[i];
+    };
+
+    // ---- compute side -------------------------------------------------------------------------
+    f32x16 acc[RB][CB];
+    f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
+    const int a_frag_off = (wm * WM + li) * LDA_S + h * 4;
+    const int b_frag_off = (h * 4) * LDB_S + wn * WN + li * CB;
+    f32x4 a_frag[2][RB];
+    bvec b_frag[2][4];
+
+    auto read_frags = [&](int stage, int o, int set) {
+        const float *as = As + stage * A_STAGE + a_frag_off + o * 8;
+        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * LDB_S;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * LDB_S);
+    };
+
+    auto mfma_octet = [&](int set) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+    };
+
+    constexpr int N_MFMA = 4 * RB * CB;
+    constexpr int N_ST = A_LD + B_LD;
+    constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
+
+    // ---- start of the stream --------------------------------------------------------------------
+    seek(ld_work);
+    load_next();
+    store_lds(0);
+    __syncthreads();
+    read_frags(0, 0, 0);
+    load_next();
+    int stage = 0;
+
+    for (unsigned work = blockIdx.x; work < total_work; work += step) {
+        int slice, tm, tn, prob, kb, ke;
+        map_workgroup(p, total_work, work, slice, tm, tn);
+        k_range(slice, prob, kb, ke);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                acc[rb][cb] = (f32x16)(0.0f);
+                if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
+            }
+        int since_flush = 0;
+
+        // Every K tile of the stream runs the same body (see tile_kernel.hpp for the order of
+        // operations inside a tile); the tile staged and the tile fetched may belong to the
+        // next work item.
+        for (int kt = kb; kt < ke; ++kt) {
+            if constexpr (TWO_LEVEL) {
+                if (since_flush == p.flush_tiles) {
+                    since_flush = 0;
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) {
+                            total[rb][cb] += acc[rb][cb];
+                            acc[rb][cb] = (f32x16)(0.0f);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                }
+                ++since_flush;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int o = 0; o < NO - 2; ++o) {
+                read_frags(stage, o + 1, (o + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_octet(o & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            read_frags(stage, NO - 1, (NO - 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_octet((NO - 2) & 1);
+            store_lds(stage ^ 1);
+#pragma unroll
+            for (int i = 0; i < N_ST; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // LDS write
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            read_frags(stage ^ 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_next();
+            mfma_octet((NO - 1) & 1);
+#pragma unroll
+            for (int i = 0; i < N_ST; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global load
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            stage ^= 1;
+        }
+        if constexpr (TWO_LEVEL) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
+        }
+
+        // Epilogue of this work item: registers -> C (or the split-K partial).  The stores are
+        // not waited for; they drain while the next item's tiles are multiplied.
+        float *out;
+        int64_t ldo;
+        if (p.splits > 1) {
+            out = p.ws + (int64_t)slice * p.m * p.n;
+            ldo = p.n;
+        } else {
+            out = p.C + (int64_t)prob * p.strideC;
+            ldo = p.ldc;
+        }
+        const int col = tn * BN + wn * WN + li * CB;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = tm * BM + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                float *dst = out + (int64_t)row * ldo + col;
+                bvec o;
+                if constexpr (CB == 1) {
+                    o = acc[rb][0][v];
+                } else {
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+                }
+                *reinterpret_cast<bvec *>(dst) = o;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s) {
+    constexpr int threads = (BM / WM) * (BN / WN) * 64;
+    constexpr int lds_used = tile_lds_bytes<BM, BN, BK, WM, WN>();
+    auto kern = sgemm_tile_stream_kernel<BM, BN, BK, WM, WN, TWO_LEVEL>;
+    int lds = lds_used;
+    if (p.max_blocks_per_cu > 0) {
+        const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
+        if (share > lds) lds = share;
+    }
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
+    if (attr != hipSuccess) return attr;
+    // a multiple of 8 workgroups (p.persistent_blocks), or one per item when there are fewer items
+    int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    if (p.persistent_blocks > 0 && p.persistent_blocks < blocks) blocks = p.persistent_blocks;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace tg
