@@ -289,9 +289,9 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double waves = (double)ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch;
         const double per_simd = std::ceil(waves / (kNumCUs * 4.0));
         const double wave_flops = 2.0 * 32 * 32 * p.k;
-        // a lone wave reads its operands with the latency exposed (~1/6 of the SIMD rate);
+        // a lone wave reads its operands with the latency exposed (~1/4 of the SIMD rate);
         // several waves on one SIMD overlap, up to about a third of the rate (measured)
-        const double t = std::max(wave_flops / (kSimdFlops / 6.0), per_simd * wave_flops / (kSimdFlops * 0.3));
+        const double t = std::max(wave_flops / (kSimdFlops / 4.0), per_simd * wave_flops / (kSimdFlops * 0.3));
         return launch + t;
     }
     int splits, per;
