@@ -268,8 +268,13 @@ def main():
             if name == args.workload:
                 continue
             steps = args.steps if ig.CONFIGS[name][3] >= 1024 else max(args.steps, 500)
-            r, bufs = time_workload(tg, torch, name, steps, args.warmup, args.tune_reps)
-            del bufs
+            r, (a2, b2, out2) = time_workload(tg, torch, name, steps, args.warmup, args.tune_reps)
+            rows2 = sorted(set(int(x) for x in np.linspace(0, r["m"] - 1, num=min(r["m"], 64))))
+            p2 = parity_on_rows(a2, b2, out2, rows2)
+            r["parity"] = {"rows_checked": len(rows2), "max_ratio": p2["max_ratio"], "rel_fro": p2["rel_fro"],
+                           "ok": bool(p2["finite"] and p2["zero_ok"] and p2["max_ratio"] <= ELEM_TOL and p2["rel_fro"] <= FRO_TOL)}
+            parity_ok = parity_ok and r["parity"]["ok"]
+            del a2, b2, out2
             extra = f"  (graph replay {r['graph_device_ms_per_step'] * 1e3:.2f} us)" if "graph_device_ms_per_step" in r else ""
             log(f"  {name}: {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.2f} us  {r['device_tflops']:.2f} TFLOP/s{extra}")
             others.append(r)

@@ -552,7 +552,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             hipEventElapsedTime(&ms, ev0, ev1);
             const double us = 1e3 * ms / n;
             best_of = std::min(best_of, us);
-            if (us * n >= 300.0 || n >= 64) break;          // long enough
+            if (round >= 1 && (us * n >= 300.0 || n >= 64)) break;   // at least two rounds, long enough
             n = std::min<int>(64, std::max<int>(n * 2, (int)(300.0 / std::max(us, 1.0)) + 1));
         }
         *usec = best_of;
