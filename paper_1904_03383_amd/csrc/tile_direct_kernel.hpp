@@ -14,8 +14,8 @@
 //    runs of consecutive floats and need no permutation.
 //  * There are no staging registers and no LDS write instructions: the loads of tile kt+1
 //    are issued right after the barrier that frees their stage, between the MFMAs of the
-//    first octet, and are waited for (vmcnt) just before the next barrier, a whole K tile
-//    later.
+//    first octet, and are waited for (vmcnt) just before the barrier that hands over their
+//    stage.  NS LDS stages form a ring, so a tile may be NS-1 K tiles in flight.
 #pragma once
 
 #include "tile_kernel.hpp"
@@ -35,9 +35,9 @@ __device__ __forceinline__ int a_swizzle(int row) {
     return (row & 6) | ((row ^ (row >> 3)) & 1);
 }
 
-template <int BM, int BN, int BK>
+template <int BM, int BN, int BK, int NS>
 constexpr int direct_lds_bytes() {
-    return 2 * (BM * BK + BK * BN) * (int)sizeof(float);
+    return NS * (BM * BK + BK * BN) * (int)sizeof(float);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
@@ -59,7 +59,7 @@ constexpr int direct_min_waves() {
             __builtin_amdgcn_global_load_lds((glb_float *)(Bg + b_off[i_]), (lds_float *)(smem + (b_stage) + (i_ * NWAVES + wave) * 256), 16, 0, 0); \
     } while (0)
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (direct_min_waves<BM, BN, BK, WM, WN, TWO_LEVEL>()))
 sgemm_tile_direct_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
@@ -72,229 +72,236 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
     static_assert(BK == 32, "BK must be 32");
-    static_assert(BK / 8 >= 3, "the K loop below is written for at least three octets per tile");
+    static_assert(NO >= 2 && NO % 2 == 0, "fragment sets alternate per octet");
     static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0 && A_LD >= 1 && B_LD >= 1,
                   "tile loads must divide evenly over the workgroup");
     static_assert(BN % 4 == 0 && (256 % BK) == 0, "one load instruction covers whole chunks and rows");
+    static_assert(NS >= 2 && NS <= 4, "two to four LDS stages");
+    static_assert((NS - 2) * (A_LD + B_LD) <= 63, "outstanding loads must fit the vmcnt field");
     typedef typename vec_of<CB>::type bvec;
 
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float *As = smem;
-    float *Bs = smem + 2 * A_STAGE;
+    float *Bs = smem + NS * A_STAGE;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, h = lane >> 5;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-    // One workgroup per work item (tile x slice); the loop below runs once.
+    // One workgroup per work item (tile x slice).
     const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
-    for (unsigned work = blockIdx.x; work < total_work; work += gridDim.x) {
-        int slice, tm, tn;
-        map_workgroup(p, total_work, work, slice, tm, tn);
-        const int prob = slice / p.splits, split = slice - prob * p.splits;
-        const int m0 = tm * BM, n0 = tn * BN;
+    int slice, tm, tn;
+    map_workgroup(p, total_work, blockIdx.x, slice, tm, tn);
+    const int prob = slice / p.splits, split = slice - prob * p.splits;
+    const int m0 = tm * BM, n0 = tn * BN;
 
-        const int kt_total = p.k / BK;
-        const int kt_begin = split * p.ktiles_per_split;
-        const int kt_stop = kt_begin + p.ktiles_per_split;
-        const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
+    const int kt_total = p.k / BK;
+    const int kt_begin = split * p.ktiles_per_split;
+    const int kt_stop = kt_begin + p.ktiles_per_split;
+    const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
-        // Tile origins are wave-uniform and advance per K tile; per-lane offsets are fixed.
-        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-        const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+    // Tile origins are wave-uniform and advance per K tile; per-lane offsets are fixed.
+    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
+    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
 
-        // Load instruction i of this wave fills LDS floats [slot*256, slot*256 + 256) of a stage,
-        // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3.
-        unsigned a_off[A_LD], b_off[B_LD];
-    #pragma unroll
-        for (int i = 0; i < A_LD; ++i) {
-            const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
-            const int row = pos / BK;
-            const int q = (pos % BK) / 4;                          // chunk position inside the row
-            a_off[i] = (unsigned)row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+    // Load instruction i of this wave fills LDS floats [slot*256, slot*256 + 256) of a stage,
+    // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3.
+    unsigned a_off[A_LD], b_off[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
+        const int row = pos / BK;
+        const int q = (pos % BK) / 4;                          // chunk position inside the row
+        a_off[i] = (unsigned)row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
+        b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)(pos % BN);
+    }
+    const int64_t b_step = (int64_t)BK * p.ldb;
+
+    f32x16 acc[RB][CB];
+    f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            acc[rb][cb] = (f32x16)(0.0f);
+            if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
         }
-    #pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
-            b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)(pos % BN);
-        }
 
-        const int64_t b_step = (int64_t)BK * p.ldb;
+    // Fragment addressing.  A: row r = wm*WM + rb*32 + li, chunk 2*o + h at position
+    // (2*o + h) ^ swz(r); rb*32 does not change swz (it only looks at the low four row bits).
+    const int a_row = wm * WM + li;
+    const int a_swz = a_swizzle<BK>(a_row);
+    const int b_frag_off = (h * 4) * BN + wn * WN + li * CB;
 
-        f32x16 acc[RB][CB];
-        f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
-    #pragma unroll
+    f32x4 a_frag[2][RB];
+    bvec b_frag[2][4];
+
+    auto read_frags = [&](int stage, int o, int set) {
+        const float *as = As + stage * A_STAGE + a_row * BK + (((2 * o + h) ^ a_swz) * 4);
+        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * BN;
+#pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-    #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                acc[rb][cb] = (f32x16)(0.0f);
-                if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
-            }
+            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
+    };
 
-        // Fragment addressing.  A: row r = wm*WM + rb*32 + li, chunk 2*o + h at position
-        // (2*o + h) ^ swz(r); rb*32 does not change swz (it only looks at the low four row bits).
-        const int a_row = wm * WM + li;
-        const int a_swz = a_swizzle<BK>(a_row);
-        const int b_frag_off = (h * 4) * BN + wn * WN + li * CB;
-
-        f32x4 a_frag[2][RB];
-        bvec b_frag[2][4];
-
-        auto read_frags = [&](int stage, int o, int set) {
-            const float *as = As + stage * A_STAGE + a_row * BK + (((2 * o + h) ^ a_swz) * 4);
-            const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * BN;
-    #pragma unroll
+    auto mfma_octet = [&](int set) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
             for (int rb = 0; rb < RB; ++rb)
-                a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
-    #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
-        };
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+    };
 
-        auto mfma_octet = [&](int set) {
-    #pragma unroll
-            for (int t = 0; t < 4; ++t)
-    #pragma unroll
+    int since_flush = 0;
+    auto maybe_flush = [&]() {
+        if constexpr (TWO_LEVEL) {
+            if (since_flush == p.flush_tiles) {
+                since_flush = 0;
+#pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-    #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                            a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
-        };
-
-        int since_flush = 0;
-        auto maybe_flush = [&]() {
-            if constexpr (TWO_LEVEL) {
-                if (since_flush == p.flush_tiles) {
-                    since_flush = 0;
-    #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-    #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) {
-                            total[rb][cb] += acc[rb][cb];
-                            acc[rb][cb] = (f32x16)(0.0f);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                }
-                ++since_flush;
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        total[rb][cb] += acc[rb][cb];
+                        acc[rb][cb] = (f32x16)(0.0f);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
             }
-        };
+            ++since_flush;
+        }
+    };
 
-        // s_waitcnt with vmcnt = 0 and the other counters left alone (gfx9 encoding: vmcnt in
-        // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
-        constexpr int kWaitVm0 = 0x0F70;
-        constexpr int N_MFMA = 4 * RB * CB;
-        constexpr int N_LD = A_LD + B_LD;
-        constexpr int MFMA_PER_LD = (N_MFMA - 2) / N_LD > 0 ? (N_MFMA - 2) / N_LD : 1;
+    // s_waitcnt that allows kOutstanding vector-memory operations to stay in flight and leaves
+    // the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4,
+    // lgkmcnt 11:8).
+    constexpr int N_MFMA = 4 * RB * CB;
+    constexpr int N_LD = A_LD + B_LD;
+    constexpr int kOutstanding = (NS - 2) * N_LD;
+    constexpr int kWaitTile = 0x0F70 | (kOutstanding & 15) | ((kOutstanding >> 4) << 14);
+    constexpr int MFMA_PER_LD = (N_MFMA - 2) / N_LD > 0 ? (N_MFMA - 2) / N_LD : 1;
 
-        if (kt_begin < kt_end) {
-            const int last = kt_end - 1;
-            TG_ISSUE_DIRECT_LOADS(0, 2 * A_STAGE);
-            if (kt_begin < last) {
+    // K loop over an NS-stage ring in LDS.  During tile t (stage t % NS) the loads of tile
+    // t+NS-1 are issued into the stage tile t-1 has just left; before the barrier at the end of
+    // tile t a wave waits until only the NS-2 youngest tiles' loads are still in flight, i.e.
+    // until its share of tile t+1 has landed.  Small tiles need the depth: a 64x64x32 tile is
+    // only 16 MFMAs per wave (0.4 us), far less than a trip to L2 or HBM.  Past the end of the
+    // K range the last tile is fetched again (in bounds, never read), which keeps every
+    // iteration, the tail included, the same instruction sequence with the same wait counts.
+    if (kt_begin < kt_end) {
+        int to_load = kt_end - kt_begin;            // tiles not fetched yet
+#pragma unroll
+        for (int st = 0; st < NS - 1; ++st) {
+            TG_ISSUE_DIRECT_LOADS(st * A_STAGE, NS * A_STAGE + st * B_STAGE);
+            if (to_load > 1) {
+                --to_load;
                 Ag += BK;
                 Bg += b_step;
             }
-            __builtin_amdgcn_s_waitcnt(kWaitVm0);
-            __syncthreads();
-            read_frags(0, 0, 0);
-            int stage = 0;
-            for (int kt = kt_begin; kt < last; ++kt) {
-                maybe_flush();
-                __builtin_amdgcn_sched_barrier(0);
-                // Every octet: two MFMAs, then the fetch of the next octet's fragments, then the
-                // rest of the MFMAs.  The compiler counts direct loads as pending LDS traffic of
-                // another kind, which turns every LDS wait into a full one (lgkmcnt(0)) while
-                // they are in flight; with this order the full wait always falls before the
-                // next fetch is issued and after the previous one had 14+ MFMAs to finish.
-                // octet 0 also starts tile kt+1 on its way into the other stage.
-                mfma_octet(0);
-                read_frags(stage, 1, 1);
-                TG_ISSUE_DIRECT_LOADS((stage ^ 1) * A_STAGE, 2 * A_STAGE + (stage ^ 1) * B_STAGE);
-                if (kt + 1 < last) {
-                    Ag += BK;
-                    Bg += b_step;
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);         // LDS reads
-    #pragma unroll
-                for (int i = 0; i < N_LD; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
-                    __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_LD, 0);   // MFMA
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);         // remaining MFMAs
-                __builtin_amdgcn_sched_barrier(0);
-    #pragma unroll
-                for (int o = 1; o < NO - 1; ++o) {
-                    mfma_octet(o & 1);
-                    read_frags(stage, o + 1, (o + 1) & 1);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                __builtin_amdgcn_s_waitcnt(kWaitVm0);    // this wave's share of tile kt+1 is in LDS
-                __syncthreads();                         // everyone's is; stage `stage` is free
-                mfma_octet((NO - 1) & 1);
-                read_frags(stage ^ 1, 0, 0);
+        }
+        __builtin_amdgcn_s_waitcnt(kWaitTile);
+        __syncthreads();
+        read_frags(0, 0, 0);
+        int stage = 0, fill = NS - 1;               // stage being multiplied / stage being filled
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            maybe_flush();
+            __builtin_amdgcn_sched_barrier(0);
+            // Every octet: two MFMAs, then the fetch of the next octet's fragments, then the
+            // rest of the MFMAs.  The compiler counts direct loads as pending LDS traffic of
+            // another kind, which turns every LDS wait into a full one (lgkmcnt(0)) while
+            // they are in flight; with this order the full wait always falls before the
+            // next fetch is issued and after the previous one had most of an octet to finish.
+            // octet 0 also starts the next tile of the ring on its way.
+            mfma_octet(0);
+            read_frags(stage, 1, 1);
+            TG_ISSUE_DIRECT_LOADS(fill * A_STAGE, NS * A_STAGE + fill * B_STAGE);
+            if (to_load > 1) {
+                --to_load;
+                Ag += BK;
+                Bg += b_step;
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);         // LDS reads
+#pragma unroll
+            for (int i = 0; i < N_LD; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_LD, 0);   // MFMA
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);         // remaining MFMAs
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int o = 1; o < NO - 1; ++o) {
+                mfma_octet(o & 1);
+                read_frags(stage, o + 1, (o + 1) & 1);
                 __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                stage ^= 1;
             }
-    #pragma unroll
-            for (int o = 0; o < NO - 1; ++o) {
-                read_frags(stage, o + 1, (o + 1) & 1);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_octet(o & 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            const int next = stage + 1 == NS ? 0 : stage + 1;
+            __builtin_amdgcn_s_waitcnt(kWaitTile);   // this wave's share of the next tile is in LDS
+            __syncthreads();                         // everyone's is; stage `stage` is free
             mfma_octet((NO - 1) & 1);
+            read_frags(next, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            fill = stage;
+            stage = next;
         }
-        if constexpr (TWO_LEVEL) {
-    #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-    #pragma unroll
-                for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
-        }
+    }
+    if constexpr (TWO_LEVEL) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
+    }
 
-        // Epilogue: registers -> C (or the split-K partial).
-        float *out;
-        int64_t ldo;
-        if (p.splits > 1) {
-            out = p.ws + (int64_t)slice * p.m * p.n;
-            ldo = p.n;
-        } else {
-            out = p.C + (int64_t)prob * p.strideC;
-            ldo = p.ldc;
-        }
-        const int col = n0 + wn * WN + li * CB;
-    #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-    #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                float *dst = out + (int64_t)row * ldo + col;
-                bvec o;
-                if constexpr (CB == 1) {
-                    o = acc[rb][0][v];
-                } else {
-    #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
-                }
-                *reinterpret_cast<bvec *>(dst) = o;
+    // Epilogue: registers -> C (or the split-K partial).
+    float *out;
+    int64_t ldo;
+    if (p.splits > 1) {
+        out = p.ws + (int64_t)slice * p.m * p.n;
+        ldo = p.n;
+    } else {
+        out = p.C + (int64_t)prob * p.strideC;
+        ldo = p.ldc;
+    }
+    const int col = n0 + wn * WN + li * CB;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+            float *dst = out + (int64_t)row * ldo + col;
+            bvec o;
+            if constexpr (CB == 1) {
+                o = acc[rb][0][v];
+            } else {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
             }
+            *reinterpret_cast<bvec *>(dst) = o;
         }
-        break;
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s) {
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
-    constexpr int lds_used = direct_lds_bytes<BM, BN, BK>();
-    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL>;
+    constexpr int lds_used = direct_lds_bytes<BM, BN, BK, NS>();
+    static_assert(lds_used <= kLdsPerCU, "stages exceed the LDS of a CU");
+    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, NS>;
     int lds = lds_used;
     if (p.max_blocks_per_cu > 0) {
         const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
@@ -303,7 +310,7 @@ hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
     if (attr != hipSuccess) return attr;
-    int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);
     return hipGetLastError();
 }
