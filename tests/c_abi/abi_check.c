@@ -1,0 +1,45 @@
+/* Plain-C consumer of include/tgemm.h: proves the header is valid C, that every entry point
+ * links, and that argument errors are reported without a GPU.  Built and run by
+ * tests/test_abi_host.py with gcc -std=c99 (no HIP headers involved). */
+#include <stdio.h>
+#include <string.h>
+
+#include "tgemm.h"
+
+#define CHECK(cond)                                                        \
+    do {                                                                   \
+        if (!(cond)) {                                                     \
+            fprintf(stderr, "abi_check: failed: %s (line %d)\n", #cond, __LINE__); \
+            return 1;                                                      \
+        }                                                                  \
+    } while (0)
+
+int main(void)
+{
+    float *fake = (float *)(size_t)0x1000; /* never dereferenced: every call below is rejected or empty */
+    char buf[128];
+
+    CHECK(tg_version() >= 100);
+    CHECK(strcmp(tg_status_string(TG_OK), "TG_OK") == 0);
+    CHECK(tg_sgemm(-1, 1, 1, fake, 1, fake, 1, fake, 1, NULL) == TG_ERR_INVALID_ARG);
+    CHECK(strstr(tg_last_error(), "negative") != NULL);
+    CHECK(tg_sgemm(0, 8, 8, NULL, 8, NULL, 8, NULL, 8, NULL) == TG_OK);
+    CHECK(tg_sgemm_batched(2, 4, 4, 4, fake, 4, 16, fake, 4, 16, fake, 4, 8, NULL) == TG_ERR_INVALID_ARG);
+    CHECK(tg_sgemm_strided(4, 4, 4, fake, 4, 0, fake, 4, 1, fake, 4, NULL) == TG_ERR_INVALID_ARG);
+    CHECK(tg_saxpy(-5, 1.0f, fake, fake, fake, NULL) == TG_ERR_INVALID_ARG);
+    CHECK(tg_saxpy(0, 1.0f, NULL, NULL, NULL, NULL) == TG_OK);
+    CHECK(tg_tune(1, 4, 4, 8, fake, 7, 0, fake, 4, 0, fake, 4, 0, NULL, 3) == TG_ERR_INVALID_ARG);
+    CHECK(tg_set_workspace(NULL, 16) == TG_ERR_INVALID_ARG);
+    CHECK(tg_set_workspace(NULL, 0) == TG_OK);
+    CHECK(tg_workspace_bytes(1, 1024, 1024, 1024) > 0);
+    CHECK(tg_num_kernels() > 0);
+    CHECK(tg_kernel_name(0, buf, sizeof buf) == TG_OK && strlen(buf) > 0);
+    CHECK(tg_force_config("no_such_kernel") == TG_ERR_INVALID_ARG);
+    CHECK(tg_force_config(NULL) == TG_OK);
+    CHECK(tg_get_config(1, 4096, 4096, 4096, buf, sizeof buf) == TG_OK && strstr(buf, "acc2") != NULL);
+    CHECK(tg_last_config() != NULL);
+    CHECK(tg_load_tune_cache("/nonexistent/file") == TG_ERR_INVALID_ARG);
+    tg_clear_tune_cache();
+    printf("abi_check: ok (%d kernel variants, version %d)\n", tg_num_kernels(), tg_version());
+    return 0;
+}

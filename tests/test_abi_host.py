@@ -197,6 +197,21 @@ def test_binding_refuses_non_device_tensors():
         tg.sgemm_batched(a[None], a[None])
 
 
+def test_header_is_plain_c_and_every_entry_point_links(tmp_path):
+    """gcc -std=c99 program that includes only tgemm.h, links libtgemm.so and calls each entry point's error path."""
+    import os
+    import subprocess
+    exe = tmp_path / "abi_check"
+    libdir = tg.library_path().parent
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", str(ROOT / "include"),
+                    str(ROOT / "tests" / "c_abi" / "abi_check.c"), "-o", str(exe),
+                    "-L", str(libdir), "-ltgemm", f"-Wl,-rpath,{libdir}"], check=True)
+    env = dict(os.environ)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi_check: ok" in r.stdout
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = ROOT / "paper_1904_03383_amd"
     for f in list(pkg.rglob("*.py")) + list(pkg.rglob("*.hip")) + list(pkg.rglob("*.cpp")) + list(pkg.rglob("*.h*")):

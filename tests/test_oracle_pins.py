@@ -193,3 +193,19 @@ def test_axpy_pins_reject_planted_mistake(idx):
         except (AssertionError, ValueError, IndexError):
             caught.append(pin.__name__)
     assert caught, f"no axpy pin noticed mutant {idx}"
+
+
+# ---- sanitizer build ------------------------------------------------------------------------------
+
+def test_oracle_c_under_address_and_ub_sanitizers(tmp_path):
+    """oracle.c compiled with -fsanitize=address,undefined and run on closed-form cases (threads, strides, row subsets)."""
+    import pathlib
+    import subprocess
+    root = pathlib.Path(__file__).resolve().parents[1]
+    exe = tmp_path / "oracle_selftest"
+    subprocess.run(["gcc", "-std=c11", "-O1", "-g", "-Wall", "-Wextra", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=all", "-pthread", str(root / "oracle" / "oracle.c"),
+                    str(root / "tests" / "c_abi" / "oracle_selftest.c"), "-o", str(exe), "-lm"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "oracle_selftest: ok" in r.stdout
