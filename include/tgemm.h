@@ -81,8 +81,12 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
  * layouts", Sec. 5.2): a column-major A with leading dimension lda is rsa = 1, csa = lda.
  * A column-major C is obtained by computing C^T = B^T.A^T: swap the operands and exchange
  * each one's two strides.  All strides are in elements and must be >= 1 (ldc >= n); the
- * operands may not overlap C.  With csa == csb == 1 this is tg_sgemm(lda = rsa, ldb = rsb);
- * otherwise the predicated kernels gather the operands element by element.
+ * operands may not overlap C.  With csa == csb == 1 this is tg_sgemm(lda = rsa, ldb = rsb).
+ * Otherwise, when a workspace of tg_strided_workspace_bytes(...) is set, each operand with a
+ * non-unit stride that more than one tile row or column would fetch is first gathered into a
+ * packed row-major copy in the workspace (one pass, every element fetched once) and the
+ * unit-stride kernels multiply the copies; tg_last_config() then ends in "+packA", "+packB" or
+ * "+packAB".  Without that room the predicated kernels gather the operands element by element.
  */
 tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k,
                            const float *A, int64_t rsa, int64_t csa,
@@ -127,6 +131,13 @@ tg_status tg_set_workspace(void *dev_ptr, size_t bytes);
 
 /* Largest workspace any split-K candidate for this problem can need (bytes). 0 on invalid sizes. */
 size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k);
+
+/*
+ * Workspace that lets tg_sgemm_strided pack its non-unit-stride operands (csa != 1: m x k floats,
+ * csb != 1: k x n floats, rows padded to a multiple of 4) and still consider every split-K
+ * candidate: the packed copies plus tg_workspace_bytes(1, m, n, k).  0 on invalid sizes.
+ */
+size_t tg_strided_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t csa, int64_t csb);
 
 /*
  * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>][:p<n>]", e.g.

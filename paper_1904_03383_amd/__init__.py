@@ -24,4 +24,5 @@ from .binding import (  # noqa: F401
     tune,
     version,
     workspace_bytes,
+    strided_workspace_bytes,
 )

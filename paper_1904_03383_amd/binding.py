@@ -27,6 +27,7 @@ SIGNATURES = {
     "tg_tune": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _int]),
     "tg_set_workspace": (_int, [_p, _sz]),
     "tg_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
+    "tg_strided_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64]),
     "tg_force_config": (_int, [_cstr]),
     "tg_get_config": (_int, [_i64, _i64, _i64, _i64, _p, _sz]),
     "tg_last_config": (_cstr, []),
@@ -227,6 +228,10 @@ def set_workspace(tensor):
 
 def workspace_bytes(batch: int, m: int, n: int, k: int) -> int:
     return int(load_library().tg_workspace_bytes(batch, m, n, k))
+
+
+def strided_workspace_bytes(m: int, n: int, k: int, csa: int, csb: int) -> int:
+    return int(load_library().tg_strided_workspace_bytes(m, n, k, csa, csb))
 
 
 def force_config(spec):

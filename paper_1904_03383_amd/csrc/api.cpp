@@ -207,6 +207,12 @@ void split_plan(const KernelInfo &ki, int64_t k, int want, int *splits, int *per
     *splits = (int)ceil_div(kt, pp);
 }
 
+// Packed copy of a rows x cols operand: rows padded to a multiple of 4 floats (16-byte rows).
+int64_t pack_ld(int64_t cols) { return (cols + 3) / 4 * 4; }
+size_t pack_bytes(int64_t rows, int64_t cols) { return (size_t)rows * (size_t)pack_ld(cols) * sizeof(float); }
+// An operand is packed when more than one 128-wide tile row/column would fetch it.
+constexpr int64_t kPackMinReuse = 128;
+
 size_t ws_need(const Problem &p, int splits) {
     return splits > 1 ? (size_t)p.batch * splits * p.m * p.n * sizeof(float) : 0;
 }
@@ -360,12 +366,12 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
 ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, p.aligned ? 1 : (p.unit() ? 0 : 2)); }
 
 // forced > tuned > heuristic.  Caller holds g_mutex.
-tg_status choose(const Problem &p, Config *out) {
+tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
     read_env_once();
     if (g_forced) {
         std::string why;
-        if (!config_valid(p, g_force_cfg, g_ws_bytes, &why)) {
-            const bool ws_issue = g_force_cfg.splits > 1 && ws_need(p, g_force_cfg.splits) > g_ws_bytes;
+        if (!config_valid(p, g_force_cfg, ws_bytes, &why)) {
+            const bool ws_issue = g_force_cfg.splits > 1 && ws_need(p, g_force_cfg.splits) > ws_bytes;
             return fail(ws_issue ? TG_ERR_WORKSPACE : TG_ERR_INVALID_ARG,
                         "forced configuration " + spec_of(g_force_cfg) + " is not valid here: " + why);
         }
@@ -373,11 +379,11 @@ tg_status choose(const Problem &p, Config *out) {
         return TG_OK;
     }
     auto it = g_cache.find(key_of(p));
-    if (it != g_cache.end() && config_valid(p, it->second.cfg, g_ws_bytes)) {
+    if (it != g_cache.end() && config_valid(p, it->second.cfg, ws_bytes)) {
         *out = it->second.cfg;
         return TG_OK;
     }
-    std::vector<Config> cands = candidates(p, g_ws_bytes);
+    std::vector<Config> cands = candidates(p, ws_bytes);
     if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
     *out = cands.front();
     return TG_OK;
@@ -457,16 +463,53 @@ tg_status run(Problem &p, void *stream) {
     if (st != TG_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (p.k == 0) { t_last_config = "zero_fill"; return zero_fill(p, s); }
-    Config c;
     void *ws;
+    size_t ws_bytes;
     {
         std::lock_guard<std::mutex> lk(g_mutex);
-        st = choose(p, &c);
         ws = g_ws;
+        ws_bytes = g_ws_bytes;
+    }
+    // Element-strided or transposed operands: when the workspace has room, gather each such
+    // operand once into a packed row-major copy and multiply that with the unit-stride kernels
+    // (a strided element costs a whole cache line per fetch; the tile kernels would fetch it once
+    // per tile column or row).  Without room the predicated kernels gather on the fly.
+    const char *packed = "";
+    if (!p.unit() && p.batch == 1) {
+        const bool want_a = p.csa != 1 && p.n > kPackMinReuse, want_b = p.csb != 1 && p.m > kPackMinReuse;
+        const size_t need_a = want_a ? pack_bytes(p.m, p.k) : 0, need_b = want_b ? pack_bytes(p.k, p.n) : 0;
+        if ((want_a || want_b) && need_a + need_b <= ws_bytes &&
+            ceil_div(p.m, 64) * ceil_div(p.k, 64) <= INT32_MAX && ceil_div(p.k, 64) * ceil_div(p.n, 64) <= INT32_MAX) {
+            char *w = static_cast<char *>(ws);
+            hipError_t e = hipSuccess;
+            if (want_a) {
+                const int64_t ld = pack_ld(p.k);
+                e = tg::launch_pack(p.A, p.lda, p.csa, reinterpret_cast<float *>(w), ld, (int)p.m, (int)p.k, s);
+                p.A = reinterpret_cast<const float *>(w); p.lda = ld; p.csa = 1;
+                w += need_a;
+            }
+            if (e == hipSuccess && want_b) {
+                const int64_t ld = pack_ld(p.n);
+                e = tg::launch_pack(p.B, p.ldb, p.csb, reinterpret_cast<float *>(w), ld, (int)p.k, (int)p.n, s);
+                p.B = reinterpret_cast<const float *>(w); p.ldb = ld; p.csb = 1;
+                w += need_b;
+            }
+            if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("pack launch failed: ") + hipGetErrorString(e));
+            ws = w;
+            ws_bytes -= need_a + need_b;
+            packed = want_a && want_b ? "+packAB" : (want_a ? "+packA" : "+packB");
+            st = validate(p);   // recompute the alignment class of the packed problem
+            if (st != TG_OK) return st;
+        }
+    }
+    Config c;
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        st = choose(p, ws_bytes, &c);
     }
     if (st != TG_OK) return st;
     st = launch(p, c, ws, s);
-    if (st == TG_OK) t_last_config = spec_of(c);
+    if (st == TG_OK) t_last_config = spec_of(c) + packed;
     return st;
 }
 
@@ -650,6 +693,15 @@ size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k) {
     return need;
 }
 
+size_t tg_strided_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t csa, int64_t csb) {
+    if (m <= 0 || n <= 0 || k <= 0 || csa < 1 || csb < 1) return 0;
+    if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX) return 0;
+    size_t need = tg_workspace_bytes(1, m, n, k);
+    if (csa != 1) need += pack_bytes(m, k);
+    if (csb != 1) need += pack_bytes(k, n);
+    return need;
+}
+
 tg_status tg_force_config(const char *spec) {
     std::lock_guard<std::mutex> lk(g_mutex);
     g_env_read = true;   // an explicit call overrides the environment
@@ -672,7 +724,7 @@ tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *bu
     tg_status st;
     {
         std::lock_guard<std::mutex> lk(g_mutex);
-        st = choose(p, &c);
+        st = choose(p, g_ws_bytes, &c);
     }
     if (st != TG_OK) return st;
     const std::string s = spec_of(c);

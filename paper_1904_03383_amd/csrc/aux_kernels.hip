@@ -166,4 +166,52 @@ hipError_t launch_saxpy(int64_t n, float alpha, const float *x, const float *y, 
     return hipGetLastError();
 }
 
+// dst[r * ld + c] = src[r * rs + c * cs] for a rows x cols matrix with arbitrary positive element
+// strides: the gather / transpose pass in front of the unit-stride kernels for the strided
+// product of Sec. 5.2.  One workgroup copies a 64 x 64 tile; all 16 loads of a thread are issued
+// before the first use so that a gather (every element in its own cache line) keeps
+// 4096 lines in flight per workgroup.  ALONG_ROWS: source lanes run down a column (the
+// source's unit-stride direction when rs < cs, e.g. a column-major operand) and the tile is
+// turned through LDS (row pitch 65 floats: conflict-free both ways) so that the writes still run
+// along a row of dst.
+template <bool ALONG_ROWS>
+__global__ void __launch_bounds__(256) pack_kernel(const float *__restrict__ src, int64_t rs, int64_t cs,
+                                                   float *__restrict__ dst, int64_t ld, int rows, int cols, int tiles_c) {
+    __shared__ float tile[ALONG_ROWS ? 64 : 1][65];
+    const int r0 = (int)(blockIdx.x / (unsigned)tiles_c) * 64;
+    const int c0 = (int)(blockIdx.x % (unsigned)tiles_c) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    float v[16];
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int slow = ty + 4 * it;
+        const int r = r0 + (ALONG_ROWS ? tx : slow);
+        const int c = c0 + (ALONG_ROWS ? slow : tx);
+        v[it] = (r < rows && c < cols) ? src[(int64_t)r * rs + (int64_t)c * cs] : 0.0f;
+    }
+    if constexpr (ALONG_ROWS) {
+#pragma unroll
+        for (int it = 0; it < 16; ++it) tile[tx][ty + 4 * it] = v[it];
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 16; ++it) v[it] = tile[ty + 4 * it][tx];
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int r = r0 + ty + 4 * it, c = c0 + tx;
+        if (r < rows && c < cols) dst[(int64_t)r * ld + c] = v[it];
+    }
+}
+
+hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int64_t ld, int rows, int cols, hipStream_t s) {
+    const int64_t tiles_r = ((int64_t)rows + 63) / 64, tiles_c = ((int64_t)cols + 63) / 64;
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    if (tiles_r * tiles_c > INT32_MAX) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(tiles_r * tiles_c));
+    if (rs < cs) hipLaunchKernelGGL(pack_kernel<true>, grid, dim3(256), 0, s, src, rs, cs, dst, ld, rows, cols, (int)tiles_c);
+    else hipLaunchKernelGGL(pack_kernel<false>, grid, dim3(256), 0, s, src, rs, cs, dst, ld, rows, cols, (int)tiles_c);
+    return hipGetLastError();
+}
+
 }  // namespace tg
+

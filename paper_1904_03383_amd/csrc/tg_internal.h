@@ -85,6 +85,9 @@ hipError_t launch_zero_fill(const GemmParams &p, hipStream_t s);
 // z = alpha * x + y over n contiguous floats (bandwidth-bound streaming kernel).
 hipError_t launch_saxpy(int64_t n, float alpha, const float *x, const float *y, float *z, hipStream_t s);
 
+// dst[r * ld + c] = src[r * rs + c * cs] (rows x cols): packs an element-strided or transposed operand.
+hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int64_t ld, int rows, int cols, hipStream_t s);
+
 constexpr int kLdsPerCU = 160 * 1024;  // gfx950
 constexpr int kLdsPadA = 4;  // floats added to each A row in LDS (conflict-free b128 reads)
 constexpr int kLdsPadB = 8;  // floats added to each B row in LDS

@@ -32,6 +32,8 @@ int main(void)
     CHECK(tg_set_workspace(NULL, 16) == TG_ERR_INVALID_ARG);
     CHECK(tg_set_workspace(NULL, 0) == TG_OK);
     CHECK(tg_workspace_bytes(1, 1024, 1024, 1024) > 0);
+    CHECK(tg_strided_workspace_bytes(1024, 1024, 1024, 32, 1) >= tg_workspace_bytes(1, 1024, 1024, 1024) + 4u * 1024 * 1024);
+    CHECK(tg_strided_workspace_bytes(1024, 1024, 1024, 0, 1) == 0);
     CHECK(tg_num_kernels() > 0);
     CHECK(tg_kernel_name(0, buf, sizeof buf) == TG_OK && strlen(buf) > 0);
     CHECK(tg_force_config("no_such_kernel") == TG_ERR_INVALID_ARG);

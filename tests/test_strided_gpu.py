@@ -119,3 +119,103 @@ def test_strided_through_each_predicated_kernel(forced):
     tg.force_config(forced)
     c = _run(to_dev(a_store)[:, ::4], to_dev(b_store).T, m, n)
     check_against_oracle(c, np.ascontiguousarray(a_store[:, ::4]), np.ascontiguousarray(b_store.T), exact=True, what=forced)
+
+
+# ---- packed path: with a workspace, strided operands are gathered once and the unit-stride kernels run ----
+
+def _with_workspace(m, n, k, csa, csb, extra=0):
+    import torch
+    nbytes = tg.strided_workspace_bytes(m, n, k, csa, csb) + extra
+    ws = torch.full((max(nbytes // 4, 4),), float("nan"), device="cuda")
+    tg.set_workspace(ws)
+    return ws
+
+
+def test_paper_strided_matmul_1024_packed():
+    """Sec. 5.2 strided matmul with a workspace: A is gathered once (+packA), then the fast kernels run."""
+    say("strided matmul 1024^3, A element stride 32, packed")
+    m = n = k = 1024
+    ws = _with_workspace(m, n, k, 32, 1)
+    for dist in ("uniform", "int"):
+        gen = ig.uniform if dist == "uniform" else ig.small_int
+        a_store = gen(651, (m, k * 32))
+        b = gen(652, (k, n))
+        c = _run(to_dev(a_store)[:, ::32], to_dev(b), m, n)
+        cfg = tg.last_config()
+        assert cfg.endswith("+packA") and "_edge" not in cfg, cfg
+        check_against_oracle(c, np.ascontiguousarray(a_store[:, ::32]), b, exact=(dist == "int"), what="packed strided 1024^3 " + dist)
+    del ws
+
+
+PACK_CASES = [
+    # (m, n, k, layout of A, layout of B, expected suffix)
+    (512, 384, 256, "T", "N", "+packA"),
+    (512, 384, 256, "N", "T", "+packB"),
+    (512, 384, 256, "T", "T", "+packAB"),
+    (300, 257, 131, "T", "T", "+packAB"),        # ragged: partial 64 x 64 pack tiles, k padded to 132
+    (200, 1000, 70, "s3", "N", "+packA"),
+    (1000, 200, 70, "N", "s5", "+packB"),
+    (1000, 100, 70, "s3", "s5", "+packB"),        # n <= 128: A is fetched by one tile column only, stays strided
+    (100, 100, 70, "s3", "s5", ""),               # nothing is re-fetched: no packing at all
+]
+
+
+def _operand(gen, seed, rows, cols, layout):
+    if layout == "T":
+        store = gen(seed, (cols, rows + 3))
+        return store[:, :rows].T, to_dev(store)[:, :rows].T
+    if layout.startswith("s"):
+        cs = int(layout[1:])
+        store = gen(seed, (rows, cols * cs + 1))
+        return store[:, :cols * cs:cs], to_dev(store)[:, :cols * cs:cs]
+    store = gen(seed, (rows, cols))
+    return store, to_dev(store)
+
+
+@pytest.mark.parametrize("case", PACK_CASES, ids=str)
+def test_packed_operands(case):
+    m, n, k, la, lb, suffix = case
+    say(f"packed {case}")
+    csa = 1 if la == "N" else 7
+    csb = 1 if lb == "N" else 7
+    ws = _with_workspace(m, n, k, csa, csb)
+    for dist in ("normal", "int"):
+        gen = ig.normal if dist == "normal" else ig.small_int
+        a_np, da = _operand(gen, 661, m, k, la)
+        b_np, db = _operand(gen, 662, k, n, lb)
+        c = _run(da, db, m, n)
+        cfg = tg.last_config()
+        if suffix:
+            assert cfg.endswith(suffix), cfg
+        else:
+            assert "+pack" not in cfg, cfg
+        check_against_oracle(c, np.ascontiguousarray(a_np), np.ascontiguousarray(b_np), exact=(dist == "int"), what=f"{case} {dist}")
+    del ws
+
+
+def test_packed_path_with_split_k_shares_the_workspace():
+    """Packed copies sit in front of the split-K partials; a forced split must still fit and be right."""
+    say("packed + split-K")
+    m, n, k = 256, 256, 1024
+    ws = _with_workspace(m, n, k, 1, 1, extra=4 * (m * k + 4 * m * n))
+    a_np, da = _operand(ig.small_int, 671, m, k, "T")
+    b = ig.small_int(672, (k, n))
+    tg.force_config("t128x128x16_w64x64:s4")
+    c = _run(da, to_dev(b), m, n)
+    assert tg.last_config().endswith("+packA") and ":s4" in tg.last_config()
+    check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=True, what="packed + split-K")
+    del ws
+
+
+def test_workspace_too_small_for_packing_falls_back_to_gather():
+    import torch
+    say("strided with a workspace too small to pack")
+    m, n, k = 256, 256, 128
+    ws = torch.empty((1024,), device="cuda")
+    tg.set_workspace(ws)
+    a_np, da = _operand(ig.small_int, 681, m, k, "T")
+    b = ig.small_int(682, (k, n))
+    c = _run(da, to_dev(b), m, n)
+    assert "+pack" not in tg.last_config() and "_edge" in tg.last_config()
+    check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=True, what="no room to pack")
+    del ws
