@@ -273,12 +273,14 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
         blocks = ceil_div(ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch, 4);
     } else {
         split_plan(ki, p.k, c.splits, &splits, &per);
-        wave_flops = 2.0 * ki.WM * ki.WN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
+        // variants with several wave groups along K give every wave only its share of the K range
+        const int kgroups = std::max(1, ki.threads / ((ki.BM / ki.WM) * (ki.BN / ki.WN) * 64));
+        wave_flops = 2.0 * ki.WM * ki.WN * std::min<int64_t>((int64_t)per * ki.BK, p.k) / kgroups;
         blocks = ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * splits * p.batch;
     }
     t = std::max(t, wave_flops / kSimdFlops);
     // workgroups are spread over at most kNumCUs CUs; each CU has 4 SIMDs
-    const double rounds = (double)ceil_div(blocks * std::min(waves_per_block, 4), (int64_t)kNumCUs * 4);
+    const double rounds = (double)ceil_div(blocks * waves_per_block, (int64_t)kNumCUs * 4);
     t = std::max(t, rounds * wave_flops / kSimdFlops);
     double bytes = 4.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n + (double)p.m * p.n);
     if (splits > 1) bytes += 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n;

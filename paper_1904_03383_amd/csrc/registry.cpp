@@ -42,23 +42,25 @@ extern template hipError_t launch_tile_stream<128, 128, 16, 64, 64, false>(const
 extern template hipError_t launch_tile_stream<128, 128, 32, 64, 64, false>(const GemmParams &, hipStream_t);
 extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(const GemmParams &, hipStream_t);
 
-// direct-to-LDS variants: (BM, BN, BK, WM, WN, two_level, LDS stages, name)
+// direct-to-LDS variants: (BM, BN, BK, WM, WN, two_level, LDS stages, wave groups along K, name)
 #define TG_DIRECT_LIST(X)                                                   \
-    X(128, 128, 32, 64, 64, false, 2, "d128x128x32_w64x64")                 \
-    X(128, 128, 32, 64, 64, true, 2, "d128x128x32_w64x64_acc2")             \
-    X(128, 256, 32, 64, 128, false, 2, "d128x256x32_w64x128")               \
-    X(128, 256, 32, 64, 128, true, 2, "d128x256x32_w64x128_acc2")           \
-    X(256, 128, 32, 128, 64, false, 2, "d256x128x32_w128x64")               \
-    X(256, 128, 32, 128, 64, true, 2, "d256x128x32_w128x64_acc2")           \
-    X(128, 256, 32, 64, 128, true, 3, "d128x256x32_w64x128_acc2_st3")       \
-    X(256, 128, 32, 128, 64, true, 3, "d256x128x32_w128x64_acc2_st3")       \
-    X(64, 64, 32, 32, 32, false, 2, "d64x64x32_w32x32")                     \
-    X(64, 64, 32, 32, 32, false, 4, "d64x64x32_w32x32_st4")
-#define TG_DDECL(BM, BN, BK, WM, WN, L2, NS, NAME) \
-    extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2, NS>(const GemmParams &, hipStream_t);
-#define TG_DROW(BM, BN, BK, WM, WN, L2, NS, NAME)                                               \
-    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, (BM / WM) * (BN / WN) * 64,         \
-     NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS>},
+    X(128, 128, 32, 64, 64, false, 2, 1, "d128x128x32_w64x64")                 \
+    X(128, 128, 32, 64, 64, true, 2, 1, "d128x128x32_w64x64_acc2")             \
+    X(128, 256, 32, 64, 128, false, 2, 1, "d128x256x32_w64x128")               \
+    X(128, 256, 32, 64, 128, true, 2, 1, "d128x256x32_w64x128_acc2")           \
+    X(256, 128, 32, 128, 64, false, 2, 1, "d256x128x32_w128x64")               \
+    X(256, 128, 32, 128, 64, true, 2, 1, "d256x128x32_w128x64_acc2")           \
+    X(128, 256, 32, 64, 128, true, 3, 1, "d128x256x32_w64x128_acc2_st3")       \
+    X(256, 128, 32, 128, 64, true, 3, 1, "d256x128x32_w128x64_acc2_st3")       \
+    X(64, 64, 32, 32, 32, false, 2, 1, "d64x64x32_w32x32")                     \
+    X(64, 64, 32, 32, 32, false, 4, 1, "d64x64x32_w32x32_st4")                  \
+    X(64, 64, 32, 32, 32, false, 2, 2, "d64x64x32_w32x32_k2")                   \
+    X(64, 64, 32, 32, 32, false, 4, 2, "d64x64x32_w32x32_k2_st4")
+#define TG_DDECL(BM, BN, BK, WM, WN, L2, NS, KG, NAME) \
+    extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, KG>(const GemmParams &, hipStream_t);
+#define TG_DROW(BM, BN, BK, WM, WN, L2, NS, KG, NAME)                                           \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, (BM / WM) * (BN / WN) * 64 * KG,    \
+     NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, KG>},
 TG_DIRECT_LIST(TG_DDECL)
 
 static const KernelInfo kTable[] = {

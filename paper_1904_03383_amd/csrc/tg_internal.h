@@ -69,8 +69,9 @@ hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();
 
-// Same, with operand tiles loaded global -> LDS directly into a ring of NS stages (exact-fit shapes, BK = 32).
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS>
+// Same, with operand tiles loaded global -> LDS directly into a ring of NS stages (exact-fit shapes, BK = 32);
+// KG wave groups share each wave tile, every group taking 1/KG of each K tile.
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s);
 
 // One wave per 32x32 C tile, operands straight from global memory (small / batched problems).

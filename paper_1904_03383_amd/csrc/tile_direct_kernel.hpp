@@ -16,6 +16,12 @@
 //    are issued right after the barrier that frees their stage, between the MFMAs of the
 //    first octet, and are waited for (vmcnt) just before the barrier that hands over their
 //    stage.  NS LDS stages form a ring, so a tile may be NS-1 K tiles in flight.
+//  * KG > 1 puts KG waves on every wave tile: wave group g multiplies octets
+//    [g*NO/KG, (g+1)*NO/KG) of every K tile, and the groups' accumulators are summed through
+//    LDS in a fixed order at the end.  A 64x64 workgroup tile (the largest that still gives
+//    1024^3 one workgroup per CU) then runs two waves per SIMD.  Measured at 1024^3 it only
+//    matches the one-group kernel (21.6 us against 21.9 us): the waits it could cover are not
+//    what limits that shape.
 #pragma once
 
 #include "tile_kernel.hpp"
@@ -59,16 +65,19 @@ constexpr int direct_min_waves() {
             __builtin_amdgcn_global_load_lds((glb_float *)(Bg + b_off[i_]), (lds_float *)(smem + (b_stage) + (i_ * NWAVES + wave) * 256), 16, 0, 0); \
     } while (0)
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS>
-__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (direct_min_waves<BM, BN, BK, WM, WN, TWO_LEVEL>()))
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG, (KG > 1 ? 2 : direct_min_waves<BM, BN, BK, WM, WN, TWO_LEVEL>()))
 sgemm_tile_direct_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
-    constexpr int NWAVES = (BM / WM) * (BN / WN);
+    constexpr int TILE_WAVES = (BM / WM) * (BN / WN);       // waves that cover the output tile once
+    constexpr int NWAVES = TILE_WAVES * KG;
     constexpr int NT = NWAVES * 64;
     constexpr int RB = WM / 32, CB = WN / 32;
     constexpr int A_STAGE = BM * BK, B_STAGE = BK * BN;      // floats, unpadded
     constexpr int A_LD = BM * BK / 4 / NT, B_LD = BK * BN / 4 / NT;
-    constexpr int NO = BK / 8;
+    constexpr int NO = BK / 8 / KG;                         // octets of a K tile per wave
+    static_assert(KG == 1 || KG == 2, "one or two wave groups along K");
+    static_assert(KG == 1 || (KG - 1) * BM * BN <= NS * (BM * BK + BK * BN), "the group sum reuses the stage area");
     static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
     static_assert(BK == 32, "BK must be 32");
@@ -87,7 +96,9 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, h = lane >> 5;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int kg = wave / TILE_WAVES, tw = wave % TILE_WAVES;   // K group, wave inside the tile
+    const int wm = tw / WAVES_N, wn = tw % WAVES_N;
+    const int o_base = kg * NO;
 
     // One workgroup per work item (tile x slice).
     const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
@@ -142,8 +153,8 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     bvec b_frag[2][4];
 
     auto read_frags = [&](int stage, int o, int set) {
-        const float *as = As + stage * A_STAGE + a_row * BK + (((2 * o + h) ^ a_swz) * 4);
-        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * BN;
+        const float *as = As + stage * A_STAGE + a_row * BK + (((2 * (o_base + o) + h) ^ a_swz) * 4);
+        const float *bs = Bs + stage * B_STAGE + b_frag_off + (o_base + o) * 8 * BN;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
             a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
@@ -267,6 +278,36 @@ sgemm_tile_direct_kernel(const GemmParams p) {
             for (int cb = 0; cb < CB; ++cb) acc[rb][cb] += total[rb][cb];
     }
 
+    // Sum over the K groups: groups 1.. park their accumulators in LDS (the stage area, once
+    // every load still in flight has landed and every wave has left the K loop), group 0 adds
+    // them in group order and stores.
+    if constexpr (KG > 1) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        constexpr int PER_WAVE = RB * CB * 16 * 64;
+        if (kg > 0) {
+            float *dst = smem + ((kg - 1) * TILE_WAVES + tw) * PER_WAVE + lane;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) dst[((rb * CB + cb) * 16 + v) * 64] = acc[rb][cb][v];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 1; g < KG; ++g) {
+            const float *src = smem + ((g - 1) * TILE_WAVES + tw) * PER_WAVE + lane;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[rb][cb][v] += src[((rb * CB + cb) * 16 + v) * 64];
+        }
+    }
+
     // Epilogue: registers -> C (or the split-K partial).
     float *out;
     int64_t ldo;
@@ -296,12 +337,12 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s) {
-    constexpr int threads = (BM / WM) * (BN / WN) * 64;
+    constexpr int threads = (BM / WM) * (BN / WN) * 64 * KG;
     constexpr int lds_used = direct_lds_bytes<BM, BN, BK, NS>();
     static_assert(lds_used <= kLdsPerCU, "stages exceed the LDS of a CU");
-    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, NS>;
+    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, NS, KG>;
     int lds = lds_used;
     if (p.max_blocks_per_cu > 0) {
         const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;

@@ -126,6 +126,11 @@ def test_workspace_arguments(lib):
     assert tg.workspace_bytes(1, 1024, 1024, 1024) >= 2 * 1024 * 1024 * 4
     assert tg.workspace_bytes(1, 0, 8, 8) == 0 and tg.workspace_bytes(1, -1, 8, 8) == 0
     assert tg.workspace_bytes(1, 4096, 4096, 4096) == 0      # enough tiles: no split-K candidate
+    # packed copies of the strided operands (rows padded to 4 floats) on top of the split-K need
+    assert tg.strided_workspace_bytes(4096, 4096, 4096, 2, 1) == 4096 * 4096 * 4
+    assert tg.strided_workspace_bytes(4096, 4096, 4096, 2, 3) == 2 * 4096 * 4096 * 4
+    assert tg.strided_workspace_bytes(10, 4096, 7, 5, 1) == tg.workspace_bytes(1, 10, 4096, 7) + 10 * 8 * 4
+    assert tg.strided_workspace_bytes(8, 8, 8, 0, 1) == 0 and tg.strided_workspace_bytes(8, 0, 8, 1, 1) == 0
 
 
 def test_force_config_grammar_and_get_config(lib):
