@@ -62,6 +62,7 @@ struct TunedEntry {
 
 std::mutex g_mutex;
 std::map<ShapeKey, TunedEntry> g_cache;
+std::map<std::pair<ShapeKey, size_t>, Config> g_heuristic_choice;   // memo of the static heuristic
 void *g_ws = nullptr;
 size_t g_ws_bytes = 0;
 bool g_forced = false;
@@ -385,9 +386,19 @@ tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
         *out = it->second.cfg;
         return TG_OK;
     }
+    // Ranking the candidates costs some 10 us; the outcome depends only on the shape class and on
+    // the workspace size, so it is kept (a call must not spend longer choosing than launching).
+    const auto hkey = std::make_pair(key_of(p), ws_bytes);
+    auto hit = g_heuristic_choice.find(hkey);
+    if (hit != g_heuristic_choice.end() && config_valid(p, hit->second, ws_bytes)) {
+        *out = hit->second;
+        return TG_OK;
+    }
     std::vector<Config> cands = candidates(p, ws_bytes);
     if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
     *out = cands.front();
+    if (g_heuristic_choice.size() >= 4096) g_heuristic_choice.clear();
+    g_heuristic_choice[hkey] = *out;
     return TG_OK;
 }
 
