@@ -618,6 +618,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
     Config best;
     double best_us = 1e300;
     std::string last_err;
+    std::vector<std::pair<double, Config>> seen;   // every configuration measured, for the final round
     const bool log = getenv("TG_LOG") != nullptr;
     for (const Config &c : cands) {
         const double lb_us = 1e6 * lower_bound_seconds(p, c);
@@ -633,6 +634,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             continue;
         }
         if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us (bound %.1f)\n", spec_of(c).c_str(), us, lb_us);
+        seen.emplace_back(us, c);
         if (us < best_us) { best_us = us; best = c; }
     }
     if (best.kernel >= 0 && tg::kernel(best.kernel).kind == tg::KIND_TILE) {
@@ -647,6 +649,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             double us = 0;
             if (time_config(c, &us) != TG_OK) continue;
             if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+            seen.emplace_back(us, c);
             if (us < best_us) { best_us = us; best = c; }
         }
     }
@@ -659,6 +662,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             double us = 0;
             if (time_config(c, &us) != TG_OK) continue;
             if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+            seen.emplace_back(us, c);
             if (us < best_us * 0.995) { best_us = us; best = c; }
         }
         // ... and, for a persistent variant, the number of workgroups per CU
@@ -669,7 +673,43 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
             double us = 0;
             if (time_config(c, &us) != TG_OK) continue;
             if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+            seen.emplace_back(us, c);
             if (us < best_us * 0.995) { best_us = us; best = c; }
+        }
+    }
+    if (best.kernel >= 0) {
+        // Final round: the leaders are often within the noise of the short timings above (1 % at
+        // 4096^3), so the three fastest kernel variants within 2 % of the best are timed again, alternating, with
+        // longer runs (>= 10 launches and >= 2 ms each); the best of two such runs decides.
+        std::stable_sort(seen.begin(), seen.end(), [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
+        std::vector<Config> finalists{best};
+        for (const auto &sc : seen) {
+            if (finalists.size() >= 3 || sc.first > best_us * 1.02) break;
+            bool dup = false;   // one entry per kernel variant: its fastest setting so far
+            for (const Config &f : finalists) dup = dup || f.kernel == sc.second.kernel;
+            if (!dup) finalists.push_back(sc.second);
+        }
+        if (finalists.size() > 1) {
+            std::vector<double> fin(finalists.size(), 1e300);
+            for (int pass = 0; pass < 2; ++pass)
+                for (size_t i = 0; i < finalists.size(); ++i) {
+                    const int n = std::min<int>(256, std::max<int>(10, (int)(2000.0 / std::max(best_us, 1.0)) + 1));
+                    tg_status r = TG_OK;
+                    hipEventRecord(ev0, s);
+                    for (int j = 0; j < n && r == TG_OK; ++j) r = launch(p, finalists[i], ws, s);
+                    hipEventRecord(ev1, s);
+                    if (hipEventSynchronize(ev1) != hipSuccess || r != TG_OK) { (void)hipGetLastError(); continue; }
+                    float ms = 0.f;
+                    hipEventElapsedTime(&ms, ev0, ev1);
+                    fin[i] = std::min(fin[i], 1e3 * ms / n);
+                }
+            size_t w = 0;
+            for (size_t i = 1; i < finalists.size(); ++i)
+                if (fin[i] < fin[w]) w = i;
+            if (fin[w] < 1e300) { best = finalists[w]; best_us = fin[w]; }
+            if (log)
+                for (size_t i = 0; i < finalists.size(); ++i)
+                    fprintf(stderr, "tgemm tune: final %-38s %.2f us%s\n", spec_of(finalists[i]).c_str(), fin[i], i == w ? "  <- chosen" : "");
         }
     }
     hipEventDestroy(ev0);
