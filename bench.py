@@ -210,6 +210,24 @@ def time_strided(tg, torch, steps, warmup, restore_ws):
                              "device_tflops": flops / (gather_ms * 1e-3) / 1e12}}
 
 
+def device_info(torch):
+    """Name, CU count and clocks of the GPU; the current shader clock is read from rocm-smi right after the
+    timed region (a child process; best effort)."""
+    import re
+    import subprocess
+    prop = torch.cuda.get_device_properties(0)
+    info = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
+            "max_clock_mhz": getattr(prop, "clock_rate", 0) / 1e3}
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
+        mm = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", r.stdout)
+        if mm:
+            info["sclk_mhz_after_run"] = int(mm.group(1))
+    except Exception:  # noqa: BLE001 - informational only
+        pass
+    return info
+
+
 def parity_on_rows(a, b, out, rows):
     """Compare sampled rows of the device result with the oracle (element-wise and Frobenius)."""
     from oracle import oracle
@@ -283,7 +301,9 @@ def main():
 
     log(f"headline workload {args.workload}")
     head, (a, b, out) = time_workload(tg, torch, args.workload, args.steps, args.warmup, args.tune_reps)
+    dev = device_info(torch)
     log(f"  {head['tile_config']}  {head['device_ms_per_step'] * 1e3:.1f} us  {head['device_tflops']:.1f} TFLOP/s")
+    log(f"  device: {dev}")
 
     rows = sorted(set(int(r) for r in np.linspace(0, head["m"] - 1, num=min(head["m"], 128))))
     par = parity_on_rows(a, b, out, rows)
@@ -361,6 +381,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": base,
         "parity": {"rows_checked": len(rows), "max_ratio": par["max_ratio"], "rel_fro": par["rel_fro"], "ok": parity_ok},
+        "device": dev,
         "workloads": [head] + others,
     }
     print(json.dumps(line), flush=True)

@@ -238,7 +238,11 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
     if (!ki.edge) {
         if (!p.aligned) return no("operands are not 16-byte aligned");
-        if (p.m % ki.BM || p.n % ki.BN || p.k % ki.BK) return no("sizes are not multiples of the tile");
+        // K must fill whole tiles; ragged m and n are handled by re-reading the last row / vector
+        // and masking the stores (the persistent variants walk exact tiles only)
+        if (p.k % ki.BK) return no("k is not a multiple of the K tile");
+        if (p.n % 4) return no("n is not a multiple of 4");
+        if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
         // the fast variants address inside a tile with 32-bit element offsets
         if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
             return no("leading dimension too large for the exact-fit kernels");
@@ -317,6 +321,9 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? 1.01 : 0.97;
     if (ki.persistent) eff *= p.k <= 256 ? 1.0 : 0.95;
     if (!p.unit()) eff *= 0.5;
+    // a tile of which at most a quarter is real output (tiny problems of a batch): the waves
+    // that hold only padding still take their share of the loads, the barrier and the MFMA pipe
+    if (p.m * 2 <= ki.BM && p.n * 2 <= ki.BN) eff *= 0.8;
     const double block_flops = 2.0 * ki.BM * ki.BN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
     double t = launch + per_cu * block_flops / cu_rate;

@@ -69,7 +69,7 @@ hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();
 
-// Same, with operand tiles loaded global -> LDS directly into a ring of NS stages (exact-fit shapes, BK = 32);
+// Same, with operand tiles loaded global -> LDS directly into a ring of NS stages (aligned operands, k % 32 == 0, n % 4 == 0);
 // KG wave groups share each wave tile, every group taking 1/KG of each K tile.
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s);

@@ -1,7 +1,7 @@
 // Workgroup-tile SGEMM kernel for gfx950 whose operand tiles travel global -> LDS directly
 // (global_load_lds_dwordx4), without passing through registers.  Same decomposition as
 // tile_kernel.hpp (matmul of Sec. 5.2 of the paper; BLOCK / THREAD / UNROLL / VECTOR
-// mapping and SHARED staging of Sec. 4); exact-fit shapes only.
+// mapping and SHARED staging of Sec. 4); aligned operands, k a multiple of BK, n of 4.
 //
 // What differs from the register-staged kernel:
 //  * A direct load writes the 64 lanes' 16-byte pieces to 1 KB of consecutive LDS, so rows
@@ -124,12 +124,17 @@ sgemm_tile_direct_kernel(const GemmParams p) {
         const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
         const int row = pos / BK;
         const int q = (pos % BK) / 4;                          // chunk position inside the row
-        a_off[i] = (unsigned)row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+        // ragged last tile row: LDS rows past the end of A are filled from its last row (in bounds;
+        // what they produce is never stored)
+        const int src_row = row < p.m - 1 - m0 ? row : p.m - 1 - m0;
+        a_off[i] = (unsigned)src_row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
         const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
-        b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)(pos % BN);
+        // ragged last tile column: vectors past the end of B re-read its last one (n % 4 == 0)
+        const int c = pos % BN < p.n - 4 - n0 ? pos % BN : p.n - 4 - n0;
+        b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c;
     }
     const int64_t b_step = (int64_t)BK * p.ldb;
 
@@ -319,6 +324,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
         ldo = p.ldc;
     }
     const int col = n0 + wn * WN + li * CB;
+    const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;      // workgroup-uniform
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -332,7 +338,8 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
             }
-            *reinterpret_cast<bvec *>(dst) = o;
+            // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
+            if (full_tile || (row < p.m && col < p.n)) *reinterpret_cast<bvec *>(dst) = o;
         }
     }
 }

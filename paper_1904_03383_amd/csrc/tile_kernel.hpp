@@ -156,14 +156,19 @@ sgemm_tile_kernel(const GemmParams p) {
             const int f = tid + i * NT;
             a_row[i] = f / (BK / 4);
             a_k[i] = (f % (BK / 4)) * 4;
-            a_off[i] = (off_t)a_row[i] * (off_t)p.lda + (off_t)a_k[i] * (off_t)csa;
+            // exact-fit variants on a ragged last tile row: rows past the end re-read the last row
+            // (in bounds; what they produce is never stored)
+            const int r = EDGE ? a_row[i] : (a_row[i] < p.m - 1 - m0 ? a_row[i] : p.m - 1 - m0);
+            a_off[i] = (off_t)r * (off_t)p.lda + (off_t)a_k[i] * (off_t)csa;
         }
     #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             const int f = tid + i * NT;
             b_row[i] = f / (BN / 4);
             b_col[i] = (f % (BN / 4)) * 4;
-            b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)b_col[i] * (off_t)csb;
+            // ... and on a ragged last tile column, vectors past the end re-read the last one (n % 4 == 0)
+            const int c = EDGE ? b_col[i] : (b_col[i] < p.n - 4 - n0 ? b_col[i] : p.n - 4 - n0);
+            b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)c * (off_t)csb;
         }
 
         f32x4 a_reg[A_LD], b_reg[B_LD];
@@ -411,7 +416,8 @@ sgemm_tile_kernel(const GemmParams p) {
     #pragma unroll
                         for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
                     }
-                    *reinterpret_cast<bvec *>(dst) = o;
+                    // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
+                    if ((full_m && full_n) || (row < p.m && col < p.n)) *reinterpret_cast<bvec *>(dst) = o;
                 } else if (full_m && full_n && vec_c) {
                     // interior tile, rows of the destination aligned for CB-float stores
                     bvec o;

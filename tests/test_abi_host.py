@@ -146,7 +146,10 @@ def test_force_config_grammar_and_get_config(lib):
         assert tg.get_config(1, 1024, 1024, 1024) == "t128x128x16_w64x64:s1:g4"
         # forced but not valid for the shape: reported, not silently replaced
         with pytest.raises(tg.TgemmError, match="not valid here"):
-            tg.get_config(1, 1000, 1024, 1024)
+            tg.get_config(1, 1024, 1024, 1000)           # k must fill whole K tiles
+        with pytest.raises(tg.TgemmError, match="not valid here"):
+            tg.get_config(1, 1024, 1022, 1024)           # n must be a multiple of 4
+        assert tg.get_config(1, 1000, 1000, 1024) == "t128x128x16_w64x64:s1:g4"   # ragged m and n are fine
         with pytest.raises(tg.TgemmError, match="single accumulator"):
             tg.get_config(1, 4096, 4096, 4096)
         tg.force_config("t128x128x16_w64x64:s4")
@@ -159,7 +162,14 @@ def test_force_config_grammar_and_get_config(lib):
     assert tg.get_config(1, 4096, 4096, 4096).split(":")[0].endswith("_acc2")       # long K: two levels
     assert "acc2" not in tg.get_config(1, 4096, 4096, 128)
     assert tg.get_config(512, 32, 32, 64).startswith("wave32")
-    assert "_edge" in tg.get_config(1, 1000, 1000, 1000) or tg.get_config(1, 1000, 1000, 1000).startswith("wave32")
+    assert "_edge" in tg.get_config(1, 1000, 1000, 1001) or tg.get_config(1, 1000, 1000, 1001).startswith("wave32")
+    assert "_edge" not in tg.get_config(1, 1000, 1000, 1024)      # ragged m, n with k % 32 == 0: exact-fit kernels
+    tg.force_config("p128x128x16_w64x64:p2")
+    try:
+        with pytest.raises(tg.TgemmError, match="not valid here"):
+            tg.get_config(1, 1000, 1024, 1024)           # the persistent variants walk whole tiles only
+    finally:
+        tg.force_config(None)
     buf = ctypes.create_string_buffer(4)
     assert lib.tg_get_config(1, 64, 64, 64, ctypes.cast(buf, ctypes.c_void_p), 4) == 1
     assert lib.tg_get_config(1, 0, 64, 64, ctypes.cast(buf, ctypes.c_void_p), 4) == 1

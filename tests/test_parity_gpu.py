@@ -145,6 +145,60 @@ def test_ragged_through_each_predicated_kernel(forced):
     check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what=str(forced))
 
 
+# Ragged m and n on the exact-fit kernels (k a multiple of the K tile, n of 4): the last tile row / column
+# re-reads the last row / vector of the operand and masks its stores.
+RAGGED_FAST = [
+    ("t128x128x16_w64x64", (1000, 1000, 1024)), ("t128x128x16_w64x64", (129, 4, 48)), ("t128x128x16_w64x64", (1, 260, 64)),
+    ("t128x128x32_w64x64_acc2", (130, 132, 2080)), ("t256x128x32_w128x64", (257, 136, 96)), ("t128x256x16_w64x128", (100, 516, 64)),
+    ("t64x64x32_w32x32", (65, 68, 96)), ("t128x64x32_w64x32", (200, 100, 64)), ("t64x128x32_w32x64", (70, 200, 64)),
+    ("d128x128x32_w64x64", (1000, 1000, 1024)), ("d128x256x32_w64x128_acc2", (300, 260, 2112)), ("d256x128x32_w128x64", (258, 132, 64)),
+    ("d128x256x32_w64x128_acc2_st3", (129, 257 * 4, 1056)), ("d64x64x32_w32x32", (1, 4, 32)), ("d64x64x32_w32x32_st4", (67, 72, 160)),
+    ("d64x64x32_w32x32_k2", (130, 68, 96)), ("d64x64x32_w32x32_k2_st4", (63, 60, 256)),
+    ("t128x128x16_w64x64:s3", (200, 136, 1024)), ("d128x128x32_w64x64:s2", (130, 260, 512)),
+]
+
+
+@pytest.mark.parametrize("spec,shape", RAGGED_FAST, ids=lambda v: v if isinstance(v, str) else "x".join(map(str, v)))
+def test_ragged_m_n_on_exact_fit_kernels(spec, shape):
+    import torch
+    m, n, k = shape
+    say(f"ragged fast {spec} {m}x{n}x{k}")
+    if ":s" in spec:
+        ws = torch.empty(4 * m * n + 4, device="cuda")
+        tg.set_workspace(ws)
+    tg.force_config(spec)
+    for dist in ("normal", "int"):
+        a, b = ig.make_operands(1, m, n, k, dist, 341, 342)
+        c = run_hip(a[0], b[0])
+        assert tg.last_config().startswith(spec)
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"{spec} {shape} {dist}")
+
+
+def test_ragged_fast_path_leaves_padding_and_neighbours_alone():
+    """Output rows past m and columns past n (inside ldc, and the memory after the last row) stay untouched."""
+    import torch
+    say("ragged fast path: no stray stores")
+    m, n, k, ldc = 130, 132, 64, 140
+    a, b = ig.make_operands(1, m, n, k, "int", 351, 352)
+    buf = torch.full((m + 3, ldc), 7.0, device="cuda")
+    for spec in ("t128x128x16_w64x64", "d128x128x32_w64x64", "d64x64x32_w32x32_k2", None):
+        tg.force_config(spec)
+        buf.fill_(7.0)
+        tg.sgemm(to_dev(a[0]), to_dev(b[0]), out=buf[:m, :n])
+        torch.cuda.synchronize()
+        host = buf.cpu().numpy()
+        assert np.all(host[:m, n:] == 7.0) and np.all(host[m:, :] == 7.0), spec
+        check_against_oracle(np.ascontiguousarray(host[:m, :n]), a[0], b[0], exact=True, what=f"no stray stores {spec}")
+
+
+def test_ragged_batched_on_exact_fit_kernels():
+    say("ragged batched fast path")
+    a, b = ig.make_operands(5, 70, 36, 64, "int", 361, 362)
+    for spec in ("t64x64x32_w32x32", "d64x64x32_w32x32", None):
+        tg.force_config(spec)
+        check_against_oracle(run_hip(a, b), a, b, exact=True, what=f"batched ragged {spec}")
+
+
 @pytest.mark.parametrize("pads", [(0, 0, 0), (4, 8, 12), (1, 3, 5)], ids=str)
 @pytest.mark.parametrize("shape", [(256, 256, 64), (130, 70, 50)], ids=str)
 def test_leading_dimensions_and_untouched_padding(shape, pads):
