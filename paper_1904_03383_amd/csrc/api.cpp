@@ -240,7 +240,9 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         if (!p.aligned) return no("operands are not 16-byte aligned");
         // K must fill whole tiles; ragged m and n are handled by re-reading the last row / vector
         // and masking the stores (the persistent variants walk exact tiles only)
-        if (p.k % ki.BK) return no("k is not a multiple of the K tile");
+        if (p.k % ki.BK && !(ki.k_tail && p.k % 4 == 0 && p.k >= ki.BK))
+            return no(ki.k_tail ? "k is neither a multiple of the K tile nor (a multiple of 4 and at least one K tile)"
+                                : "k is not a multiple of the K tile");
         if (p.n % 4) return no("n is not a multiple of 4");
         if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
         // the fast variants address inside a tile with 32-bit element offsets

@@ -7,10 +7,10 @@ namespace tg {
 #define TG_DECL(BM, BN, BK, WM, WN, L2, EDGE) \
     extern template hipError_t launch_tile<BM, BN, BK, WM, WN, L2, EDGE>(const GemmParams &, hipStream_t);
 #define TG_ROW(BM, BN, BK, WM, WN, L2, EDGE, NAME)                                              \
-    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, EDGE, false, (BM / WM) * (BN / WN) * 64,          \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, EDGE, false, !EDGE, (BM / WM) * (BN / WN) * 64,  \
      tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE>},
 #define TG_PROW(BM, BN, BK, WM, WN, NAME)                                                       \
-    {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, true, (BM / WM) * (BN / WN) * 64,       \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, true, false, (BM / WM) * (BN / WN) * 64, \
      tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile_stream<BM, BN, BK, WM, WN, false>},
 
 // (BM, BN, BK, WM, WN, two_level, edge, name)
@@ -59,7 +59,7 @@ extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(cons
 #define TG_DDECL(BM, BN, BK, WM, WN, L2, NS, KG, NAME) \
     extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, KG>(const GemmParams &, hipStream_t);
 #define TG_DROW(BM, BN, BK, WM, WN, L2, NS, KG, NAME)                                           \
-    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, (BM / WM) * (BN / WN) * 64 * KG,    \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, false, (BM / WM) * (BN / WN) * 64 * KG, \
      NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, KG>},
 TG_DIRECT_LIST(TG_DDECL)
 
@@ -69,7 +69,7 @@ static const KernelInfo kTable[] = {
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")
     TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
     TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")
-    {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, 256, 0, &launch_wave32},
+    {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, false, 256, 0, &launch_wave32},
 };
 
 int num_kernels() { return (int)(sizeof(kTable) / sizeof(kTable[0])); }

@@ -49,6 +49,7 @@ struct KernelInfo {
     bool two_level;      // has second-level accumulators (needed for long K)
     bool edge;           // predicated variant: any m, n, k, leading dimension and alignment
     bool persistent;     // workgroups loop over tiles (launch with a fixed number of workgroups per CU)
+    bool k_tail;         // exact-fit variant that also takes k % BK != 0 (k % 4 == 0, k >= BK)
     int threads;
     int lds_bytes;
     launch_fn launch;

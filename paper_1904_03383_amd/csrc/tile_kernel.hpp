@@ -144,8 +144,14 @@ sgemm_tile_kernel(const GemmParams p) {
         // checks that a tile spans fewer than 2^31 elements), predicated ones 64-bit.
         // (csa, csb: element strides along k of A / along n of B, honoured by the predicated variants)
         const int64_t csa = EDGE ? p.csa : 1, csb = EDGE ? p.csb : 1;
-        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK * csa;
-        const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + (int64_t)n0 * csb;
+        // Exact-fit variants with k not a multiple of BK: the k % BK leftover elements form K tile 0,
+        // zero-padded on its way through the staging registers in the prologue; every later tile is
+        // a full one that starts `tail` elements further on, so the K loop itself never tests k.
+        // (k % 4 == 0 keeps the 16-byte alignment of the rows of A.)
+        const int tail = EDGE ? 0 : p.k % BK;
+        const int64_t k_begin = EDGE || tail == 0 || kt_begin == 0 ? (int64_t)kt_begin * BK : (int64_t)(kt_begin - 1) * BK + tail;
+        const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + k_begin * csa;
+        const float *Bg = p.B + (int64_t)prob * p.strideB + k_begin * p.ldb + (int64_t)n0 * csb;
         typedef typename std::conditional<EDGE, int64_t, unsigned>::type off_t;
 
         // Per-thread slots of the tile loads: slot f = tid + i*NT is one 16-byte vector.
@@ -233,6 +239,20 @@ sgemm_tile_kernel(const GemmParams p) {
             if (advance) {
                 Ag += BK * csa;
                 Bg += (int64_t)BK * p.ldb;
+            }
+        };
+
+        // K tile 0 of a k that leaves a remainder: only its first `tail` columns of A / rows of B exist.
+        auto load_global_tail = [&](bool advance) {
+    #pragma unroll
+            for (int i = 0; i < A_LD; ++i)
+                a_reg[i] = a_k[i] < tail ? *reinterpret_cast<const f32x4 *>(Ag + a_off[i]) : (f32x4)(0.0f);
+    #pragma unroll
+            for (int i = 0; i < B_LD; ++i)
+                b_reg[i] = b_row[i] < tail ? *reinterpret_cast<const f32x4 *>(Bg + b_off[i]) : (f32x4)(0.0f);
+            if (advance) {
+                Ag += tail;
+                Bg += (int64_t)tail * p.ldb;
             }
         };
 
@@ -328,7 +348,8 @@ sgemm_tile_kernel(const GemmParams p) {
         constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
         if (kt_begin < kt_end) {
             const int last = kt_end - 1;
-            load_global(kt_begin, kt_begin < last);
+            if (!EDGE && tail != 0 && kt_begin == 0) load_global_tail(kt_begin < last);
+            else load_global(kt_begin, kt_begin < last);
             store_lds(0);
             __syncthreads();
             read_frags(0, 0, 0);

@@ -146,7 +146,14 @@ def test_force_config_grammar_and_get_config(lib):
         assert tg.get_config(1, 1024, 1024, 1024) == "t128x128x16_w64x64:s1:g4"
         # forced but not valid for the shape: reported, not silently replaced
         with pytest.raises(tg.TgemmError, match="not valid here"):
-            tg.get_config(1, 1024, 1024, 1000)           # k must fill whole K tiles
+            tg.get_config(1, 1024, 1024, 1001)           # a K remainder must be a multiple of 4 ...
+        with pytest.raises(tg.TgemmError, match="not valid here"):
+            tg.get_config(1, 1024, 1024, 12)             # ... and k at least one K tile
+        assert tg.get_config(1, 1024, 1024, 1000) == "t128x128x16_w64x64:s1:g4"   # remainder tile goes first
+        tg.force_config("d128x128x32_w64x64")
+        with pytest.raises(tg.TgemmError, match="not valid here"):
+            tg.get_config(1, 1024, 1024, 1000)           # the direct-to-LDS variants need whole K tiles
+        tg.force_config("t128x128x16_w64x64:s1:g4")
         with pytest.raises(tg.TgemmError, match="not valid here"):
             tg.get_config(1, 1024, 1022, 1024)           # n must be a multiple of 4
         assert tg.get_config(1, 1000, 1000, 1024) == "t128x128x16_w64x64:s1:g4"   # ragged m and n are fine
@@ -164,6 +171,8 @@ def test_force_config_grammar_and_get_config(lib):
     assert tg.get_config(512, 32, 32, 64).startswith("wave32")
     assert "_edge" in tg.get_config(1, 1000, 1000, 1001) or tg.get_config(1, 1000, 1000, 1001).startswith("wave32")
     assert "_edge" not in tg.get_config(1, 1000, 1000, 1024)      # ragged m, n with k % 32 == 0: exact-fit kernels
+    assert tg.get_config(1, 1000, 1000, 1000).startswith("t")     # k % 4 == 0: register-staged exact-fit kernels
+    assert "_edge" not in tg.get_config(1, 1000, 1000, 1000)
     tg.force_config("p128x128x16_w64x64:p2")
     try:
         with pytest.raises(tg.TgemmError, match="not valid here"):

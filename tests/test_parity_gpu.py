@@ -174,6 +174,51 @@ def test_ragged_m_n_on_exact_fit_kernels(spec, shape):
         check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"{spec} {shape} {dist}")
 
 
+# k not a multiple of the K tile on the register-staged exact-fit kernels (k % 4 == 0, k >= BK): the
+# remainder is multiplied first, as a zero-padded K tile.
+K_TAIL = [
+    ("t128x128x16_w64x64", (256, 256, 20)), ("t128x128x16_w64x64", (1000, 1000, 1000)), ("t128x128x32_w64x64", (128, 128, 36)),
+    ("t128x128x32_w64x64_acc2", (130, 132, 2076)), ("t256x128x32_w128x64", (256, 128, 60)), ("t128x256x16_w64x128_acc2", (100, 516, 1044)),
+    ("t64x64x32_w32x32", (65, 68, 100)), ("t128x64x32_w64x32", (200, 100, 92)), ("t64x128x32_w32x64", (70, 200, 68)),
+    ("t128x128x16_w64x64:s3", (200, 136, 1000)), ("t128x128x32_w64x64:s2", (128, 128, 2020)), ("t64x64x32_w32x32:s4", (64, 64, 1028)),
+]
+
+
+@pytest.mark.parametrize("spec,shape", K_TAIL, ids=lambda v: v if isinstance(v, str) else "x".join(map(str, v)))
+def test_k_remainder_on_exact_fit_kernels(spec, shape):
+    import torch
+    m, n, k = shape
+    say(f"k tail {spec} {m}x{n}x{k}")
+    if ":s" in spec:
+        ws = torch.empty(4 * m * n + 4, device="cuda")
+        tg.set_workspace(ws)
+    tg.force_config(spec)
+    for dist in ("normal", "int"):
+        a, b = ig.make_operands(1, m, n, k, dist, 371, 372)
+        c = run_hip(a[0], b[0])
+        assert tg.last_config().startswith(spec)
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"{spec} {shape} {dist}")
+
+
+def test_k_remainder_reads_nothing_past_the_operands():
+    """A and B sit at the very end of their allocations and are followed by NaN-poisoned memory inside the same
+    buffer; with lda > k the columns between k and lda hold NaN too.  Nothing of that may reach C."""
+    import torch
+    say("k tail: poisoned surroundings")
+    m, n, k, lda = 130, 132, 1000, 1004
+    a, b = ig.make_operands(1, m, n, k, "int", 381, 382)
+    abuf = torch.full((m + 2, lda), float("nan"), device="cuda")
+    abuf[:m, :k] = to_dev(a[0])
+    bbuf = torch.full((k + 2, n + 4), float("nan"), device="cuda")
+    bbuf[:k, :n] = to_dev(b[0])
+    for spec in ("t128x128x16_w64x64", "t64x64x32_w32x32", "t128x128x32_w64x64", None):
+        tg.force_config(spec)
+        out = torch.full((m, n), float("nan"), device="cuda")
+        tg.sgemm(abuf[:m, :k], bbuf[:k, :n], out=out)
+        torch.cuda.synchronize()
+        check_against_oracle(out.cpu().numpy(), a[0], b[0], exact=True, what=f"poisoned surroundings {spec}")
+
+
 def test_ragged_fast_path_leaves_padding_and_neighbours_alone():
     """Output rows past m and columns past n (inside ldc, and the memory after the last row) stay untouched."""
     import torch
