@@ -246,3 +246,12 @@ def test_product_package_does_not_import_the_oracle():
     for f in (ROOT / "oracle").glob("*"):
         if f.suffix in (".py", ".c"):
             assert "paper_1904_03383_amd" not in f.read_text() and "tgemm" not in f.read_text(), f
+
+
+def test_tune_cli_shape_parser():
+    from paper_1904_03383_amd.tune import parse_shape
+    assert parse_shape("4096x4096x128") == (1, 4096, 4096, 128)
+    assert parse_shape("512:32x32X64") == (512, 32, 32, 64)
+    for bad in ("0x4x4", "4x4", "2:4x4x0", "axbxc"):
+        with pytest.raises(ValueError):
+            parse_shape(bad)
