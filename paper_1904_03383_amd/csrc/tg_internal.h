@@ -3,6 +3,9 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdint>
 #include <stdint.h>
 
 namespace tg {
@@ -91,6 +94,19 @@ hipError_t launch_saxpy(int64_t n, float alpha, const float *x, const float *y, 
 hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int64_t ld, int rows, int cols, hipStream_t s);
 
 constexpr int kLdsPerCU = 160 * 1024;  // gfx950
+
+// Raises a kernel's dynamic LDS limit to the whole LDS of a CU, once per device (`done` holds one
+// bit per device index of this process; the runtime keeps the attribute per device).
+inline hipError_t allow_full_lds(const void *kernel, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 constexpr int kLdsPadA = 4;  // floats added to each A row in LDS (conflict-free b128 reads)
 constexpr int kLdsPadB = 8;  // floats added to each B row in LDS
 

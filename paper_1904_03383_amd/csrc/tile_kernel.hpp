@@ -473,8 +473,8 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t s) {
         const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
         if (share > lds) lds = share;
     }
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
+    static std::atomic<uint64_t> lds_limit_raised{0};   // one bit per device: the attribute is kept per device
+    const hipError_t attr = allow_full_lds(reinterpret_cast<const void *>(kern), lds_limit_raised);
     if (attr != hipSuccess) return attr;
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, s, p);

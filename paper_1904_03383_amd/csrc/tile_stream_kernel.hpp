@@ -269,8 +269,8 @@ hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s) {
         const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
         if (share > lds) lds = share;
     }
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCU);
+    static std::atomic<uint64_t> lds_limit_raised{0};   // one bit per device: the attribute is kept per device
+    const hipError_t attr = allow_full_lds(reinterpret_cast<const void *>(kern), lds_limit_raised);
     if (attr != hipSuccess) return attr;
     // a multiple of 8 workgroups (p.persistent_blocks), or one per item when there are fewer items
     int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
