@@ -216,8 +216,7 @@ def device_info(torch):
     import re
     import subprocess
     prop = torch.cuda.get_device_properties(0)
-    info = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
-            "max_clock_mhz": getattr(prop, "clock_rate", 0) / 1e3}
+    info = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count}
     try:
         r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
         mm = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", r.stdout)

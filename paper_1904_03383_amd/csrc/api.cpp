@@ -687,38 +687,70 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
         }
     }
     if (best.kernel >= 0) {
-        // Final round: the leaders are often within the noise of the short timings above (1 % at
-        // 4096^3), so the three fastest kernel variants within 2 % of the best are timed again, alternating, with
-        // longer runs (>= 10 launches and >= 2 ms each); the best of two such runs decides.
+        // Final round.  Long kernels: the leaders are often within the noise of the short timings
+        // above (1 % at 4096^3), so the three fastest kernel variants within 2 % of the best are
+        // timed again, alternating, with longer runs (>= 10 launches and >= 2 ms each).
+        // Launch-bound kernels (under ~12 us per call): back-to-back calls only measure the host's
+        // launch rate, which is the same for every candidate, so up to six variants within 25 %
+        // are timed as replays of a captured graph on a private stream, i.e. by their device time.
+        // The best of two such runs decides.
+        const bool launch_bound = best_us < 12.0;
+        const size_t max_finalists = launch_bound ? 6 : 3;
+        const double window = launch_bound ? 1.25 : 1.02;
         std::stable_sort(seen.begin(), seen.end(), [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
         std::vector<Config> finalists{best};
         for (const auto &sc : seen) {
-            if (finalists.size() >= 3 || sc.first > best_us * 1.02) break;
+            if (finalists.size() >= max_finalists || sc.first > best_us * window) break;
             bool dup = false;   // one entry per kernel variant: its fastest setting so far
             for (const Config &f : finalists) dup = dup || f.kernel == sc.second.kernel;
             if (!dup) finalists.push_back(sc.second);
         }
         if (finalists.size() > 1) {
             std::vector<double> fin(finalists.size(), 1e300);
+            hipStream_t ts = nullptr;   // private stream: the caller's may be the null stream, which cannot be captured
+            bool use_graph = launch_bound && hipStreamSynchronize(s) == hipSuccess && hipStreamCreate(&ts) == hipSuccess;
             for (int pass = 0; pass < 2; ++pass)
                 for (size_t i = 0; i < finalists.size(); ++i) {
                     const int n = std::min<int>(256, std::max<int>(10, (int)(2000.0 / std::max(best_us, 1.0)) + 1));
                     tg_status r = TG_OK;
+                    float ms = 0.f;
+                    if (use_graph) {
+                        const int per_graph = 32, replays = 4;
+                        hipGraph_t graph = nullptr;
+                        hipGraphExec_t exec = nullptr;
+                        bool ok = hipStreamBeginCapture(ts, hipStreamCaptureModeThreadLocal) == hipSuccess;
+                        for (int j = 0; ok && j < per_graph && r == TG_OK; ++j) r = launch(p, finalists[i], ws, ts);
+                        ok = ok && hipStreamEndCapture(ts, &graph) == hipSuccess && r == TG_OK && graph != nullptr;
+                        ok = ok && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
+                        ok = ok && hipGraphLaunch(exec, ts) == hipSuccess;   // warm-up replay
+                        if (ok) {
+                            hipEventRecord(ev0, ts);
+                            for (int j = 0; j < replays && ok; ++j) ok = hipGraphLaunch(exec, ts) == hipSuccess;
+                            hipEventRecord(ev1, ts);
+                            ok = hipEventSynchronize(ev1) == hipSuccess && ok;
+                        }
+                        if (exec) hipGraphExecDestroy(exec);
+                        if (graph) hipGraphDestroy(graph);
+                        if (!ok) { (void)hipGetLastError(); hipStreamSynchronize(ts); continue; }
+                        hipEventElapsedTime(&ms, ev0, ev1);
+                        fin[i] = std::min(fin[i], 1e3 * ms / (per_graph * replays));
+                        continue;
+                    }
                     hipEventRecord(ev0, s);
                     for (int j = 0; j < n && r == TG_OK; ++j) r = launch(p, finalists[i], ws, s);
                     hipEventRecord(ev1, s);
                     if (hipEventSynchronize(ev1) != hipSuccess || r != TG_OK) { (void)hipGetLastError(); continue; }
-                    float ms = 0.f;
                     hipEventElapsedTime(&ms, ev0, ev1);
                     fin[i] = std::min(fin[i], 1e3 * ms / n);
                 }
+            if (ts) { hipStreamSynchronize(ts); hipStreamDestroy(ts); }
             size_t w = 0;
             for (size_t i = 1; i < finalists.size(); ++i)
                 if (fin[i] < fin[w]) w = i;
-            if (fin[w] < 1e300) { best = finalists[w]; best_us = fin[w]; }
+            if (fin[w] < 1e300) { best = finalists[w]; if (!use_graph) best_us = fin[w]; }
             if (log)
                 for (size_t i = 0; i < finalists.size(); ++i)
-                    fprintf(stderr, "tgemm tune: final %-38s %.2f us%s\n", spec_of(finalists[i]).c_str(), fin[i], i == w ? "  <- chosen" : "");
+                    fprintf(stderr, "tgemm tune: final%s %-38s %.2f us%s\n", use_graph ? " (graph replay)" : "", spec_of(finalists[i]).c_str(), fin[i], i == w ? "  <- chosen" : "");
         }
     }
     hipEventDestroy(ev0);
