@@ -110,7 +110,9 @@ tg_status tg_saxpy(int64_t n, float alpha, const float *x, const float *y, float
  * Runs every candidate configuration that is valid for this problem on the caller's
  * buffers (`reps` timed launches each after a warm-up, reps <= 0 selects 5), remembers
  * the fastest for this (batch, m, n, k, alignment class) and leaves a valid product in C.
- * Candidates whose roofline lower bound already exceeds the best time seen are skipped.
+ * Candidates whose roofline lower bound already exceeds the best time seen are skipped; the leaders are
+ * timed again with longer runs (launch-bound problems: as replays of a graph captured on a private
+ * stream created for the duration of the call).  Must not be called while `stream` is being captured.
  * Blocking: synchronises `stream`.  tg_sgemm / tg_sgemm_batched never time anything;
  * without a tuned entry they use a static heuristic.
  */
