@@ -79,9 +79,14 @@ def _check(status: int):
 
 
 def _stream_handle(stream=None) -> int:
+    """hipStream_t of `stream` (a torch.cuda.Stream) or of torch's current stream, as an integer."""
     import torch
-    s = stream if stream is not None else torch.cuda.current_stream()
-    return int(s.cuda_stream)
+    if stream is not None:
+        return int(stream.cuda_stream)
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)     # avoids building a Stream object per call
+    if raw is not None:
+        return int(raw(torch.cuda.current_device()))
+    return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _require_f32_cuda(name, t):
@@ -98,23 +103,38 @@ def _ld(t, rows_dim, cols) -> int:
     return max(int(ld), 1)
 
 
+def _row_major_ld(t, rows, cols, strides) -> int:
+    """Leading dimension of a 2-D row-major view given its (row, column) strides."""
+    if cols > 1 and strides[1] != 1:
+        raise ValueError("matrices must have unit stride along their rows (row-major)")
+    if rows > 1 and strides[0] < cols:
+        raise ValueError("rows of a matrix overlap (row stride smaller than the row length)")
+    ld = strides[0] if rows > 1 else cols
+    return ld if ld > 1 else 1
+
+
 def sgemm(a, b, out=None, stream=None):
     """C = A.B for 2-D float32 device tensors a (m,k), b (k,n); returns out (m,n).  -> tg_sgemm"""
     import torch
     _require_f32_cuda("a", a)
     _require_f32_cuda("b", b)
-    if a.dim() != 2 or b.dim() != 2 or a.shape[1] != b.shape[0]:
-        raise ValueError(f"shape mismatch: {tuple(a.shape)} x {tuple(b.shape)}")
-    m, k = a.shape
-    n = b.shape[1]
+    sa, sb = a.shape, b.shape
+    if len(sa) != 2 or len(sb) != 2 or sa[1] != sb[0]:
+        raise ValueError(f"shape mismatch: {tuple(sa)} x {tuple(sb)}")
+    m, k = sa
+    n = sb[1]
     if out is None:
         out = torch.empty((m, n), dtype=torch.float32, device=a.device)
-    _require_f32_cuda("out", out)
-    if tuple(out.shape) != (m, n):
-        raise ValueError("out has the wrong shape")
-    st = load_library().tg_sgemm(m, n, k, a.data_ptr(), _ld(a, 0, k), b.data_ptr(), _ld(b, 0, n),
-                                 out.data_ptr(), _ld(out, 0, n), _stream_handle(stream))
-    _check(st)
+    else:
+        _require_f32_cuda("out", out)
+        so = out.shape
+        if len(so) != 2 or so[0] != m or so[1] != n:
+            raise ValueError("out has the wrong shape")
+    st = load_library().tg_sgemm(m, n, k, a.data_ptr(), _row_major_ld(a, m, k, a.stride()),
+                                 b.data_ptr(), _row_major_ld(b, k, n, b.stride()),
+                                 out.data_ptr(), _row_major_ld(out, m, n, out.stride()), _stream_handle(stream))
+    if st != TG_OK:
+        _check(st)
     return out
 
 
@@ -172,29 +192,32 @@ def _batched_args(a, b, out):
     import torch
     _require_f32_cuda("a", a)
     _require_f32_cuda("b", b)
-    if a.dim() != 3 or b.dim() != 3 or a.shape[0] != b.shape[0] or a.shape[2] != b.shape[1]:
-        raise ValueError(f"shape mismatch: {tuple(a.shape)} x {tuple(b.shape)}")
-    batch, m, k = a.shape
-    n = b.shape[2]
+    sa, sb = a.shape, b.shape
+    if len(sa) != 3 or len(sb) != 3 or sa[0] != sb[0] or sa[2] != sb[1]:
+        raise ValueError(f"shape mismatch: {tuple(sa)} x {tuple(sb)}")
+    batch, m, k = sa
+    n = sb[2]
     if out is None:
         out = torch.empty((batch, m, n), dtype=torch.float32, device=a.device)
-    _require_f32_cuda("out", out)
-    if tuple(out.shape) != (batch, m, n):
-        raise ValueError("out has the wrong shape")
-
-    def bstride(t, one):
-        return int(t.stride(0)) if batch > 1 else one
+    else:
+        _require_f32_cuda("out", out)
+        if tuple(out.shape) != (batch, m, n):
+            raise ValueError("out has the wrong shape")
+    ta, tb, to = a.stride(), b.stride(), out.stride()
+    multi = batch > 1
     args = (batch, m, n, k,
-            a.data_ptr(), _ld(a, 1, k), bstride(a, m * k),
-            b.data_ptr(), _ld(b, 1, n), bstride(b, k * n),
-            out.data_ptr(), _ld(out, 1, n), bstride(out, m * n))
+            a.data_ptr(), _row_major_ld(a, m, k, ta[1:]), ta[0] if multi else m * k,
+            b.data_ptr(), _row_major_ld(b, k, n, tb[1:]), tb[0] if multi else k * n,
+            out.data_ptr(), _row_major_ld(out, m, n, to[1:]), to[0] if multi else m * n)
     return args, out
 
 
 def sgemm_batched(a, b, out=None, stream=None):
     """out[i] = a[i].b[i] for 3-D float32 device tensors (batch,m,k), (batch,k,n).  -> tg_sgemm_batched"""
     args, out = _batched_args(a, b, out)
-    _check(load_library().tg_sgemm_batched(*args, _stream_handle(stream)))
+    st = load_library().tg_sgemm_batched(*args, _stream_handle(stream))
+    if st != TG_OK:
+        _check(st)
     return out
 
 
