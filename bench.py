@@ -41,7 +41,7 @@ def algorithmic_bytes(batch, m, n, k):
     return 4.0 * batch * (m * k + k * n + m * n)
 
 
-def time_workload(tg, torch, name, steps, warmup, reps_tune):
+def time_workload(tg, torch, name, steps, warmup, reps_tune, vendor=False):
     """Tune, warm up, then time `steps` back-to-back calls.  Returns a dict of measurements."""
     from paper_1904_03383_amd import inputgen as ig
     batch, m, n, k, dist = ig.CONFIGS[name]
@@ -122,6 +122,26 @@ def time_workload(tg, torch, name, steps, warmup, reps_tune):
         res["cold_sets"] = sets
         res["cold_algorithmic_gbs"] = nbytes / (res["cold_device_ms_per_step"] * 1e-3) / 1e9
         del das, dbs, outs
+    if vendor:
+        # Context only (--vendor-context): the same product through torch.matmul, i.e. the vendor BLAS
+        # behind PyTorch-ROCm, same buffers, same timing loop.  Not a target and not part of `value`.
+        ref = torch.empty_like(out)
+        for _ in range(max(warmup, 3)):
+            torch.matmul(da, db, out=ref)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for _ in range(steps):
+            torch.matmul(da, db, out=ref)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        res["torch_matmul_device_ms_per_step"] = ev0.elapsed_time(ev1) / steps
+        if batch == 1:
+            # its error against the oracle on the same sampled rows (the vendor kernels keep one accumulation level)
+            rows_v = sorted(set(int(r) for r in np.linspace(0, m - 1, num=min(m, 64))))
+            pv = parity_on_rows(a, b, ref, rows_v)
+            res["torch_matmul_rel_fro"] = pv["rel_fro"]
+            res["torch_matmul_max_ratio"] = pv["max_ratio"]
+        del ref
     ideal_compute = flops / (PEAK_MFMA_F32_TFLOPS * 1e12)
     ideal_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
     res["bound"] = "mfma" if ideal_compute >= ideal_hbm else "hbm"
@@ -270,6 +290,8 @@ def main():
     ap.add_argument("--workload", default="c5_4096")
     ap.add_argument("--no-others", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--vendor-context", action="store_true",
+                    help="also time torch.matmul (the vendor BLAS behind PyTorch) on every GEMM workload, for context")
     ap.add_argument("--tune-reps", type=int, default=5)
     ap.add_argument("--tune-cache", default=None,
                     help="file of tuned configurations: loaded (and tuning skipped) if it exists, else written")
@@ -299,9 +321,10 @@ def main():
         log(f"loaded tuned configurations from {cache}; not tuning")
 
     log(f"headline workload {args.workload}")
-    head, (a, b, out) = time_workload(tg, torch, args.workload, args.steps, args.warmup, args.tune_reps)
+    head, (a, b, out) = time_workload(tg, torch, args.workload, args.steps, args.warmup, args.tune_reps, args.vendor_context)
     dev = device_info(torch)
-    log(f"  {head['tile_config']}  {head['device_ms_per_step'] * 1e3:.1f} us  {head['device_tflops']:.1f} TFLOP/s")
+    log(f"  {head['tile_config']}  {head['device_ms_per_step'] * 1e3:.1f} us  {head['device_tflops']:.1f} TFLOP/s"
+        + (f"  (torch.matmul {head['torch_matmul_device_ms_per_step'] * 1e3:.1f} us)" if "torch_matmul_device_ms_per_step" in head else ""))
     log(f"  device: {dev}")
 
     rows = sorted(set(int(r) for r in np.linspace(0, head["m"] - 1, num=min(head["m"], 128))))
@@ -322,7 +345,7 @@ def main():
             if name == args.workload:
                 continue
             steps = args.steps if ig.CONFIGS[name][3] >= 1024 else max(args.steps, 500)
-            r, (a2, b2, out2) = time_workload(tg, torch, name, steps, args.warmup, args.tune_reps)
+            r, (a2, b2, out2) = time_workload(tg, torch, name, steps, args.warmup, args.tune_reps, args.vendor_context)
             rows2 = sorted(set(int(x) for x in np.linspace(0, r["m"] - 1, num=min(r["m"], 64))))
             p2 = parity_on_rows(a2, b2, out2, rows2)
             r["parity"] = {"rows_checked": len(rows2), "max_ratio": p2["max_ratio"], "rel_fro": p2["rel_fro"],
@@ -330,6 +353,8 @@ def main():
             parity_ok = parity_ok and r["parity"]["ok"]
             del a2, b2, out2
             extra = f"  (graph replay {r['graph_device_ms_per_step'] * 1e3:.2f} us)" if "graph_device_ms_per_step" in r else ""
+            if "torch_matmul_device_ms_per_step" in r:
+                extra += f"  (torch.matmul {r['torch_matmul_device_ms_per_step'] * 1e3:.2f} us)"
             log(f"  {name}: {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.2f} us  {r['device_tflops']:.2f} TFLOP/s{extra}")
             others.append(r)
 

@@ -355,7 +355,7 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             if (s > 1) {
                 const KernelInfo &k = tg::kernel(ki);
                 const int64_t base = ceil_div(p.m, k.BM) * ceil_div(p.n, k.BN) * p.batch;
-                if (base >= 2 * kNumCUs || base * s > 4 * kNumCUs) continue;
+                if (base >= kNumCUs || base * s > 4 * kNumCUs) continue;
             }
             out.push_back(c);
         }

@@ -52,6 +52,7 @@ extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(cons
     X(256, 128, 32, 128, 64, true, 2, 1, "d256x128x32_w128x64_acc2")           \
     X(128, 256, 32, 64, 128, true, 3, 1, "d128x256x32_w64x128_acc2_st3")       \
     X(256, 128, 32, 128, 64, true, 3, 1, "d256x128x32_w128x64_acc2_st3")       \
+    X(256, 256, 32, 128, 128, false, 2, 1, "d256x256x32_w128x128")             \
     X(64, 64, 32, 32, 32, false, 2, 1, "d64x64x32_w32x32")                     \
     X(64, 64, 32, 32, 32, false, 4, 1, "d64x64x32_w32x32_st4")                  \
     X(64, 64, 32, 32, 32, false, 2, 2, "d64x64x32_w32x32_k2")                   \
