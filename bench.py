@@ -231,17 +231,22 @@ def time_strided(tg, torch, steps, warmup, restore_ws):
 
 
 def device_info(torch):
-    """Name, CU count and clocks of the GPU; the current shader clock is read from rocm-smi right after the
-    timed region (a child process; best effort)."""
+    """Name, CU count and current shader clock of the GPU.  The clock comes from sysfs (the active line of
+    pp_dpm_sclk), read as a plain file right after the timed region: no child process is started, a process
+    that has initialised the GPU must not exec."""
+    import glob
     import re
-    import subprocess
     prop = torch.cuda.get_device_properties(0)
     info = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count}
     try:
-        r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
-        mm = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", r.stdout)
-        if mm:
-            info["sclk_mhz_after_run"] = int(mm.group(1))
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+            for line in open(path).read().splitlines():
+                mm = re.search(r"(\d+)\s*Mhz\s*\*", line, re.IGNORECASE)
+                if mm:
+                    info["sclk_mhz_after_run"] = int(mm.group(1))
+                    break
+            if "sclk_mhz_after_run" in info:
+                break
     except Exception:  # noqa: BLE001 - informational only
         pass
     return info
@@ -301,6 +306,9 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
 
+    from oracle import oracle as _oracle
+    _oracle.host_cores()
+    _oracle._load()          # the CPU oracle is loaded before anything touches the GPU
     import torch
     import paper_1904_03383_amd as tg
     from paper_1904_03383_amd import inputgen as ig

@@ -21,7 +21,10 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(str(_build.build()))
+        # Load what is built; compile only when nothing is there (a stale-looking timestamp must not start a
+        # compiler from a process that may already hold the GPU: rebuilding is `python -m oracle.build`).
+        path = _build.LIB if _build.LIB.exists() else _build.build()
+        lib = ctypes.CDLL(str(path))
         i64, p = ctypes.c_int64, ctypes.c_void_p
         lib.oracle_sgemm_f64.argtypes = [i64, i64, i64, i64, p, i64, i64, p, i64, i64,
                                          p, i64, i64, p, p, i64, ctypes.c_int]

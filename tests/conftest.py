@@ -8,3 +8,10 @@ if str(ROOT) not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+
+
+def pytest_sessionstart(session):
+    """Load the CPU oracle before any test can touch the GPU: a process that has initialised the GPU must not
+    start another program, so nothing may be left to compile by then."""
+    from oracle import oracle
+    oracle._load()
