@@ -535,6 +535,230 @@ tg_status run(Problem &p, void *stream) {
     return st;
 }
 
+// The timing tuner behind tg_tune: one object per call.
+//   1. sweep: every candidate (sorted by the cost model) is timed briefly; one whose lower bound
+//      already exceeds the best time seen is skipped (the branch-and-bound cut of Sec. 5.1 of
+//      the paper, applied to a flat candidate set);
+//   2. refine: tile-order group, cap on workgroups per CU and (persistent variants) workgroups
+//      per CU of the winner;
+//   3. final round among the leading kernel variants, with timings that can tell them apart.
+class Tuner {
+  public:
+    Tuner(const Problem &p, void *ws, size_t ws_bytes, hipStream_t stream, int reps)
+        : p_(p), ws_(ws), ws_bytes_(ws_bytes), s_(stream), reps_(reps), log_(getenv("TG_LOG") != nullptr) {
+        events_ok_ = hipEventCreate(&ev0_) == hipSuccess && hipEventCreate(&ev1_) == hipSuccess;
+    }
+    ~Tuner() {
+        if (ev0_) hipEventDestroy(ev0_);
+        if (ev1_) hipEventDestroy(ev1_);
+    }
+    Tuner(const Tuner &) = delete;
+    Tuner &operator=(const Tuner &) = delete;
+
+    tg_status run(Config *best, double *best_us) {
+        if (!events_ok_) return fail(TG_ERR_HIP, "hipEventCreate failed");
+        const std::vector<Config> cands = candidates(p_, ws_bytes_);
+        if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
+        sweep(cands);
+        if (best_.kernel < 0) return fail(TG_ERR_HIP, "every candidate failed to run: " + last_err_);
+        if (tg::kernel(best_.kernel).kind == tg::KIND_TILE) {
+            refine_group();
+            refine_occupancy();
+            refine_persistence();
+        }
+        final_round();
+        *best = best_;
+        *best_us = best_us_;
+        return TG_OK;
+    }
+
+  private:
+    // One brief timing: warm-up launch, then `n` back-to-back launches between two events.
+    // Short kernels are repeated more often (until about 0.3 ms is covered) so that launch
+    // jitter does not decide between candidates.
+    tg_status time_briefly(const Config &c, double *usec) {
+        tg_status r = launch(p_, c, ws_, s_);   // warm-up (also loads the code object)
+        if (r != TG_OK) return r;
+        int n = reps_;
+        double best_of = 1e300;
+        for (int round = 0; round < 3; ++round) {
+            hipEventRecord(ev0_, s_);
+            for (int i = 0; i < n && r == TG_OK; ++i) r = launch(p_, c, ws_, s_);
+            hipEventRecord(ev1_, s_);
+            const hipError_t e = hipEventSynchronize(ev1_);
+            if (r != TG_OK) return r;
+            if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
+            float ms = 0.f;
+            hipEventElapsedTime(&ms, ev0_, ev1_);
+            const double us = 1e3 * ms / n;
+            best_of = std::min(best_of, us);
+            if (round >= 1 && (us * n >= 300.0 || n >= 64)) break;   // at least two rounds, long enough
+            n = std::min<int>(64, std::max<int>(n * 2, (int)(300.0 / std::max(us, 1.0)) + 1));
+        }
+        *usec = best_of;
+        return TG_OK;
+    }
+
+    // Times `c`, records it and makes it the leader when it beats the best by `margin`.
+    void consider(const Config &c, double margin) {
+        double us = 0;
+        if (time_briefly(c, &us) != TG_OK) {
+            last_err_ = t_error;
+            (void)hipGetLastError();   // clear the error so the next candidate starts clean
+            return;
+        }
+        if (log_) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
+        seen_.emplace_back(us, c);
+        if (us < best_us_ * margin) { best_us_ = us; best_ = c; }
+    }
+
+    void sweep(const std::vector<Config> &cands) {
+        for (const Config &c : cands) {
+            const double lb_us = 1e6 * lower_bound_seconds(p_, c);
+            if (lb_us >= best_us_) {
+                if (log_) fprintf(stderr, "tgemm tune: %-44s pruned (bound %.1f us >= best %.1f us)\n", spec_of(c).c_str(), lb_us, best_us_);
+                continue;
+            }
+            consider(c, 1.0);
+        }
+    }
+
+    void refine_group() {
+        static const int kGroups[] = {1, 2, 4, 16, 32};
+        const int tiles_m = (int)ceil_div(p_.m, tg::kernel(best_.kernel).BM);
+        const Config base = best_;
+        for (int g : kGroups) {
+            if (g >= 2 * tiles_m && g != 1) continue;
+            Config c = base;
+            c.group = g;
+            consider(c, 1.0);
+        }
+    }
+
+    void refine_occupancy() {
+        const Config base = best_;
+        for (int occ = 1; occ <= 4; ++occ) {
+            Config c = base;
+            c.occ = occ;
+            consider(c, 0.995);
+        }
+    }
+
+    void refine_persistence() {
+        const Config base = best_;
+        for (int per_cu = 1; per_cu <= 4 && tg::kernel(base.kernel).persistent; ++per_cu) {
+            Config c = base;
+            c.persist = per_cu;
+            consider(c, 0.995);
+        }
+    }
+
+    // `n` back-to-back launches on the caller's stream; microseconds per launch, or < 0 on failure.
+    double time_run(const Config &c, int n) {
+        tg_status r = TG_OK;
+        hipEventRecord(ev0_, s_);
+        for (int j = 0; j < n && r == TG_OK; ++j) r = launch(p_, c, ws_, s_);
+        hipEventRecord(ev1_, s_);
+        if (hipEventSynchronize(ev1_) != hipSuccess || r != TG_OK) {
+            (void)hipGetLastError();
+            return -1.0;
+        }
+        float ms = 0.f;
+        hipEventElapsedTime(&ms, ev0_, ev1_);
+        return 1e3 * ms / n;
+    }
+
+    // Device time per launch: 32 launches captured into a graph on `ts`, replayed four times.
+    double time_graph(const Config &c, hipStream_t ts) {
+        const int per_graph = 32, replays = 4;
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+        tg_status r = TG_OK;
+        bool ok = hipStreamBeginCapture(ts, hipStreamCaptureModeThreadLocal) == hipSuccess;
+        for (int j = 0; ok && j < per_graph && r == TG_OK; ++j) r = launch(p_, c, ws_, ts);
+        ok = ok && hipStreamEndCapture(ts, &graph) == hipSuccess && r == TG_OK && graph != nullptr;
+        ok = ok && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
+        ok = ok && hipGraphLaunch(exec, ts) == hipSuccess;   // warm-up replay
+        if (ok) {
+            hipEventRecord(ev0_, ts);
+            for (int j = 0; j < replays && ok; ++j) ok = hipGraphLaunch(exec, ts) == hipSuccess;
+            hipEventRecord(ev1_, ts);
+            ok = hipEventSynchronize(ev1_) == hipSuccess && ok;
+        }
+        if (exec) hipGraphExecDestroy(exec);
+        if (graph) hipGraphDestroy(graph);
+        if (!ok) {
+            (void)hipGetLastError();
+            hipStreamSynchronize(ts);
+            return -1.0;
+        }
+        float ms = 0.f;
+        hipEventElapsedTime(&ms, ev0_, ev1_);
+        return 1e3 * ms / (per_graph * replays);
+    }
+
+    // Long kernels: the leaders are often within the noise of the brief timings (1 % at 4096^3),
+    // so the three fastest kernel variants within 2 % of the best are timed again, alternating,
+    // with longer runs (>= 10 launches and >= 2 ms each).
+    // Launch-bound kernels (under ~12 us per call): back-to-back calls only measure the host's
+    // launch rate, which is the same for every candidate, so up to six variants within 25 % are
+    // timed as replays of a captured graph on a private stream, i.e. by their device time.
+    // The best of two such runs decides.
+    void final_round() {
+        const bool launch_bound = best_us_ < 12.0;
+        const size_t max_finalists = launch_bound ? 6 : 3;
+        const double window = launch_bound ? 1.25 : 1.02;
+        std::stable_sort(seen_.begin(), seen_.end(),
+                         [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
+        std::vector<Config> finalists{best_};
+        for (const auto &sc : seen_) {
+            if (finalists.size() >= max_finalists || sc.first > best_us_ * window) break;
+            bool dup = false;   // one entry per kernel variant: its fastest setting so far
+            for (const Config &f : finalists) dup = dup || f.kernel == sc.second.kernel;
+            if (!dup) finalists.push_back(sc.second);
+        }
+        if (finalists.size() < 2) return;
+
+        hipStream_t ts = nullptr;   // private stream: the caller's may be the null stream, which cannot be captured
+        const bool use_graph = launch_bound && hipStreamSynchronize(s_) == hipSuccess && hipStreamCreate(&ts) == hipSuccess;
+        const int n = std::min<int>(256, std::max<int>(10, (int)(2000.0 / std::max(best_us_, 1.0)) + 1));
+        std::vector<double> fin(finalists.size(), 1e300);
+        for (int pass = 0; pass < 2; ++pass)
+            for (size_t i = 0; i < finalists.size(); ++i) {
+                const double us = use_graph ? time_graph(finalists[i], ts) : time_run(finalists[i], n);
+                if (us >= 0) fin[i] = std::min(fin[i], us);
+            }
+        if (ts) {
+            hipStreamSynchronize(ts);
+            hipStreamDestroy(ts);
+        }
+        size_t w = 0;
+        for (size_t i = 1; i < finalists.size(); ++i)
+            if (fin[i] < fin[w]) w = i;
+        if (fin[w] < 1e300) {
+            best_ = finalists[w];
+            if (!use_graph) best_us_ = fin[w];   // (a graph time is not comparable with the per-call times in the cache)
+        }
+        if (log_)
+            for (size_t i = 0; i < finalists.size(); ++i)
+                fprintf(stderr, "tgemm tune: final%s %-38s %.2f us%s\n", use_graph ? " (graph replay)" : "",
+                        spec_of(finalists[i]).c_str(), fin[i], i == w ? "  <- chosen" : "");
+    }
+
+    const Problem &p_;
+    void *ws_;
+    size_t ws_bytes_;
+    hipStream_t s_;
+    int reps_;
+    bool log_;
+    bool events_ok_ = false;
+    hipEvent_t ev0_ = nullptr, ev1_ = nullptr;
+    Config best_;
+    double best_us_ = 1e300;
+    std::string last_err_;
+    std::vector<std::pair<double, Config>> seen_;   // every configuration measured, for the final round
+};
+
 }  // namespace
 
 extern "C" {
@@ -581,7 +805,6 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
     if (p.batch == 0 || p.m == 0 || p.n == 0 || p.k == 0) return run(p, stream);
     st = check_device();
     if (st != TG_OK) return st;
-    if (reps <= 0) reps = 5;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     void *ws;
@@ -591,171 +814,13 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
         ws = g_ws;
         ws_bytes = g_ws_bytes;
     }
-    std::vector<Config> cands = candidates(p, ws_bytes);
-    if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
-
-    hipEvent_t ev0, ev1;
-    if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess)
-        return fail(TG_ERR_HIP, "hipEventCreate failed");
-
-    // One timing: warm-up launch, then `n` back-to-back launches between two events.  Short
-    // kernels are repeated more often (until about 0.3 ms is covered) so that launch jitter
-    // does not decide between candidates.
-    auto time_config = [&](const Config &c, double *usec) -> tg_status {
-        tg_status r = launch(p, c, ws, s);   // warm-up (also loads the code object)
-        if (r != TG_OK) return r;
-        int n = reps;
-        double best_of = 1e300;
-        for (int round = 0; round < 3; ++round) {
-            hipEventRecord(ev0, s);
-            for (int i = 0; i < n && r == TG_OK; ++i) r = launch(p, c, ws, s);
-            hipEventRecord(ev1, s);
-            hipError_t e = hipEventSynchronize(ev1);
-            if (r != TG_OK) return r;
-            if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
-            float ms = 0.f;
-            hipEventElapsedTime(&ms, ev0, ev1);
-            const double us = 1e3 * ms / n;
-            best_of = std::min(best_of, us);
-            if (round >= 1 && (us * n >= 300.0 || n >= 64)) break;   // at least two rounds, long enough
-            n = std::min<int>(64, std::max<int>(n * 2, (int)(300.0 / std::max(us, 1.0)) + 1));
-        }
-        *usec = best_of;
-        return TG_OK;
-    };
-
     Config best;
-    double best_us = 1e300;
-    std::string last_err;
-    std::vector<std::pair<double, Config>> seen;   // every configuration measured, for the final round
-    const bool log = getenv("TG_LOG") != nullptr;
-    for (const Config &c : cands) {
-        const double lb_us = 1e6 * lower_bound_seconds(p, c);
-        if (lb_us >= best_us) {
-            if (log) fprintf(stderr, "tgemm tune: %-44s pruned (bound %.1f us >= best %.1f us)\n", spec_of(c).c_str(), lb_us, best_us);
-            continue;
-        }
-        double us = 0;
-        tg_status r = time_config(c, &us);
-        if (r != TG_OK) {
-            last_err = t_error;
-            (void)hipGetLastError();   // clear the error so the next candidate starts clean
-            continue;
-        }
-        if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us (bound %.1f)\n", spec_of(c).c_str(), us, lb_us);
-        seen.emplace_back(us, c);
-        if (us < best_us) { best_us = us; best = c; }
+    double best_us = 0;
+    {
+        Tuner tuner(p, ws, ws_bytes, s, reps <= 0 ? 5 : reps);
+        st = tuner.run(&best, &best_us);
     }
-    if (best.kernel >= 0 && tg::kernel(best.kernel).kind == tg::KIND_TILE) {
-        // refine the tile-order group of the winner
-        static const int kGroups[] = {1, 2, 4, 16, 32};
-        const int tiles_m = (int)ceil_div(p.m, tg::kernel(best.kernel).BM);
-        Config base = best;
-        for (int g : kGroups) {
-            if (g >= 2 * tiles_m && g != 1) continue;
-            Config c = base;
-            c.group = g;
-            double us = 0;
-            if (time_config(c, &us) != TG_OK) continue;
-            if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
-            seen.emplace_back(us, c);
-            if (us < best_us) { best_us = us; best = c; }
-        }
-    }
-    if (best.kernel >= 0 && tg::kernel(best.kernel).kind == tg::KIND_TILE) {
-        // refine the cap on workgroups per CU of the winner
-        Config base = best;
-        for (int occ = 1; occ <= 4; ++occ) {
-            Config c = base;
-            c.occ = occ;
-            double us = 0;
-            if (time_config(c, &us) != TG_OK) continue;
-            if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
-            seen.emplace_back(us, c);
-            if (us < best_us * 0.995) { best_us = us; best = c; }
-        }
-        // ... and, for a persistent variant, the number of workgroups per CU
-        base = best;
-        for (int per_cu = 1; per_cu <= 4 && tg::kernel(base.kernel).persistent; ++per_cu) {
-            Config c = base;
-            c.persist = per_cu;
-            double us = 0;
-            if (time_config(c, &us) != TG_OK) continue;
-            if (log) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
-            seen.emplace_back(us, c);
-            if (us < best_us * 0.995) { best_us = us; best = c; }
-        }
-    }
-    if (best.kernel >= 0) {
-        // Final round.  Long kernels: the leaders are often within the noise of the short timings
-        // above (1 % at 4096^3), so the three fastest kernel variants within 2 % of the best are
-        // timed again, alternating, with longer runs (>= 10 launches and >= 2 ms each).
-        // Launch-bound kernels (under ~12 us per call): back-to-back calls only measure the host's
-        // launch rate, which is the same for every candidate, so up to six variants within 25 %
-        // are timed as replays of a captured graph on a private stream, i.e. by their device time.
-        // The best of two such runs decides.
-        const bool launch_bound = best_us < 12.0;
-        const size_t max_finalists = launch_bound ? 6 : 3;
-        const double window = launch_bound ? 1.25 : 1.02;
-        std::stable_sort(seen.begin(), seen.end(), [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
-        std::vector<Config> finalists{best};
-        for (const auto &sc : seen) {
-            if (finalists.size() >= max_finalists || sc.first > best_us * window) break;
-            bool dup = false;   // one entry per kernel variant: its fastest setting so far
-            for (const Config &f : finalists) dup = dup || f.kernel == sc.second.kernel;
-            if (!dup) finalists.push_back(sc.second);
-        }
-        if (finalists.size() > 1) {
-            std::vector<double> fin(finalists.size(), 1e300);
-            hipStream_t ts = nullptr;   // private stream: the caller's may be the null stream, which cannot be captured
-            bool use_graph = launch_bound && hipStreamSynchronize(s) == hipSuccess && hipStreamCreate(&ts) == hipSuccess;
-            for (int pass = 0; pass < 2; ++pass)
-                for (size_t i = 0; i < finalists.size(); ++i) {
-                    const int n = std::min<int>(256, std::max<int>(10, (int)(2000.0 / std::max(best_us, 1.0)) + 1));
-                    tg_status r = TG_OK;
-                    float ms = 0.f;
-                    if (use_graph) {
-                        const int per_graph = 32, replays = 4;
-                        hipGraph_t graph = nullptr;
-                        hipGraphExec_t exec = nullptr;
-                        bool ok = hipStreamBeginCapture(ts, hipStreamCaptureModeThreadLocal) == hipSuccess;
-                        for (int j = 0; ok && j < per_graph && r == TG_OK; ++j) r = launch(p, finalists[i], ws, ts);
-                        ok = ok && hipStreamEndCapture(ts, &graph) == hipSuccess && r == TG_OK && graph != nullptr;
-                        ok = ok && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
-                        ok = ok && hipGraphLaunch(exec, ts) == hipSuccess;   // warm-up replay
-                        if (ok) {
-                            hipEventRecord(ev0, ts);
-                            for (int j = 0; j < replays && ok; ++j) ok = hipGraphLaunch(exec, ts) == hipSuccess;
-                            hipEventRecord(ev1, ts);
-                            ok = hipEventSynchronize(ev1) == hipSuccess && ok;
-                        }
-                        if (exec) hipGraphExecDestroy(exec);
-                        if (graph) hipGraphDestroy(graph);
-                        if (!ok) { (void)hipGetLastError(); hipStreamSynchronize(ts); continue; }
-                        hipEventElapsedTime(&ms, ev0, ev1);
-                        fin[i] = std::min(fin[i], 1e3 * ms / (per_graph * replays));
-                        continue;
-                    }
-                    hipEventRecord(ev0, s);
-                    for (int j = 0; j < n && r == TG_OK; ++j) r = launch(p, finalists[i], ws, s);
-                    hipEventRecord(ev1, s);
-                    if (hipEventSynchronize(ev1) != hipSuccess || r != TG_OK) { (void)hipGetLastError(); continue; }
-                    hipEventElapsedTime(&ms, ev0, ev1);
-                    fin[i] = std::min(fin[i], 1e3 * ms / n);
-                }
-            if (ts) { hipStreamSynchronize(ts); hipStreamDestroy(ts); }
-            size_t w = 0;
-            for (size_t i = 1; i < finalists.size(); ++i)
-                if (fin[i] < fin[w]) w = i;
-            if (fin[w] < 1e300) { best = finalists[w]; if (!use_graph) best_us = fin[w]; }
-            if (log)
-                for (size_t i = 0; i < finalists.size(); ++i)
-                    fprintf(stderr, "tgemm tune: final%s %-38s %.2f us%s\n", use_graph ? " (graph replay)" : "", spec_of(finalists[i]).c_str(), fin[i], i == w ? "  <- chosen" : "");
-        }
-    }
-    hipEventDestroy(ev0);
-    hipEventDestroy(ev1);
-    if (best.kernel < 0) return fail(TG_ERR_HIP, "every candidate failed to run: " + last_err);
+    if (st != TG_OK) return st;
 
     st = launch(p, best, ws, s);   // leave C holding the product computed by the winner
     hipError_t e = hipStreamSynchronize(s);
