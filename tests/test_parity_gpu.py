@@ -155,6 +155,9 @@ RAGGED_FAST = [
     ("d128x256x32_w64x128_acc2_st3", (129, 257 * 4, 1056)), ("d64x64x32_w32x32", (1, 4, 32)), ("d64x64x32_w32x32_st4", (67, 72, 160)),
     ("d64x64x32_w32x32_k2", (130, 68, 96)), ("d64x64x32_w32x32_k2_st4", (63, 60, 256)),
     ("t128x128x16_w64x64:s3", (200, 136, 1024)), ("d128x128x32_w64x64:s2", (130, 260, 512)),
+    # 32-row tiles for skinny products (m <= 32, wide n)
+    ("t32x256x32_w32x64", (7, 260, 96)), ("d32x256x32_w32x64", (32, 516, 64)), ("t32x256x32_w32x64_acc2", (20, 256, 2080)),
+    ("d32x256x32_w32x64:s4", (9, 520, 1024)), ("t32x256x32_w32x64", (70, 300, 64)),
 ]
 
 
@@ -181,6 +184,7 @@ K_TAIL = [
     ("t128x128x32_w64x64_acc2", (130, 132, 2076)), ("t256x128x32_w128x64", (256, 128, 60)), ("t128x256x16_w64x128_acc2", (100, 516, 1044)),
     ("t64x64x32_w32x32", (65, 68, 100)), ("t128x64x32_w64x32", (200, 100, 92)), ("t64x128x32_w32x64", (70, 200, 68)),
     ("t128x128x16_w64x64:s3", (200, 136, 1000)), ("t128x128x32_w64x64:s2", (128, 128, 2020)), ("t64x64x32_w32x32:s4", (64, 64, 1028)),
+    ("t32x256x32_w32x64", (30, 256, 100)), ("t32x256x32_w32x64:s2", (5, 512, 1000)),
 ]
 
 
