@@ -33,6 +33,8 @@ namespace tg {
     X(64, 128, 32, 32, 64, false, false, "t64x128x32_w32x64")               \
     X(32, 256, 32, 32, 64, false, false, "t32x256x32_w32x64")               \
     X(32, 256, 32, 32, 64, true, false, "t32x256x32_w32x64_acc2")           \
+    X(256, 32, 32, 64, 32, false, false, "t256x32x32_w64x32")               \
+    X(256, 32, 32, 64, 32, true, false, "t256x32x32_w64x32_acc2")           \
     X(128, 128, 16, 64, 64, false, true, "t128x128x16_w64x64_edge")         \
     X(128, 128, 16, 64, 64, true, true, "t128x128x16_w64x64_acc2_edge")     \
     X(64, 64, 16, 32, 32, false, true, "t64x64x16_w32x32_edge")             \
@@ -56,6 +58,7 @@ extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(cons
     X(256, 128, 32, 128, 64, true, 3, 1, "d256x128x32_w128x64_acc2_st3")       \
     X(256, 256, 32, 128, 128, false, 2, 1, "d256x256x32_w128x128")             \
     X(32, 256, 32, 32, 64, false, 2, 1, "d32x256x32_w32x64")                   \
+    X(256, 32, 32, 64, 32, false, 2, 1, "d256x32x32_w64x32")                   \
     X(64, 64, 32, 32, 32, false, 2, 1, "d64x64x32_w32x32")                     \
     X(64, 64, 32, 32, 32, false, 4, 1, "d64x64x32_w32x32_st4")                  \
     X(64, 64, 32, 32, 32, false, 2, 2, "d64x64x32_w32x32_k2")                   \

@@ -16,4 +16,5 @@ template hipError_t launch_tile_direct<64, 64, 32, 32, 32, false, 2, 2>(const Ge
 template hipError_t launch_tile_direct<64, 64, 32, 32, 32, false, 4, 2>(const GemmParams &, hipStream_t);
 template hipError_t launch_tile_direct<256, 256, 32, 128, 128, false, 2, 1>(const GemmParams &, hipStream_t);
 template hipError_t launch_tile_direct<32, 256, 32, 32, 64, false, 2, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_direct<256, 32, 32, 64, 32, false, 2, 1>(const GemmParams &, hipStream_t);
 }  // namespace tg

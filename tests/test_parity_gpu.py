@@ -158,6 +158,9 @@ RAGGED_FAST = [
     # 32-row tiles for skinny products (m <= 32, wide n)
     ("t32x256x32_w32x64", (7, 260, 96)), ("d32x256x32_w32x64", (32, 516, 64)), ("t32x256x32_w32x64_acc2", (20, 256, 2080)),
     ("d32x256x32_w32x64:s4", (9, 520, 1024)), ("t32x256x32_w32x64", (70, 300, 64)),
+    # ... and 32-column tiles for tall ones (n <= 32)
+    ("t256x32x32_w64x32", (300, 8, 96)), ("d256x32x32_w64x32", (520, 32, 64)), ("t256x32x32_w64x32_acc2", (260, 20, 2080)),
+    ("d256x32x32_w64x32:s4", (515, 12, 1024)), ("t256x32x32_w64x32", (300, 72, 64)),
 ]
 
 
@@ -185,6 +188,7 @@ K_TAIL = [
     ("t64x64x32_w32x32", (65, 68, 100)), ("t128x64x32_w64x32", (200, 100, 92)), ("t64x128x32_w32x64", (70, 200, 68)),
     ("t128x128x16_w64x64:s3", (200, 136, 1000)), ("t128x128x32_w64x64:s2", (128, 128, 2020)), ("t64x64x32_w32x32:s4", (64, 64, 1028)),
     ("t32x256x32_w32x64", (30, 256, 100)), ("t32x256x32_w32x64:s2", (5, 512, 1000)),
+    ("t256x32x32_w64x32", (256, 28, 100)), ("t256x32x32_w64x32:s2", (512, 4, 1000)),
 ]
 
 
