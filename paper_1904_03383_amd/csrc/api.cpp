@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <initializer_list>
 #include <map>
 #include <mutex>
 #include <string>
@@ -214,8 +215,18 @@ size_t pack_bytes(int64_t rows, int64_t cols) { return (size_t)rows * (size_t)pa
 // An operand is packed when more than one 128-wide tile row/column would fetch it.
 constexpr int64_t kPackMinReuse = 128;
 
+// Product of non-negative factors, saturating at INT64_MAX.
+int64_t sat_mul(std::initializer_list<int64_t> f) {
+    int64_t r = 1;
+    for (int64_t x : f)
+        if (mul_ovf(r, x, &r)) return INT64_MAX;
+    return r;
+}
+
 size_t ws_need(const Problem &p, int splits) {
-    return splits > 1 ? (size_t)p.batch * splits * p.m * p.n * sizeof(float) : 0;
+    if (splits <= 1) return 0;
+    const int64_t bytes = sat_mul({p.batch, (int64_t)splits, p.m, p.n, (int64_t)sizeof(float)});
+    return bytes == INT64_MAX ? SIZE_MAX : (size_t)bytes;
 }
 
 // Is this configuration usable for this problem?  (static validity filter of the tuner:
@@ -232,7 +243,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         if (!p.unit()) return no("the wave kernel needs unit element strides");
         if (c.splits != 1) return no("the wave kernel has no split-K");
         if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
-        if (ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch > (int64_t)4 * INT32_MAX) return no("too many tiles");
+        if (sat_mul({ceil_div(p.m, 32), ceil_div(p.n, 32), p.batch}) > (int64_t)4 * INT32_MAX) return no("too many tiles");
         return true;
     }
     if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
@@ -258,7 +269,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         if (per < 2) return no("K range shorter than two tiles");
         if (ws_need(p, c.splits) > ws_bytes) return no("workspace too small for this split");
     }
-    const int64_t blocks = ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * c.splits * p.batch;
+    const int64_t blocks = sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), (int64_t)c.splits, p.batch});
     if (blocks > INT32_MAX) return no("too many workgroups");
     return true;
 }
@@ -549,8 +560,8 @@ class Tuner {
         events_ok_ = hipEventCreate(&ev0_) == hipSuccess && hipEventCreate(&ev1_) == hipSuccess;
     }
     ~Tuner() {
-        if (ev0_) hipEventDestroy(ev0_);
-        if (ev1_) hipEventDestroy(ev1_);
+        if (ev0_) (void)hipEventDestroy(ev0_);
+        if (ev1_) (void)hipEventDestroy(ev1_);
     }
     Tuner(const Tuner &) = delete;
     Tuner &operator=(const Tuner &) = delete;
@@ -582,14 +593,14 @@ class Tuner {
         int n = reps_;
         double best_of = 1e300;
         for (int round = 0; round < 3; ++round) {
-            hipEventRecord(ev0_, s_);
+            hipError_t e = hipEventRecord(ev0_, s_);
             for (int i = 0; i < n && r == TG_OK; ++i) r = launch(p_, c, ws_, s_);
-            hipEventRecord(ev1_, s_);
-            const hipError_t e = hipEventSynchronize(ev1_);
+            if (e == hipSuccess) e = hipEventRecord(ev1_, s_);
+            if (e == hipSuccess) e = hipEventSynchronize(ev1_);
             if (r != TG_OK) return r;
-            if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
             float ms = 0.f;
-            hipEventElapsedTime(&ms, ev0_, ev1_);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev0_, ev1_);
+            if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("tuning run failed: ") + hipGetErrorString(e));
             const double us = 1e3 * ms / n;
             best_of = std::min(best_of, us);
             if (round >= 1 && (us * n >= 300.0 || n >= 64)) break;   // at least two rounds, long enough
@@ -656,15 +667,16 @@ class Tuner {
     // `n` back-to-back launches on the caller's stream; microseconds per launch, or < 0 on failure.
     double time_run(const Config &c, int n) {
         tg_status r = TG_OK;
-        hipEventRecord(ev0_, s_);
+        hipError_t e = hipEventRecord(ev0_, s_);
         for (int j = 0; j < n && r == TG_OK; ++j) r = launch(p_, c, ws_, s_);
-        hipEventRecord(ev1_, s_);
-        if (hipEventSynchronize(ev1_) != hipSuccess || r != TG_OK) {
+        if (e == hipSuccess) e = hipEventRecord(ev1_, s_);
+        if (e == hipSuccess) e = hipEventSynchronize(ev1_);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev0_, ev1_);
+        if (e != hipSuccess || r != TG_OK) {
             (void)hipGetLastError();
             return -1.0;
         }
-        float ms = 0.f;
-        hipEventElapsedTime(&ms, ev0_, ev1_);
         return 1e3 * ms / n;
     }
 
@@ -679,21 +691,21 @@ class Tuner {
         ok = ok && hipStreamEndCapture(ts, &graph) == hipSuccess && r == TG_OK && graph != nullptr;
         ok = ok && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
         ok = ok && hipGraphLaunch(exec, ts) == hipSuccess;   // warm-up replay
+        float ms = 0.f;
         if (ok) {
-            hipEventRecord(ev0_, ts);
+            ok = hipEventRecord(ev0_, ts) == hipSuccess;
             for (int j = 0; j < replays && ok; ++j) ok = hipGraphLaunch(exec, ts) == hipSuccess;
-            hipEventRecord(ev1_, ts);
+            ok = ok && hipEventRecord(ev1_, ts) == hipSuccess;
             ok = hipEventSynchronize(ev1_) == hipSuccess && ok;
+            ok = ok && hipEventElapsedTime(&ms, ev0_, ev1_) == hipSuccess;
         }
-        if (exec) hipGraphExecDestroy(exec);
-        if (graph) hipGraphDestroy(graph);
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
         if (!ok) {
             (void)hipGetLastError();
-            hipStreamSynchronize(ts);
+            (void)hipStreamSynchronize(ts);
             return -1.0;
         }
-        float ms = 0.f;
-        hipEventElapsedTime(&ms, ev0_, ev1_);
         return 1e3 * ms / (per_graph * replays);
     }
 
@@ -729,8 +741,8 @@ class Tuner {
                 if (us >= 0) fin[i] = std::min(fin[i], us);
             }
         if (ts) {
-            hipStreamSynchronize(ts);
-            hipStreamDestroy(ts);
+            (void)hipStreamSynchronize(ts);
+            (void)hipStreamDestroy(ts);
         }
         size_t w = 0;
         for (size_t i = 1; i < finalists.size(); ++i)

@@ -255,3 +255,15 @@ def test_tune_cli_shape_parser():
     for bad in ("0x4x4", "4x4", "2:4x4x0", "axbxc"):
         with pytest.raises(ValueError):
             parse_shape(bad)
+
+
+def test_host_logic_survives_random_sizes_specs_and_cache_files(tmp_path):
+    """tests/c_abi/host_fuzz.c: 40000 random shapes through the chooser, 20000 random specs, 300 random cache files."""
+    import subprocess
+    exe = tmp_path / "host_fuzz"
+    pkg = ROOT / "paper_1904_03383_amd"
+    subprocess.run(["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-I", str(ROOT / "include"), str(ROOT / "tests" / "c_abi" / "host_fuzz.c"),
+                    "-L", str(pkg), "-ltgemm", f"-Wl,-rpath,{pkg}", "-o", str(exe)], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, cwd=tmp_path)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "fuzz: ok" in r.stdout
