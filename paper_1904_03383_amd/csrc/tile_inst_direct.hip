@@ -1,4 +1,4 @@
-// Explicit instantiations: direct-to-LDS variants (exact-fit shapes).
+// Explicit instantiations: direct-to-LDS variants (aligned operands, k % 32 == 0, n % 4 == 0).
 // <BM, BN, BK, WM, WN, two_level, LDS stages, wave groups along K>
 #include "tile_direct_kernel.hpp"
 namespace tg {

@@ -19,6 +19,12 @@
 //    B fragment is one CB*4-byte LDS read and a C row segment is one CB*4-byte store.
 //  * MFMA 32x32x2 result layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4,
 //    column l%32 of the 32x32 block.
+//
+// Two builds of the same template.  EDGE = false ("exact-fit" in names and messages): aligned
+// operands and 16-byte loads with no test in the K loop; m and n need not be multiples of
+// the tile (a last tile row / column re-reads the operand's last row / last vector and masks
+// its stores) and k need not be a multiple of BK (the remainder goes first, as a zero-padded
+// K tile).  EDGE = true: every access predicated, any size, alignment and element stride.
 #pragma once
 
 #include "tg_internal.h"
