@@ -82,6 +82,19 @@ def time_workload(tg, torch, name, steps, warmup, reps_tune, vendor=False):
         "frac_hbm_peak": nbytes / (dev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "flops": flops, "bytes": nbytes,
     }
+    # Ten more timed blocks of R back-to-back calls each (R such that a block lasts >= 5 ms, at least 20 calls):
+    # their median and minimum show how steady the figure above is.
+    reps = max(20, int(5.0 / max(dev_ms, 1e-3)) + 1)
+    blocks_ms = []
+    for _ in range(10):
+        ev0.record(stream)
+        for _ in range(reps):
+            call(da, db, out=out)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        blocks_ms.append(ev0.elapsed_time(ev1) / reps)
+    res["repeat_stats"] = {"blocks": 10, "calls_per_block": reps, "median_ms": float(np.median(blocks_ms)),
+                           "min_ms": float(min(blocks_ms)), "max_ms": float(max(blocks_ms))}
     if dev_ms < 0.1:
         # Launch-bound workload: per-call time is dominated by the host launch path.  Replay the
         # same calls from a HIP graph to show the device-side rate (reported separately).
