@@ -49,25 +49,37 @@ def test_workload_integer_variant_is_bit_exact(name):
     check_against_oracle(c, a, b, exact=True, what=name + "/int")
 
 
-def test_workload_c5_tuned_configuration_matches_oracle():
-    """4096^3 in the launch configuration the benchmark times (after tg_tune)."""
+@pytest.mark.parametrize("name", list(ig.CONFIGS))
+def test_workload_in_the_tuned_configuration_matches_oracle(name):
+    """Every workload in the launch configuration the benchmark times: after tg_tune, with the benchmark's
+    split-K workspace set; all elements against the oracle, and the integer variant bit for bit."""
     import torch
-    say("c5_4096 after tune")
-    a, b = _squeeze(*ig.make_config("c5_4096"))
+    say(f"{name} after tune")
+    ws_bytes = max(tg.workspace_bytes(*ig.CONFIGS[w][:4]) for w in ig.CONFIGS)
+    ws = torch.empty(max(ws_bytes // 4, 4), dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    a, b = _squeeze(*ig.make_config(name))
     da, db = to_dev(a), to_dev(b)
+    call = tg.sgemm if a.ndim == 2 else tg.sgemm_batched
     tg.clear_tune_cache()
     try:
         c = tg.tune(da, db, reps=2)
         torch.cuda.synchronize()
         tuned = tg.last_config()
-        c2 = tg.sgemm(da, db)
+        c2 = call(da, db)
         torch.cuda.synchronize()
         assert tg.last_config() == tuned
         assert torch.equal(c, c2)
-        m = check_against_oracle(c2.cpu().numpy(), a, b, what="c5 tuned " + tuned)
+        m = check_against_oracle(c2.cpu().numpy(), a, b, what=f"{name} tuned {tuned}")
         say(f"  tuned {tuned}  rel_fro {m['rel_fro']:.2e}")
+        ai, bi = _squeeze(*ig.make_config(name, dist="int"))
+        ci = call(to_dev(ai), to_dev(bi))
+        torch.cuda.synchronize()
+        assert tg.last_config() == tuned
+        check_against_oracle(ci.cpu().numpy(), ai, bi, exact=True, what=f"{name}/int tuned {tuned}")
     finally:
         tg.clear_tune_cache()
+        del ws
 
 
 # ---- every kernel variant, forced -----------------------------------------------------------
