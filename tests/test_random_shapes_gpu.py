@@ -144,3 +144,32 @@ def test_random_strided_layouts_are_bit_exact(chunk):
         cfg = tg.last_config()
         assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.sgemm_f64(a, b)), f"case {chunk}.{idx} ({cfg})"
         del ws, keep_a, keep_b
+
+
+EXTREME = [
+    (1, 1 << 21, 4, 8), (1, 3, 1 << 20, 5), (1, 8, 8, 1 << 18), (1, 1 << 16, 1, 33), (1, 1, 1 << 16, 64),
+    (100000, 4, 4, 4), (3000, 1, 33, 7), (1, 65536 + 3, 36, 4), (2, 40, 8, 40000),
+]
+
+
+@pytest.mark.parametrize("case", EXTREME, ids=str)
+@pytest.mark.parametrize("with_ws", [False, True], ids=["nows", "ws"])
+def test_extreme_aspect_ratios(case, with_ws):
+    """Very tall, very wide, very deep and very many: grid sizes, 64-bit offsets and split-K plans at their edges."""
+    import torch
+    from oracle import oracle
+    batch, m, n, k = case
+    say(f"extreme {case} workspace={with_ws}")
+    a = ig.small_int(9950, (batch, m, k))
+    b = ig.small_int(9951, (batch, k, n))
+    ws = None
+    if with_ws:
+        ws = torch.empty(max(tg.workspace_bytes(batch, m, n, k) // 4, 4), device="cuda")
+        tg.set_workspace(ws)
+    out = torch.full((batch, m, n), float("nan"), device="cuda")
+    tg.sgemm_batched(torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda(), out=out)
+    torch.cuda.synchronize()
+    cfg = tg.last_config()
+    ref = oracle.sgemm_f64(a, b)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), ref), f"{case} ({cfg})"
+    del ws
