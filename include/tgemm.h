@@ -156,6 +156,23 @@ tg_status tg_force_config(const char *spec);
 /* Writes the spec that a call with these sizes (packed, aligned operands) would use now. */
 tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *buf, size_t len);
 
+/*
+ * The search space of tg_tune, for inspection (Sec. 5.1 of the paper: candidates are ranked by a
+ * cost model and cut by a lower bound on their run time before they are timed).
+ * tg_num_candidates: how many configurations tg_tune would consider for these sizes (packed,
+ * aligned operands, the workspace as it is now); -1 with tg_last_error set when the sizes are
+ * invalid.  tg_candidate: the idx-th of them in the order they are timed (cheapest by the cost
+ * model first): its spec into spec[len] (host buffer), and, where the pointers are not NULL, the
+ * lower bound on its run time and the cost model's estimate, both in microseconds.  The bound
+ * holds for any kernel with that tiling on this chip: the MFMA peak, one wave's share on its one
+ * SIMD, whole rounds of workgroups over the 256 CUs, and one pass of the operands over HBM; a
+ * candidate whose bound is not below the best time measured so far is skipped without a launch.
+ * Neither call touches the GPU.
+ */
+int tg_num_candidates(int64_t batch, int64_t m, int64_t n, int64_t k);
+tg_status tg_candidate(int64_t batch, int64_t m, int64_t n, int64_t k, int idx, char *spec, size_t len,
+                       double *lower_bound_us, double *model_us);
+
 /* Spec the most recent successful tg_sgemm/tg_sgemm_batched/tg_tune call on this thread ran (or "" ). */
 const char *tg_last_config(void);
 

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     TgemmError,
     clear_tune_cache,
     force_config,
+    candidates,
     get_config,
     kernel_names,
     last_config,

@@ -30,6 +30,8 @@ SIGNATURES = {
     "tg_strided_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64]),
     "tg_force_config": (_int, [_cstr]),
     "tg_get_config": (_int, [_i64, _i64, _i64, _i64, _p, _sz]),
+    "tg_num_candidates": (_int, [_i64, _i64, _i64, _i64]),
+    "tg_candidate": (_int, [_i64, _i64, _i64, _i64, _int, _p, _sz, _p, _p]),
     "tg_last_config": (_cstr, []),
     "tg_num_kernels": (_int, []),
     "tg_kernel_name": (_int, [_int, _p, _sz]),
@@ -265,6 +267,23 @@ def get_config(batch: int, m: int, n: int, k: int) -> str:
     buf = ctypes.create_string_buffer(256)
     _check(load_library().tg_get_config(batch, m, n, k, ctypes.cast(buf, ctypes.c_void_p), 256))
     return buf.value.decode()
+
+
+def candidates(batch: int, m: int, n: int, k: int):
+    """The configurations ``tune`` would consider, in timing order: (spec, lower_bound_us, model_us) each."""
+    lib = load_library()
+    count = lib.tg_num_candidates(batch, m, n, k)
+    if count < 0:
+        raise TgemmError(1, lib.tg_last_error().decode())
+    buf = ctypes.create_string_buffer(256)
+    bound, model = ctypes.c_double(), ctypes.c_double()
+    out = []
+    for i in range(count):
+        _check(lib.tg_candidate(batch, m, n, k, i, ctypes.cast(buf, ctypes.c_void_p), 256,
+                                ctypes.cast(ctypes.byref(bound), ctypes.c_void_p),
+                                ctypes.cast(ctypes.byref(model), ctypes.c_void_p)))
+        out.append((buf.value.decode(), bound.value, model.value))
+    return out
 
 
 def last_config() -> str:

@@ -773,6 +773,15 @@ class Tuner {
     std::vector<std::pair<double, Config>> seen_;   // every configuration measured, for the final round
 };
 
+// The packed, aligned problem of these sizes (no operands: for queries only).
+tg_status query_problem(int64_t batch, int64_t m, int64_t n, int64_t k, Problem *out) {
+    if (batch <= 0 || m <= 0 || n <= 0 || k <= 0) return fail(TG_ERR_INVALID_ARG, "sizes must be positive");
+    if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
+    *out = Problem{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, false};
+    out->aligned = k % 4 == 0 && n % 4 == 0;
+    return TG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -889,12 +898,10 @@ tg_status tg_force_config(const char *spec) {
 
 tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *buf, size_t len) {
     if (!buf || len == 0) return fail(TG_ERR_INVALID_ARG, "no output buffer");
-    if (batch <= 0 || m <= 0 || n <= 0 || k <= 0) return fail(TG_ERR_INVALID_ARG, "sizes must be positive");
-    if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
-    Problem p{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, false};
-    p.aligned = k % 4 == 0 && n % 4 == 0;
+    Problem p;
+    tg_status st = query_problem(batch, m, n, k, &p);
+    if (st != TG_OK) return st;
     Config c;
-    tg_status st;
     {
         std::lock_guard<std::mutex> lk(g_mutex);
         st = choose(p, g_ws_bytes, &c);
@@ -907,6 +914,33 @@ tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *bu
 }
 
 const char *tg_last_config(void) { return t_last_config.c_str(); }
+
+int tg_num_candidates(int64_t batch, int64_t m, int64_t n, int64_t k) {
+    Problem p;
+    if (query_problem(batch, m, n, k, &p) != TG_OK) return -1;
+    std::lock_guard<std::mutex> lk(g_mutex);
+    return (int)candidates(p, g_ws_bytes).size();
+}
+
+tg_status tg_candidate(int64_t batch, int64_t m, int64_t n, int64_t k, int idx, char *spec, size_t len,
+                       double *lower_bound_us, double *model_us) {
+    if (!spec || len == 0) return fail(TG_ERR_INVALID_ARG, "no output buffer");
+    Problem p;
+    tg_status st = query_problem(batch, m, n, k, &p);
+    if (st != TG_OK) return st;
+    std::vector<Config> cands;
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        cands = candidates(p, g_ws_bytes);
+    }
+    if (idx < 0 || idx >= (int)cands.size()) return fail(TG_ERR_INVALID_ARG, "candidate index out of range");
+    const std::string s = spec_of(cands[idx]);
+    if (s.size() + 1 > len) return fail(TG_ERR_INVALID_ARG, "output buffer too small");
+    memcpy(spec, s.c_str(), s.size() + 1);
+    if (lower_bound_us) *lower_bound_us = 1e6 * lower_bound_seconds(p, cands[idx]);
+    if (model_us) *model_us = 1e6 * heuristic_seconds(p, cands[idx]);
+    return TG_OK;
+}
 
 int tg_num_kernels(void) { return tg::num_kernels(); }
 

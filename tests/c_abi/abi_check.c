@@ -40,6 +40,13 @@ int main(void)
     CHECK(tg_force_config(NULL) == TG_OK);
     CHECK(tg_get_config(1, 4096, 4096, 4096, buf, sizeof buf) == TG_OK && strstr(buf, "acc2") != NULL);
     CHECK(tg_last_config() != NULL);
+    {
+        double bound = 0, model = 0;
+        CHECK(tg_num_candidates(1, 4096, 4096, 4096) > 0);
+        CHECK(tg_candidate(1, 4096, 4096, 4096, 0, buf, sizeof buf, &bound, &model) == TG_OK);
+        CHECK(bound > 800.0 && model >= bound && strstr(buf, "acc2") != NULL);
+        CHECK(tg_candidate(1, 4096, 4096, 4096, -1, buf, sizeof buf, NULL, NULL) == TG_ERR_INVALID_ARG);
+    }
     CHECK(tg_load_tune_cache("/nonexistent/file") == TG_ERR_INVALID_ARG);
     tg_clear_tune_cache();
     printf("abi_check: ok (%d kernel variants, version %d)\n", tg_num_kernels(), tg_version());

@@ -267,3 +267,93 @@ def test_host_logic_survives_random_sizes_specs_and_cache_files(tmp_path):
     r = subprocess.run([str(exe)], capture_output=True, text=True, cwd=tmp_path)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "fuzz: ok" in r.stdout
+
+
+# --- the tuner's search space: cost-model order and the lower-bound cut (Sec. 5.1) ---------------
+
+PEAK_FLOPS = 157.3e12   # published fp32 MFMA rate of the chip
+PEAK_HBM = 8e12
+SEARCH_SHAPES = [(1, 256, 256, 32), (1, 1024, 1024, 1024), (512, 32, 32, 64), (1, 4096, 4096, 128),
+                 (1, 4096, 4096, 4096), (1, 1000, 1000, 1000), (1, 32, 8192, 8192), (7, 130, 68, 36),
+                 (1, 33, 65, 17)]
+
+
+@pytest.mark.parametrize("shape", SEARCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_candidates_are_valid_ordered_and_bounded(lib, shape):
+    batch, m, n, k = shape
+    cands = tg.candidates(batch, m, n, k)
+    assert cands and len({c[0] for c in cands}) == len(cands)
+    names = set(tg.kernel_names())
+    flops = 2.0 * batch * m * n * k
+    data = 4.0 * batch * (m * k + k * n + m * n)
+    floor_us = 1e6 * max(flops / PEAK_FLOPS, data / PEAK_HBM)
+    models = [c[2] for c in cands]
+    assert models == sorted(models)                    # timed cheapest-first, so the cut bites early
+    for spec, bound_us, model_us in cands:
+        assert spec.split(":")[0] in names
+        # no configuration can beat the chip: every bound includes the whole-chip floor ...
+        assert bound_us >= floor_us * (1 - 1e-12)
+        # ... and the cost model (which adds launch cost and an efficiency below 1) never undercuts it
+        assert model_us >= bound_us, (spec, bound_us, model_us)
+        # the spec is usable as it stands
+        tg.force_config(spec)
+        assert tg.get_config(batch, m, n, k) == spec
+    tg.force_config(None)
+    # what an untuned call runs is the head of the list
+    assert tg.get_config(batch, m, n, k) == cands[0][0]
+
+
+def test_lower_bound_reflects_tile_quantisation_and_wave_share(lib):
+    by = {spec: (lb, model) for spec, lb, model in tg.candidates(1, 4096, 4096, 4096)}
+    simd_flops = 64 * 2.4e9            # one SIMD: 64 flop per clock at 2.4 GHz; 1024 of them make the chip
+    chip_us = 1e6 * 2.0 * 4096 ** 3 / (1024 * simd_flops)
+    # 128x128 tiles: 1024 workgroups of 4 waves = exactly 4 full rounds over 256 CUs x 4 SIMDs: the chip floor
+    assert by["t128x128x32_w64x64_acc2:s1:g8"][0] == pytest.approx(chip_us, rel=1e-9)
+    # 256x256 tiles at 1024^3: 16 workgroups on 16 CUs, each wave owns 128x128x1024 -> 16x the chip floor
+    mid = {spec: lb for spec, lb, _ in tg.candidates(1, 1024, 1024, 1024)}
+    assert mid["d256x256x32_w128x128:s1:g8"] == pytest.approx(1e6 * 2.0 * 128 * 128 * 1024 / simd_flops, rel=1e-9)
+    assert mid["d64x64x32_w32x32:s1:g8"] == pytest.approx(1e6 * 2.0 * 1024 ** 3 / (1024 * simd_flops), rel=1e-9)
+    # a small problem: one 64x64 tile per CU at most -> a wave's own 32x32xK share on its SIMD binds,
+    # which is far above the whole-chip floor
+    small = {spec: lb for spec, lb, _ in tg.candidates(1, 256, 256, 32)}
+    assert small["t64x64x32_w32x32:s1:g8"] == pytest.approx(1e6 * 2.0 * 32 * 32 * 32 / simd_flops, rel=1e-9)
+    # 1000^3 on 128x128 tiles: 64 workgroups -> one round of 64x64x1000(+tail) per wave
+    rag = {spec: lb for spec, lb, _ in tg.candidates(1, 1000, 1000, 1000)}
+    assert rag["t128x128x16_w64x64:s1:g8"] == pytest.approx(1e6 * 2.0 * 64 * 64 * 1000 / simd_flops, rel=1e-9)
+
+
+def test_lower_bound_cut_never_drops_a_config_that_could_win(lib):
+    """Replay of the sweep on the host: candidates are taken in order, one is skipped when its bound is
+    not below the best time so far.  With any timings that respect the bounds (time >= bound), the
+    configuration with the smallest time is never among the skipped ones."""
+    import random
+    rng = random.Random(5)
+    for shape in SEARCH_SHAPES:
+        cands = tg.candidates(*shape)
+        for _ in range(20):
+            times = [lb * (1.0 + rng.random() * rng.choice([0.05, 0.5, 3.0])) for _, lb, _ in cands]
+            best, skipped = float("inf"), []
+            for i, (_, lb, _) in enumerate(cands):
+                if lb >= best:
+                    skipped.append(i)
+                    continue
+                best = min(best, times[i])
+            assert best == min(times)
+            assert all(times[i] >= best for i in skipped)
+    # and the cut does bite: at 1024^3 the big tiles leave most of the chip idle, and their bounds say so
+    mid = tg.candidates(1, 1024, 1024, 1024)
+    assert max(lb for _, lb, _ in mid) > 10 * min(lb for _, lb, _ in mid)
+
+
+def test_candidate_argument_checks(lib):
+    buf = ctypes.create_string_buffer(64)
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert lib.tg_num_candidates(1, 0, 64, 64) == -1 and b"positive" in lib.tg_last_error()
+    assert lib.tg_candidate(1, 64, 64, 64, 0, None, 0, None, None) == 1
+    assert lib.tg_candidate(1, 64, 64, 64, 0, p, 2, None, None) == 1          # buffer too small
+    count = lib.tg_num_candidates(1, 64, 64, 64)
+    assert count > 0
+    assert lib.tg_candidate(1, 64, 64, 64, count, p, 64, None, None) == 1      # index out of range
+    assert lib.tg_candidate(1, 64, 64, 64, -1, p, 64, None, None) == 1
+    assert lib.tg_candidate(1, 64, 64, 64, 0, p, 64, None, None) == 0 and buf.value
+    assert lib.tg_candidate(1, 2 ** 31, 64, 64, 0, p, 64, None, None) == 2

@@ -451,3 +451,37 @@ def test_tune_picks_a_valid_configuration_and_is_used_afterwards():
         check_against_oracle(c3.cpu().numpy(), a, b, what="c2 without workspace")
     finally:
         tg.clear_tune_cache()
+
+
+@pytest.mark.parametrize("shape", [(1, 256, 256, 32), (1, 1024, 1024, 1024), (512, 32, 32, 64), (1, 4096, 4096, 128),
+                                   (1, 1000, 1000, 1000)], ids=lambda s: "x".join(map(str, s)))
+def test_lower_bound_of_every_candidate_holds_on_the_device(shape):
+    """The cut of the search (Sec. 5.1) is only safe if no configuration ever runs faster than its bound:
+    time every candidate the tuner would consider, forced, and compare.  Times come from events around 20
+    back-to-back launches, so they include launch gaps and can only be above the kernel's own time."""
+    import torch
+    batch, m, n, k = shape
+    say(f"lower bounds vs device times at {shape}")
+    g = torch.Generator(device="cpu").manual_seed(11)
+    a = torch.rand((batch, m, k), generator=g, dtype=torch.float32).cuda()
+    b = torch.rand((batch, k, n), generator=g, dtype=torch.float32).cuda()
+    out = torch.empty((batch, m, n), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(tg.workspace_bytes(batch, m, n, k) // 4, 1), dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    cands = tg.candidates(batch, m, n, k)
+    assert cands
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    worst = (10.0, "")
+    for spec, bound_us, _ in cands:
+        tg.force_config(spec)
+        tg.sgemm_batched(a, b, out=out)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(20):
+            tg.sgemm_batched(a, b, out=out)
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 20
+        worst = min(worst, (us / bound_us, spec))
+        assert us >= bound_us, f"{spec}: {us:.2f} us measured is below its lower bound {bound_us:.2f} us"
+    say(f"  {len(cands)} candidates; tightest: {worst[1]} at {worst[0]:.2f}x its bound")
