@@ -6,11 +6,15 @@ Nothing is loaded at import time; the shared library is opened on first use and 
 absence is an error (there is no fallback path).
 """
 from .binding import (  # noqa: F401
+    MATH_BF16_PIECES,
+    MATH_FP32_MFMA,
     TgemmError,
     clear_tune_cache,
     force_config,
     candidates,
     get_config,
+    get_math,
+    set_math,
     kernel_names,
     last_config,
     library_path,

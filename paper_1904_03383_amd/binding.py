@@ -29,6 +29,8 @@ SIGNATURES = {
     "tg_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
     "tg_strided_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64]),
     "tg_force_config": (_int, [_cstr]),
+    "tg_set_math": (_int, [_int]),
+    "tg_get_math": (_int, []),
     "tg_get_config": (_int, [_i64, _i64, _i64, _i64, _p, _sz]),
     "tg_num_candidates": (_int, [_i64, _i64, _i64, _i64]),
     "tg_candidate": (_int, [_i64, _i64, _i64, _i64, _int, _p, _sz, _p, _p]),
@@ -261,6 +263,18 @@ def strided_workspace_bytes(m: int, n: int, k: int, csa: int, csb: int) -> int:
 
 def force_config(spec):
     _check(load_library().tg_force_config(spec.encode() if spec else None))
+
+
+MATH_FP32_MFMA, MATH_BF16_PIECES = 0, 1
+
+
+def set_math(mode: int):
+    """Which arithmetic the automatic choice may use: MATH_FP32_MFMA (default) or MATH_BF16_PIECES."""
+    _check(load_library().tg_set_math(mode))
+
+
+def get_math() -> int:
+    return int(load_library().tg_get_math())
 
 
 def get_config(batch: int, m: int, n: int, k: int) -> str:

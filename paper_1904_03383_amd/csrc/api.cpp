@@ -7,6 +7,7 @@
 #include "../../include/tgemm.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -31,6 +32,8 @@ constexpr int kLongK = 1024;                // K range above which second-level 
 constexpr int kFlushK = 1024;               // K terms between folds of the first-level accumulators (measured at 4096^3:
                                             // 512 -> 4.1e-7 relative Frobenius error, 1024 -> 5.7e-7 and 0.5 % faster,
                                             // 2048 -> 8.1e-7, never -> 1.15e-6)
+constexpr int kLongKPieces = 8192;          // longest K range of the bf16-piece kernels: their leading chain rounds once per
+                                            // 16 terms, so 8192 terms are 512 roundings (4096 terms measured: 3.9e-7)
 constexpr int kWaveMaxK = 2048;             // longest K the single-accumulator wave kernel may take
 constexpr int kDefaultGroup = 8;
 using tg::kLdsPerCU;
@@ -69,6 +72,7 @@ std::map<std::pair<ShapeKey, size_t>, Config> g_heuristic_choice;   // memo of t
 void *g_ws = nullptr;
 size_t g_ws_bytes = 0;
 bool g_forced = false;
+std::atomic<int> g_math{TG_MATH_FP32_MFMA};   // which arithmetic the automatic choice may use (read by the tuner without the lock)
 bool g_env_read = false;
 Config g_force_cfg;
 int g_device_ok[64] = {0};  // 0 unknown, 1 gfx950, -1 other
@@ -266,7 +270,8 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     split_plan(ki, p.k, c.splits, &splits, &per);
     if (splits != c.splits) return no("split count leaves an empty K range");
     const int64_t k_range = std::min<int64_t>((int64_t)per * ki.BK, p.k);
-    if (k_range > kLongK && !ki.two_level) return no("K range too long for a single accumulator level");
+    if (ki.pieces ? k_range > kLongKPieces : (k_range > kLongK && !ki.two_level))
+        return no("K range too long for a single accumulator level");
     if (c.splits > 1) {
         if (per < 2) return no("K range shorter than two tiles");
         if (ws_need(p, c.splits) > ws_bytes) return no("workspace too small for this split");
@@ -283,7 +288,9 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
 double lower_bound_seconds(const Problem &p, const Config &c) {
     const KernelInfo &ki = tg::kernel(c.kernel);
     const double flops = 2.0 * p.batch * p.m * p.n * p.k;
-    double t = flops / kPeakFlops;
+    // the bf16 pipe multiplies 16x as fast as the fp32 one, and a piece kernel needs `pieces` products per product
+    const double speed = ki.pieces ? 16.0 / ki.pieces : 1.0;
+    double t = flops / (kPeakFlops * speed);
     int splits = 1, per = 1;
     int waves_per_block = ki.threads / 64;
     double wave_flops;
@@ -298,10 +305,10 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
         wave_flops = 2.0 * ki.WM * ki.WN * std::min<int64_t>((int64_t)per * ki.BK, p.k) / kgroups;
         blocks = ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * splits * p.batch;
     }
-    t = std::max(t, wave_flops / kSimdFlops);
+    t = std::max(t, wave_flops / (kSimdFlops * speed));
     // workgroups are spread over at most kNumCUs CUs; each CU has 4 SIMDs
     const double rounds = (double)ceil_div(blocks * waves_per_block, (int64_t)kNumCUs * 4);
-    t = std::max(t, rounds * wave_flops / kSimdFlops);
+    t = std::max(t, rounds * wave_flops / (kSimdFlops * speed));
     double bytes = 4.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n + (double)p.m * p.n);
     if (splits > 1) bytes += 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n;
     t = std::max(t, bytes / kPeakHbm);
@@ -340,6 +347,8 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     // that hold only padding still take their share of the loads, the barrier and the MFMA pipe
     if (p.m * 2 <= ki.BM && p.n * 2 <= ki.BN) eff *= 0.8;
     const double block_flops = 2.0 * ki.BM * ki.BN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
+    // bf16-piece kernels: 16/pieces times the multiply rate, at about 3/4 of the efficiency (measured)
+    if (ki.pieces) eff = 0.75 * 16.0 / ki.pieces;
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
     double t = launch + per_cu * block_flops / cu_rate;
     if (splits > 1) t += 3e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
@@ -358,6 +367,7 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             c.persist = tg::kernel(ki).persistent ? 2 : 0;
             if (!config_valid(p, c, ws_bytes)) continue;
             const KernelInfo &kinfo = tg::kernel(ki);
+            if (kinfo.pieces && g_math != TG_MATH_BF16_PIECES) continue;   // only on request
             if (kinfo.kind == tg::KIND_TILE && kinfo.two_level) {
                 // second-level accumulators only cost registers when the K range is short
                 int sp, per;
@@ -388,7 +398,8 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
     return out;
 }
 
-ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, p.aligned ? 1 : (p.unit() ? 0 : 2)); }
+// Shape class of a problem: operand layout (0 unaligned, 1 aligned, 2 element-strided) + 4 x math mode.
+ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, (p.aligned ? 1 : (p.unit() ? 0 : 2)) + 4 * g_math); }
 
 // forced > tuned > heuristic.  Caller holds g_mutex.
 tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
@@ -404,7 +415,8 @@ tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
         return TG_OK;
     }
     auto it = g_cache.find(key_of(p));
-    if (it != g_cache.end() && config_valid(p, it->second.cfg, ws_bytes)) {
+    if (it != g_cache.end() && config_valid(p, it->second.cfg, ws_bytes) &&
+        (g_math == TG_MATH_BF16_PIECES || !tg::kernel(it->second.cfg.kernel).pieces)) {
         *out = it->second.cfg;
         return TG_OK;
     }
@@ -882,6 +894,19 @@ size_t tg_strided_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t csa, 
     if (csa != 1) need += pack_bytes(m, k);
     if (csb != 1) need += pack_bytes(k, n);
     return need;
+}
+
+tg_status tg_set_math(int mode) {
+    if (mode != TG_MATH_FP32_MFMA && mode != TG_MATH_BF16_PIECES) return fail(TG_ERR_INVALID_ARG, "unknown math mode");
+    std::lock_guard<std::mutex> lk(g_mutex);
+    if (mode != g_math) g_heuristic_choice.clear();
+    g_math = mode;
+    return TG_OK;
+}
+
+int tg_get_math(void) {
+    std::lock_guard<std::mutex> lk(g_mutex);
+    return g_math;
 }
 
 tg_status tg_force_config(const char *spec) {

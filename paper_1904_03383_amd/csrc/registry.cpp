@@ -70,9 +70,21 @@ extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(cons
      NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, KG>},
 TG_DIRECT_LIST(TG_DDECL)
 
+// bf16-piece variants: (BM, BN, BK, WM, WN, piece products, name)
+#define TG_PIECES_LIST(X)                                                   \
+    X(128, 256, 32, 64, 128, 6, "e128x256x32_w64x128_x6")                   \
+    X(128, 256, 32, 64, 128, 9, "e128x256x32_w64x128_x9")
+#define TG_EDECL(BM, BN, BK, WM, WN, NP, NAME) \
+    extern template hipError_t launch_tile_pieces<BM, BN, BK, WM, WN, NP>(const GemmParams &, hipStream_t);
+#define TG_EROW(BM, BN, BK, WM, WN, NP, NAME)                                                   \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, false, false, (BM / WM) * (BN / WN) * 64, \
+     2 * 3 * (BK / 8) * ((BM + 4) + (BN + 4)) * 16, &launch_tile_pieces<BM, BN, BK, WM, WN, NP>, NP},
+TG_PIECES_LIST(TG_EDECL)
+
 static const KernelInfo kTable[] = {
     TG_TILE_LIST(TG_ROW)
     TG_DIRECT_LIST(TG_DROW)
+    TG_PIECES_LIST(TG_EROW)
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")
     TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
     TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")

@@ -56,6 +56,7 @@ struct KernelInfo {
     int threads;
     int lds_bytes;
     launch_fn launch;
+    int pieces;          // 0: fp32 MFMA; 6 or 9: every fp32 product formed from that many bf16 piece products
 };
 
 // Kernel table (registry.cpp).
@@ -77,6 +78,13 @@ constexpr int tile_lds_bytes();
 // KG wave groups share each wave tile, every group taking 1/KG of each K tile.
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s);
+
+// Workgroup-tile kernel on the bf16 matrix pipe: operands cut into three bf16 pieces each, NP piece
+// products per fp32 product (aligned operands, k % BK == 0, n % 4 == 0).
+template <int BM, int BN, int BK, int WM, int WN, int NP>
+hipError_t launch_tile_pieces(const GemmParams &p, hipStream_t s);
+template <int BM, int BN, int BK>
+constexpr int pieces_lds_bytes();
 
 // One wave per 32x32 C tile, operands straight from global memory (small / batched problems).
 hipError_t launch_wave32(const GemmParams &p, hipStream_t s);
