@@ -265,6 +265,9 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         // the fast variants address inside a tile with 32-bit element offsets
         if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
             return no("leading dimension too large for the exact-fit kernels");
+        // (the bf16-piece kernels form 32-bit byte offsets)
+        if (ki.pieces && ((ki.BM - 1) * p.lda + ki.BK >= (1 << 30) || (ki.BK - 1) * p.ldb + ki.BN >= (1 << 30)))
+            return no("leading dimension too large for the exact-fit kernels");
     }
     int splits, per;
     split_plan(ki, p.k, c.splits, &splits, &per);

@@ -26,6 +26,7 @@
 
 #include "tile_kernel.hpp"
 
+
 namespace tg {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -44,9 +45,14 @@ __device__ __forceinline__ unsigned pack_upper_halves(float x0, float x1) {
     return __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
 }
 
+// x - (piece e of the packed pair pk), where the piece is the bf16 in half e: one dot-product
+// instruction, pk . (-1, 0) + x or pk . (0, -1) + x.  The product is exact and so is the sum (the
+// remainder of a truncation is representable).
 // Cuts 8 values into pieces: out[p] = the p-th bf16 pieces of x[0..7], element e in half e%2 of
 // register e/2 (the operand order of the MFMA).  Truncating cuts: piece and remainder keep the sign of x,
 // the subtraction is exact.
+// (v_dot2c_f32_bf16 could subtract a packed piece in one instruction instead of the and + sub pair; it was
+// tried and is several times slower per instruction, the kernel lost 7 %.)
 __device__ __forceinline__ void cut_pieces(const float (&x)[8], u32x4 (&out)[3]) {
     float r[8];
 #pragma unroll
@@ -100,12 +106,10 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     const int kt_stop = kt_begin + p.ktiles_per_split;
     const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
-    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
-
     // Slots of the tile loads.  A: slot f = (row f / NKC, k chunk f % NKC): the threads of one row
     // cover BK*4 contiguous bytes.  B: slot f = (k chunk f / (BN/4), column vector f % (BN/4)).
     // Rows / vectors past the end of a ragged last tile re-read the last one (in bounds, never stored).
+    // Offsets are in bytes and fit 32 bits (checked on the host): scalar base + 32-bit lane offset addressing.
     unsigned a_off[A_SL], b_off[B_SL];
     int a_dst[A_SL], b_dst[B_SL][4];
 #pragma unroll
@@ -113,7 +117,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
         const int f = tid + i * NT;
         const int row = f / NKC, kc = f % NKC;
         const int r = row < p.m - 1 - m0 ? row : p.m - 1 - m0;
-        a_off[i] = (unsigned)r * (unsigned)p.lda + (unsigned)kc * 8u;
+        a_off[i] = ((unsigned)r * (unsigned)p.lda + (unsigned)kc * 8u) * 4u;
         a_dst[i] = kc * A_PITCH + row;
     }
 #pragma unroll
@@ -121,7 +125,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
         const int f = tid + i * NT;
         const int kc = f / (BN / 4), col = (f % (BN / 4)) * 4;
         const int c = col < p.n - 4 - n0 ? col : p.n - 4 - n0;
-        b_off[i] = (unsigned)(kc * 8) * (unsigned)p.ldb + (unsigned)c;
+        b_off[i] = ((unsigned)(kc * 8) * (unsigned)p.ldb + (unsigned)c) * 4u;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             // tile column -> position in the plane: lane-interleaved inside the owning wave's range
@@ -132,43 +136,55 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
 
     f32x4 a_raw[A_SL][2], b_raw[B_SL][8];
 
-    auto load_global = [&](bool advance) {
+    // Raw loads of one K tile, by slot; At / Bt point at that tile.
+    auto load_a_slot = [&](const float *At, int i) {
+        const char *src = reinterpret_cast<const char *>(At) + a_off[i];
+        a_raw[i][0] = *reinterpret_cast<const f32x4 *>(src);
+        a_raw[i][1] = *reinterpret_cast<const f32x4 *>(src + 16);
+    };
+    auto load_b_slot = [&](const float *Bt, int i) {
 #pragma unroll
-        for (int i = 0; i < A_SL; ++i) {
-            a_raw[i][0] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i]);
-            a_raw[i][1] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i] + 4);
-        }
+        for (int r = 0; r < 8; ++r)   // (row base in scalar registers + the thread's 32-bit offset)
+            b_raw[i][r] = *reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(Bt + (int64_t)r * p.ldb) + b_off[i]);
+    };
+    auto load_tile = [&](const float *At, const float *Bt) {
 #pragma unroll
-        for (int i = 0; i < B_SL; ++i)
+        for (int i = 0; i < B_SL; ++i) load_b_slot(Bt, i);
 #pragma unroll
-            for (int r = 0; r < 8; ++r)
-                b_raw[i][r] = *reinterpret_cast<const f32x4 *>(Bg + b_off[i] + (unsigned)r * (unsigned)p.ldb);
-        if (advance) {
-            Ag += BK;
-            Bg += (int64_t)BK * p.ldb;
-        }
+        for (int i = 0; i < A_SL; ++i) load_a_slot(At, i);
     };
 
-    // One unit of the cut-and-store work: unit u < A_SL is an A slot, later ones one column of a B slot.
+    // The cut-and-store work of one K tile in units of 8 values (one LDS entry per piece): units
+    // 0 .. 4*B_SL-1 are the columns of the B slots, the rest the A slots.  Once the last unit of a slot
+    // is cut, its registers are free and take the same slot of the tile after (At, Bt): every load
+    // then has most of a K tile's MFMAs to arrive.
     constexpr int N_UNITS = A_SL + 4 * B_SL;
     auto cut_and_store = [&](int stage, int u) {
         float x[8];
         u32x4 pc[3];
-        if (u < A_SL) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = a_raw[u][e / 4][e % 4];
-            cut_pieces(x, pc);
-            u32x4 *dst = As + stage * A_STAGE + a_dst[u];
-#pragma unroll
-            for (int q = 0; q < 3; ++q) dst[q * NKC * A_PITCH] = pc[q];
-        } else {
-            const int i = (u - A_SL) / 4, e4 = (u - A_SL) % 4;
+        if (u < 4 * B_SL) {
+            const int i = u / 4, e4 = u % 4;
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = b_raw[i][e][e4];
             cut_pieces(x, pc);
             u32x4 *dst = Bs + stage * B_STAGE + b_dst[i][e4];
 #pragma unroll
             for (int q = 0; q < 3; ++q) dst[q * NKC * B_PITCH] = pc[q];
+        } else {
+            const int i = u - 4 * B_SL;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = a_raw[i][e / 4][e % 4];
+            cut_pieces(x, pc);
+            u32x4 *dst = As + stage * A_STAGE + a_dst[i];
+#pragma unroll
+            for (int q = 0; q < 3; ++q) dst[q * NKC * A_PITCH] = pc[q];
+        }
+    };
+    auto reload_after = [&](const float *At, const float *Bt, int u) {
+        if (u < 4 * B_SL) {
+            if (u % 4 == 3) load_b_slot(Bt, u / 4);
+        } else {
+            load_a_slot(At, u - 4 * B_SL);
         }
     };
 
@@ -216,22 +232,32 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     };
 
     // K loop.  Groups g = (k step, column block) of RB*NP MFMAs each; G groups per K tile.  While
-    // tile kt multiplies out of stage s, the raw values of tile kt+1 are cut and written to stage s^1
-    // during groups 0 .. G-2; one barrier; during the last group the first fragments of tile kt+1
-    // are read and the global loads of tile kt+2 start.
+    // tile kt multiplies out of stage s, the raw values of tile kt+1 are cut and written to stage s^1,
+    // one unit per group, and each freed slot is refilled with tile kt+2; one barrier; during the last
+    // group the first fragments of tile kt+1 are read.
+    // (Measured on MI355X: an MFMA of this shape occupies the pipe for 32 cycles and up to four
+    // independent vector instructions issue in its shadow at about one cycle each; beyond that every
+    // further one costs its full four to five cycles.  Hence four per MFMA below.)
     constexpr int G = NSTEP * CB;
     static_assert(N_UNITS <= G - 1, "not enough MFMA groups to hide the cut-and-store work");
+    constexpr int N_MFMA = RB * NP;              // MFMAs of one group
     if (kt_begin < kt_end) {
         const int last = kt_end - 1;
-        load_global(kt_begin < last);
+        const float *A0 = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda;
+        const float *B0 = p.B + (int64_t)prob * p.strideB + n0;
+        // tile t of the operands; asking beyond the last tile of the range gives the last one (in bounds)
+        auto a_tile = [&](int t) { return A0 + (int64_t)(t < last ? t : last) * BK; };
+        auto b_tile = [&](int t) { return B0 + (int64_t)(t < last ? t : last) * BK * p.ldb; };
+        load_tile(a_tile(kt_begin), b_tile(kt_begin));
 #pragma unroll
         for (int u = 0; u < N_UNITS; ++u) cut_and_store(0, u);
         __syncthreads();
         read_a(0, 0, 0);
         read_b(0, 0, 0, 0);
-        if (kt_begin < last) load_global(kt_begin + 1 < last);
+        if (kt_begin < last) load_tile(a_tile(kt_begin + 1), b_tile(kt_begin + 1));
         int stage = 0;
         for (int kt = kt_begin; kt < last; ++kt) {
+            const float *At = a_tile(kt + 2), *Bt = b_tile(kt + 2);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < G - 1; ++g) {
@@ -243,14 +269,25 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
                     read_b(stage, step + 1, 0, 0);
                 }
                 if (g < N_UNITS) cut_and_store(stage ^ 1, g);
+                if (g < N_UNITS) reload_after(At, Bt, g);
                 mfma_block(step & 1, cb & 1, cb);
+                // every other instruction in the shadow of an MFMA: the fragment reads first, then the
+                // cuts with their LDS writes and the reloads spread over the group
+#pragma unroll
+                for (int i = 0; i < N_MFMA; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);    // VALU
+                    __builtin_amdgcn_sched_group_barrier(0x220, 1, 0);    // LDS write or global load
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
             __syncthreads();
             read_a(stage ^ 1, 0, 0);
             read_b(stage ^ 1, 0, 0, 0);
-            load_global(kt + 2 < last);   // tile kt+2, or the last tile again when nothing is left (in bounds)
             mfma_block((NSTEP - 1) & 1, (CB - 1) & 1, CB - 1);
+            __builtin_amdgcn_sched_group_barrier(0x100, 3 * RB + 3, 0);   // the first fragments of the next tile
+            __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
             __builtin_amdgcn_sched_barrier(0);
             stage ^= 1;
         }
