@@ -40,6 +40,10 @@ int main(void)
     CHECK(tg_force_config(NULL) == TG_OK);
     CHECK(tg_get_config(1, 4096, 4096, 4096, buf, sizeof buf) == TG_OK && strstr(buf, "acc2") != NULL);
     CHECK(tg_last_config() != NULL);
+    CHECK(tg_get_math() == TG_MATH_FP32_MFMA && tg_set_math(99) == TG_ERR_INVALID_ARG);
+    CHECK(tg_set_math(TG_MATH_BF16_PIECES) == TG_OK && tg_get_math() == TG_MATH_BF16_PIECES);
+    CHECK(tg_get_config(1, 4096, 4096, 4096, buf, sizeof buf) == TG_OK && buf[0] == 'e');
+    CHECK(tg_set_math(TG_MATH_FP32_MFMA) == TG_OK);
     {
         double bound = 0, model = 0;
         CHECK(tg_num_candidates(1, 4096, 4096, 4096) > 0);

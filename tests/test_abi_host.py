@@ -357,3 +357,36 @@ def test_candidate_argument_checks(lib):
     assert lib.tg_candidate(1, 64, 64, 64, -1, p, 64, None, None) == 1
     assert lib.tg_candidate(1, 64, 64, 64, 0, p, 64, None, None) == 0 and buf.value
     assert lib.tg_candidate(1, 2 ** 31, 64, 64, 0, p, 64, None, None) == 2
+
+
+# --- math mode ------------------------------------------------------------------------------------
+
+def test_math_mode_gates_the_piece_kernels(lib):
+    assert tg.get_math() == tg.MATH_FP32_MFMA
+    assert lib.tg_set_math(7) == 1 and b"math mode" in lib.tg_last_error()
+    shape = (1, 4096, 4096, 4096)
+    try:
+        fp32 = tg.candidates(*shape)
+        assert not any(s.startswith("e") for s, _, _ in fp32)
+        tg.set_math(tg.MATH_BF16_PIECES)
+        assert tg.get_math() == tg.MATH_BF16_PIECES
+        both = tg.candidates(*shape)
+        pieces = {s: (lb, model) for s, lb, model in both if s.startswith("e")}
+        assert set(pieces) == {"e128x256x32_w64x128_x6:s1:g8", "e128x256x32_w64x128_x9:s1:g8"}
+        assert {s for s, _, _ in fp32} == {s for s, _, _ in both} - set(pieces)
+        # bounds: 16/6 and 16/9 of the fp32 pipe's rate
+        chip_us = 1e6 * 2.0 * 4096 ** 3 / (1024 * 64 * 2.4e9)
+        assert pieces["e128x256x32_w64x128_x6:s1:g8"][0] == pytest.approx(chip_us * 6 / 16, rel=1e-9)
+        assert pieces["e128x256x32_w64x128_x9:s1:g8"][0] == pytest.approx(chip_us * 9 / 16, rel=1e-9)
+        # the cost model ranks the six-product kernel first for this size
+        assert tg.get_config(*shape).startswith("e128x256x32_w64x128_x6")
+        # not offered where they cannot run: k not a multiple of 32, or a K range beyond 8192 without a split
+        assert not any(s.startswith("e") for s, _, _ in tg.candidates(1, 4096, 4096, 4080))
+        assert not any(s.startswith("e") for s, _, _ in tg.candidates(1, 512, 512, 16384))
+    finally:
+        tg.set_math(tg.MATH_FP32_MFMA)
+    assert not tg.get_config(*shape).startswith("e")
+    # a forced piece kernel is accepted in either mode
+    tg.force_config("e128x256x32_w64x128_x9")
+    assert tg.get_config(*shape) == "e128x256x32_w64x128_x9:s1:g8"
+    tg.force_config(None)

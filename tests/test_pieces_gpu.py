@@ -1,0 +1,175 @@
+"""GPU parity of the bf16-piece kernels (names starting with "e": every fp32 product formed from six or
+nine products of bf16 pieces on the bf16 matrix instructions, summed in fp32) against the CPU oracle.
+Same bar as the fp32 kernels: per element 1e-5 * sum|a||b|, relative Frobenius 1e-6, integer-valued
+inputs bit exact; plus the cases that are particular to cutting operands into pieces (wide exponent
+ranges, integers that need all three pieces, non-finite inputs) and the math-mode switch."""
+import numpy as np
+import pytest
+
+import paper_1904_03383_amd as tg
+from paper_1904_03383_amd import inputgen as ig
+
+from gpu_common import check_against_oracle, run_hip, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+X6, X9 = "e128x256x32_w64x128_x6", "e128x256x32_w64x128_x9"
+
+
+@pytest.fixture(autouse=True)
+def _clean_library_state():
+    tg.force_config(None)
+    tg.set_workspace(None)
+    tg.set_math(tg.MATH_FP32_MFMA)
+    yield
+    tg.force_config(None)
+    tg.set_workspace(None)
+    tg.set_math(tg.MATH_FP32_MFMA)
+    tg.clear_tune_cache()
+
+
+SHAPES = [(128, 256, 32), (1, 4, 32), (100, 200, 64), (129, 260, 128), (257, 516, 96), (384, 768, 1024), (1000, 1000, 992)]
+
+
+@pytest.mark.parametrize("name", [X6, X9])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_forced_piece_kernel_matches_oracle(name, shape):
+    m, n, k = shape
+    say(f"{name} on {m}x{n}x{k}")
+    tg.force_config(name)
+    for dist in ("uniform", "normal", "int"):
+        a, b = ig.make_operands(1, m, n, k, dist, 701, 702)
+        c = run_hip(a[0], b[0])
+        assert tg.last_config().startswith(name)
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"{name} {shape} {dist}")
+
+
+@pytest.mark.parametrize("name", [X6, X9])
+def test_headline_size_all_elements(name):
+    """4096^3 with the benchmark's operands: every element against the oracle."""
+    say(f"{name} at 4096^3")
+    a, b = ig.make_config("c5_4096")
+    tg.force_config(name)
+    c = run_hip(a[0], b[0])
+    m = check_against_oracle(c, a[0], b[0], what=name + " 4096^3")
+    say(f"  rel_fro {m['rel_fro']:.2e} max_ratio {m['max_ratio']:.2e}")
+    # the leading chain rounds once per 16 terms: better than the fp32 kernels' 5.7e-7 here
+    assert m["rel_fro"] < 5e-7
+
+
+@pytest.mark.parametrize("name", [X6, X9])
+def test_wide_exponent_range(name):
+    """Entries spread over 2^-30 .. 2^30: the pieces keep fp32's exponent range, nothing is scaled."""
+    say(f"{name}, wide exponents")
+    rng = np.random.default_rng(711)
+    m, n, k = 200, 260, 512
+    a = (rng.standard_normal((m, k)) * np.exp2(rng.integers(-30, 31, (m, k)))).astype(np.float32)
+    b = (rng.standard_normal((k, n)) * np.exp2(rng.integers(-30, 31, (k, n)))).astype(np.float32)
+    tg.force_config(name)
+    check_against_oracle(run_hip(a, b), a, b, what=name + " wide exponents")
+
+
+@pytest.mark.parametrize("name", [X6, X9])
+def test_integers_that_need_every_piece(name):
+    """Integers up to 2^11 use two pieces (all four cross products are among the six); up to 2^23 with
+    zero low bits in one operand they use three; sums kept below 2^24 so that fp32 holds them exactly."""
+    say(f"{name}, multi-piece integers")
+    rng = np.random.default_rng(713)
+    tg.force_config(name)
+    a = rng.integers(-2047, 2048, (130, 32)).astype(np.float32)
+    b = rng.integers(-120, 121, (32, 260)).astype(np.float32)
+    check_against_oracle(run_hip(a, b), a, b, exact=True, what=name + " 11-bit x 7-bit")
+    if name == X9:
+        # 23-bit integers times +-1/0: every piece of A matters, only the nine-product form keeps them all
+        a = rng.integers(-(2 ** 22), 2 ** 22, (130, 32)).astype(np.float32)
+        b = np.zeros((32, 260), np.float32)
+        b[rng.integers(0, 32, 260), np.arange(260)] = rng.choice([-1.0, 1.0], 260)
+        check_against_oracle(run_hip(a, b), a, b, exact=True, what=name + " 23-bit selection")
+
+
+def test_batched_padded_and_split_k():
+    import torch
+    say("piece kernel: batch of 3, padded leading dimensions, split-K")
+    batch, m, n, k = 3, 130, 260, 256
+    a, b = ig.make_operands(batch, m, n, k, "int", 721, 722)
+    tg.force_config(X6)
+    c = run_hip(a, b)
+    for i in range(batch):
+        check_against_oracle(c[i], a[i], b[i], exact=True, what=f"batched {i}")
+    # padded rows: operands and result are views into wider buffers
+    da = torch.zeros((m, k + 12), device="cuda"); da[:, :k] = to_dev(a[0])
+    db = torch.zeros((k, n + 8), device="cuda"); db[:, :n] = to_dev(b[0])
+    out = torch.full((m, n + 4), float("nan"), device="cuda")
+    tg.sgemm(da[:, :k], db[:, :n], out=out[:, :n])
+    torch.cuda.synchronize()
+    assert tg.last_config().startswith(X6)
+    check_against_oracle(out[:, :n].cpu().numpy(), a[0], b[0], exact=True, what="padded")
+    assert torch.isnan(out[:, n:]).all()
+    ws = torch.empty(4 * m * n, device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config(X6 + ":s4")
+    check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what="split-K")
+    assert tg.last_config().startswith(X6 + ":s4")
+
+
+def test_k_range_limit_and_validity_messages():
+    import torch
+    say("piece kernel: validity")
+    tg.force_config(X6)
+    a = torch.zeros((128, 48), device="cuda"); b = torch.zeros((48, 256), device="cuda")
+    with pytest.raises(tg.TgemmError, match="multiple of the K tile"):
+        tg.sgemm(a, b)
+    a = torch.zeros((8, 16384), device="cuda"); b = torch.zeros((16384, 8), device="cuda")
+    with pytest.raises(tg.TgemmError, match="K range too long"):
+        tg.sgemm(a, b)
+    ws = torch.empty(2 * 8 * 8, device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config(X6 + ":s2")     # two ranges of 8192
+    a.fill_(1.0); b.fill_(1.0)
+    c = tg.sgemm(a, b)
+    torch.cuda.synchronize()
+    assert (c == 16384.0).all()
+
+
+def test_non_finite_inputs_poison_their_row_or_column():
+    """NaN behaves as in fp32.  An infinite input gives NaN (its remainder inf - inf is NaN), documented as
+    the one difference from fp32 arithmetic on non-finite values."""
+    import torch
+    say("piece kernel: NaN / inf")
+    m, n, k = 128, 256, 64
+    a = torch.ones((m, k), device="cuda"); b = torch.ones((k, n), device="cuda")
+    a[5, 7] = float("nan"); b[9, 100] = float("inf")
+    tg.force_config(X6)
+    c = tg.sgemm(a, b)
+    torch.cuda.synchronize()
+    bad = torch.isnan(c)
+    expect = torch.zeros_like(bad); expect[5, :] = True; expect[:, 100] = True
+    assert torch.equal(bad, expect)
+    assert (c[~bad] == float(k)).all()
+
+
+def test_math_mode_switch_and_tuning():
+    import torch
+    say("math mode: candidates, tuning, cache per mode")
+    m = n = k = 2048
+    names = lambda: [s.split(":")[0] for s, _, _ in tg.candidates(1, m, n, k)]
+    assert tg.get_math() == tg.MATH_FP32_MFMA and not any(x.startswith("e") for x in names())
+    a, b = ig.make_operands(1, m, n, k, "normal", 731, 732)
+    da, db = to_dev(a[0]), to_dev(b[0])
+    tg.tune(da, db, reps=2)
+    tuned_fp32 = tg.last_config()
+    assert not tuned_fp32.startswith("e")
+    tg.set_math(tg.MATH_BF16_PIECES)
+    assert tg.get_math() == tg.MATH_BF16_PIECES and X6 in names() and X9 in names()
+    c = tg.tune(da, db, reps=2)
+    tuned = tg.last_config()
+    say(f"  fp32 mode: {tuned_fp32}; piece mode: {tuned}")
+    check_against_oracle(c.cpu().numpy(), a[0], b[0], what="tuned in piece mode " + tuned)
+    assert tg.get_config(1, m, n, k) == tuned
+    # back in fp32 mode the entry tuned there is used again, never a piece kernel
+    tg.set_math(tg.MATH_FP32_MFMA)
+    assert tg.get_config(1, m, n, k) == tuned_fp32
+    c2 = tg.sgemm(da, db)
+    torch.cuda.synchronize()
+    assert tg.last_config() == tuned_fp32
+    check_against_oracle(c2.cpu().numpy(), a[0], b[0], what="fp32 mode after piece mode")
