@@ -24,6 +24,7 @@ ROOT = pathlib.Path(__file__).resolve().parent
 sys.path.insert(0, str(ROOT))
 
 PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (the opt-in piece kernels run on it)
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 ELEM_TOL, FRO_TOL = 1e-5, 1e-6
 
@@ -243,6 +244,50 @@ def time_strided(tg, torch, steps, warmup, restore_ws):
                              "device_tflops": flops / (gather_ms * 1e-3) / 1e12}}
 
 
+def time_pieces(tg, torch, steps, warmup, reps_tune):
+    """The headline product in the opt-in math mode that forms fp32 products from bf16 pieces on the bf16
+    matrix instructions (fp32 in, fp32 out, same accuracy bar).  Reported beside the headline, never as it:
+    `device_tflops` counts 2mnk (fp32-equivalent work), `bf16_mfma_tflops` the piece products actually issued."""
+    from paper_1904_03383_amd import inputgen as ig
+    name = "c5_4096"
+    batch, m, n, k, dist = ig.CONFIGS[name]
+    a, b = ig.make_config(name)
+    a, b = a[0], b[0]
+    da, db = torch.from_numpy(a).to("cuda"), torch.from_numpy(b).to("cuda")
+    tg.set_math(tg.MATH_BF16_PIECES)
+    try:
+        out = tg.tune(da, db, reps=reps_tune) if reps_tune > 0 else tg.sgemm(da, db)
+        cfg = tg.last_config()
+        stream = torch.cuda.current_stream()
+        for _ in range(warmup):
+            tg.sgemm(da, db, out=out)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for _ in range(steps):
+            tg.sgemm(da, db, out=out)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        assert tg.last_config() == cfg
+    finally:
+        tg.set_math(tg.MATH_FP32_MFMA)
+    dev_ms = ev0.elapsed_time(ev1) / steps
+    flops = algorithmic_flops(batch, m, n, k)
+    pieces = 9 if "_x9" in cfg else 6 if "_x6" in cfg else 0
+    rows = sorted(set(int(r) for r in np.linspace(0, m - 1, num=64)))
+    par = parity_on_rows(a, b, out, rows)
+    res = {"workload": name + " in math mode BF16_PIECES (opt-in)", "batch": batch, "m": m, "n": n, "k": k, "dist": dist,
+           "tile_config": cfg, "device_ms_per_step": dev_ms, "device_tflops": flops / (dev_ms * 1e-3) / 1e12,
+           "frac_mfma_peak": flops / (dev_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
+           "piece_products_per_product": pieces,
+           "parity": {"rows_checked": len(rows), "max_ratio": par["max_ratio"], "rel_fro": par["rel_fro"],
+                      "ok": bool(par["finite"] and par["zero_ok"] and par["max_ratio"] <= ELEM_TOL and par["rel_fro"] <= FRO_TOL)}}
+    if pieces:
+        res["bf16_mfma_tflops"] = pieces * flops / (dev_ms * 1e-3) / 1e12
+        res["frac_bf16_mfma_peak"] = res["bf16_mfma_tflops"] / PEAK_MFMA_BF16_TFLOPS
+    return res
+
+
 def device_info(torch):
     """Name, CU count and current shader clock of the GPU.  The clock comes from sysfs (the active line of
     pp_dpm_sclk), read as a plain file right after the timed region: no child process is started, a process
@@ -391,6 +436,13 @@ def main():
         log(f"  strided matmul 1024^3 (A element stride 32): {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.1f} us  "
             f"{r['device_tflops']:.2f} TFLOP/s  parity_ok={r['parity_ok']}  (no workspace: {r['no_workspace']['tile_config']} "
             f"{r['no_workspace']['device_ms_per_step'] * 1e3:.1f} us)")
+        others.append(r)
+
+    if not args.no_others:
+        r = time_pieces(tg, torch, args.steps, args.warmup, args.tune_reps)
+        log(f"  {r['workload']}: {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.1f} us  {r['device_tflops']:.1f} TFLOP/s fp32-equivalent"
+            f"  rel_fro {r['parity']['rel_fro']:.2e}  parity_ok={r['parity']['ok']}")
+        parity_ok = parity_ok and r["parity"]["ok"]
         others.append(r)
 
     if args.copy_calibration:
