@@ -165,7 +165,12 @@ tg_status tg_force_config(const char *spec);
  *     3.9e-7 (fp32 mode: 5.7e-7); integer-valued inputs stay bit exact.  What differs from fp32
  *     arithmetic: an infinite input gives NaN where fp32 gives infinity; inputs below 2^-110 in magnitude
  *     lose their last pieces to underflow (they are treated as shorter significands).
- * A forced configuration (tg_force_config) may name an "e" kernel in either mode.  Tuned entries are kept
+ *     Kernels whose names start with "c" do the same arithmetic with the operands cut ahead: two passes
+ *     write the pieces of A and B into the workspace (6 bytes per element of A and B, every tile padded
+ *     with zeros; tg_workspace_bytes includes it while this mode is on) and the product streams them in.
+ *     They take any m and k and any alignment of A and B (C's rows 16-byte aligned, n a multiple of 4);
+ *     "e" kernels need 16-byte aligned operands and k a multiple of 32.
+ * A forced configuration (tg_force_config) may name an "e" or "c" kernel in either mode.  Tuned entries are kept
  * per mode.  Returns TG_ERR_INVALID_ARG for an unknown mode.
  */
 #define TG_MATH_FP32_MFMA 0

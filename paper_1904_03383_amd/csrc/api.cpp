@@ -55,6 +55,7 @@ struct Problem {
     const float *B; int64_t ldb, strideB;
     float *C; int64_t ldc, strideC;
     bool aligned;   // every row of A, B, C (and every problem) starts on a 16-byte boundary
+    bool c_aligned = false;   // ... of C alone
     int64_t csa = 1, csb = 1;   // element strides along k of A / along n of B (strided entry point)
     bool unit() const { return csa == 1 && csb == 1; }
 };
@@ -184,6 +185,7 @@ tg_status validate(Problem &p) {
     if (p.m > INT32_MAX || p.n > INT32_MAX || p.k > INT32_MAX || p.batch > INT32_MAX)
         return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    p.c_aligned = a16(p.C) && p.ldc % 4 == 0 && (p.batch <= 1 || p.strideC % 4 == 0);
     p.aligned = a16(p.A) && a16(p.B) && a16(p.C) && p.lda % 4 == 0 && p.ldb % 4 == 0 && p.ldc % 4 == 0 &&
                 (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0 && p.strideC % 4 == 0)) && p.unit();
     return TG_OK;
@@ -235,6 +237,22 @@ size_t ws_need(const Problem &p, int splits) {
     return bytes == INT64_MAX ? SIZE_MAX : (size_t)bytes;
 }
 
+// Bytes of the piece images a cut-ahead kernel writes (A's, then B's; every tile padded to full size).
+size_t planes_need(const Problem &p, const KernelInfo &ki) {
+    if (!ki.precut) return 0;
+    const int64_t rows = sat_mul({ceil_div(p.m, ki.BM), (int64_t)ki.BM}), cols = sat_mul({ceil_div(p.n, ki.BN), (int64_t)ki.BN});
+    if (rows == INT64_MAX || cols == INT64_MAX) return SIZE_MAX;
+    const int64_t bytes = sat_mul({p.batch, ceil_div(p.k, ki.BK), rows + cols, (int64_t)(3 * (ki.BK / 8) * 16)});
+    return bytes == INT64_MAX ? SIZE_MAX : (size_t)bytes;
+}
+
+// Workspace of a configuration: split-K partials (rounded up to 256 bytes), then the piece images.
+size_t ws_total(const Problem &p, const Config &c) {
+    const size_t a = ws_need(p, c.splits), b = planes_need(p, tg::kernel(c.kernel));
+    if (a == SIZE_MAX || b == SIZE_MAX || a > SIZE_MAX - 256 - b) return SIZE_MAX;
+    return b == 0 ? a : (a + 255) / 256 * 256 + b;
+}
+
 // Is this configuration usable for this problem?  (static validity filter of the tuner:
 // divisibility, alignment, accumulation depth, LDS capacity, workspace)
 bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::string *why = nullptr) {
@@ -253,7 +271,14 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         return true;
     }
     if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
-    if (!ki.edge) {
+    if (ki.precut) {
+        // the cutting passes take any A and B; the product kernel stores 16-byte vectors
+        if (!p.c_aligned) return no("C is not 16-byte aligned");
+        if (p.n % 4) return no("n is not a multiple of 4");
+        if (ws_total(p, c) > ws_bytes) return no("workspace too small for the piece images");
+        if (sat_mul({p.batch, ceil_div(p.k, ki.BK), std::max(ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN))}) > INT32_MAX)
+            return no("too many workgroups");
+    } else if (!ki.edge) {
         if (!p.aligned) return no("operands are not 16-byte aligned");
         // K must fill whole tiles; ragged m and n are handled by re-reading the last row / vector
         // and masking the stores (the persistent variants walk exact tiles only)
@@ -277,7 +302,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         return no("K range too long for a single accumulator level");
     if (c.splits > 1) {
         if (per < 2) return no("K range shorter than two tiles");
-        if (ws_need(p, c.splits) > ws_bytes) return no("workspace too small for this split");
+        if (ws_total(p, c) > ws_bytes) return no("workspace too small for this split");
     }
     const int64_t blocks = sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), (int64_t)c.splits, p.batch});
     if (blocks > INT32_MAX) return no("too many workgroups");
@@ -315,6 +340,8 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
     double bytes = 4.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n + (double)p.m * p.n);
     if (splits > 1) bytes += 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n;
     t = std::max(t, bytes / kPeakHbm);
+    // kernels that cut ahead first stream both operands through two passes of their own (4 bytes in, 6 out)
+    if (ki.precut) t += 10.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n) / kPeakHbm;
     return t;
 }
 
@@ -351,10 +378,11 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     if (p.m * 2 <= ki.BM && p.n * 2 <= ki.BN) eff *= 0.8;
     const double block_flops = 2.0 * ki.BM * ki.BN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
     // bf16-piece kernels: 16/pieces times the multiply rate, at about 3/4 of the efficiency (measured)
-    if (ki.pieces) eff = 0.75 * 16.0 / ki.pieces;
+    if (ki.pieces) eff = (ki.precut ? 0.9 : 0.75) * 16.0 / ki.pieces;
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
     double t = launch + per_cu * block_flops / cu_rate;
     if (splits > 1) t += 3e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
+    if (ki.precut) t += 6e-6 + 10.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n) / (kPeakHbm * 0.6);
     return t;
 }
 
@@ -410,7 +438,7 @@ tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
     if (g_forced) {
         std::string why;
         if (!config_valid(p, g_force_cfg, ws_bytes, &why)) {
-            const bool ws_issue = g_force_cfg.splits > 1 && ws_need(p, g_force_cfg.splits) > ws_bytes;
+            const bool ws_issue = ws_total(p, g_force_cfg) > ws_bytes;
             return fail(ws_issue ? TG_ERR_WORKSPACE : TG_ERR_INVALID_ARG,
                         "forced configuration " + spec_of(g_force_cfg) + " is not valid here: " + why);
         }
@@ -485,6 +513,7 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
         split_plan(ki, p.k, c.splits, &g.splits, &g.ktiles_per_split);
         g.ws = static_cast<float *>(ws);
     }
+    if (ki.precut) g.planes = static_cast<char *>(ws) + (ws_need(p, c.splits) + 255) / 256 * 256;
     hipError_t e = ki.launch(g, stream);
     if (e == hipSuccess && g.splits > 1) {
         if (p.n % 4 != 0) g.flags &= ~tg::kFlagVecC;
@@ -794,6 +823,7 @@ tg_status query_problem(int64_t batch, int64_t m, int64_t n, int64_t k, Problem 
     if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     *out = Problem{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, false};
     out->aligned = k % 4 == 0 && n % 4 == 0;
+    out->c_aligned = n % 4 == 0;
     return TG_OK;
 }
 
@@ -886,7 +916,8 @@ size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k) {
     if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return 0;
     Problem p{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, true};
     size_t need = 0;
-    for (const Config &c : candidates(p, SIZE_MAX)) need = std::max(need, ws_need(p, c.splits));
+    p.c_aligned = true;
+    for (const Config &c : candidates(p, SIZE_MAX)) need = std::max(need, ws_total(p, c));
     return need;
 }
 

@@ -80,11 +80,22 @@ TG_DIRECT_LIST(TG_DDECL)
     {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, false, false, (BM / WM) * (BN / WN) * 64, \
      2 * 3 * (BK / 8) * ((BM + 4) + (BN + 4)) * 16, &launch_tile_pieces<BM, BN, BK, WM, WN, NP>, NP},
 TG_PIECES_LIST(TG_EDECL)
+// the same with the operands cut ahead into a workspace image ("c" names)
+#define TG_CDECL(BM, BN, BK, WM, WN, NP, NAME) \
+    extern template hipError_t launch_tile_precut<BM, BN, BK, WM, WN, NP>(const GemmParams &, hipStream_t);
+#define TG_CROW(BM, BN, BK, WM, WN, NP, NAME)                                                   \
+    {"c" NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, false, false, (BM / WM) * (BN / WN) * 64, \
+     2 * 3 * (BK / 8) * (BM + BN) * 16, &launch_tile_precut<BM, BN, BK, WM, WN, NP>, NP, true},
+#define TG_PRECUT_LIST(X)                                                   \
+    X(128, 256, 32, 64, 128, 6, "128x256x32_w64x128_x6")                    \
+    X(128, 256, 32, 64, 128, 9, "128x256x32_w64x128_x9")
+TG_PRECUT_LIST(TG_CDECL)
 
 static const KernelInfo kTable[] = {
     TG_TILE_LIST(TG_ROW)
     TG_DIRECT_LIST(TG_DROW)
     TG_PIECES_LIST(TG_EROW)
+    TG_PRECUT_LIST(TG_CROW)
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")
     TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
     TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")

@@ -17,6 +17,7 @@ struct GemmParams {
     const float *B;
     float *C;             // final output
     float *ws;            // split-K partial sums: [batch][splits][m][n], ld = n (nullptr if splits == 1)
+    void *planes;         // piece images of A and B written by the cutting passes (kernels that cut ahead), else nullptr
     int64_t lda, ldb, ldc;
     int64_t csa, csb;     // element strides along k of A and along n of B (1 except for the strided entry point;
                           // only the predicated kernels honour values other than 1)
@@ -57,6 +58,7 @@ struct KernelInfo {
     int lds_bytes;
     launch_fn launch;
     int pieces;          // 0: fp32 MFMA; 6 or 9: every fp32 product formed from that many bf16 piece products
+    bool precut;         // piece kernel whose operands are cut by separate passes into a workspace image
 };
 
 // Kernel table (registry.cpp).
@@ -85,6 +87,12 @@ template <int BM, int BN, int BK, int WM, int WN, int NP>
 hipError_t launch_tile_pieces(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK>
 constexpr int pieces_lds_bytes();
+
+// The same product with the operands cut ahead: two passes write the pieces of A and B into
+// GemmParams::planes (6 bytes per element, padded to whole tiles), the product kernel streams those images
+// into LDS.  Any m, n, k and any alignment or element stride of A and B; C's rows 16-byte aligned, n % 4 == 0.
+template <int BM, int BN, int BK, int WM, int WN, int NP>
+hipError_t launch_tile_precut(const GemmParams &p, hipStream_t s);
 
 // One wave per 32x32 C tile, operands straight from global memory (small / batched problems).
 hipError_t launch_wave32(const GemmParams &p, hipStream_t s);

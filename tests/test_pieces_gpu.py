@@ -14,6 +14,7 @@ from gpu_common import check_against_oracle, run_hip, say, to_dev
 pytestmark = pytest.mark.gpu
 
 X6, X9 = "e128x256x32_w64x128_x6", "e128x256x32_w64x128_x9"
+C6, C9 = "c128x256x32_w64x128_x6", "c128x256x32_w64x128_x9"   # operands cut ahead into the workspace
 
 
 @pytest.fixture(autouse=True)
@@ -173,3 +174,68 @@ def test_math_mode_switch_and_tuning():
     torch.cuda.synchronize()
     assert tg.last_config() == tuned_fp32
     check_against_oracle(c2.cpu().numpy(), a[0], b[0], what="fp32 mode after piece mode")
+
+
+# ---- kernels that cut the operands ahead (separate passes into a workspace image) ----------------
+
+CUT_AHEAD_SHAPES = [(1, 4, 1), (7, 12, 5), (129, 260, 100), (128, 256, 32), (257, 516, 97), (1000, 1000, 1000), (300, 516, 2052)]
+
+
+@pytest.mark.parametrize("name", [C6, C9])
+@pytest.mark.parametrize("shape", CUT_AHEAD_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_cut_ahead_kernel_any_k(name, shape):
+    """The cutting passes pad with zeros: any m and k (n a multiple of 4 for the vector stores)."""
+    import torch
+    m, n, k = shape
+    say(f"{name} on {m}x{n}x{k}")
+    ws = torch.empty(tg.workspace_bytes(1, m, n, k) // 4 + (1 << 22), device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config(name)
+    for dist in ("normal", "int"):
+        a, b = ig.make_operands(1, m, n, k, dist, 741, 742)
+        c = run_hip(a[0], b[0])
+        assert tg.last_config().startswith(name)
+        check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"{name} {shape} {dist}")
+
+
+def test_cut_ahead_workspace_rules_unaligned_operands_batches_and_split_k():
+    import torch
+    say("cut-ahead kernel: workspace, unaligned A and B, batch, split-K")
+    m, n, k = 130, 260, 250
+    a, b = ig.make_operands(1, m, n, k, "int", 751, 752)
+    tg.force_config(C6)
+    with pytest.raises(tg.TgemmError) as err:         # no workspace: a workspace error that says why
+        tg.sgemm(to_dev(a[0]), to_dev(b[0]))
+    assert err.value.status_name == "TG_ERR_WORKSPACE" and "piece images" in str(err.value)
+    # images: 2 tile rows of 128 and 2 tile columns of 256 over 8 K tiles, 3 planes of 4 chunks of 16 bytes
+    images = 8 * (2 * 128 + 2 * 256) * 3 * 4 * 16
+    tg.set_math(tg.MATH_BF16_PIECES)
+    assert tg.workspace_bytes(1, m, n, k) >= images
+    tg.set_math(tg.MATH_FP32_MFMA)
+    ws = torch.empty(images // 4, device="cuda")
+    tg.set_workspace(ws)
+    check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what="exact-size workspace")
+    # A and B views that start 4 bytes into their buffers and have odd leading dimensions
+    bufa = torch.zeros(m * (k + 3) + 1, device="cuda"); bufb = torch.zeros(k * (n + 1) + 1, device="cuda")
+    da = bufa[1:].view(m, k + 3)[:, :k]; db = bufb[1:].view(k, n + 1)[:, :n]
+    da.copy_(to_dev(a[0])); db.copy_(to_dev(b[0]))
+    out = torch.full((m, n), float("nan"), device="cuda")
+    tg.sgemm(da, db, out=out)
+    torch.cuda.synchronize()
+    assert tg.last_config().startswith(C6)
+    check_against_oracle(out.cpu().numpy(), a[0], b[0], exact=True, what="unaligned A and B")
+    # batch of 3 and split-K (partials first, images after them)
+    a3, b3 = ig.make_operands(3, m, n, k, "int", 753, 754)
+    ws = torch.empty((3 * images + 4 * 3 * m * n * 4 + 1024) // 4, device="cuda")
+    tg.set_workspace(ws)
+    c = run_hip(a3, b3)
+    for i in range(3):
+        check_against_oracle(c[i], a3[i], b3[i], exact=True, what=f"batched {i}")
+    tg.force_config(C6 + ":s4")
+    c = run_hip(a3, b3)
+    assert tg.last_config().startswith(C6 + ":s4")
+    for i in range(3):
+        check_against_oracle(c[i], a3[i], b3[i], exact=True, what=f"batched split-K {i}")
+    # n not a multiple of 4 (C's rows aligned all the same): refused with the reason
+    with pytest.raises(tg.TgemmError, match="multiple of 4"):
+        tg.sgemm(torch.zeros((8, 8), device="cuda"), torch.zeros((8, 6), device="cuda"), out=torch.zeros((8, 8), device="cuda")[:, :6])
