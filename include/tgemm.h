@@ -163,8 +163,11 @@ tg_status tg_force_config(const char *spec);
  *     on the bf16 matrix instructions, which multiply 16 times as fast, and sum in fp32 with the leading
  *     and the small terms in separate accumulators.  Measured relative Frobenius error at k = 4096:
  *     3.9e-7 (fp32 mode: 5.7e-7); integer-valued inputs stay bit exact.  What differs from fp32
- *     arithmetic: an infinite input gives NaN where fp32 gives infinity; inputs below 2^-110 in magnitude
- *     lose their last pieces to underflow (they are treated as shorter significands).
+ *     arithmetic: an infinite input gives NaN where fp32 gives infinity; and the underflow cliff sits
+ *     higher: a product a*b below about 2^-100 in magnitude (say both operands scaled below 2^-50) has
+ *     low-order piece products under 2^-126, which are lost, so where such products dominate an element
+ *     its accuracy degrades towards that of the leading pieces (fp32 arithmetic keeps full relative
+ *     accuracy down to 2^-126).  Products up to the overflow threshold behave as in fp32.
  *     Kernels whose names start with "c" do the same arithmetic with the operands cut ahead: two passes
  *     write the pieces of A and B into the workspace (6 bytes per element of A and B, every tile padded
  *     with zeros; tg_workspace_bytes includes it while this mode is on) and the product streams them in.

@@ -71,6 +71,19 @@ def test_wide_exponent_range(name):
 
 
 @pytest.mark.parametrize("name", [X6, X9])
+@pytest.mark.parametrize("log2_scale", [-45, 55])
+def test_uniformly_tiny_and_huge_operands(name, log2_scale):
+    """Both operands scaled by 2^-45 (products near 2^-90: every piece product still above the underflow
+    threshold) and by 2^55 (sums near 2^120, below overflow): same bar as at unit scale."""
+    say(f"{name}, operands scaled by 2^{log2_scale}")
+    a, b = ig.make_operands(1, 200, 260, 512, "normal", 715, 716)
+    a = (a[0] * np.float32(2.0 ** log2_scale)).astype(np.float32)
+    b = (b[0] * np.float32(2.0 ** log2_scale)).astype(np.float32)
+    tg.force_config(name)
+    check_against_oracle(run_hip(a, b), a, b, what=f"{name} scale 2^{log2_scale}")
+
+
+@pytest.mark.parametrize("name", [X6, X9])
 def test_integers_that_need_every_piece(name):
     """Integers up to 2^11 use two pieces (all four cross products are among the six); up to 2^23 with
     zero low bits in one operand they use three; sums kept below 2^24 so that fp32 holds them exactly."""
