@@ -252,3 +252,63 @@ def test_cut_ahead_workspace_rules_unaligned_operands_batches_and_split_k():
     # n not a multiple of 4 (C's rows aligned all the same): refused with the reason
     with pytest.raises(tg.TgemmError, match="multiple of 4"):
         tg.sgemm(torch.zeros((8, 8), device="cuda"), torch.zeros((8, 6), device="cuda"), out=torch.zeros((8, 8), device="cuda")[:, :6])
+
+
+# ---- seeded random shapes and placements through the piece kernels ------------------------------
+
+def _random_piece_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        batch = int(rng.choice([1, 1, 2, 3]))
+        m = int(rng.integers(1, 400))
+        n = 4 * int(rng.integers(1, 150))
+        k = int(rng.choice([rng.integers(1, 700), 32 * rng.integers(1, 20)]))
+        pads = (int(rng.choice([0, 4, 1, 3])), int(rng.choice([0, 4, 1, 3])), int(rng.choice([0, 4, 8])))   # lda-k, ldb-n, ldc-n
+        offs = (int(rng.choice([0, 4, 1])), int(rng.choice([0, 4, 1])), int(rng.choice([0, 4])))            # element offsets of A, B, C
+        gaps = (int(rng.choice([0, 4, 7])), int(rng.choice([0, 4, 7])), int(rng.choice([0, 4, 8])))         # extra batch strides
+        out.append((batch, m, n, k, pads, offs, gaps, int(rng.integers(0, 3))))
+    return out
+
+
+PIECE_CASES = _random_piece_cases(20261127, 48)
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_random_shapes_and_placements_are_bit_exact(chunk):
+    """Any m and k, n a multiple of 4, A and B anywhere (odd leading dimensions, odd base offsets, odd batch
+    strides), C on 16-byte boundaries: the cut-ahead kernels take all of it; the kernel that cuts in its loop
+    is forced too whenever the case meets its rules (16-byte aligned operands, k a multiple of 32)."""
+    import torch
+    from oracle import oracle
+    from test_random_shapes_gpu import _place
+    ws = torch.empty(1 << 24, device="cuda")       # 64 MiB
+    for idx in range(chunk * 8, chunk * 8 + 8):
+        batch, m, n, k, pads, offs, gaps, pick = PIECE_CASES[idx]
+        a = ig.small_int(9100 + idx, (batch, m, k))
+        b = ig.small_int(9300 + idx, (batch, k, n))
+        aligned = all(x % 4 == 0 for x in pads + offs + gaps) and k % 4 == 0
+        specs = [(C6, C9, C6 + ":s2")[pick]]
+        if specs[0].endswith(":s2") and k <= 96:        # each K range needs at least two K tiles
+            specs = [C6]
+        if aligned and k % 32 == 0:
+            specs.append(X6)
+        _, da = _place(a, pads[0], offs[0], gaps[0], float("nan"))
+        _, db = _place(b, pads[1], offs[1], gaps[1], float("nan"))
+        ref = oracle.sgemm_f64(a, b)
+        for spec in specs:
+            say(f"random piece case {idx}: {spec} batch {batch} {m}x{n}x{k} pads {pads} offsets {offs} gaps {gaps}")
+            tg.set_workspace(ws)
+            tg.force_config(spec)
+            cflat, dc = _place(np.zeros((batch, m, n), np.float32), pads[2], offs[2], gaps[2], 7.0)
+            cflat.fill_(7.0)
+            if batch == 1:
+                tg.sgemm(da[0], db[0], out=dc[0])
+            else:
+                tg.sgemm_batched(da, db, out=dc)
+            torch.cuda.synchronize()
+            assert tg.last_config().startswith(spec)
+            assert np.array_equal(dc.cpu().numpy().astype(np.float64), ref), f"case {idx} ({spec}): result differs from the oracle"
+            mask = torch.ones_like(cflat, dtype=torch.bool)
+            torch.as_strided(mask, (batch, m, n), dc.stride(), offs[2]).fill_(False)
+            assert bool((cflat[mask] == 7.0).all()), f"case {idx} ({spec}): stores outside the output"
