@@ -390,3 +390,25 @@ def test_math_mode_gates_the_piece_kernels(lib):
     tg.force_config("e128x256x32_w64x128_x9")
     assert tg.get_config(*shape) == "e128x256x32_w64x128_x9:s1:g8"
     tg.force_config(None)
+
+
+def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):
+    """A cache file holds the math mode in the shape class (4 x mode + layout class): an entry tuned in the
+    piece mode is used only there."""
+    f = tmp_path / "cache.txt"
+    f.write_text("tgemm-tune-cache 3 gfx950\n"
+                 "1 4096 4096 4096 1 t128x256x32_w64x128_acc2 1 4 0 0 975.0\n"
+                 "1 4096 4096 4096 5 e128x256x32_w64x128_x9 1 2 0 0 830.0\n")
+    try:
+        tg.load_tune_cache(f)
+        assert tg.get_config(1, 4096, 4096, 4096) == "t128x256x32_w64x128_acc2:s1:g4"
+        tg.set_math(tg.MATH_BF16_PIECES)
+        assert tg.get_config(1, 4096, 4096, 4096) == "e128x256x32_w64x128_x9:s1:g2"
+        out = tmp_path / "again.txt"
+        tg.save_tune_cache(out)
+        lines = sorted(out.read_text().splitlines()[1:])
+        assert [l.split()[4:6] for l in lines] == [["1", "t128x256x32_w64x128_acc2"], ["5", "e128x256x32_w64x128_x9"]]
+    finally:
+        tg.set_math(tg.MATH_FP32_MFMA)
+        tg.clear_tune_cache()
+    assert tg.get_config(1, 4096, 4096, 4096).startswith("d128x256x32_w64x128_acc2")
