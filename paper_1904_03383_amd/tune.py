@@ -3,7 +3,8 @@
     python -m paper_1904_03383_amd.tune 4096x4096x4096 1024x1024x1024 512:32x32x64 --out tuned.txt
 
 A shape is ``MxNxK`` or ``BATCH:MxNxK``.  Operands are random, packed and resident in device memory;
-a split-K workspace of the size the library asks for is set for the duration.  Later processes load
+a workspace of the size the library asks for is set for the duration.  ``--math pieces`` tunes for the
+opt-in math mode that also considers the bf16-piece kernels (entries are kept per mode).  Later processes load
 the file with ``tg.load_tune_cache(path)`` (C: ``tg_load_tune_cache``) and never time anything.
 """
 from __future__ import annotations
@@ -29,6 +30,8 @@ def main(argv=None) -> int:
     ap.add_argument("--out", required=True, help="tune cache file to write (merged with --merge)")
     ap.add_argument("--merge", default=None, help="existing tune cache to load first")
     ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--math", choices=["fp32", "pieces"], default="fp32",
+                    help="math mode to tune for (pieces: TG_MATH_BF16_PIECES)")
     args = ap.parse_args(argv)
     shapes = [parse_shape(s) for s in args.shapes]
 
@@ -39,6 +42,7 @@ def main(argv=None) -> int:
     tg.load_library()
     if args.merge:
         tg.load_tune_cache(args.merge)
+    tg.set_math(tg.MATH_BF16_PIECES if args.math == "pieces" else tg.MATH_FP32_MFMA)
     ws_bytes = max(tg.workspace_bytes(*s) for s in shapes)
     ws = torch.empty(max(ws_bytes // 4, 4), dtype=torch.float32, device="cuda")
     tg.set_workspace(ws)
@@ -52,6 +56,7 @@ def main(argv=None) -> int:
         tg.save_tune_cache(args.out)
     finally:
         tg.set_workspace(None)
+        tg.set_math(tg.MATH_FP32_MFMA)
     return 0
 
 
