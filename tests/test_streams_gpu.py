@@ -44,7 +44,7 @@ def test_calls_are_ordered_on_a_side_stream():
     assert torch.equal(twice, out * 2.0) and torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("case", ["sgemm", "batched", "k0", "saxpy", "strided_packed", "split_k"])
+@pytest.mark.parametrize("case", ["sgemm", "batched", "k0", "saxpy", "strided_packed", "split_k", "pieces", "pieces_cut_ahead"])
 def test_graph_capture_replays_match_eager(case):
     """Every entry point captured into a HIP graph; each of several replays (with eager work and
     synchronisation in between, inputs changed before each) must equal the eager result."""
@@ -74,6 +74,18 @@ def test_graph_capture_replays_match_eager(case):
         tg.set_workspace(ws)
         out = torch.empty((256, 256), device="cuda")
         fn = lambda: tg.sgemm_strided(x, y, out=out)
+    elif case == "pieces":
+        x, y = to_dev(ig.small_int(721, (200, 96))), to_dev(ig.small_int(722, (96, 260)))
+        tg.force_config("e128x256x32_w64x128_x6")
+        out = torch.empty((200, 260), device="cuda")
+        fn = lambda: tg.sgemm(x, y, out=out)
+    elif case == "pieces_cut_ahead":              # three kernels per call: two cutting passes and the product
+        x, y = to_dev(ig.small_int(723, (200, 90))), to_dev(ig.small_int(724, (90, 260)))
+        ws = torch.empty(1 << 20, device="cuda")
+        tg.set_workspace(ws)
+        tg.force_config("c128x256x32_w64x128_x9")
+        out = torch.empty((200, 260), device="cuda")
+        fn = lambda: tg.sgemm(x, y, out=out)
     else:
         x, y = to_dev(ig.small_int(719, (128, 1024))), to_dev(ig.small_int(720, (1024, 128)))
         ws = torch.empty(4 * 128 * 128 + 4, device="cuda")
