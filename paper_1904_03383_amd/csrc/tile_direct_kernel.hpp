@@ -339,7 +339,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
                 for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
             }
             // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
-            if (full_tile || (row < p.m && col < p.n)) *reinterpret_cast<bvec *>(dst) = o;
+            if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, p.splits == 1);
         }
     }
 }

@@ -327,7 +327,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
             // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
-            if (full_tile || (row < p.m && col < p.n)) *reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col) = o;
+            if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col), o, p.splits == 1);
         }
     }
 }

@@ -286,7 +286,7 @@ sgemm_tile_precut_kernel(const GemmParams p) {
             cvec o;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
-            if (full_tile || (row < p.m && col < p.n)) *reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col) = o;
+            if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col), o, p.splits == 1);
         }
     }
 }

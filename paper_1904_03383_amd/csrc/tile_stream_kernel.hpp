@@ -253,7 +253,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
                 }
-                *reinterpret_cast<bvec *>(dst) = o;
+                store_result(reinterpret_cast<bvec *>(dst), o, p.splits == 1);
             }
         }
     }
