@@ -379,7 +379,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     const double block_flops = 2.0 * ki.BM * ki.BN * std::min<int64_t>((int64_t)per * ki.BK, p.k);
     // bf16-piece kernels: 16/pieces times the multiply rate; measured at 4096^3 they deliver 53 % of that
     // (cutting in the loop) and 59 % (cut ahead): the bf16 pipe runs at 1.8 GHz under load, not 2.4
-    if (ki.pieces) eff = (ki.precut ? 0.59 : 0.53) * 16.0 / ki.pieces;
+    // (the in-loop cut costs vector instructions in proportion to BM + BN per BM * BN of products: smaller tiles
+    // pay more; measured 0.53 / 0.45 / 0.36 of the bf16 rate for 128x256 / 128x128 / 64x64)
+    if (ki.pieces) {
+        const double tile = ki.precut ? 1.0 : std::min(1.0, 0.55 + 0.45 * ((double)ki.BM * ki.BN / (ki.BM + ki.BN)) / (128.0 * 256 / 384));
+        eff = (ki.precut ? 0.59 : 0.53) * tile * 16.0 / ki.pieces;
+    }
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
     double t = launch + per_cu * block_flops / cu_rate;
     if (splits > 1) t += 3e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);

@@ -73,7 +73,9 @@ TG_DIRECT_LIST(TG_DDECL)
 // bf16-piece variants: (BM, BN, BK, WM, WN, piece products, name)
 #define TG_PIECES_LIST(X)                                                   \
     X(128, 256, 32, 64, 128, 6, "e128x256x32_w64x128_x6")                   \
-    X(128, 256, 32, 64, 128, 9, "e128x256x32_w64x128_x9")
+    X(128, 256, 32, 64, 128, 9, "e128x256x32_w64x128_x9")                   \
+    X(128, 128, 32, 64, 64, 6, "e128x128x32_w64x64_x6")                     \
+    X(64, 64, 32, 32, 32, 6, "e64x64x32_w32x32_x6")
 #define TG_EDECL(BM, BN, BK, WM, WN, NP, NAME) \
     extern template hipError_t launch_tile_pieces<BM, BN, BK, WM, WN, NP>(const GemmParams &, hipStream_t);
 #define TG_EROW(BM, BN, BK, WM, WN, NP, NAME)                                                   \

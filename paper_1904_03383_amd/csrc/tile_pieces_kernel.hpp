@@ -67,8 +67,24 @@ __device__ __forceinline__ void cut_pieces(const float (&x)[8], u32x4 (&out)[3])
     for (int e = 0; e < 8; e += 2) out[2][e / 2] = pack_upper_halves(r[e], r[e + 1]);
 }
 
+// Columns of B per load slot: four (16-byte loads) when that still gives every thread a slot, else two, else one.
+template <int BN, int BK, int NT>
+constexpr int pieces_b_cols() {
+    return (BK / 8) * (BN / 4) >= NT ? 4 : ((BK / 8) * (BN / 2) >= NT ? 2 : 1);
+}
+
+// Small wave tiles leave room for two waves per SIMD (two workgroups per CU cover each other's waits).
+template <int BM, int BN, int BK, int WM, int WN>
+constexpr int pieces_min_waves() {
+    constexpr int nt = (BM / WM) * (BN / WN) * 64;
+    constexpr int acc = 2 * (WM / 32) * (WN / 32) * 16;
+    constexpr int frags = 2 * 3 * 4 * (WM / 32 + 1);
+    constexpr int raw = (BM * BK + BK * BN) / nt;
+    return acc + frags + raw + 64 <= 256 ? 2 : 1;
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int NP>
-__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, 1)
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (pieces_min_waves<BM, BN, BK, WM, WN>()))
 sgemm_tile_pieces_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -77,14 +93,16 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     constexpr int NSTEP = BK / 16;         // MFMA k steps per K tile
     constexpr int A_PITCH = BM + kPiecePadA, B_PITCH = BN + kPiecePadB;   // entries per k chunk
     constexpr int A_STAGE = 3 * NKC * A_PITCH, B_STAGE = 3 * NKC * B_PITCH;
+    constexpr int BC = pieces_b_cols<BN, BK, NT>();   // columns of B per load slot
     constexpr int A_SL = BM * NKC / NT;          // A slots per thread: 8 consecutive k of one row
-    constexpr int B_SL = NKC * (BN / 4) / NT;    // B slots per thread: 8 consecutive k of 4 columns
+    constexpr int B_SL = NKC * (BN / BC) / NT;   // B slots per thread: 8 consecutive k of BC columns
     static_assert(NP == 6 || NP == 9, "6 or 9 piece products per fp32 product");
     static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
-    static_assert(NSTEP >= 2 && NSTEP % 2 == 0 && CB % 2 == 0, "fragment sets alternate per k step and per column block");
-    static_assert((BM * NKC) % NT == 0 && (NKC * (BN / 4)) % NT == 0 && A_SL >= 1 && B_SL >= 1,
+    static_assert(NSTEP >= 2 && NSTEP % 2 == 0, "fragment sets alternate per k step and per group");
+    static_assert((BM * NKC) % NT == 0 && (NKC * (BN / BC)) % NT == 0 && A_SL >= 1 && B_SL >= 1,
                   "tile loads must divide evenly over the workgroup");
+    typedef typename vec_of<BC>::type braw;
 
     extern __shared__ __attribute__((aligned(16))) u32x4 smem_pieces[];
     u32x4 *As = smem_pieces;
@@ -107,11 +125,11 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
     // Slots of the tile loads.  A: slot f = (row f / NKC, k chunk f % NKC): the threads of one row
-    // cover BK*4 contiguous bytes.  B: slot f = (k chunk f / (BN/4), column vector f % (BN/4)).
+    // cover BK*4 contiguous bytes.  B: slot f = (k chunk f / (BN/BC), column group f % (BN/BC)) of BC columns.
     // Rows / vectors past the end of a ragged last tile re-read the last one (in bounds, never stored).
     // Offsets are in bytes and fit 32 bits (checked on the host): scalar base + 32-bit lane offset addressing.
     unsigned a_off[A_SL], b_off[B_SL];
-    int a_dst[A_SL], b_dst[B_SL][4];
+    int a_dst[A_SL], b_dst[B_SL][BC];
 #pragma unroll
     for (int i = 0; i < A_SL; ++i) {
         const int f = tid + i * NT;
@@ -123,18 +141,19 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
 #pragma unroll
     for (int i = 0; i < B_SL; ++i) {
         const int f = tid + i * NT;
-        const int kc = f / (BN / 4), col = (f % (BN / 4)) * 4;
-        const int c = col < p.n - 4 - n0 ? col : p.n - 4 - n0;
+        const int kc = f / (BN / BC), col = (f % (BN / BC)) * BC;
+        const int c = col < p.n - BC - n0 ? col : p.n - BC - n0;   // (n % 4 == 0: at least BC columns exist)
         b_off[i] = ((unsigned)(kc * 8) * (unsigned)p.ldb + (unsigned)c) * 4u;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < BC; ++e) {
             // tile column -> position in the plane: lane-interleaved inside the owning wave's range
             const int j = col + e, jj = j % WN;
             b_dst[i][e] = kc * B_PITCH + (j / WN) * WN + (jj % CB) * 32 + jj / CB;
         }
     }
 
-    f32x4 a_raw[A_SL][2], b_raw[B_SL][8];
+    f32x4 a_raw[A_SL][2];
+    braw b_raw[B_SL][8];
 
     // Raw loads of one K tile, by slot; At / Bt point at that tile.
     auto load_a_slot = [&](const float *At, int i) {
@@ -145,7 +164,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     auto load_b_slot = [&](const float *Bt, int i) {
 #pragma unroll
         for (int r = 0; r < 8; ++r)   // (row base in scalar registers + the thread's 32-bit offset)
-            b_raw[i][r] = *reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(Bt + (int64_t)r * p.ldb) + b_off[i]);
+            b_raw[i][r] = *reinterpret_cast<const braw *>(reinterpret_cast<const char *>(Bt + (int64_t)r * p.ldb) + b_off[i]);
     };
     auto load_tile = [&](const float *At, const float *Bt) {
 #pragma unroll
@@ -155,23 +174,23 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     };
 
     // The cut-and-store work of one K tile in units of 8 values (one LDS entry per piece): units
-    // 0 .. 4*B_SL-1 are the columns of the B slots, the rest the A slots.  Once the last unit of a slot
+    // 0 .. BC*B_SL-1 are the columns of the B slots, the rest the A slots.  Once the last unit of a slot
     // is cut, its registers are free and take the same slot of the tile after (At, Bt): every load
     // then has most of a K tile's MFMAs to arrive.
-    constexpr int N_UNITS = A_SL + 4 * B_SL;
+    constexpr int N_UNITS = A_SL + BC * B_SL;
     auto cut_and_store = [&](int stage, int u) {
         float x[8];
         u32x4 pc[3];
-        if (u < 4 * B_SL) {
-            const int i = u / 4, e4 = u % 4;
+        if (u < BC * B_SL) {
+            const int i = u / BC, ec = u % BC;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = b_raw[i][e][e4];
+            for (int e = 0; e < 8; ++e) x[e] = vec_get(b_raw[i][e], ec);
             cut_pieces(x, pc);
-            u32x4 *dst = Bs + stage * B_STAGE + b_dst[i][e4];
+            u32x4 *dst = Bs + stage * B_STAGE + b_dst[i][ec];
 #pragma unroll
             for (int q = 0; q < 3; ++q) dst[q * NKC * B_PITCH] = pc[q];
         } else {
-            const int i = u - 4 * B_SL;
+            const int i = u - BC * B_SL;
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = a_raw[i][e / 4][e % 4];
             cut_pieces(x, pc);
@@ -181,10 +200,10 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
         }
     };
     auto reload_after = [&](const float *At, const float *Bt, int u) {
-        if (u < 4 * B_SL) {
-            if (u % 4 == 3) load_b_slot(Bt, u / 4);
+        if (u < BC * B_SL) {
+            if (u % BC == BC - 1) load_b_slot(Bt, u / BC);
         } else {
-            load_a_slot(At, u - 4 * B_SL);
+            load_a_slot(At, u - BC * B_SL);
         }
     };
 
@@ -239,8 +258,12 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     // independent vector instructions issue in its shadow at about one cycle each; beyond that every
     // further one costs its full four to five cycles.  Hence four per MFMA below.)
     constexpr int G = NSTEP * CB;
-    static_assert(N_UNITS <= G - 1, "not enough MFMA groups to hide the cut-and-store work");
-    constexpr int N_MFMA = RB * NP;              // MFMAs of one group
+    static_assert(G % 2 == 0, "the B fragment sets alternate per group");
+    constexpr int UPG = (N_UNITS + G - 2) / (G - 1);   // units per group (1 for the large tile)
+    constexpr int N_MFMA = RB * NP;                    // MFMAs of one group
+    // vector instructions of one group's cutting (44 per unit) spread over its MFMAs, four at least
+    constexpr int VALU_PER_MFMA = (UPG * 44 + N_MFMA - 1) / N_MFMA > 4 ? (UPG * 44 + N_MFMA - 1) / N_MFMA : 4;
+    constexpr int MEM_PER_MFMA = (UPG * 11 + N_MFMA - 1) / N_MFMA;   // LDS writes (3 per unit) and reloads (up to 8)
     if (kt_begin < kt_end) {
         const int last = kt_end - 1;
         const float *A0 = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda;
@@ -263,29 +286,35 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
             for (int g = 0; g < G - 1; ++g) {
                 const int step = g / CB, cb = g % CB;
                 if (cb + 1 < CB) {
-                    read_b(stage, step, cb + 1, (cb + 1) & 1);
+                    read_b(stage, step, cb + 1, (g + 1) & 1);
                 } else {
                     read_a(stage, step + 1, (step + 1) & 1);
-                    read_b(stage, step + 1, 0, 0);
+                    read_b(stage, step + 1, 0, (g + 1) & 1);
                 }
-                if (g < N_UNITS) cut_and_store(stage ^ 1, g);
-                if (g < N_UNITS) reload_after(At, Bt, g);
-                mfma_block(step & 1, cb & 1, cb);
+#pragma unroll
+                for (int uu = 0; uu < UPG; ++uu) {
+                    const int u = g * UPG + uu;
+                    if (u < N_UNITS) {
+                        cut_and_store(stage ^ 1, u);
+                        reload_after(At, Bt, u);
+                    }
+                }
+                mfma_block(step & 1, g & 1, cb);
                 // every other instruction in the shadow of an MFMA: the fragment reads first, then the
                 // cuts with their LDS writes and the reloads spread over the group
 #pragma unroll
                 for (int i = 0; i < N_MFMA; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // LDS read
-                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);    // VALU
-                    __builtin_amdgcn_sched_group_barrier(0x220, 1, 0);    // LDS write or global load
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // VALU
+                    __builtin_amdgcn_sched_group_barrier(0x220, MEM_PER_MFMA, 0);    // LDS write or global load
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
             __syncthreads();
             read_a(stage ^ 1, 0, 0);
             read_b(stage ^ 1, 0, 0, 0);
-            mfma_block((NSTEP - 1) & 1, (CB - 1) & 1, CB - 1);
+            mfma_block((NSTEP - 1) & 1, (G - 1) & 1, CB - 1);
             __builtin_amdgcn_sched_group_barrier(0x100, 3 * RB + 3, 0);   // the first fragments of the next tile
             __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -295,12 +324,12 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
         for (int g = 0; g < G; ++g) {
             const int step = g / CB, cb = g % CB;
             if (cb + 1 < CB) {
-                read_b(stage, step, cb + 1, (cb + 1) & 1);
+                read_b(stage, step, cb + 1, (g + 1) & 1);
             } else if (step + 1 < NSTEP) {
                 read_a(stage, step + 1, (step + 1) & 1);
-                read_b(stage, step + 1, 0, 0);
+                read_b(stage, step + 1, 0, (g + 1) & 1);
             }
-            mfma_block(step & 1, cb & 1, cb);
+            mfma_block(step & 1, g & 1, cb);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -324,8 +353,12 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
         for (int v = 0; v < 16; ++v) {
             const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
             cvec o;
+            if constexpr (CB == 1) {
+                o = acc_hi[rb][0][v] + acc_lo[rb][0][v];
+            } else {
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
+                for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
+            }
             // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
             if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col), o, p.splits == 1);
         }

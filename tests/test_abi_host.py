@@ -372,7 +372,8 @@ def test_math_mode_gates_the_piece_kernels(lib):
         assert tg.get_math() == tg.MATH_BF16_PIECES
         both = tg.candidates(*shape)
         pieces = {s: (lb, model) for s, lb, model in both if s.startswith("e")}
-        assert set(pieces) == {"e128x256x32_w64x128_x6:s1:g8", "e128x256x32_w64x128_x9:s1:g8"}
+        assert set(pieces) == {"e128x256x32_w64x128_x6:s1:g8", "e128x256x32_w64x128_x9:s1:g8",
+                               "e128x128x32_w64x64_x6:s1:g8", "e64x64x32_w32x32_x6:s1:g8"}
         assert {s for s, _, _ in fp32} == {s for s, _, _ in both} - set(pieces)
         # bounds: 16/6 and 16/9 of the fp32 pipe's rate
         chip_us = 1e6 * 2.0 * 4096 ** 3 / (1024 * 64 * 2.4e9)

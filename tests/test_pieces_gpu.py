@@ -14,6 +14,7 @@ from gpu_common import check_against_oracle, run_hip, say, to_dev
 pytestmark = pytest.mark.gpu
 
 X6, X9 = "e128x256x32_w64x128_x6", "e128x256x32_w64x128_x9"
+E128, E64 = "e128x128x32_w64x64_x6", "e64x64x32_w32x32_x6"     # smaller tiles of the same kernel
 C6, C9 = "c128x256x32_w64x128_x6", "c128x256x32_w64x128_x9"   # operands cut ahead into the workspace
 
 
@@ -32,7 +33,7 @@ def _clean_library_state():
 SHAPES = [(128, 256, 32), (1, 4, 32), (100, 200, 64), (129, 260, 128), (257, 516, 96), (384, 768, 1024), (1000, 1000, 992)]
 
 
-@pytest.mark.parametrize("name", [X6, X9])
+@pytest.mark.parametrize("name", [X6, X9, E128, E64])
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_forced_piece_kernel_matches_oracle(name, shape):
     m, n, k = shape
@@ -58,7 +59,7 @@ def test_headline_size_all_elements(name):
     assert m["rel_fro"] < 5e-7
 
 
-@pytest.mark.parametrize("name", [X6, X9])
+@pytest.mark.parametrize("name", [X6, X9, E128, E64])
 def test_wide_exponent_range(name):
     """Entries spread over 2^-30 .. 2^30: the pieces keep fp32's exponent range, nothing is scaled."""
     say(f"{name}, wide exponents")
@@ -292,7 +293,7 @@ def test_random_shapes_and_placements_are_bit_exact(chunk):
         if specs[0].endswith(":s2") and k <= 96:        # each K range needs at least two K tiles
             specs = [C6]
         if aligned and k % 32 == 0:
-            specs.append(X6)
+            specs.append((X6, E128, E64)[idx % 3])
         _, da = _place(a, pads[0], offs[0], gaps[0], float("nan"))
         _, db = _place(b, pads[1], offs[1], gaps[1], float("nan"))
         ref = oracle.sgemm_f64(a, b)
