@@ -313,3 +313,19 @@ def test_random_shapes_and_placements_are_bit_exact(chunk):
             mask = torch.ones_like(cflat, dtype=torch.bool)
             torch.as_strided(mask, (batch, m, n), dc.stride(), offs[2]).fill_(False)
             assert bool((cflat[mask] == 7.0).all()), f"case {idx} ({spec}): stores outside the output"
+
+
+@pytest.mark.parametrize("name", [X6, X9, C6])
+def test_longest_k_range_keeps_the_bar(name):
+    """K = 8192 is the longest range one workgroup may take (512 roundings of the leading chain); twice that
+    goes through split-K.  Same bar as everywhere."""
+    import torch
+    say(f"{name} at K = 8192 and 16384")
+    ws = torch.empty(1 << 25, device="cuda")
+    tg.set_workspace(ws)
+    for k, spec in ((8192, name), (16384, name + ":s2")):
+        a, b = ig.make_operands(1, 192, 260, k, "normal", 761, 762)
+        tg.force_config(spec)
+        c = run_hip(a[0], b[0])
+        m = check_against_oracle(c, a[0], b[0], what=f"{spec} K={k}")
+        say(f"  {spec} K={k}: rel_fro {m['rel_fro']:.2e}")
