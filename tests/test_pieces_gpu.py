@@ -329,3 +329,27 @@ def test_longest_k_range_keeps_the_bar(name):
         c = run_hip(a[0], b[0])
         m = check_against_oracle(c, a[0], b[0], what=f"{spec} K={k}")
         say(f"  {spec} K={k}: rel_fro {m['rel_fro']:.2e}")
+
+
+def test_worst_case_for_the_dropped_terms():
+    """Every element has an all-ones significand (2 - 2^-23 times a power of two), all of one sign: the three
+    piece products that the six-product form leaves out are then as large as they can be, about 2^-23 of each
+    product, and all add up.  Both forms must stay within the bars, and the difference between them must be
+    what the dropped terms explain: present, and at most 2^-22 of sum|a||b|."""
+    from oracle import oracle
+    say("six against nine products, all-ones significands")
+    rng = np.random.default_rng(771)
+    m, n, k = 130, 260, 4096
+    ones = np.float32(2.0) - np.float32(2.0 ** -23)
+    a = (ones * np.exp2(rng.integers(-3, 4, (m, k)))).astype(np.float32)
+    b = (ones * np.exp2(rng.integers(-3, 4, (k, n)))).astype(np.float32)
+    out = {}
+    for name in (X6, X9):
+        tg.force_config(name)
+        out[name] = run_hip(a, b)
+        mm = check_against_oracle(out[name], a, b, what=name + " all-ones significands")
+        say(f"  {name}: rel_fro {mm['rel_fro']:.2e} max_ratio {mm['max_ratio']:.2e}")
+    _, s_abs = oracle.sgemm_f64(a, b, want_abs=True)
+    gap = (out[X9].astype(np.float64) - out[X6].astype(np.float64)) / s_abs
+    say(f"  (nine - six) / sum|a||b|: mean {gap.mean():.2e} max {gap.max():.2e}")
+    assert 2.0 ** -25 < gap.mean() < 2.0 ** -22 and gap.max() < 2.0 ** -21 and gap.min() > -2.0 ** -22
