@@ -142,9 +142,12 @@ size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k);
 size_t tg_strided_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t csa, int64_t csb);
 
 /*
- * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>][:p<n>]", e.g.
+ * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>][:p<n>][:t<rows>x<splits>]", e.g.
  * "t128x128x16_w64x64:s1:g8" (split-K factor; tile rows per ordering group; cap on
- * workgroups per CU; persistent launch with n workgroups per CU that loop over the tiles);
+ * workgroups per CU; persistent launch with n workgroups per CU that loop over the tiles;
+ * tail split: the last <rows> tile rows of every problem go out as a second launch with split-K
+ * <splits>, which fills the chip once more for a fraction of a round when the tile count is a little
+ * above a multiple of what the chip holds; needs the workspace like any split-K);
  * kernel names are listed by tg_kernel_name.
  * tg_force_config(spec) makes every later call use that configuration when it is valid
  * for the problem (otherwise the call fails with TG_ERR_INVALID_ARG, or TG_ERR_WORKSPACE

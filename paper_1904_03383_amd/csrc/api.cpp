@@ -47,6 +47,11 @@ struct Config {
     int group = kDefaultGroup;
     int occ = 0;   // cap on workgroups per CU (0 = whatever fits)
     int persist = 0;   // > 0: persistent launch with this many workgroups per CU
+    // Tail split: the last `tail` tile rows of every problem go out as a second launch with split-K
+    // `tail_splits`, so that a tile count just above a multiple of what the chip holds does not cost a
+    // whole extra round of workgroups (0 = one launch).
+    int tail = 0;
+    int tail_splits = 1;
 };
 
 struct Problem {
@@ -88,6 +93,7 @@ std::string spec_of(const Config &c) {
     int n = snprintf(buf, sizeof buf, "%s:s%d:g%d", tg::kernel(c.kernel).name, c.splits, c.group);
     if (c.occ > 0) n += snprintf(buf + n, sizeof buf - n, ":o%d", c.occ);
     if (c.persist > 0) n += snprintf(buf + n, sizeof buf - n, ":p%d", c.persist);
+    if (c.tail > 0) n += snprintf(buf + n, sizeof buf - n, ":t%dx%d", c.tail, c.tail_splits);
     return buf;
 }
 
@@ -97,7 +103,7 @@ int find_kernel(const std::string &name) {
     return -1;
 }
 
-// "<kernel>[:s<splits>][:g<group>][:o<cap on workgroups per CU>][:p<persistent workgroups per CU>]"
+// "<kernel>[:s<splits>][:g<group>][:o<cap on workgroups per CU>][:p<persistent workgroups per CU>][:t<tail tile rows>x<tail splits>]"
 bool parse_spec(const char *spec, Config &out, std::string &why) {
     std::string s(spec);
     size_t pos = s.find(':');
@@ -108,9 +114,19 @@ bool parse_spec(const char *spec, Config &out, std::string &why) {
     while (pos != std::string::npos) {
         size_t next = s.find(':', pos + 1);
         std::string tok = s.substr(pos + 1, next == std::string::npos ? std::string::npos : next - pos - 1);
-        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g' && tok[0] != 'o' && tok[0] != 'p')) { why = "bad token '" + tok + "'"; return false; }
+        if (tok.size() < 2 || (tok[0] != 's' && tok[0] != 'g' && tok[0] != 'o' && tok[0] != 'p' && tok[0] != 't')) { why = "bad token '" + tok + "'"; return false; }
         char *end = nullptr;
         long v = strtol(tok.c_str() + 1, &end, 10);
+        if (tok[0] == 't') {   // t<rows>x<splits>
+            if (*end != 'x' || v < 1 || v > 4096) { why = "bad value in '" + tok + "'"; return false; }
+            char *end2 = nullptr;
+            const long v2 = strtol(end + 1, &end2, 10);
+            if (end2 == end + 1 || *end2 != '\0' || v2 < 2 || v2 > 4096) { why = "bad value in '" + tok + "'"; return false; }
+            c.tail = (int)v;
+            c.tail_splits = (int)v2;
+            pos = next;
+            continue;
+        }
         if (*end != '\0' || v < 1 || v > 4096) { why = "bad value in '" + tok + "'"; return false; }
         if (tok[0] == 's') c.splits = (int)v;
         else if (tok[0] == 'g') c.group = (int)v;
@@ -246,8 +262,43 @@ size_t planes_need(const Problem &p, const KernelInfo &ki) {
     return bytes == INT64_MAX ? SIZE_MAX : (size_t)bytes;
 }
 
+// The two launches of a configuration with a tail split: rows [0, m1) with the configuration as it
+// stands, rows [m1, m) with split-K tail_splits.  (Every problem of a batch is cut at the same row.)
+void tail_parts(const Problem &p, const Config &c, Problem *p1, Config *c1, Problem *p2, Config *c2) {
+    const KernelInfo &ki = tg::kernel(c.kernel);
+    const int64_t m1 = (ceil_div(p.m, ki.BM) - c.tail) * ki.BM;
+    *p1 = p;
+    p1->m = m1;
+    *p2 = p;
+    p2->m = p.m - m1;
+    if (p.A) p2->A = p.A + m1 * p.lda;
+    if (p.C) p2->C = p.C + m1 * p.ldc;
+    *c1 = c;
+    c1->tail = 0;
+    c1->tail_splits = 1;
+    *c2 = *c1;
+    c2->splits = c.tail_splits;
+    // a tail range of at most kLongK terms does not need the second accumulator level: same tile without it
+    if (ki.two_level) {
+        int sp, per;
+        split_plan(ki, p.k, c.tail_splits, &sp, &per);
+        const std::string name = ki.name;
+        const size_t at = name.find("_acc2");
+        if ((int64_t)per * ki.BK <= kLongK && at != std::string::npos) {
+            const int sib = find_kernel(name.substr(0, at) + name.substr(at + 5));
+            if (sib >= 0) c2->kernel = sib;
+        }
+    }
+}
+
 // Workspace of a configuration: split-K partials (rounded up to 256 bytes), then the piece images.
 size_t ws_total(const Problem &p, const Config &c) {
+    if (c.tail > 0 && c.kernel >= 0 && c.tail < ceil_div(p.m, tg::kernel(c.kernel).BM)) {
+        Problem p1, p2;
+        Config c1, c2;
+        tail_parts(p, c, &p1, &c1, &p2, &c2);
+        return ws_total(p2, c2);
+    }
     const size_t a = ws_need(p, c.splits), b = planes_need(p, tg::kernel(c.kernel));
     if (a == SIZE_MAX || b == SIZE_MAX || a > SIZE_MAX - 256 - b) return SIZE_MAX;
     return b == 0 ? a : (a + 255) / 256 * 256 + b;
@@ -263,6 +314,16 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     if (c.occ < 0 || c.occ > 16) return no("occupancy cap must be 0..16");
     if (c.persist < 0 || c.persist > 16) return no("persistent workgroups per CU must be 0..16");
     if ((c.persist > 0) != ki.persistent) return no("p<n> goes with the persistent kernel variants (names starting with p), and only with them");
+    if (c.tail != 0) {
+        if (c.tail < 0 || c.tail_splits < 2) return no("a tail split needs t<rows>x<splits> with rows >= 1 and splits >= 2");
+        if (ki.kind != tg::KIND_TILE || ki.persistent || ki.precut) return no("no tail split for this kernel");
+        if (c.splits != 1) return no("a tail split goes with s1");
+        if (c.tail >= ceil_div(p.m, ki.BM)) return no("the tail must leave at least one tile row");
+        Problem p1, p2;
+        Config c1, c2;
+        tail_parts(p, c, &p1, &c1, &p2, &c2);
+        return config_valid(p1, c1, ws_bytes, why) && config_valid(p2, c2, ws_bytes, why);
+    }
     if (ki.kind == tg::KIND_WAVE) {
         if (!p.unit()) return no("the wave kernel needs unit element strides");
         if (c.splits != 1) return no("the wave kernel has no split-K");
@@ -314,6 +375,12 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
 // than exist, and operands/results cross HBM at least once (Sec. 5.1 of the paper prunes
 // candidates with such a bound; this is the flat-set version of that cut).
 double lower_bound_seconds(const Problem &p, const Config &c) {
+    if (c.tail > 0) {   // two launches, one after the other
+        Problem p1, p2;
+        Config c1, c2;
+        tail_parts(p, c, &p1, &c1, &p2, &c2);
+        return lower_bound_seconds(p1, c1) + lower_bound_seconds(p2, c2);
+    }
     const KernelInfo &ki = tg::kernel(c.kernel);
     const double flops = 2.0 * p.batch * p.m * p.n * p.k;
     // the bf16 pipe multiplies 16x as fast as the fp32 one, and a piece kernel needs `pieces` products per product
@@ -348,6 +415,12 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
 // Rough cost model used only to rank candidates and as the fallback when nothing is tuned.
 // A CU delivers its MFMA rate once it holds four waves; workgroups beyond one per CU queue up.
 double heuristic_seconds(const Problem &p, const Config &c) {
+    if (c.tail > 0) {   // the second launch follows the first without a host round trip
+        Problem p1, p2;
+        Config c1, c2;
+        tail_parts(p, c, &p1, &c1, &p2, &c2);
+        return heuristic_seconds(p1, c1) + heuristic_seconds(p2, c2) - 2e-6;
+    }
     const KernelInfo &ki = tg::kernel(c.kernel);
     const double launch = 4e-6;
     if (ki.kind == tg::KIND_WAVE) {
@@ -420,6 +493,34 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             out.push_back(c);
         }
     }
+    // Tail splits: when the tile count is a little above a multiple of what the chip holds at once, the
+    // last round would run nearly empty; its tile rows go out as a second launch, split along K so that
+    // they fill the chip once more for a fraction of a round.
+    if (p.batch == 1) {
+        const size_t n_plain = out.size();
+        for (size_t i = 0; i < n_plain; ++i) {
+            const Config base = out[i];
+            const KernelInfo &k = tg::kernel(base.kernel);
+            if (k.kind != tg::KIND_TILE || k.persistent || k.precut || base.splits != 1) continue;
+            const int64_t tm = ceil_div(p.m, k.BM), tn = ceil_div(p.n, k.BN), tiles = tm * tn;
+            for (int per_cu = 1; per_cu <= 2; ++per_cu) {
+                if (per_cu * k.lds_bytes > kLdsPerCU) break;
+                const int64_t slots = (int64_t)kNumCUs * per_cu;
+                const int64_t rest = tiles % slots;
+                if (tiles <= slots || rest == 0 || 2 * rest > slots) continue;
+                const int64_t rows = ceil_div(rest, tn);
+                if (rows >= tm) continue;
+                int split = 0;
+                for (int sp : kSplits)
+                    if (sp >= 2 && rows * tn * sp <= slots) split = sp;
+                if (split == 0) continue;
+                Config h = base;
+                h.tail = (int)rows;
+                h.tail_splits = split;
+                if (config_valid(p, h, ws_bytes)) out.push_back(h);
+            }
+        }
+    }
     // an edge kernel is only interesting when no exact-fit kernel exists
     bool have_exact = false;
     for (const Config &c : out)
@@ -490,6 +591,13 @@ void choose_xcd_split(const KernelInfo &ki, const Problem &p, GemmParams &g) {
 }
 
 tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream) {
+    if (c.tail > 0) {
+        Problem p1, p2;
+        Config c1, c2;
+        tail_parts(p, c, &p1, &c1, &p2, &c2);
+        const tg_status st = launch(p1, c1, ws, stream);
+        return st != TG_OK ? st : launch(p2, c2, ws, stream);
+    }
     const KernelInfo &ki = tg::kernel(c.kernel);
     GemmParams g;
     memset(&g, 0, sizeof g);
@@ -1021,14 +1129,14 @@ tg_status tg_save_tune_cache(const char *path) {
     if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
     FILE *f = fopen(path, "w");
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
-    fprintf(f, "tgemm-tune-cache 3 gfx950\n");
+    fprintf(f, "tgemm-tune-cache 4 gfx950\n");
     std::lock_guard<std::mutex> lk(g_mutex);
     for (const auto &kv : g_cache) {
         const ShapeKey &k = kv.first;
-        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
+        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
                 (long long)std::get<2>(k), (long long)std::get<3>(k), std::get<4>(k),
                 tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.cfg.occ,
-                kv.second.cfg.persist, kv.second.usec);
+                kv.second.cfg.persist, kv.second.cfg.tail, kv.second.cfg.tail_splits, kv.second.usec);
     }
     fclose(f);
     return TG_OK;
@@ -1040,25 +1148,37 @@ tg_status tg_load_tune_cache(const char *path) {
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
     char head[64] = {0}, arch[32] = {0};
     int ver = 0;
-    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || ver != 3 ||
+    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || (ver != 3 && ver != 4) ||
         strcmp(arch, "gfx950") != 0) {
         fclose(f);
-        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3)");
+        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3 or 4)");
     }
     std::lock_guard<std::mutex> lk(g_mutex);
-    long long b, m, n, k;
-    int al, splits, group, occ, persist;
-    char name[128];
-    double us;
-    while (fscanf(f, "%lld %lld %lld %lld %d %127s %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ,
-                  &persist, &us) == 11) {
+    // one entry per line; version 4 added the two tail-split fields before the time
+    char line[512];
+    while (fgets(line, sizeof line, f)) {
+        long long b, m, n, k;
+        int al, splits, group, occ, persist, tail = 0, tail_splits = 1;
+        char name[128];
+        double us;
+        int got;
+        if (ver == 3)
+            got = sscanf(line, "%lld %lld %lld %lld %d %127s %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ,
+                         &persist, &us) == 11;
+        else
+            got = sscanf(line, "%lld %lld %lld %lld %d %127s %d %d %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group,
+                         &occ, &persist, &tail, &tail_splits, &us) == 13;
+        if (!got) continue;
         Config c;
         c.kernel = find_kernel(name);
         c.splits = splits;
         c.group = group;
         c.occ = occ;
         c.persist = persist;
-        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0 || persist < 0) continue;   // entry from another build: ignore
+        c.tail = tail;
+        c.tail_splits = tail_splits;
+        // entry from another build or a damaged line: ignore
+        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0 || persist < 0 || tail < 0 || tail_splits < 1) continue;
         g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
     }
     fclose(f);

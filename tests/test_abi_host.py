@@ -198,9 +198,23 @@ def test_tune_cache_file_round_trip(tmp_path, lib):
         tg.save_tune_cache(out)
         text = out.read_text().splitlines()
         assert tg.get_config(1, 512, 512, 512) == "p128x128x32_w64x64:s1:g2:o2:p3"
-        assert text[0] == "tgemm-tune-cache 3 gfx950" and len(text) == 3
-        assert text[1].startswith("1 512 512 512 1 p128x128x32_w64x64 1 2 2 3")
-        assert text[2].startswith("1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 0")
+        # written in the current format (version 4: two tail-split fields before the time); version 3 files load
+        assert text[0] == "tgemm-tune-cache 4 gfx950" and len(text) == 3
+        assert text[1].startswith("1 512 512 512 1 p128x128x32_w64x64 1 2 2 3 0 1 ")
+        assert text[2].startswith("1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 0 0 1 ")
+        v4 = tmp_path / "v4.txt"
+        v4.write_text("tgemm-tune-cache 4 gfx950\n"
+                      "1 3072 3072 3072 1 t128x256x32_w64x128_acc2 1 8 0 0 3 6 440.0\n"
+                      "this line is damaged\n"
+                      "1 640 512 256 1 t128x128x16_w64x64 1 2 0 0 0 1 9.0\n")
+        tg.clear_tune_cache()
+        tg.load_tune_cache(v4)
+        assert tg.get_config(1, 640, 512, 256) == "t128x128x16_w64x64:s1:g2"
+        # (the tail-split entry needs a workspace to be used; without one the heuristic answers)
+        assert ":t" not in tg.get_config(1, 3072, 3072, 3072)
+        lib.tg_set_workspace(ctypes.c_void_p(0x10000), 1 << 30)
+        assert tg.get_config(1, 3072, 3072, 3072) == "t128x256x32_w64x128_acc2:s1:g8:t3x6"
+        lib.tg_set_workspace(None, 0)
         bad = tmp_path / "bad.txt"
         bad.write_text("something else\n")
         with pytest.raises(tg.TgemmError):
@@ -391,6 +405,40 @@ def test_math_mode_gates_the_piece_kernels(lib):
     tg.force_config("e128x256x32_w64x128_x9")
     assert tg.get_config(*shape) == "e128x256x32_w64x128_x9:s1:g8"
     tg.force_config(None)
+
+
+def test_tail_split_grammar_validity_and_candidates(lib):
+    """t<rows>x<splits>: the last tile rows go out as a second launch with split-K (Sec. 5.1's space grows by
+    one decision; here it is offered when the tile count is a little above a multiple of the chip's slots)."""
+    for bad in ("t128x256x32_w64x128_acc2:t3", "t128x256x32_w64x128_acc2:t0x4", "t128x256x32_w64x128_acc2:t3x1", "t128x256x32_w64x128_acc2:tx4"):
+        assert lib.tg_force_config(bad.encode()) == 1, bad
+    try:
+        lib.tg_set_workspace(ctypes.c_void_p(0x10000), 1 << 30)
+        tg.force_config("t128x256x32_w64x128_acc2:t3x6")
+        assert tg.get_config(1, 3072, 3072, 3072) == "t128x256x32_w64x128_acc2:s1:g8:t3x6"
+        buf = ctypes.create_string_buffer(256)
+        p = ctypes.cast(buf, ctypes.c_void_p)
+        tg.force_config("t128x256x32_w64x128_acc2:t24x2")          # 3072 rows are 24 tile rows: none left for the first launch
+        assert lib.tg_get_config(1, 3072, 3072, 3072, p, 256) == 1 and b"at least one tile row" in lib.tg_last_error()
+        tg.force_config("p128x128x16_w64x64:p1:t1x2")
+        assert lib.tg_get_config(1, 1024, 1024, 64, p, 256) == 1 and b"no tail split" in lib.tg_last_error()
+        tg.force_config("t128x256x32_w64x128_acc2:s2:t3x6")
+        assert lib.tg_get_config(1, 3072, 3072, 3072, p, 256) == 1 and b"goes with s1" in lib.tg_last_error()
+        tg.force_config(None)
+        # 3072^3 on 128x256 tiles: 288 tiles = 256 + 32 -> the last 3 tile rows (36 tiles), split 6 ways
+        specs = {s: (lb, model) for s, lb, model in tg.candidates(1, 3072, 3072, 3072)}
+        assert "t128x256x32_w64x128_acc2:s1:g8:t3x6" in specs and "d128x256x32_w64x128_acc2:s1:g8:t3x6" in specs
+        plain, tail = specs["t128x256x32_w64x128_acc2:s1:g8"], specs["t128x256x32_w64x128_acc2:s1:g8:t3x6"]
+        assert tail[1] < 0.75 * plain[1]              # the cost model sees one round and a bit instead of two
+        assert tail[0] <= tail[1]
+        # 4096^3 fills its two rounds exactly: nothing to split off
+        assert not any(":t" in s for s, _, _ in tg.candidates(1, 4096, 4096, 4096))
+        # and without a workspace no tail split is offered
+        lib.tg_set_workspace(None, 0)
+        assert not any(":t" in s for s, _, _ in tg.candidates(1, 3072, 3072, 3072))
+    finally:
+        tg.force_config(None)
+        lib.tg_set_workspace(None, 0)
 
 
 def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):

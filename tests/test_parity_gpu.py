@@ -488,3 +488,48 @@ def test_lower_bound_of_every_candidate_holds_on_the_device(shape):
         worst = min(worst, (us / bound_us, spec))
         assert us >= bound_us, f"{spec}: {us:.2f} us measured is below its lower bound {bound_us:.2f} us"
     say(f"  {len(cands)} candidates; tightest: {worst[1]} at {worst[0]:.2f}x its bound")
+
+
+# ---- tail split: the last tile rows as a second launch with split-K -----------------------------
+
+TAIL_SPLITS = [("t128x128x16_w64x64:t1x2", (1, 700, 520, 256)), ("t128x256x32_w64x128_acc2:t2x3", (1, 640, 516, 2112)),
+               ("d128x128x32_w64x64:t1x4", (1, 300, 260, 512)), ("t64x64x32_w32x32:t3x2", (1, 500, 200, 192)),
+               ("t128x128x32_w64x64_acc2:t1x2", (3, 390, 132, 2080)), ("t128x128x16_w64x64_edge:t2x2", (1, 517, 203, 301))]
+
+
+@pytest.mark.parametrize("spec,shape", TAIL_SPLITS, ids=lambda v: v if isinstance(v, str) else "x".join(map(str, v)))
+def test_tail_split_matches_oracle(spec, shape):
+    import torch
+    batch, m, n, k = shape
+    say(f"tail split {spec} on {shape}")
+    ws = torch.empty(8 * batch * 256 * n + 64, device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config(spec)
+    for dist in ("normal", "int"):
+        a, b = ig.make_operands(batch, m, n, k, dist, 351, 352)
+        c = run_hip(a[0], b[0]) if batch == 1 else run_hip(a, b)
+        assert tg.last_config().endswith(spec.split(":", 1)[1]) and tg.last_config().startswith(spec.split(":")[0])
+        for i in range(batch):
+            check_against_oracle(c if batch == 1 else c[i], a[i], b[i], exact=(dist == "int"), what=f"{spec} {shape} {dist}")
+
+
+def test_tuner_offers_and_times_tail_splits():
+    """3072^3 on 128x256 tiles is 288 tiles for 256 CUs: the tuner must at least consider a tail split, and
+    whatever it picks must match the oracle on sampled rows and not be slower than the best single launch."""
+    import torch
+    say("tuner at 3072^3 with workspace")
+    m = n = k = 3072
+    a, b = ig.make_operands(1, m, n, k, "normal", 361, 362)
+    da, db = to_dev(a[0]), to_dev(b[0])
+    ws = torch.empty(tg.workspace_bytes(1, m, n, k) // 4 + 64, device="cuda")
+    tg.set_workspace(ws)
+    assert any(":t" in s for s, _, _ in tg.candidates(1, m, n, k))
+    tg.clear_tune_cache()
+    try:
+        c = tg.tune(da, db, reps=2)
+        tuned = tg.last_config()
+        say(f"  tuned {tuned}")
+        rows = np.linspace(0, m - 1, 48).astype(int)
+        check_against_oracle(c.cpu().numpy()[rows], a[0][rows], b[0], what="tuned 3072^3 " + tuned)
+    finally:
+        tg.clear_tune_cache()
