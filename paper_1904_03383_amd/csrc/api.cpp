@@ -507,17 +507,25 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
                 if (per_cu * k.lds_bytes > kLdsPerCU) break;
                 const int64_t slots = (int64_t)kNumCUs * per_cu;
                 const int64_t rest = tiles % slots;
-                if (tiles <= slots || rest == 0 || 2 * rest > slots) continue;
+                if (tiles <= slots || rest == 0) continue;
                 const int64_t rows = ceil_div(rest, tn);
                 if (rows >= tm) continue;
-                int split = 0;
-                for (int sp : kSplits)
-                    if (sp >= 2 && rows * tn * sp <= slots) split = sp;
-                if (split == 0) continue;
-                Config h = base;
-                h.tail = (int)rows;
-                h.tail_splits = split;
-                if (config_valid(p, h, ws_bytes)) out.push_back(h);
+                // the K split of the tail: the two that the cost model likes best, if it likes them better
+                // than the single launch (a tail of more than half a round can still gain: 140 tiles split
+                // 3 ways are 2 rounds of a third of K)
+                const double plain = heuristic_seconds(p, base);
+                std::vector<std::pair<double, Config>> ranked;
+                for (int sp : kSplits) {
+                    if (sp < 2) continue;
+                    Config h = base;
+                    h.tail = (int)rows;
+                    h.tail_splits = sp;
+                    if (!config_valid(p, h, ws_bytes)) continue;
+                    const double t = heuristic_seconds(p, h);
+                    if (t < plain) ranked.emplace_back(t, h);
+                }
+                std::sort(ranked.begin(), ranked.end(), [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
+                for (size_t r = 0; r < ranked.size() && r < 2; ++r) out.push_back(ranked[r].second);
             }
         }
     }
