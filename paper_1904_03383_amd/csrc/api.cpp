@@ -496,13 +496,14 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
     // Tail splits: when the tile count is a little above a multiple of what the chip holds at once, the
     // last round would run nearly empty; its tile rows go out as a second launch, split along K so that
     // they fill the chip once more for a fraction of a round.
-    if (p.batch == 1) {
+    {
         const size_t n_plain = out.size();
         for (size_t i = 0; i < n_plain; ++i) {
             const Config base = out[i];
             const KernelInfo &k = tg::kernel(base.kernel);
             if (k.kind != tg::KIND_TILE || k.persistent || k.precut || base.splits != 1) continue;
-            const int64_t tm = ceil_div(p.m, k.BM), tn = ceil_div(p.n, k.BN), tiles = tm * tn;
+            // (every problem of a batch is cut at the same tile row: a tile row of the batch is batch * tn tiles)
+            const int64_t tm = ceil_div(p.m, k.BM), tn = ceil_div(p.n, k.BN) * p.batch, tiles = tm * tn;
             for (int per_cu = 1; per_cu <= 2; ++per_cu) {
                 if (per_cu * k.lds_bytes > kLdsPerCU) break;
                 const int64_t slots = (int64_t)kNumCUs * per_cu;

@@ -533,3 +533,21 @@ def test_tuner_offers_and_times_tail_splits():
         check_against_oracle(c.cpu().numpy()[rows], a[0][rows], b[0], what="tuned 3072^3 " + tuned)
     finally:
         tg.clear_tune_cache()
+
+
+def test_tail_split_is_offered_for_batches_too():
+    """Four 1536^3 problems on 128x256 tiles are 288 tiles: the heuristic (no tuning) takes a tail split; every
+    problem is cut at the same tile row."""
+    import torch
+    say("batched tail split, heuristic choice")
+    batch, m, n, k = 4, 1536, 1536, 1536
+    ws = torch.empty(tg.workspace_bytes(batch, m, n, k) // 4 + 64, device="cuda")
+    tg.set_workspace(ws)
+    chosen = tg.get_config(batch, m, n, k)
+    assert ":t" in chosen, chosen
+    a, b = ig.make_operands(batch, m, n, k, "int", 371, 372)
+    c = run_hip(a, b)
+    assert tg.last_config() == chosen
+    rows = np.linspace(0, m - 1, 24).astype(int)
+    for i in range(batch):
+        check_against_oracle(c[i][rows], a[i][rows], b[i], exact=True, what=f"batched tail split {i}")
