@@ -45,7 +45,7 @@ typedef enum {
     TG_OK = 0,
     TG_ERR_INVALID_ARG = 1, /* null pointer with non-empty extent, negative size, ld or stride too small, overflow */
     TG_ERR_UNSUPPORTED = 2, /* current device is not gfx950, or size beyond 2^31-1 per dimension */
-    TG_ERR_WORKSPACE = 3,   /* a forced split-K configuration needs more workspace than was set */
+    TG_ERR_WORKSPACE = 3,   /* a forced configuration needs more workspace than was set */
     TG_ERR_HIP = 4,         /* a HIP runtime call failed; text in tg_last_error() */
     TG_ERR_INTERNAL = 5
 } tg_status;
@@ -123,15 +123,16 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
                   void *stream, int reps);
 
 /*
- * Split-K workspace (device memory, caller-owned, 16-byte aligned).  Split-K
- * configurations are considered only while a workspace of at least
- * tg_workspace_bytes(...) is set; otherwise a non-split configuration is used.
+ * Workspace (device memory, caller-owned, 16-byte aligned): split-K partial products (also those of
+ * the K-split tail launch of a tail split), packed copies of strided operands, and the piece images
+ * of the "c" kernels.  Configurations that need it are considered only while a workspace of
+ * sufficient size is set (tg_workspace_bytes(...) covers every candidate); otherwise one that needs none is used.
  * Pass (NULL, 0) to remove it.  Calls that use the workspace concurrently on different
  * streams race; give concurrent streams separate processes or no workspace.
  */
 tg_status tg_set_workspace(void *dev_ptr, size_t bytes);
 
-/* Largest workspace any split-K candidate for this problem can need (bytes). 0 on invalid sizes. */
+/* Largest workspace any candidate for this problem can need in the current math mode (bytes). 0 on invalid sizes. */
 size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k);
 
 /*
