@@ -173,3 +173,47 @@ def test_extreme_aspect_ratios(case, with_ws):
     ref = oracle.sgemm_f64(a, b)
     assert np.array_equal(out.cpu().numpy().astype(np.float64), ref), f"{case} ({cfg})"
     del ws
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_untuned_choices_with_a_workspace_in_both_math_modes(chunk):
+    """Mid-size random shapes with a large workspace set and nothing tuned: the static heuristic then picks
+    among every family (register-staged, direct-to-LDS, predicated, split-K, tail splits and, in the piece
+    mode, the bf16-piece kernels cutting in the loop or ahead).  Integer inputs, sampled rows, bit for bit."""
+    import torch
+    from oracle import oracle
+    rng = np.random.default_rng(8800 + chunk)
+    ws = torch.empty(1 << 27, device="cuda")      # 512 MiB
+    families = set()
+    try:
+        for it in range(14):
+            batch = int(rng.choice([1, 1, 1, 2, 3]))
+            m = int(rng.integers(200, 3500))
+            n = int(rng.integers(50, 900)) * 4
+            k = int(rng.choice([rng.integers(32, 3000), 32 * rng.integers(1, 100), 4 * rng.integers(8, 700)]))
+            if batch > 1:
+                m, n = min(m, 1200), min(n, 1200)
+            mode = int(rng.integers(0, 2))
+            tg.set_math(mode)
+            tg.set_workspace(ws)
+            a = ig.small_int(9900 + 100 * chunk + it, (batch, m, k))
+            b = ig.small_int(9950 + 100 * chunk + it, (batch, k, n))
+            da, db = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+            out = torch.full((batch, m, n), float("nan"), device="cuda")
+            say(f"untuned case {chunk}.{it}: mode {mode} batch {batch} {m}x{n}x{k}")
+            if batch == 1:
+                tg.sgemm(da[0], db[0], out=out[0])
+            else:
+                tg.sgemm_batched(da, db, out=out)
+            torch.cuda.synchronize()
+            cfg = tg.last_config()
+            families.add(cfg[0] + ("+tail" if ":t" in cfg else "") + ("+split" if ":s1:" not in cfg + ":" else ""))
+            rows = np.unique(rng.integers(0, m, 32))
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all(), cfg
+            for i in range(batch):
+                assert np.array_equal(got[i][rows].astype(np.float64), oracle.sgemm_f64(a[i][rows], b[i])), \
+                    f"case {chunk}.{it} ({cfg}): result differs from the oracle"
+    finally:
+        tg.set_math(tg.MATH_FP32_MFMA)
+    say(f"  families used: {sorted(families)}")
