@@ -124,8 +124,11 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
 
 /*
  * Workspace (device memory, caller-owned, 16-byte aligned): split-K partial products (also those of
- * the K-split tail launch of a tail split), packed copies of strided operands, and the piece images
- * of the "c" kernels.  Configurations that need it are considered only while a workspace of
+ * the K-split tail launch of a tail split), packed copies of strided operands, aligned zero-padded copies
+ * of unit-stride operands that are off the 16-byte grid or have k or n not a multiple of 4 (made for
+ * single products with m, n >= 256 when there is room: m x k and k x n floats, each rounded up to
+ * multiples of 4; tg_last_config() then ends in "+alignA", "+alignB" or "+alignAB"; without room the
+ * predicated kernels take such operands as they are), and the piece images of the "c" kernels.  Configurations that need it are considered only while a workspace of
  * sufficient size is set (tg_workspace_bytes(...) covers every candidate); otherwise one that needs none is used.
  * Pass (NULL, 0) to remove it.  Calls that use the workspace concurrently on different
  * streams race; give concurrent streams separate processes or no workspace.
@@ -175,7 +178,7 @@ tg_status tg_force_config(const char *spec);
  *     Kernels whose names start with "c" do the same arithmetic with the operands cut ahead: two passes
  *     write the pieces of A and B into the workspace (6 bytes per element of A and B, every tile padded
  *     with zeros; tg_workspace_bytes includes it while this mode is on) and the product streams them in.
- *     They take any m and k and any alignment of A and B (C's rows 16-byte aligned, n a multiple of 4);
+ *     They take any m, n, k and any alignment of A, B and C;
  *     "e" kernels need 16-byte aligned operands and k a multiple of 32.
  * A forced configuration (tg_force_config) may name an "e" or "c" kernel in either mode.  Tuned entries are kept
  * per mode.  Returns TG_ERR_INVALID_ARG for an unknown mode.

@@ -59,9 +59,12 @@ struct Problem {
     const float *A; int64_t lda, strideA;
     const float *B; int64_t ldb, strideB;
     float *C; int64_t ldc, strideC;
-    bool aligned;   // every row of A, B, C (and every problem) starts on a 16-byte boundary
-    bool c_aligned = false;   // ... of C alone
+    bool aligned;   // every row of A and B (and every problem) starts on a 16-byte boundary, unit element strides
+                    // (C's alignment only decides between vector and element stores)
     int64_t csa = 1, csb = 1;   // element strides along k of A / along n of B (strided entry point)
+    bool c_vec = true;          // C's rows start on 16-byte boundaries (the persistent kernels only store vectors)
+    int64_t nb = 0;             // columns of B the exact-fit kernels may fetch (0: n); n rounded up to 4 for a padded copy
+    int64_t b_cols() const { return nb ? nb : n; }
     bool unit() const { return csa == 1 && csb == 1; }
 };
 
@@ -201,9 +204,9 @@ tg_status validate(Problem &p) {
     if (p.m > INT32_MAX || p.n > INT32_MAX || p.k > INT32_MAX || p.batch > INT32_MAX)
         return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-    p.c_aligned = a16(p.C) && p.ldc % 4 == 0 && (p.batch <= 1 || p.strideC % 4 == 0);
-    p.aligned = a16(p.A) && a16(p.B) && a16(p.C) && p.lda % 4 == 0 && p.ldb % 4 == 0 && p.ldc % 4 == 0 &&
-                (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0 && p.strideC % 4 == 0)) && p.unit();
+    p.c_vec = a16(p.C) && p.ldc % 4 == 0 && (p.batch <= 1 || p.strideC % 4 == 0);
+    p.aligned = a16(p.A) && a16(p.B) && p.lda % 4 == 0 && p.ldb % 4 == 0 &&
+                (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0)) && p.unit();
     return TG_OK;
 }
 
@@ -333,9 +336,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     }
     if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
     if (ki.precut) {
-        // the cutting passes take any A and B; the product kernel stores 16-byte vectors
-        if (!p.c_aligned) return no("C is not 16-byte aligned");
-        if (p.n % 4) return no("n is not a multiple of 4");
+        // the cutting passes take any A and B, the product kernel any C
         if (ws_total(p, c) > ws_bytes) return no("workspace too small for the piece images");
         if (sat_mul({p.batch, ceil_div(p.k, ki.BK), std::max(ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN))}) > INT32_MAX)
             return no("too many workgroups");
@@ -346,8 +347,9 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         if (p.k % ki.BK && !(ki.k_tail && p.k % 4 == 0 && p.k >= ki.BK))
             return no(ki.k_tail ? "k is neither a multiple of the K tile nor (a multiple of 4 and at least one K tile)"
                                 : "k is not a multiple of the K tile");
-        if (p.n % 4) return no("n is not a multiple of 4");
+        if (p.b_cols() % 4) return no("n is not a multiple of 4");
         if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
+        if (ki.persistent && !p.c_vec) return no("C is not 16-byte aligned");
         // the fast variants address inside a tile with 32-bit element offsets
         if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
             return no("leading dimension too large for the exact-fit kernels");
@@ -615,6 +617,7 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     g.csa = p.csa; g.csb = p.csb;
     g.strideA = p.strideA; g.strideB = p.strideB; g.strideC = p.strideC;
     g.m = (int)p.m; g.n = (int)p.n; g.k = (int)p.k; g.batch = (int)p.batch;
+    g.nb = (int)p.b_cols();
     g.tiles_m = (int)ceil_div(p.m, ki.BM);
     g.tiles_n = (int)ceil_div(p.n, ki.BN);
     g.group = std::min(c.group, g.tiles_m);
@@ -655,6 +658,50 @@ tg_status zero_fill(const Problem &p, hipStream_t stream) {
     hipError_t e = tg::launch_zero_fill(g, stream);
     if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("zero fill failed: ") + hipGetErrorString(e));
     return TG_OK;
+}
+
+// Unit-stride operands that the exact-fit kernels cannot take as they are (a base or leading dimension off
+// the 16-byte grid, k or n not a multiple of 4): when the product is large enough for it to pay and the
+// workspace has room, A and/or B are copied once into aligned, zero-padded buffers at the front of the
+// workspace and the product runs on the copies with k rounded up to a multiple of 4 (the padding is zero
+// on both sides) and B fetched up to n rounded up.  C is written where it is (element stores if need be).
+// Without room the predicated kernels take the operands as they are.  One problem only (no batches).
+constexpr int64_t kAlignMinSize = 256;   // m and n from which the copies pay (a copy costs what one tile row's fetch does)
+tg_status align_operands(Problem &p, void *&ws, size_t &ws_bytes, hipStream_t s, std::string *tag) {
+    if (!p.unit() || p.batch != 1 || p.m < kAlignMinSize || p.n < kAlignMinSize || p.k < 32) return TG_OK;
+    // (in the piece mode, products of the size those kernels win at go to the ones that cut ahead, which take
+    // the operands as they are: their cutting passes are the only copy needed)
+    if (g_math == TG_MATH_BF16_PIECES && p.m * p.n >= (int64_t)1 << 20 && p.k >= 512) return TG_OK;
+    auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    const bool k_odd = p.k % 4 != 0, n_odd = p.n % 4 != 0;
+    const bool copy_a = k_odd || !a16(p.A) || p.lda % 4 != 0;
+    const bool copy_b = k_odd || n_odd || !a16(p.B) || p.ldb % 4 != 0;
+    if (!copy_a && !copy_b) return TG_OK;
+    const int64_t k4 = pack_ld(p.k), n4 = pack_ld(p.n);
+    const size_t need_a = copy_a ? (size_t)p.m * k4 * sizeof(float) : 0;
+    const size_t need_b = copy_b ? (size_t)k4 * n4 * sizeof(float) : 0;
+    if (need_a + need_b > ws_bytes || (reinterpret_cast<uintptr_t>(ws) & 15u) != 0) return TG_OK;
+    char *w = static_cast<char *>(ws);
+    hipError_t e = hipSuccess;
+    if (copy_a) {
+        e = tg::launch_pad_copy(p.A, p.lda, (int)p.m, (int)p.k, reinterpret_cast<float *>(w), k4, (int)p.m, s);
+        p.A = reinterpret_cast<const float *>(w);
+        p.lda = k4;
+        w += need_a;
+    }
+    if (e == hipSuccess && copy_b) {
+        e = tg::launch_pad_copy(p.B, p.ldb, (int)p.k, (int)p.n, reinterpret_cast<float *>(w), n4, (int)k4, s);
+        p.B = reinterpret_cast<const float *>(w);
+        p.ldb = n4;
+        p.nb = n4;
+        w += need_b;
+    }
+    if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("copy launch failed: ") + hipGetErrorString(e));
+    ws = w;
+    ws_bytes -= need_a + need_b;
+    p.k = k4;
+    *tag = copy_a && copy_b ? "+alignAB" : (copy_a ? "+alignA" : "+alignB");
+    return validate(p);   // the alignment class of the copies
 }
 
 tg_status run(Problem &p, void *stream) {
@@ -704,6 +751,11 @@ tg_status run(Problem &p, void *stream) {
             if (st != TG_OK) return st;
         }
     }
+    std::string copied;
+    if (packed[0] == '\0') {   // (operands gathered just above are not copied a second time)
+        st = align_operands(p, ws, ws_bytes, s, &copied);
+        if (st != TG_OK) return st;
+    }
     Config c;
     {
         std::lock_guard<std::mutex> lk(g_mutex);
@@ -711,7 +763,7 @@ tg_status run(Problem &p, void *stream) {
     }
     if (st != TG_OK) return st;
     st = launch(p, c, ws, s);
-    if (st == TG_OK) t_last_config = spec_of(c) + packed;
+    if (st == TG_OK) t_last_config = spec_of(c) + packed + copied;
     return st;
 }
 
@@ -946,7 +998,6 @@ tg_status query_problem(int64_t batch, int64_t m, int64_t n, int64_t k, Problem 
     if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     *out = Problem{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, false};
     out->aligned = k % 4 == 0 && n % 4 == 0;
-    out->c_aligned = n % 4 == 0;
     return TG_OK;
 }
 
@@ -1005,6 +1056,9 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
         ws = g_ws;
         ws_bytes = g_ws_bytes;
     }
+    std::string copied;
+    st = align_operands(p, ws, ws_bytes, s, &copied);   // as a call would: the tuned entry is for the copies' shape class
+    if (st != TG_OK) return st;
     Config best;
     double best_us = 0;
     {
@@ -1021,7 +1075,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
         std::lock_guard<std::mutex> lk(g_mutex);
         g_cache[key_of(p)] = TunedEntry{best, best_us};
     }
-    t_last_config = spec_of(best);
+    t_last_config = spec_of(best) + copied;
     return TG_OK;
 }
 
@@ -1039,7 +1093,6 @@ size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k) {
     if (m > INT32_MAX || n > INT32_MAX || k > INT32_MAX || batch > INT32_MAX) return 0;
     Problem p{batch, m, n, k, nullptr, k, m * k, nullptr, n, k * n, nullptr, n, m * n, true};
     size_t need = 0;
-    p.c_aligned = true;
     for (const Config &c : candidates(p, SIZE_MAX)) need = std::max(need, ws_total(p, c));
     return need;
 }

@@ -213,6 +213,32 @@ __global__ void __launch_bounds__(256) pack_kernel(const float *__restrict__ src
     }
 }
 
+// dst[r * ld + c] = src[r * rs + c] for r < rows, c < cols, and +0.0 on the rest of rows_out x ld (ld a multiple
+// of 4, dst 16-byte aligned): the aligned, zero-padded copy of an operand whose base, leading dimension or
+// extents keep the exact-fit kernels from using 16-byte loads.  One 16-byte store per thread.
+__global__ void __launch_bounds__(256) pad_copy_kernel(const float *__restrict__ src, int64_t rs, int rows, int cols,
+                                                       float *__restrict__ dst, int64_t ld, int rows_out) {
+    const int64_t vecs = ld / 4;
+    const int64_t total = (int64_t)rows_out * vecs;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = idx / vecs;
+        const int c = (int)(idx - r * vecs) * 4;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (r < rows && c + e < cols) ? src[r * rs + c + e] : 0.0f;
+        *reinterpret_cast<f32x4 *>(dst + r * ld + c) = v;
+    }
+}
+
+hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, float *dst, int64_t ld, int rows_out, hipStream_t s) {
+    const int64_t items = (int64_t)rows_out * (ld / 4);
+    if (items <= 0) return hipSuccess;
+    int64_t blocks = (items + 255) / 256;
+    if (blocks > INT32_MAX) blocks = INT32_MAX;
+    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, rs, rows, cols, dst, ld, rows_out);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int64_t ld, int rows, int cols, hipStream_t s) {
     const int64_t tiles_r = ((int64_t)rows + 63) / 64, tiles_c = ((int64_t)cols + 63) / 64;
     if (rows <= 0 || cols <= 0) return hipSuccess;

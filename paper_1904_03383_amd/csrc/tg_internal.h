@@ -23,6 +23,8 @@ struct GemmParams {
                           // only the predicated kernels honour values other than 1)
     int64_t strideA, strideB, strideC;
     int m, n, k;
+    int nb;               // columns of B the exact-fit kernels may fetch: n, or n rounded up to a multiple of 4 when
+                          // B's rows are known to have the room (an aligned copy with zero padding)
     int batch;
     int splits;           // number of K ranges; each writes its own partial product
     int ktiles_per_split; // K tiles (of the kernel's BK) per range
@@ -90,7 +92,7 @@ constexpr int pieces_lds_bytes();
 
 // The same product with the operands cut ahead: two passes write the pieces of A and B into
 // GemmParams::planes (6 bytes per element, padded to whole tiles), the product kernel streams those images
-// into LDS.  Any m, n, k and any alignment or element stride of A and B; C's rows 16-byte aligned, n % 4 == 0.
+// into LDS.  Any m, n, k, alignment and element stride.
 template <int BM, int BN, int BK, int WM, int WN, int NP>
 hipError_t launch_tile_precut(const GemmParams &p, hipStream_t s);
 
@@ -108,6 +110,9 @@ hipError_t launch_saxpy(int64_t n, float alpha, const float *x, const float *y, 
 
 // dst[r * ld + c] = src[r * rs + c * cs] (rows x cols): packs an element-strided or transposed operand.
 hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int64_t ld, int rows, int cols, hipStream_t s);
+
+// dst[r * ld + c] = src[r * rs + c] (r < rows, c < cols), +0.0 elsewhere on rows_out x ld: aligned, zero-padded copy.
+hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, float *dst, int64_t ld, int rows_out, hipStream_t s);
 
 constexpr int kLdsPerCU = 160 * 1024;  // gfx950
 

@@ -133,7 +133,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     for (int i = 0; i < B_LD; ++i) {
         const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
         // ragged last tile column: vectors past the end of B re-read its last one (n % 4 == 0)
-        const int c = pos % BN < p.n - 4 - n0 ? pos % BN : p.n - 4 - n0;
+        const int c = pos % BN < p.nb - 4 - n0 ? pos % BN : p.nb - 4 - n0;
         b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c;
     }
     const int64_t b_step = (int64_t)BK * p.ldb;
@@ -325,6 +325,8 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     }
     const int col = n0 + wn * WN + li * CB;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;      // workgroup-uniform
+    // CB-float stores need aligned destination rows and n a multiple of CB (a split-K partial has rows of n floats)
+    const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -338,8 +340,13 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
             }
-            // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
-            if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, p.splits == 1);
+            if (vec_c) {
+                if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, p.splits == 1);
+            } else if (row < p.m) {   // C not aligned for vectors (or n not a multiple of CB): element by element
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    if (col + cb < p.n) dst[cb] = vec_get(o, cb);
+            }
         }
     }
 }

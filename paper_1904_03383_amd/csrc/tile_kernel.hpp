@@ -189,7 +189,7 @@ sgemm_tile_kernel(const GemmParams p) {
             b_row[i] = f / (BN / 4);
             b_col[i] = (f % (BN / 4)) * 4;
             // ... and on a ragged last tile column, vectors past the end re-read the last one (n % 4 == 0)
-            const int c = EDGE ? b_col[i] : (b_col[i] < p.n - 4 - n0 ? b_col[i] : p.n - 4 - n0);
+            const int c = EDGE ? b_col[i] : (b_col[i] < p.nb - 4 - n0 ? b_col[i] : p.nb - 4 - n0);
             b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)c * (off_t)csb;
         }
 
@@ -438,8 +438,9 @@ sgemm_tile_kernel(const GemmParams p) {
         }
         const int col = n0 + wn * WN + li * CB;
         const bool final_c = p.splits == 1;
-        // CB-float stores need aligned destination rows: C by host flag, a split-K partial (ld = n) when CB divides n
-        const bool vec_c = p.splits > 1 ? (p.n % CB == 0) : (p.flags & kFlagVecC) != 0;
+        // CB-float stores need aligned destination rows (C: host flag; a split-K partial has rows of n floats)
+        // and n a multiple of CB, so that a vector that starts inside the matrix ends inside it
+        const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
     #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
     #pragma unroll
@@ -454,8 +455,13 @@ sgemm_tile_kernel(const GemmParams p) {
     #pragma unroll
                         for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
                     }
-                    // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
-                    if ((full_m && full_n) || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, final_c);
+                    if (vec_c) {
+                        if ((full_m && full_n) || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, final_c);
+                    } else if (row < p.m) {   // C not aligned for vectors (or n not a multiple of CB): element by element
+    #pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            if (col + cb < p.n) dst[cb] = vec_get(o, cb);
+                    }
                 } else if (full_m && full_n && vec_c) {
                     // interior tile, rows of the destination aligned for CB-float stores
                     bvec o;

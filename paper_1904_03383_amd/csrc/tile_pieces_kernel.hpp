@@ -142,7 +142,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     for (int i = 0; i < B_SL; ++i) {
         const int f = tid + i * NT;
         const int kc = f / (BN / BC), col = (f % (BN / BC)) * BC;
-        const int c = col < p.n - BC - n0 ? col : p.n - BC - n0;   // (n % 4 == 0: at least BC columns exist)
+        const int c = col < p.nb - BC - n0 ? col : p.nb - BC - n0;   // (nb % 4 == 0: at least BC columns exist)
         b_off[i] = ((unsigned)(kc * 8) * (unsigned)p.ldb + (unsigned)c) * 4u;
 #pragma unroll
         for (int e = 0; e < BC; ++e) {
@@ -347,6 +347,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     typedef typename vec_of<CB>::type cvec;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;
     const int col = n0 + wn * WN + li * CB;
+    const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -359,8 +360,14 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
             }
-            // n % 4 == 0 and col % CB == 0: a vector that starts inside the matrix ends inside it
-            if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col), o, p.splits == 1);
+            float *dst = out + (int64_t)row * ldo + col;
+            if (vec_c) {
+                if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(dst), o, p.splits == 1);
+            } else if (row < p.m) {   // C not aligned for vectors (or n not a multiple of CB): element by element
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    if (col + cb < p.n) dst[cb] = vec_get(o, cb);
+            }
         }
     }
 }

@@ -8,7 +8,7 @@
 // cutting once per element instead of once per workgroup that uses it costs 6 bytes of workspace per
 // operand element and two bandwidth-bound passes, and takes 264 of the ~380 non-MFMA instructions per
 // K tile out of the loop.  The passes pad every tile with zeros, so m, n and k are arbitrary here and A
-// and B need no alignment (C's rows: 16 bytes, n % 4 == 0, for the vector stores).
+// and B need no alignment; C is stored with 16-byte vectors when its rows allow it, else element by element.
 //
 // Workspace image.  A: [problem][tile row tm][K tile kt] blocks of 3 * (BK/8) * BM 16-byte entries,
 // entry (piece q, k chunk c, row r) at (q * BK/8 + c) * BM + r, holding the piece-q bf16 values of
@@ -278,6 +278,9 @@ sgemm_tile_precut_kernel(const GemmParams p) {
     typedef typename vec_of<CB>::type cvec;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;
     const int col = n0 + wn * WN + li * CB;
+    // CB-float stores need aligned destination rows and n a multiple of CB (C: host flag; a split-K partial
+    // has rows of n floats); otherwise element by element
+    const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -286,7 +289,14 @@ sgemm_tile_precut_kernel(const GemmParams p) {
             cvec o;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
-            if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(out + (int64_t)row * ldo + col), o, p.splits == 1);
+            float *dst = out + (int64_t)row * ldo + col;
+            if (vec_c) {
+                if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(dst), o, p.splits == 1);
+            } else if (row < p.m) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    if (col + cb < p.n) dst[cb] = o[cb];
+            }
         }
     }
 }

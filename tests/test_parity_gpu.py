@@ -551,3 +551,40 @@ def test_tail_split_is_offered_for_batches_too():
     rows = np.linspace(0, m - 1, 24).astype(int)
     for i in range(batch):
         check_against_oracle(c[i][rows], a[i][rows], b[i], exact=True, what=f"batched tail split {i}")
+
+
+# ---- operands off the 16-byte grid: aligned copies in the workspace, element stores for C ------
+
+def test_unaligned_and_odd_operands_are_copied_when_the_workspace_has_room():
+    import torch
+    from test_random_shapes_gpu import _place
+    say("aligned copies of A and B, element stores for C")
+    ws = torch.empty(1 << 22, device="cuda")
+    cases = [  # (m, n, k, pads (lda-k, ldb-n, ldc-n), offsets (A, B, C), expected suffix)
+        (517, 771, 333, (0, 0, 0), (0, 0, 0), "+alignAB"),      # k and n odd
+        (300, 516, 256, (0, 0, 0), (1, 0, 0), "+alignA"),       # A one float off the grid
+        (300, 518, 256, (0, 0, 0), (0, 0, 0), "+alignB"),       # n not a multiple of 4
+        (384, 512, 256, (4, 3, 0), (0, 0, 0), "+alignB"),       # odd leading dimension of B
+        (384, 512, 256, (0, 0, 1), (0, 0, 3), ""),              # only C off the grid: no copy, element stores
+    ]
+    for m, n, k, pads, offs, suffix in cases:
+        a = ig.small_int(381, (1, m, k))
+        b = ig.small_int(382, (1, k, n))
+        _, da = _place(a, pads[0], offs[0], 0, float("nan"))
+        _, db = _place(b, pads[1], offs[1], 0, float("nan"))
+        for with_ws in (True, False):
+            tg.set_workspace(ws if with_ws else None)
+            cflat, dc = _place(np.zeros((1, m, n), np.float32), pads[2], offs[2], 0, 7.0)
+            cflat.fill_(7.0)
+            tg.sgemm(da[0], db[0], out=dc[0])
+            torch.cuda.synchronize()
+            cfg = tg.last_config()
+            say(f"  {m}x{n}x{k} pads {pads} offsets {offs} workspace {with_ws}: {cfg}")
+            if with_ws:
+                assert cfg.endswith(suffix) and "_edge" not in cfg and ("+align" in cfg) == bool(suffix), cfg
+            else:
+                assert "+align" not in cfg and (suffix == "" or "_edge" in cfg or cfg.startswith("wave32")), cfg
+            check_against_oracle(dc[0].cpu().numpy(), a[0], b[0], exact=True, what=f"{m}x{n}x{k} {cfg}")
+            mask = torch.ones_like(cflat, dtype=torch.bool)
+            torch.as_strided(mask, (1, m, n), dc.stride(), offs[2]).fill_(False)
+            assert bool((cflat[mask] == 7.0).all()), f"{cfg}: stores outside the output"

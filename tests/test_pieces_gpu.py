@@ -250,9 +250,18 @@ def test_cut_ahead_workspace_rules_unaligned_operands_batches_and_split_k():
     assert tg.last_config().startswith(C6 + ":s4")
     for i in range(3):
         check_against_oracle(c[i], a3[i], b3[i], exact=True, what=f"batched split-K {i}")
-    # n not a multiple of 4 (C's rows aligned all the same): refused with the reason
-    with pytest.raises(tg.TgemmError, match="multiple of 4"):
-        tg.sgemm(torch.zeros((8, 8), device="cuda"), torch.zeros((8, 6), device="cuda"), out=torch.zeros((8, 8), device="cuda")[:, :6])
+    # n not a multiple of 4 and C at an odd offset with an odd leading dimension: stored element by element
+    a5, b5 = ig.make_operands(1, 70, 203, 45, "int", 755, 756)
+    bufc = torch.full((70 * 205 + 3,), 7.0, device="cuda")
+    dc = bufc[1:1 + 70 * 205].view(70, 205)[:, :203]
+    tg.force_config(C9)
+    tg.sgemm(to_dev(a5[0]), to_dev(b5[0]), out=dc)
+    torch.cuda.synchronize()
+    assert tg.last_config().startswith(C9)
+    check_against_oracle(dc.cpu().numpy(), a5[0], b5[0], exact=True, what="unaligned C, n = 203")
+    mask = torch.ones_like(bufc, dtype=torch.bool)
+    torch.as_strided(mask, (70, 203), (205, 1), 1).fill_(False)
+    assert bool((bufc[mask] == 7.0).all())
 
 
 # ---- seeded random shapes and placements through the piece kernels ------------------------------
@@ -263,11 +272,11 @@ def _random_piece_cases(seed, count):
     for _ in range(count):
         batch = int(rng.choice([1, 1, 2, 3]))
         m = int(rng.integers(1, 400))
-        n = 4 * int(rng.integers(1, 150))
+        n = int(rng.choice([4 * rng.integers(1, 150), rng.integers(1, 600)]))
         k = int(rng.choice([rng.integers(1, 700), 32 * rng.integers(1, 20)]))
-        pads = (int(rng.choice([0, 4, 1, 3])), int(rng.choice([0, 4, 1, 3])), int(rng.choice([0, 4, 8])))   # lda-k, ldb-n, ldc-n
-        offs = (int(rng.choice([0, 4, 1])), int(rng.choice([0, 4, 1])), int(rng.choice([0, 4])))            # element offsets of A, B, C
-        gaps = (int(rng.choice([0, 4, 7])), int(rng.choice([0, 4, 7])), int(rng.choice([0, 4, 8])))         # extra batch strides
+        pads = (int(rng.choice([0, 4, 1, 3])), int(rng.choice([0, 4, 1, 3])), int(rng.choice([0, 4, 8, 1])))   # lda-k, ldb-n, ldc-n
+        offs = (int(rng.choice([0, 4, 1])), int(rng.choice([0, 4, 1])), int(rng.choice([0, 4, 3])))            # element offsets of A, B, C
+        gaps = (int(rng.choice([0, 4, 7])), int(rng.choice([0, 4, 7])), int(rng.choice([0, 4, 8, 5])))         # extra batch strides
         out.append((batch, m, n, k, pads, offs, gaps, int(rng.integers(0, 3))))
     return out
 
@@ -277,9 +286,9 @@ PIECE_CASES = _random_piece_cases(20261127, 48)
 
 @pytest.mark.parametrize("chunk", range(6))
 def test_random_shapes_and_placements_are_bit_exact(chunk):
-    """Any m and k, n a multiple of 4, A and B anywhere (odd leading dimensions, odd base offsets, odd batch
-    strides), C on 16-byte boundaries: the cut-ahead kernels take all of it; the kernel that cuts in its loop
-    is forced too whenever the case meets its rules (16-byte aligned operands, k a multiple of 32)."""
+    """Any m, n and k, A, B and C anywhere (odd leading dimensions, odd base offsets, odd batch strides): the
+    cut-ahead kernels take all of it; the kernel that cuts in its loop is forced too whenever the case meets
+    its rules (16-byte aligned operands, k a multiple of 32)."""
     import torch
     from oracle import oracle
     from test_random_shapes_gpu import _place
@@ -288,7 +297,7 @@ def test_random_shapes_and_placements_are_bit_exact(chunk):
         batch, m, n, k, pads, offs, gaps, pick = PIECE_CASES[idx]
         a = ig.small_int(9100 + idx, (batch, m, k))
         b = ig.small_int(9300 + idx, (batch, k, n))
-        aligned = all(x % 4 == 0 for x in pads + offs + gaps) and k % 4 == 0
+        aligned = all(x % 4 == 0 for x in pads + offs + gaps) and k % 4 == 0 and n % 4 == 0
         specs = [(C6, C9, C6 + ":s2")[pick]]
         if specs[0].endswith(":s2") and k <= 96:        # each K range needs at least two K tiles
             specs = [C6]
