@@ -331,7 +331,7 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         if (!p.unit()) return no("the wave kernel needs unit element strides");
         if (c.splits != 1) return no("the wave kernel has no split-K");
         if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
-        if (sat_mul({ceil_div(p.m, 32), ceil_div(p.n, 32), p.batch}) > (int64_t)4 * INT32_MAX) return no("too many tiles");
+        if (sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), p.batch}) > (int64_t)4 * INT32_MAX) return no("too many tiles");
         return true;
     }
     if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
@@ -393,8 +393,8 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
     double wave_flops;
     int64_t blocks;
     if (ki.kind == tg::KIND_WAVE) {
-        wave_flops = 2.0 * 32 * 32 * p.k;
-        blocks = ceil_div(ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch, 4);
+        wave_flops = 2.0 * ki.BM * ki.BN * p.k;
+        blocks = ceil_div(sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), p.batch}), 4);
     } else {
         split_plan(ki, p.k, c.splits, &splits, &per);
         // variants with several wave groups along K give every wave only its share of the K range
@@ -426,9 +426,9 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     const KernelInfo &ki = tg::kernel(c.kernel);
     const double launch = 4e-6;
     if (ki.kind == tg::KIND_WAVE) {
-        const double waves = (double)ceil_div(p.m, 32) * ceil_div(p.n, 32) * p.batch;
+        const double waves = (double)ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * p.batch;
         const double per_simd = std::ceil(waves / (kNumCUs * 4.0));
-        const double wave_flops = 2.0 * 32 * 32 * p.k;
+        const double wave_flops = 2.0 * ki.BM * ki.BN * p.k;
         // a lone wave reads its operands with the latency exposed (~1/4 of the SIMD rate);
         // several waves on one SIMD overlap, up to about a third of the rate (measured)
         const double t = std::max(wave_flops / (kSimdFlops / 4.0), per_simd * wave_flops / (kSimdFlops * 0.3));

@@ -10,7 +10,61 @@ namespace tg {
 // would only add latency.  Four independent waves share a 256-thread workgroup.
 // Lane l (i = l % 32, h = l / 32) reads A[row i][8o+4h .. 8o+4h+3] and B[8o+4h+t][col i]
 // (t = 0..3) and issues four v_mfma_f32_32x32x2_f32, so MFMA t multiplies the k pair
-// (8o+t, 8o+4+t); every access is predicated, any m, n, k and leading dimension works.
+// (8o+t, 8o+4+t).  Any m, n, k and leading dimension works: rows and columns past the edge
+// are clamped to the last valid one (their products land in accumulator entries that are
+// never stored), only the last k mod 8 terms are predicated.
+//
+// The kernel is latency bound (a few waves per CU, each waiting on its own loads), so the
+// loads of up to 64 k are all issued before the first MFMA that needs them: a 32x32x64
+// problem of a batch waits for memory once instead of four times.
+template <int OCT, bool VECA>
+__device__ __forceinline__ void wave32_chunk(const float *a, const float *b, int64_t ldb, f32x16 &acc) {
+    f32x4 av[OCT];
+    float bv[OCT][4];
+#pragma unroll
+    for (int o = 0; o < OCT; ++o) {
+        if constexpr (VECA) {
+            av[o] = *reinterpret_cast<const f32x4 *>(a + 8 * o);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) av[o][e] = a[8 * o + e];
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < OCT; ++o)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bv[o][t] = b[(int64_t)(8 * o + t) * ldb];
+    __builtin_amdgcn_sched_barrier(0);   // left alone the scheduler sinks every load to just before its use
+#pragma unroll
+    for (int o = 0; o < OCT; ++o)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[o][t], bv[o][t], acc, 0, 0, 0);
+}
+
+template <bool VECA>
+__device__ __forceinline__ void wave32_body(const GemmParams &p, const float *a_row, const float *b_col, int h,
+                                            f32x16 &acc) {
+    // a_row and b_col already point at this lane half's k offset 4h.
+    int k0 = 0;
+    for (; k0 + 64 <= p.k; k0 += 64) wave32_chunk<8, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    if (k0 + 32 <= p.k) {
+        wave32_chunk<4, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        k0 += 32;
+    }
+    for (; k0 + 8 <= p.k; k0 += 8) wave32_chunk<1, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    if (k0 < p.k) {
+        const int left = p.k - k0 - 4 * h;   // terms of the last, partial octet that belong to this lane half
+        float a[4], b[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = e < left ? a_row[k0 + e] : 0.0f;
+            b[e] = e < left ? b_col[(int64_t)(k0 + e) * p.ldb] : 0.0f;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
+    }
+}
+
 __global__ void __launch_bounds__(256) sgemm_wave32_kernel(const GemmParams p) {
     const int lane = threadIdx.x & 63;
     const int li = lane & 31, h = lane >> 5;
@@ -21,32 +75,17 @@ __global__ void __launch_bounds__(256) sgemm_wave32_kernel(const GemmParams p) {
     const int t_in = (int)(wid - (int64_t)prob * tiles);
     const int tm = t_in / p.tiles_n, tn = t_in - tm * p.tiles_n;
 
-    const int row = tm * 32 + li, col = tn * 32 + li;
-    const bool row_ok = row < p.m, col_ok = col < p.n;
-    const float *a_row = p.A + (int64_t)prob * p.strideA + (int64_t)row * p.lda;
-    const float *b_col = p.B + (int64_t)prob * p.strideB + col;
-    const bool vec_a = (p.flags & kFlagVecA) != 0;
+    const int col = tn * 32 + li;
+    const int row_c = min(tm * 32 + li, p.m - 1), col_c = min(col, p.n - 1);
+    const float *a_row = p.A + (int64_t)prob * p.strideA + (int64_t)row_c * p.lda + 4 * h;
+    const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(4 * h) * p.ldb + col_c;
 
     f32x16 acc = (f32x16)(0.0f);
-#pragma unroll 2
-    for (int k0 = 0; k0 < p.k; k0 += 8) {
-        const int kk = k0 + 4 * h;
-        f32x4 a;
-        if (vec_a && row_ok && kk + 3 < p.k) {
-            a = *reinterpret_cast<const f32x4 *>(a_row + kk);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) a[e] = (row_ok && kk + e < p.k) ? a_row[kk + e] : 0.0f;
-        }
-        float b[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) b[t] = (col_ok && kk + t < p.k) ? b_col[(int64_t)(kk + t) * p.ldb] : 0.0f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
-    }
+    if (p.flags & kFlagVecA) wave32_body<true>(p, a_row, b_col, h, acc);
+    else wave32_body<false>(p, a_row, b_col, h, acc);
 
     float *c = p.C + (int64_t)prob * p.strideC;
-    if (col_ok) {
+    if (col < p.n) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = tm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
@@ -59,6 +98,99 @@ hipError_t launch_wave32(const GemmParams &p, hipStream_t s) {
     const int64_t waves = (int64_t)p.tiles_m * p.tiles_n * p.batch;
     const int64_t blocks = (waves + 3) / 4;
     hipLaunchKernelGGL(sgemm_wave32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// The same with one wave per 16x16 tile and v_mfma_f32_16x16x4_f32: four times as many waves, each with a
+// quarter of the loads and of the MFMA work, for problems too small to give every SIMD a 32x32 tile (a batch
+// of 512 products of 32x32x64 has 512 such tiles for 1024 SIMDs).  Lane l (i = l % 16, q = l / 16) supplies
+// A[row i][k = q] and B[k = q][col i] to the instruction and receives rows 4q .. 4q+3 of column i.  As above
+// a lane reads four consecutive k of its row at once (16c+4q .. 16c+4q+3) and feeds element t to the t-th of
+// four MFMAs, which therefore multiplies the k set {16c+t, 16c+4+t, 16c+8+t, 16c+12+t}.
+template <int CH, bool VECA>
+__device__ __forceinline__ void wave16_chunk(const float *a, const float *b, int64_t ldb, f32x4 &acc) {
+    f32x4 av[CH];
+    float bv[CH][4];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        if constexpr (VECA) {
+            av[c] = *reinterpret_cast<const f32x4 *>(a + 16 * c);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) av[c][e] = a[16 * c + e];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bv[c][t] = b[(int64_t)(16 * c + t) * ldb];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[c][t], bv[c][t], acc, 0, 0, 0);
+}
+
+template <bool VECA>
+__device__ __forceinline__ void wave16_body(const GemmParams &p, const float *a_row, const float *b_col, int q,
+                                            f32x4 &acc) {
+    // a_row and b_col already point at this lane quarter's k offset 4q.
+    int k0 = 0;
+    for (; k0 + 64 <= p.k; k0 += 64) wave16_chunk<4, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    if (k0 + 32 <= p.k) {
+        wave16_chunk<2, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        k0 += 32;
+    }
+    if (k0 + 16 <= p.k) {
+        wave16_chunk<1, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        k0 += 16;
+    }
+    if (k0 < p.k) {
+        const int left = p.k - k0 - 4 * q;   // terms of the last, partial chunk that belong to this lane quarter
+        float a[4], b[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = e < left ? a_row[k0 + e] : 0.0f;
+            b[e] = e < left ? b_col[(int64_t)(k0 + e) * p.ldb] : 0.0f;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
+    }
+}
+
+__global__ void __launch_bounds__(256) sgemm_wave16_kernel(const GemmParams p) {
+    const int lane = threadIdx.x & 63;
+    const int li = lane & 15, q = lane >> 4;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= tiles * p.batch) return;   // whole wave leaves; the kernel has no barrier
+    const int prob = (int)(wid / tiles);
+    const int t_in = (int)(wid - (int64_t)prob * tiles);
+    const int tm = t_in / p.tiles_n, tn = t_in - tm * p.tiles_n;
+
+    const int col = tn * 16 + li;
+    const int row_c = min(tm * 16 + li, p.m - 1), col_c = min(col, p.n - 1);
+    const float *a_row = p.A + (int64_t)prob * p.strideA + (int64_t)row_c * p.lda + 4 * q;
+    const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(4 * q) * p.ldb + col_c;
+
+    f32x4 acc = (f32x4)(0.0f);
+    if (p.flags & kFlagVecA) wave16_body<true>(p, a_row, b_col, q, acc);
+    else wave16_body<false>(p, a_row, b_col, q, acc);
+
+    float *c = p.C + (int64_t)prob * p.strideC;
+    if (col < p.n) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = tm * 16 + 4 * q + v;
+            if (r < p.m) c[(int64_t)r * p.ldc + col] = acc[v];
+        }
+    }
+}
+
+hipError_t launch_wave16(const GemmParams &p, hipStream_t s) {
+    const int64_t waves = (int64_t)p.tiles_m * p.tiles_n * p.batch;
+    const int64_t blocks = (waves + 3) / 4;
+    hipLaunchKernelGGL(sgemm_wave16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

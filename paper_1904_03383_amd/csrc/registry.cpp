@@ -102,6 +102,7 @@ static const KernelInfo kTable[] = {
     TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
     TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")
     {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, false, 256, 0, &launch_wave32},
+    {"wave16", KIND_WAVE, 16, 16, 16, 16, 16, false, true, false, false, 256, 0, &launch_wave16},
 };
 
 int num_kernels() { return (int)(sizeof(kTable) / sizeof(kTable[0])); }

@@ -98,6 +98,7 @@ hipError_t launch_tile_precut(const GemmParams &p, hipStream_t s);
 
 // One wave per 32x32 C tile, operands straight from global memory (small / batched problems).
 hipError_t launch_wave32(const GemmParams &p, hipStream_t s);
+hipError_t launch_wave16(const GemmParams &p, hipStream_t s);
 
 // C[b][i][j] = sum_s ws[b][s][i][j], fixed order s = 0..splits-1 (deterministic).
 hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s);

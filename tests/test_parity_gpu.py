@@ -86,7 +86,7 @@ def test_workload_in_the_tuned_configuration_matches_oracle(name):
 
 def _shape_for(name: str):
     """A shape valid for the named variant that spans several tiles (ragged for predicated ones)."""
-    if name == "wave32":
+    if name in ("wave32", "wave16"):
         return 1, 70, 45, 61
     body = name.split("_")[0][1:]
     bm, bn, bk = (int(x) for x in body.split("x"))
@@ -150,7 +150,7 @@ def test_ragged_shapes(shape):
         check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"ragged {shape} {dist}")
 
 
-@pytest.mark.parametrize("forced", [None, "t128x128x16_w64x64_edge", "t64x64x16_w32x32_edge", "wave32"])
+@pytest.mark.parametrize("forced", [None, "t128x128x16_w64x64_edge", "t64x64x16_w32x32_edge", "wave32", "wave16"])
 def test_ragged_through_each_predicated_kernel(forced):
     m, n, k = 150, 139, 77
     say(f"ragged {m}x{n}x{k} forced={forced}")
@@ -302,7 +302,7 @@ def test_unaligned_base_pointers():
     assert da.data_ptr() % 16 == 4
     tg.sgemm(da, db, out=out)
     torch.cuda.synchronize()
-    assert "_edge" in tg.last_config() or tg.last_config().startswith("wave32")
+    assert "_edge" in tg.last_config() or tg.last_config().startswith("wave")
     check_against_oracle(out.cpu().numpy(), a[1:].reshape(m, k), b[1:].reshape(k, n), exact=True, what="unaligned")
 
 
@@ -409,7 +409,7 @@ def test_output_may_start_as_nan():
 
 @pytest.mark.parametrize("spec,shape", [("t128x128x16_w64x64", (512, 512, 512)),
                                         ("t128x128x16_w64x64:s4", (256, 256, 2048)),
-                                        ("wave32", (96, 96, 200))], ids=str)
+                                        ("wave32", (96, 96, 200)), ("wave16", (96, 96, 200))], ids=str)
 def test_repeated_launches_are_bit_identical(spec, shape):
     """No atomics and a barrier between LDS stages: 50 launches must agree bit for bit."""
     import torch
@@ -583,7 +583,7 @@ def test_unaligned_and_odd_operands_are_copied_when_the_workspace_has_room():
             if with_ws:
                 assert cfg.endswith(suffix) and "_edge" not in cfg and ("+align" in cfg) == bool(suffix), cfg
             else:
-                assert "+align" not in cfg and (suffix == "" or "_edge" in cfg or cfg.startswith("wave32")), cfg
+                assert "+align" not in cfg and (suffix == "" or "_edge" in cfg or cfg.startswith("wave")), cfg
             check_against_oracle(dc[0].cpu().numpy(), a[0], b[0], exact=True, what=f"{m}x{n}x{k} {cfg}")
             mask = torch.ones_like(cflat, dtype=torch.bool)
             torch.as_strided(mask, (1, m, n), dc.stride(), offs[2]).fill_(False)
