@@ -330,8 +330,9 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     if (ki.kind == tg::KIND_WAVE) {
         if (!p.unit()) return no("the wave kernel needs unit element strides");
         if (c.splits != 1) return no("the wave kernel has no split-K");
-        if (p.k > kWaveMaxK) return no("k too long for the single-accumulator wave kernel");
-        if (sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), p.batch}) > (int64_t)4 * INT32_MAX) return no("too many tiles");
+        const int kw = std::max(1, ki.kwaves);   // waves that share a tile, each with its part of K
+        if (p.k > (int64_t)kWaveMaxK * kw) return no("k too long for the single-accumulator wave kernel");
+        if (sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), p.batch}) > (int64_t)(4 / kw) * INT32_MAX) return no("too many tiles");
         return true;
     }
     if (ki.lds_bytes > kLdsPerCU) return no("tile needs more LDS than a CU has");
@@ -393,8 +394,9 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
     double wave_flops;
     int64_t blocks;
     if (ki.kind == tg::KIND_WAVE) {
-        wave_flops = 2.0 * ki.BM * ki.BN * p.k;
-        blocks = ceil_div(sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), p.batch}), 4);
+        const int kw = std::max(1, ki.kwaves);
+        wave_flops = 2.0 * ki.BM * ki.BN * (double)ceil_div(p.k, kw);
+        blocks = ceil_div(sat_mul({ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN), p.batch, (int64_t)kw}), 4);
     } else {
         split_plan(ki, p.k, c.splits, &splits, &per);
         // variants with several wave groups along K give every wave only its share of the K range
@@ -426,13 +428,19 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     const KernelInfo &ki = tg::kernel(c.kernel);
     const double launch = 4e-6;
     if (ki.kind == tg::KIND_WAVE) {
-        const double waves = (double)ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * p.batch;
+        const int kw = std::max(1, ki.kwaves);
+        const double waves = (double)ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * p.batch * kw;
         const double per_simd = std::ceil(waves / (kNumCUs * 4.0));
-        const double wave_flops = 2.0 * ki.BM * ki.BN * p.k;
+        const double wave_flops = 2.0 * ki.BM * ki.BN * (double)ceil_div(p.k, kw);
         // a lone wave reads its operands with the latency exposed (~1/4 of the SIMD rate);
         // several waves on one SIMD overlap, up to about a third of the rate (measured)
-        const double t = std::max(wave_flops / (kSimdFlops / 4.0), per_simd * wave_flops / (kSimdFlops * 0.3));
-        return launch + t;
+        double t = std::max(wave_flops / (kSimdFlops / 4.0), per_simd * wave_flops / (kSimdFlops * 0.3));
+        // every tile fetches its own operands: L2 delivers about 10 TB/s (512^3 with 16x16 tiles: 6.4 us measured).
+        // The four waves of a workgroup are neighbouring tiles of one tile row and share its A rows in L1, unless
+        // they split K among themselves.
+        const double a_share = kw > 1 ? 1.0 : 4.0;
+        t = std::max(t, 4.0 * p.batch * (double)p.m * p.n * p.k * (1.0 / (ki.BM * a_share) + 1.0 / ki.BN) / 10e12);
+        return launch + t + (kw > 1 ? 0.3e-6 : 0.0);   // the partial tiles meet in LDS behind a barrier
     }
     int splits, per;
     split_plan(ki, p.k, c.splits, &splits, &per);

@@ -132,26 +132,30 @@ __device__ __forceinline__ void wave16_chunk(const float *a, const float *b, int
 }
 
 template <bool VECA>
-__device__ __forceinline__ void wave16_body(const GemmParams &p, const float *a_row, const float *b_col, int q,
+__device__ __forceinline__ void wave16_body(const float *a_row, const float *b_col, int64_t ldb, int klen, int q,
                                             f32x4 &acc) {
-    // a_row and b_col already point at this lane quarter's k offset 4q.
+    // a_row and b_col already point at the first k of the range plus this lane quarter's offset 4q.
     int k0 = 0;
-    for (; k0 + 64 <= p.k; k0 += 64) wave16_chunk<4, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
-    if (k0 + 32 <= p.k) {
-        wave16_chunk<2, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    for (; k0 + 128 <= klen; k0 += 128) wave16_chunk<8, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
+    if (k0 + 64 <= klen) {
+        wave16_chunk<4, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
+        k0 += 64;
+    }
+    if (k0 + 32 <= klen) {
+        wave16_chunk<2, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
         k0 += 32;
     }
-    if (k0 + 16 <= p.k) {
-        wave16_chunk<1, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    if (k0 + 16 <= klen) {
+        wave16_chunk<1, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
         k0 += 16;
     }
-    if (k0 < p.k) {
-        const int left = p.k - k0 - 4 * q;   // terms of the last, partial chunk that belong to this lane quarter
+    if (k0 < klen) {
+        const int left = klen - k0 - 4 * q;   // terms of the last, partial chunk that belong to this lane quarter
         float a[4], b[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             a[e] = e < left ? a_row[k0 + e] : 0.0f;
-            b[e] = e < left ? b_col[(int64_t)(k0 + e) * p.ldb] : 0.0f;
+            b[e] = e < left ? b_col[(int64_t)(k0 + e) * ldb] : 0.0f;
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
@@ -174,8 +178,8 @@ __global__ void __launch_bounds__(256) sgemm_wave16_kernel(const GemmParams p) {
     const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(4 * q) * p.ldb + col_c;
 
     f32x4 acc = (f32x4)(0.0f);
-    if (p.flags & kFlagVecA) wave16_body<true>(p, a_row, b_col, q, acc);
-    else wave16_body<false>(p, a_row, b_col, q, acc);
+    if (p.flags & kFlagVecA) wave16_body<true>(a_row, b_col, p.ldb, p.k, q, acc);
+    else wave16_body<false>(a_row, b_col, p.ldb, p.k, q, acc);
 
     float *c = p.C + (int64_t)prob * p.strideC;
     if (col < p.n) {
@@ -191,6 +195,55 @@ hipError_t launch_wave16(const GemmParams &p, hipStream_t s) {
     const int64_t waves = (int64_t)p.tiles_m * p.tiles_n * p.batch;
     const int64_t blocks = (waves + 3) / 4;
     hipLaunchKernelGGL(sgemm_wave16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// A few tiles with a long K (256x256x1024 has 256 tiles of 16x16 for 1024 SIMDs): the four waves of a workgroup
+// share one 16x16 tile, each multiplies a quarter of K (in whole 16-k steps), the four partial tiles meet in
+// LDS and wave 0 adds them in wave order, so the result does not depend on timing.
+__global__ void __launch_bounds__(256) sgemm_wave16k4_kernel(const GemmParams p) {
+    __shared__ f32x4 part[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int li = lane & 15, q = lane >> 4;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t wid = blockIdx.x;        // one workgroup per tile: the grid is exactly tiles * batch
+    const int prob = (int)(wid / tiles);
+    const int t_in = (int)(wid - (int64_t)prob * tiles);
+    const int tm = t_in / p.tiles_n, tn = t_in - tm * p.tiles_n;
+
+    const int steps = (p.k + 15) / 16, per = (steps + 3) / 4;
+    const int k_begin = min(w * per * 16, p.k), k_end = min((w + 1) * per * 16, p.k);
+
+    const int col = tn * 16 + li;
+    const int row_c = min(tm * 16 + li, p.m - 1), col_c = min(col, p.n - 1);
+    const float *a_row = p.A + (int64_t)prob * p.strideA + (int64_t)row_c * p.lda + k_begin + 4 * q;
+    const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(k_begin + 4 * q) * p.ldb + col_c;
+
+    f32x4 acc = (f32x4)(0.0f);
+    // k_begin is a multiple of 16, so a 16-byte aligned row stays 16-byte aligned
+    if (p.flags & kFlagVecA) wave16_body<true>(a_row, b_col, p.ldb, k_end - k_begin, q, acc);
+    else wave16_body<false>(a_row, b_col, p.ldb, k_end - k_begin, q, acc);
+
+    part[w][lane] = acc;
+    __syncthreads();
+    if (w != 0) return;
+    f32x4 sum = part[0][lane];
+#pragma unroll
+    for (int s = 1; s < 4; ++s) sum += part[s][lane];
+
+    float *c = p.C + (int64_t)prob * p.strideC;
+    if (col < p.n) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = tm * 16 + 4 * q + v;
+            if (r < p.m) c[(int64_t)r * p.ldc + col] = sum[v];
+        }
+    }
+}
+
+hipError_t launch_wave16k4(const GemmParams &p, hipStream_t s) {
+    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.batch;
+    hipLaunchKernelGGL(sgemm_wave16k4_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

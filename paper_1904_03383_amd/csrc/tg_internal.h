@@ -61,6 +61,7 @@ struct KernelInfo {
     launch_fn launch;
     int pieces;          // 0: fp32 MFMA; 6 or 9: every fp32 product formed from that many bf16 piece products
     bool precut;         // piece kernel whose operands are cut by separate passes into a workspace image
+    int kwaves;          // KIND_WAVE: waves of a workgroup that share one tile, each with its part of K (0 = one wave per tile)
 };
 
 // Kernel table (registry.cpp).
@@ -99,6 +100,7 @@ hipError_t launch_tile_precut(const GemmParams &p, hipStream_t s);
 // One wave per 32x32 C tile, operands straight from global memory (small / batched problems).
 hipError_t launch_wave32(const GemmParams &p, hipStream_t s);
 hipError_t launch_wave16(const GemmParams &p, hipStream_t s);
+hipError_t launch_wave16k4(const GemmParams &p, hipStream_t s);
 
 // C[b][i][j] = sum_s ws[b][s][i][j], fixed order s = 0..splits-1 (deterministic).
 hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s);

@@ -86,7 +86,7 @@ def test_workload_in_the_tuned_configuration_matches_oracle(name):
 
 def _shape_for(name: str):
     """A shape valid for the named variant that spans several tiles (ragged for predicated ones)."""
-    if name in ("wave32", "wave16"):
+    if name.startswith("wave"):
         return 1, 70, 45, 61
     body = name.split("_")[0][1:]
     bm, bn, bk = (int(x) for x in body.split("x"))
@@ -150,7 +150,7 @@ def test_ragged_shapes(shape):
         check_against_oracle(c, a[0], b[0], exact=(dist == "int"), what=f"ragged {shape} {dist}")
 
 
-@pytest.mark.parametrize("forced", [None, "t128x128x16_w64x64_edge", "t64x64x16_w32x32_edge", "wave32", "wave16"])
+@pytest.mark.parametrize("forced", [None, "t128x128x16_w64x64_edge", "t64x64x16_w32x32_edge", "wave32", "wave16", "wave16k4"])
 def test_ragged_through_each_predicated_kernel(forced):
     m, n, k = 150, 139, 77
     say(f"ragged {m}x{n}x{k} forced={forced}")
@@ -409,7 +409,7 @@ def test_output_may_start_as_nan():
 
 @pytest.mark.parametrize("spec,shape", [("t128x128x16_w64x64", (512, 512, 512)),
                                         ("t128x128x16_w64x64:s4", (256, 256, 2048)),
-                                        ("wave32", (96, 96, 200)), ("wave16", (96, 96, 200))], ids=str)
+                                        ("wave32", (96, 96, 200)), ("wave16", (96, 96, 200)), ("wave16k4", (96, 96, 200))], ids=str)
 def test_repeated_launches_are_bit_identical(spec, shape):
     """No atomics and a barrier between LDS stages: 50 launches must agree bit for bit."""
     import torch
