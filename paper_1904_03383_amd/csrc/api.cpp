@@ -432,9 +432,14 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double waves = (double)ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * p.batch * kw;
         const double per_simd = std::ceil(waves / (kNumCUs * 4.0));
         const double wave_flops = 2.0 * ki.BM * ki.BN * (double)ceil_div(p.k, kw);
-        // a lone wave reads its operands with the latency exposed (~1/4 of the SIMD rate);
+        // a lone wave reads its operands with the latency exposed: one round trip per 64 k (32x32 tiles: half
+        // the SIMD rate, 64x64x2048 in 49 us) or per 128 k (16x16 tiles: a third, the same product in 20.6 us);
         // several waves on one SIMD overlap, up to about a third of the rate (measured)
-        double t = std::max(wave_flops / (kSimdFlops / 4.0), per_simd * wave_flops / (kSimdFlops * 0.3));
+        // (waves that split K share nothing in L1 and overlap a little worse: 0.24 measured at 2000x100x500)
+        double t = std::max(wave_flops / (kSimdFlops * (ki.BM == 32 ? 0.5 : 0.33)), per_simd * wave_flops / (kSimdFlops * (kw > 1 ? 0.24 : 0.3)));
+        // the result leaves in rows of one tile width: 64-byte pieces from 16x16 tiles, full lines from 32x32
+        // (2048x2048x32: 16 MB of C in 10 us and 7.2 us)
+        t = std::max(t, 4.0 * p.batch * (double)p.m * p.n / (ki.BN == 16 ? 1.6e12 : 2.3e12));
         // every tile fetches its own operands: L2 delivers about 10 TB/s (512^3 with 16x16 tiles: 6.4 us measured).
         // The four waves of a workgroup are neighbouring tiles of one tile row and share its A rows in L1, unless
         // they split K among themselves.
@@ -453,7 +458,17 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     // cost the predicated kernels another factor of about two)
     double eff = 1.0 / (1.0 + 12.0 / ki.WM + 12.0 / ki.WN) * (ki.edge ? 0.75 : 1.0) * (ki.two_level ? 0.97 : 1.0);
     eff *= ki.BK >= 32 ? 1.0 : 0.985;
-    if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? 1.01 : 0.97;
+    // (direct-to-LDS loads: ~1 % ahead on the large tiles, 4-10 % on 64x64 tiles with k >= 256, behind on 128x128)
+    if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? 1.01 : (ki.WM * ki.WN == 32 * 32 ? 1.04 : 0.97);
+    if (ki.name[0] == 'd') {
+        // deeper rings and wave groups along K are there for the tuner to try; untuned, the plain form goes first
+        // (a ring deeper than the K range only adds loads: 1536x1536x64 11.3 us against 9.2 us)
+        const int stages = ki.lds_bytes / ((ki.BM * ki.BK + ki.BK * ki.BN) * 4);
+        if (stages > 2) eff *= p.k < 8 * ki.BK ? 0.85 : 0.995;
+        if (ki.threads > (ki.BM / ki.WM) * (ki.BN / ki.WN) * 64) eff *= 0.97;
+    }
+    // the 32-wide and 32-tall tiles are for skinny products; on others they re-fetch the long operand too often
+    if ((ki.BN <= 32 && p.n > 32) || (ki.BM <= 32 && p.m > 32)) eff *= 0.9;
     if (ki.persistent) eff *= p.k <= 256 ? 1.0 : 0.95;
     if (!p.unit()) eff *= 0.5;
     // a tile of which at most a quarter is real output (tiny problems of a batch): the waves
@@ -469,8 +484,10 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         eff = (ki.precut ? 0.59 : 0.53) * tile * 16.0 / ki.pieces;
     }
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
-    double t = launch + per_cu * block_flops / cu_rate;
-    if (splits > 1) t += 3e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
+    // 1 us: the first K tile's trip through LDS and the epilogue, which the wave kernels do not have (a sweep of
+    // 30 small and mid-size shapes: the model's first choice then averages 5 % above the best measured candidate)
+    double t = launch + 1e-6 + per_cu * block_flops / cu_rate;
+    if (splits > 1) t += 4e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
     if (ki.precut) t += 6e-6 + 10.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n) / (kPeakHbm * 0.6);
     return t;
 }
