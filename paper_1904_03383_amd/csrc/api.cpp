@@ -329,6 +329,8 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
     }
     if (ki.kind == tg::KIND_WAVE) {
         if (!p.unit()) return no("the wave kernel needs unit element strides");
+        if (!ki.edge && (!p.aligned || p.n % (ki.BN / 16) != 0))
+            return no("the wide wave tiles need 16-byte aligned operands and n a multiple of their lane width");
         if (c.splits != 1) return no("the wave kernel has no split-K");
         const int kw = std::max(1, ki.kwaves);   // waves that share a tile, each with its part of K
         if (p.k > (int64_t)kWaveMaxK * kw) return no("k too long for the single-accumulator wave kernel");
@@ -439,7 +441,7 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         double t = std::max(wave_flops / (kSimdFlops * (ki.BM == 32 ? 0.5 : 0.33)), per_simd * wave_flops / (kSimdFlops * (kw > 1 ? 0.24 : 0.3)));
         // the result leaves in rows of one tile width: 64-byte pieces from 16x16 tiles, full lines from 32x32
         // (2048x2048x32: 16 MB of C in 10 us and 7.2 us)
-        t = std::max(t, 4.0 * p.batch * (double)p.m * p.n / (ki.BN == 16 ? 1.6e12 : 2.3e12));
+        t = std::max(t, 4.0 * p.batch * (double)p.m * p.n / (ki.BN <= 16 ? 1.6e12 : 2.3e12));
         // every tile fetches its own operands: L2 delivers about 10 TB/s (512^3 with 16x16 tiles: 6.4 us measured).
         // The four waves of a workgroup are neighbouring tiles of one tile row and share its A rows in L1, unless
         // they split K among themselves.

@@ -198,6 +198,117 @@ hipError_t launch_wave16(const GemmParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Wider tiles of the same kind: a wave owns CB = 2 or 4 blocks of 16x16 side by side, lane i the CB adjacent
+// columns CB*i .. CB*i+CB-1 of the 16 x 16*CB tile, so that a B fragment for all its blocks is one 8- or 16-byte
+// load, a row of C leaves as full 128-byte lines and the A fragment is shared by the blocks (a quarter to a half
+// of the load instructions per product).  For aligned operands (16-byte rows of A and B, n a multiple of CB).
+template <int CH, int CB>
+__device__ __forceinline__ void wave16w_chunk(const float *a, const float *b, int64_t ldb, f32x4 (&acc)[CB]) {
+    typedef typename vec_of<CB>::type bvec;
+    f32x4 av[CH];
+    bvec bv[CH][4];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) av[c] = *reinterpret_cast<const f32x4 *>(a + 16 * c);
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bv[c][t] = *reinterpret_cast<const bvec *>(b + (int64_t)(16 * c + t) * ldb);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < CB; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[c][t], vec_get(bv[c][t], j), acc[j], 0, 0, 0);
+}
+
+template <int CB>
+__global__ void __launch_bounds__(256) sgemm_wave16w_kernel(const GemmParams p) {
+    typedef typename vec_of<CB>::type bvec;
+    constexpr int CHMAX = CB == 2 ? 8 : 4;   // k per round trip: 128 or 64 (96 or 80 registers of operands)
+    const int lane = threadIdx.x & 63;
+    const int li = lane & 15, q = lane >> 4;
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= tiles * p.batch) return;   // whole wave leaves; the kernel has no barrier
+    const int prob = (int)(wid / tiles);
+    const int t_in = (int)(wid - (int64_t)prob * tiles);
+    const int tm = t_in / p.tiles_n, tn = t_in - tm * p.tiles_n;
+
+    // n is a multiple of CB, so a lane's columns are all inside or all outside; those outside re-read the last
+    // CB columns (never stored), rows likewise
+    const int col = tn * 16 * CB + CB * li;
+    const int row_c = min(tm * 16 + li, p.m - 1), col_c = min(col, p.n - CB);
+    const float *a_row = p.A + (int64_t)prob * p.strideA + (int64_t)row_c * p.lda + 4 * q;
+    const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(4 * q) * p.ldb + col_c;
+
+    f32x4 acc[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) acc[j] = (f32x4)(0.0f);
+    int k0 = 0;
+    for (; k0 + 16 * CHMAX <= p.k; k0 += 16 * CHMAX)
+        wave16w_chunk<CHMAX, CB>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    if (CHMAX == 8 && k0 + 64 <= p.k) {
+        wave16w_chunk<4, CB>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        k0 += 64;
+    }
+    if (k0 + 32 <= p.k) {
+        wave16w_chunk<2, CB>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        k0 += 32;
+    }
+    if (k0 + 16 <= p.k) {
+        wave16w_chunk<1, CB>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        k0 += 16;
+    }
+    if (k0 < p.k) {
+        const int left = p.k - k0 - 4 * q;   // terms of the last, partial chunk that belong to this lane quarter
+        float a[4];
+        bvec b[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = e < left ? a_row[k0 + e] : 0.0f;
+            if (e < left) b[e] = *reinterpret_cast<const bvec *>(b_col + (int64_t)(k0 + e) * p.ldb);
+            else b[e] = (bvec)(0.0f);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < CB; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], vec_get(b[t], j), acc[j], 0, 0, 0);
+    }
+
+    float *c = p.C + (int64_t)prob * p.strideC;
+    if (col < p.n) {
+        const bool vec_c = (p.flags & kFlagVecC) != 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = tm * 16 + 4 * q + v;
+            if (r >= p.m) continue;
+            float *dst = c + (int64_t)r * p.ldc + col;
+            if (vec_c) {
+                bvec o;
+#pragma unroll
+                for (int j = 0; j < CB; ++j) o[j] = acc[j][v];
+                *reinterpret_cast<bvec *>(dst) = o;
+            } else {
+#pragma unroll
+                for (int j = 0; j < CB; ++j) dst[j] = acc[j][v];
+            }
+        }
+    }
+}
+
+template <int CB>
+hipError_t launch_wave16w(const GemmParams &p, hipStream_t s) {
+    const int64_t waves = (int64_t)p.tiles_m * p.tiles_n * p.batch;
+    const int64_t blocks = (waves + 3) / 4;
+    hipLaunchKernelGGL(sgemm_wave16w_kernel<CB>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+template hipError_t launch_wave16w<2>(const GemmParams &, hipStream_t);
+template hipError_t launch_wave16w<4>(const GemmParams &, hipStream_t);
+
 // A few tiles with a long K (256x256x1024 has 256 tiles of 16x16 for 1024 SIMDs): the four waves of a workgroup
 // share one 16x16 tile, each multiplies a quarter of K (in whole 16-k steps), the four partial tiles meet in
 // LDS and wave 0 adds them in wave order, so the result does not depend on timing.

@@ -103,6 +103,8 @@ static const KernelInfo kTable[] = {
     TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")
     {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, false, 256, 0, &launch_wave32},
     {"wave16", KIND_WAVE, 16, 16, 16, 16, 16, false, true, false, false, 256, 0, &launch_wave16},
+    {"wave16x32", KIND_WAVE, 16, 32, 16, 16, 32, false, false, false, false, 256, 0, &launch_wave16w<2>},
+    {"wave16x64", KIND_WAVE, 16, 64, 16, 16, 64, false, false, false, false, 256, 0, &launch_wave16w<4>},
     {"wave16k4", KIND_WAVE, 16, 16, 16, 16, 16, false, true, false, false, 256, 4096, &launch_wave16k4, 0, false, 4},
 };
 

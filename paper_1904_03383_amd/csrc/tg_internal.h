@@ -101,6 +101,7 @@ hipError_t launch_tile_precut(const GemmParams &p, hipStream_t s);
 hipError_t launch_wave32(const GemmParams &p, hipStream_t s);
 hipError_t launch_wave16(const GemmParams &p, hipStream_t s);
 hipError_t launch_wave16k4(const GemmParams &p, hipStream_t s);
+template <int CB> hipError_t launch_wave16w(const GemmParams &p, hipStream_t s);   // 16 x 16*CB tile per wave, aligned operands
 
 // C[b][i][j] = sum_s ws[b][s][i][j], fixed order s = 0..splits-1 (deterministic).
 hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s);

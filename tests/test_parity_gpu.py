@@ -86,6 +86,8 @@ def test_workload_in_the_tuned_configuration_matches_oracle(name):
 
 def _shape_for(name: str):
     """A shape valid for the named variant that spans several tiles (ragged for predicated ones)."""
+    if name.startswith("wave16x"):          # aligned operands, n a multiple of 4; ragged tiles and a partial k step
+        return 1, 70, 44, 76
     if name.startswith("wave"):
         return 1, 70, 45, 61
     body = name.split("_")[0][1:]
@@ -306,6 +308,37 @@ def test_unaligned_base_pointers():
     check_against_oracle(out.cpu().numpy(), a[1:].reshape(m, k), b[1:].reshape(k, n), exact=True, what="unaligned")
 
 
+@pytest.mark.parametrize("name", ["wave16x32", "wave16x64"])
+@pytest.mark.parametrize("batch", [1, 3])
+def test_wide_wave_tiles(name, batch):
+    """16x32 and 16x64 tiles per wave: aligned A and B, ragged m and n, a partial last k step, and a C whose rows
+    are not 16-byte aligned (element stores) with a sentinel behind every row."""
+    import torch
+    m, n, k, ldc = 50, 36, 44, 39
+    say(f"{name} batch {batch} {m}x{n}x{k} ldc {ldc}")
+    a, b = ig.make_operands(batch, m, n, k, "int", 361, 362)
+    da, db = to_dev(a), to_dev(b)
+    buf = torch.full((batch * m * ldc + 1,), -777.0, device="cuda")
+    out = buf[1:].view(batch, m, ldc)[:, :, :n]
+    assert out.data_ptr() % 16 == 4
+    tg.force_config(name)
+    if batch == 1:
+        tg.sgemm(da[0], db[0], out=out[0])
+    else:
+        tg.sgemm_batched(da, db, out=out)
+    torch.cuda.synchronize()
+    assert tg.last_config().startswith(name)
+    host = buf[1:].view(batch, m, ldc).cpu().numpy()
+    assert np.all(host[:, :, n:] == -777.0)
+    for i in range(batch):
+        check_against_oracle(host[i, :, :n], a[i], b[i], exact=True, what=f"{name} problem {i}")
+    # aligned C: vector stores
+    tg.force_config(name)
+    c = run_hip(a, b) if batch > 1 else run_hip(a[0], b[0])[None]
+    for i in range(batch):
+        check_against_oracle(c[i], a[i], b[i], exact=True, what=f"{name} aligned problem {i}")
+
+
 @pytest.mark.parametrize("case", [(3, 32, 32, 64), (5, 70, 33, 20), (2, 256, 128, 96), (1, 64, 64, 64), (130, 16, 16, 16)], ids=str)
 def test_batched_shapes(case):
     batch, m, n, k = case
@@ -409,7 +442,8 @@ def test_output_may_start_as_nan():
 
 @pytest.mark.parametrize("spec,shape", [("t128x128x16_w64x64", (512, 512, 512)),
                                         ("t128x128x16_w64x64:s4", (256, 256, 2048)),
-                                        ("wave32", (96, 96, 200)), ("wave16", (96, 96, 200)), ("wave16k4", (96, 96, 200))], ids=str)
+                                        ("wave32", (96, 96, 200)), ("wave16", (96, 96, 200)), ("wave16k4", (96, 96, 200)), ("wave16x32", (96, 96, 200)),
+                                        ("wave16x64", (96, 96, 200))], ids=str)
 def test_repeated_launches_are_bit_identical(spec, shape):
     """No atomics and a barrier between LDS stages: 50 launches must agree bit for bit."""
     import torch
