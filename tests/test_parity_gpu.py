@@ -339,6 +339,25 @@ def test_wide_wave_tiles(name, batch):
         check_against_oracle(c[i], a[i], b[i], exact=True, what=f"{name} aligned problem {i}")
 
 
+@pytest.mark.parametrize("name,kmax", [("wave32", 2048), ("wave16", 2048), ("wave16x32", 2048), ("wave16x64", 2048),
+                                       ("wave16k4", 8192)])
+def test_wave_kernels_at_their_longest_k(name, kmax):
+    """One accumulator chain per wave: the longest K a wave kernel accepts must still meet the Frobenius bar on
+    normal(0,1) operands (the case that forces the second accumulation level on the tile kernels), and one more
+    k is refused."""
+    m, n = 96, 64
+    say(f"{name} at k = {kmax}")
+    a, b = ig.make_operands(1, m, n, kmax, "normal", 371, 372)
+    tg.force_config(name)
+    c = run_hip(a[0], b[0])
+    assert tg.last_config().startswith(name)
+    met = check_against_oracle(c, a[0], b[0], what=f"{name} k {kmax}")
+    say(f"  rel_fro {met['rel_fro']:.2e}")
+    a2, b2 = ig.make_operands(1, 16, 16, kmax + 4, "int", 373, 374)
+    with pytest.raises(tg.TgemmError, match="k too long"):
+        run_hip(a2[0], b2[0])
+
+
 @pytest.mark.parametrize("case", [(3, 32, 32, 64), (5, 70, 33, 20), (2, 256, 128, 96), (1, 64, 64, 64), (130, 16, 16, 16)], ids=str)
 def test_batched_shapes(case):
     batch, m, n, k = case
