@@ -62,7 +62,6 @@ struct Problem {
     bool aligned;   // every row of A and B (and every problem) starts on a 16-byte boundary, unit element strides
                     // (C's alignment only decides between vector and element stores)
     int64_t csa = 1, csb = 1;   // element strides along k of A / along n of B (strided entry point)
-    bool c_vec = true;          // C's rows start on 16-byte boundaries (the persistent kernels only store vectors)
     int64_t nb = 0;             // columns of B the exact-fit kernels may fetch (0: n); n rounded up to 4 for a padded copy
     int64_t b_cols() const { return nb ? nb : n; }
     bool unit() const { return csa == 1 && csb == 1; }
@@ -204,7 +203,6 @@ tg_status validate(Problem &p) {
     if (p.m > INT32_MAX || p.n > INT32_MAX || p.k > INT32_MAX || p.batch > INT32_MAX)
         return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-    p.c_vec = a16(p.C) && p.ldc % 4 == 0 && (p.batch <= 1 || p.strideC % 4 == 0);
     p.aligned = a16(p.A) && a16(p.B) && p.lda % 4 == 0 && p.ldb % 4 == 0 &&
                 (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0)) && p.unit();
     return TG_OK;
@@ -352,7 +350,6 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
                                 : "k is not a multiple of the K tile");
         if (p.b_cols() % 4) return no("n is not a multiple of 4");
         if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
-        if (ki.persistent && !p.c_vec) return no("C is not 16-byte aligned");
         // the fast variants address inside a tile with 32-bit element offsets
         if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
             return no("leading dimension too large for the exact-fit kernels");
@@ -656,11 +653,9 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     g.persistent_blocks = c.persist > 0 ? c.persist * kNumCUs : 0;   // a multiple of 8
     g.flags = 0;
     {
-        auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-        const bool multi = p.batch > 1;
-        if (p.csa == 1 && a16(p.A) && p.lda % 4 == 0 && (!multi || p.strideA % 4 == 0)) g.flags |= tg::kFlagVecA;
-        if (p.csb == 1 && a16(p.B) && p.ldb % 4 == 0 && (!multi || p.strideB % 4 == 0)) g.flags |= tg::kFlagVecB;
-        if (a16(p.C) && p.ldc % 4 == 0 && (!multi || p.strideC % 4 == 0)) g.flags |= tg::kFlagVecC;
+        if (p.csa == 1) g.flags |= tg::kFlagVecA;
+        if (p.csb == 1) g.flags |= tg::kFlagVecB;
+        if (p.n % 4 == 0) g.flags |= tg::kFlagVecC;
     }
     if (ki.kind == tg::KIND_TILE && c.splits > 1) {
         split_plan(ki, p.k, c.splits, &g.splits, &g.ktiles_per_split);
@@ -669,7 +664,6 @@ tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream
     if (ki.precut) g.planes = static_cast<char *>(ws) + (ws_need(p, c.splits) + 255) / 256 * 256;
     hipError_t e = ki.launch(g, stream);
     if (e == hipSuccess && g.splits > 1) {
-        if (p.n % 4 != 0) g.flags &= ~tg::kFlagVecC;
         e = tg::launch_splitk_reduce(g, stream);
     }
     if (e != hipSuccess)
@@ -693,9 +687,13 @@ tg_status zero_fill(const Problem &p, hipStream_t stream) {
 // workspace and the product runs on the copies with k rounded up to a multiple of 4 (the padding is zero
 // on both sides) and B fetched up to n rounded up.  C is written where it is (element stores if need be).
 // Without room the predicated kernels take the operands as they are.  One problem only (no batches).
+constexpr double kAlignMinWork = 4.2e8;   // m * n * k from which they pay
 constexpr int64_t kAlignMinSize = 256;   // m and n from which the copies pay (a copy costs what one tile row's fetch does)
 tg_status align_operands(Problem &p, void *&ws, size_t &ws_bytes, hipStream_t s, std::string *tag) {
     if (!p.unit() || p.batch != 1 || p.m < kAlignMinSize || p.n < kAlignMinSize || p.k < 32) return TG_OK;
+    // below about 750^3 the wave kernels, which take any operands, beat two copy launches plus a tile kernel
+    // (701^3: 17.8 us against 21.9 us with copies; 801^3: 39.9 us on the predicated tiles against 30.3 us)
+    if ((double)p.m * p.n * p.k < kAlignMinWork) return TG_OK;
     // (in the piece mode, products of the size those kernels win at go to the ones that cut ahead, which take
     // the operands as they are: their cutting passes are the only copy needed)
     if (g_math == TG_MATH_BF16_PIECES && p.m * p.n >= (int64_t)1 << 20 && p.k >= 512) return TG_OK;

@@ -17,18 +17,13 @@ namespace tg {
 // The kernel is latency bound (a few waves per CU, each waiting on its own loads), so the
 // loads of up to 64 k are all issued before the first MFMA that needs them: a 32x32x64
 // problem of a batch waits for memory once instead of four times.
-template <int OCT, bool VECA>
+template <int OCT>
 __device__ __forceinline__ void wave32_chunk(const float *a, const float *b, int64_t ldb, f32x16 &acc) {
     f32x4 av[OCT];
     float bv[OCT][4];
 #pragma unroll
     for (int o = 0; o < OCT; ++o) {
-        if constexpr (VECA) {
-            av[o] = *reinterpret_cast<const f32x4 *>(a + 8 * o);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) av[o][e] = a[8 * o + e];
-        }
+        av[o] = *reinterpret_cast<const f32x4_a4 *>(a + 8 * o);   // one 16-byte load at any 4-byte alignment
     }
 #pragma unroll
     for (int o = 0; o < OCT; ++o)
@@ -41,17 +36,16 @@ __device__ __forceinline__ void wave32_chunk(const float *a, const float *b, int
         for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[o][t], bv[o][t], acc, 0, 0, 0);
 }
 
-template <bool VECA>
 __device__ __forceinline__ void wave32_body(const GemmParams &p, const float *a_row, const float *b_col, int h,
                                             f32x16 &acc) {
     // a_row and b_col already point at this lane half's k offset 4h.
     int k0 = 0;
-    for (; k0 + 64 <= p.k; k0 += 64) wave32_chunk<8, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    for (; k0 + 64 <= p.k; k0 += 64) wave32_chunk<8>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
     if (k0 + 32 <= p.k) {
-        wave32_chunk<4, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+        wave32_chunk<4>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
         k0 += 32;
     }
-    for (; k0 + 8 <= p.k; k0 += 8) wave32_chunk<1, VECA>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
+    for (; k0 + 8 <= p.k; k0 += 8) wave32_chunk<1>(a_row + k0, b_col + (int64_t)k0 * p.ldb, p.ldb, acc);
     if (k0 < p.k) {
         const int left = p.k - k0 - 4 * h;   // terms of the last, partial octet that belong to this lane half
         float a[4], b[4];
@@ -81,8 +75,7 @@ __global__ void __launch_bounds__(256) sgemm_wave32_kernel(const GemmParams p) {
     const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(4 * h) * p.ldb + col_c;
 
     f32x16 acc = (f32x16)(0.0f);
-    if (p.flags & kFlagVecA) wave32_body<true>(p, a_row, b_col, h, acc);
-    else wave32_body<false>(p, a_row, b_col, h, acc);
+    wave32_body(p, a_row, b_col, h, acc);
 
     float *c = p.C + (int64_t)prob * p.strideC;
     if (col < p.n) {
@@ -107,18 +100,13 @@ hipError_t launch_wave32(const GemmParams &p, hipStream_t s) {
 // A[row i][k = q] and B[k = q][col i] to the instruction and receives rows 4q .. 4q+3 of column i.  As above
 // a lane reads four consecutive k of its row at once (16c+4q .. 16c+4q+3) and feeds element t to the t-th of
 // four MFMAs, which therefore multiplies the k set {16c+t, 16c+4+t, 16c+8+t, 16c+12+t}.
-template <int CH, bool VECA>
+template <int CH>
 __device__ __forceinline__ void wave16_chunk(const float *a, const float *b, int64_t ldb, f32x4 &acc) {
     f32x4 av[CH];
     float bv[CH][4];
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        if constexpr (VECA) {
-            av[c] = *reinterpret_cast<const f32x4 *>(a + 16 * c);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) av[c][e] = a[16 * c + e];
-        }
+        av[c] = *reinterpret_cast<const f32x4_a4 *>(a + 16 * c);
     }
 #pragma unroll
     for (int c = 0; c < CH; ++c)
@@ -131,22 +119,21 @@ __device__ __forceinline__ void wave16_chunk(const float *a, const float *b, int
         for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[c][t], bv[c][t], acc, 0, 0, 0);
 }
 
-template <bool VECA>
 __device__ __forceinline__ void wave16_body(const float *a_row, const float *b_col, int64_t ldb, int klen, int q,
                                             f32x4 &acc) {
     // a_row and b_col already point at the first k of the range plus this lane quarter's offset 4q.
     int k0 = 0;
-    for (; k0 + 128 <= klen; k0 += 128) wave16_chunk<8, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
+    for (; k0 + 128 <= klen; k0 += 128) wave16_chunk<8>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
     if (k0 + 64 <= klen) {
-        wave16_chunk<4, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
+        wave16_chunk<4>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
         k0 += 64;
     }
     if (k0 + 32 <= klen) {
-        wave16_chunk<2, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
+        wave16_chunk<2>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
         k0 += 32;
     }
     if (k0 + 16 <= klen) {
-        wave16_chunk<1, VECA>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
+        wave16_chunk<1>(a_row + k0, b_col + (int64_t)k0 * ldb, ldb, acc);
         k0 += 16;
     }
     if (k0 < klen) {
@@ -178,8 +165,7 @@ __global__ void __launch_bounds__(256) sgemm_wave16_kernel(const GemmParams p) {
     const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(4 * q) * p.ldb + col_c;
 
     f32x4 acc = (f32x4)(0.0f);
-    if (p.flags & kFlagVecA) wave16_body<true>(a_row, b_col, p.ldb, p.k, q, acc);
-    else wave16_body<false>(a_row, b_col, p.ldb, p.k, q, acc);
+    wave16_body(a_row, b_col, p.ldb, p.k, q, acc);
 
     float *c = p.C + (int64_t)prob * p.strideC;
     if (col < p.n) {
@@ -208,7 +194,7 @@ __device__ __forceinline__ void wave16w_chunk(const float *a, const float *b, in
     f32x4 av[CH];
     bvec bv[CH][4];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) av[c] = *reinterpret_cast<const f32x4 *>(a + 16 * c);
+    for (int c = 0; c < CH; ++c) av[c] = *reinterpret_cast<const f32x4_a4 *>(a + 16 * c);
 #pragma unroll
     for (int c = 0; c < CH; ++c)
 #pragma unroll
@@ -280,21 +266,14 @@ __global__ void __launch_bounds__(256) sgemm_wave16w_kernel(const GemmParams p) 
 
     float *c = p.C + (int64_t)prob * p.strideC;
     if (col < p.n) {
-        const bool vec_c = (p.flags & kFlagVecC) != 0;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int r = tm * 16 + 4 * q + v;
             if (r >= p.m) continue;
-            float *dst = c + (int64_t)r * p.ldc + col;
-            if (vec_c) {
-                bvec o;
+            bvec o;
 #pragma unroll
-                for (int j = 0; j < CB; ++j) o[j] = acc[j][v];
-                *reinterpret_cast<bvec *>(dst) = o;
-            } else {
-#pragma unroll
-                for (int j = 0; j < CB; ++j) dst[j] = acc[j][v];
-            }
+            for (int j = 0; j < CB; ++j) o[j] = acc[j][v];
+            store_result(c + (int64_t)r * p.ldc + col, o, false);   // one vector store at any 4-byte alignment
         }
     }
 }
@@ -331,9 +310,7 @@ __global__ void __launch_bounds__(256) sgemm_wave16k4_kernel(const GemmParams p)
     const float *b_col = p.B + (int64_t)prob * p.strideB + (int64_t)(k_begin + 4 * q) * p.ldb + col_c;
 
     f32x4 acc = (f32x4)(0.0f);
-    // k_begin is a multiple of 16, so a 16-byte aligned row stays 16-byte aligned
-    if (p.flags & kFlagVecA) wave16_body<true>(a_row, b_col, p.ldb, k_end - k_begin, q, acc);
-    else wave16_body<false>(a_row, b_col, p.ldb, k_end - k_begin, q, acc);
+    wave16_body(a_row, b_col, p.ldb, k_end - k_begin, q, acc);
 
     part[w][lane] = acc;
     __syncthreads();
@@ -374,7 +351,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p) 
             const float *src = p.ws + b * p.splits * mn + i * p.n + j;
             f32x4 sum = *reinterpret_cast<const f32x4 *>(src);
             for (int s = 1; s < p.splits; ++s) sum += *reinterpret_cast<const f32x4 *>(src + s * mn);
-            *reinterpret_cast<f32x4 *>(p.C + b * p.strideC + i * p.ldc + j) = sum;
+            store_result(p.C + b * p.strideC + i * p.ldc + j, sum, false);   // rows of C need no 16-byte alignment
         }
     } else {
         const int64_t total = (int64_t)p.batch * mn;

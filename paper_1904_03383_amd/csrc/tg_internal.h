@@ -39,9 +39,9 @@ struct GemmParams {
     int flags;            // kFlag* bits, computed on the host from pointers and strides
 };
 
-constexpr int kFlagVecA = 1;  // rows of A: unit element stride, 16-byte aligned (base, leading dimension, batch stride)
-constexpr int kFlagVecC = 2;  // rows of C: 16-byte aligned
-constexpr int kFlagVecB = 4;  // rows of B: unit element stride, 16-byte aligned
+constexpr int kFlagVecA = 1;  // rows of A have unit element stride: four consecutive k are one 16-byte load (any 4-byte alignment)
+constexpr int kFlagVecC = 2;  // n is a multiple of 4: the split-K reduction adds and stores 16-byte vectors
+constexpr int kFlagVecB = 4;  // rows of B have unit element stride
 
 typedef hipError_t (*launch_fn)(const GemmParams &, hipStream_t);
 

@@ -325,8 +325,8 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     }
     const int col = n0 + wn * WN + li * CB;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;      // workgroup-uniform
-    // CB-float stores need aligned destination rows and n a multiple of CB (a split-K partial has rows of n floats)
-    const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
+    const bool lane_vec = col + CB <= p.n;
+    const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -340,13 +340,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
             }
-            if (vec_c) {
-                if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, p.splits == 1);
-            } else if (row < p.m) {   // C not aligned for vectors (or n not a multiple of CB): element by element
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    if (col + cb < p.n) dst[cb] = vec_get(o, cb);
-            }
+            if (full_tile || row < p.m) store_lane<CB>(dst, o, lane_vec, col, p.n, nt);
         }
     }
 }

@@ -35,6 +35,9 @@ namespace tg {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// Four consecutive floats at any 4-byte aligned address: still one global_load_dwordx4 (global memory accesses
+// need dword alignment only), so rows that are off the 16-byte grid cost no extra instructions.
+typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 template <int N> struct vec_of;
@@ -46,15 +49,39 @@ template <> struct vec_of<4> { typedef f32x4 type; };
 // with the non-temporal hint and does not displace operand panels from L2 (measured: 4096x4096x128
 // 41.7 -> 40.0 us, 1024^3 23.1 -> 22.9 us, no change at 4096^3); split-K partials, which the reduction
 // reads next, are stored normally.
+// The destination needs 4-byte alignment only (one global_store_dwordx2/x4 either way), so rows of C that are
+// off the 16-byte grid are stored the same way as aligned ones.
+// (The hint is only kept by the compiler on naturally aligned vector stores: `nt` must imply that.)
 template <typename V>
-__device__ __forceinline__ void store_result(V *dst, V v, bool final_c) {
-    if (final_c) __builtin_nontemporal_store(v, dst);
-    else *dst = v;
+__device__ __forceinline__ void store_result(float *dst, V v, bool nt) {
+    typedef V VA __attribute__((aligned(4)));
+    if (nt) __builtin_nontemporal_store(v, reinterpret_cast<V *>(dst));
+    else *reinterpret_cast<VA *>(dst) = v;
+}
+
+// Whether the CB-float groups of this lane are naturally aligned in every row of the destination.
+template <int CB>
+__device__ __forceinline__ bool rows_aligned(const float *first, int64_t ld) {
+    return (reinterpret_cast<uintptr_t>(first) & (4 * CB - 1)) == 0 && ld % CB == 0;
 }
 
 __device__ __forceinline__ float vec_get(float v, int) { return v; }
 __device__ __forceinline__ float vec_get(f32x2 v, int i) { return v[i]; }
 __device__ __forceinline__ float vec_get(f32x4 v, int i) { return v[i]; }
+
+// The CB results of one lane, columns col .. col+CB-1 of one row: one vector store where all of them exist
+// (lane_vec = col + CB <= n, the same for every row of the lane), element by element in the last, partial
+// group of an n that is not a multiple of CB.
+template <int CB, typename V>
+__device__ __forceinline__ void store_lane(float *dst, V o, bool lane_vec, int col, int n, bool nt) {
+    if (lane_vec) {
+        store_result(dst, o, nt);
+    } else {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+            if (col + cb < n) dst[cb] = vec_get(o, cb);
+    }
+}
 
 // Workgroup id -> (slice, tile row, tile column);  slice = problem * splits + split.
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn, and each XCD has its own
@@ -200,7 +227,7 @@ sgemm_tile_kernel(const GemmParams p) {
         // the range (when nothing is left to prefetch) stays inside the matrices.
         // Predicated variants: a tile that lies wholly inside the matrices (the common case even
         // for ragged sizes) is fetched without per-element tests, with 16-byte loads when the
-        // operand's rows allow it (unit element stride, 16-byte aligned rows: host flags), else
+        // operand has unit element stride (host flags; the rows need not be 16-byte aligned), else
         // with four plain loads per slot; only tiles that cross an edge take the tested path.
         const bool full_m = m0 + BM <= p.m, full_n = n0 + BN <= p.n;      // workgroup-uniform
         const bool vec_a = (p.flags & kFlagVecA) != 0, vec_b = (p.flags & kFlagVecB) != 0;
@@ -213,7 +240,7 @@ sgemm_tile_kernel(const GemmParams p) {
                     a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
                 } else if (full_m && full_k) {
                     if (vec_a) {
-                        a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                        a_reg[i] = *reinterpret_cast<const f32x4_a4 *>(src);
                     } else {
                         f32x4 v;
     #pragma unroll
@@ -236,7 +263,7 @@ sgemm_tile_kernel(const GemmParams p) {
                     b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
                 } else if (full_n && full_k) {
                     if (vec_b) {
-                        b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                        b_reg[i] = *reinterpret_cast<const f32x4_a4 *>(src);
                     } else {
                         f32x4 v;
     #pragma unroll
@@ -438,47 +465,22 @@ sgemm_tile_kernel(const GemmParams p) {
         }
         const int col = n0 + wn * WN + li * CB;
         const bool final_c = p.splits == 1;
-        // CB-float stores need aligned destination rows (C: host flag; a split-K partial has rows of n floats)
-        // and n a multiple of CB, so that a vector that starts inside the matrix ends inside it
-        const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
+        const bool lane_vec = col + CB <= p.n;
+        const bool nt = final_c && rows_aligned<CB>(out + col, ldo);
     #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
     #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
                 float *dst = out + (int64_t)row * ldo + col;
-                if constexpr (!EDGE) {
-                    bvec o;
-                    if constexpr (CB == 1) {
-                        o = acc[rb][0][v];
-                    } else {
-    #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
-                    }
-                    if (vec_c) {
-                        if ((full_m && full_n) || (row < p.m && col < p.n)) store_result(reinterpret_cast<bvec *>(dst), o, final_c);
-                    } else if (row < p.m) {   // C not aligned for vectors (or n not a multiple of CB): element by element
-    #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb)
-                            if (col + cb < p.n) dst[cb] = vec_get(o, cb);
-                    }
-                } else if (full_m && full_n && vec_c) {
-                    // interior tile, rows of the destination aligned for CB-float stores
-                    bvec o;
-                    if constexpr (CB == 1) {
-                        o = acc[rb][0][v];
-                    } else {
-    #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
-                    }
-                    store_result(reinterpret_cast<bvec *>(dst), o, final_c);
+                bvec o;
+                if constexpr (CB == 1) {
+                    o = acc[rb][0][v];
                 } else {
-                    if (row < p.m) {
     #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb)
-                            if (col + cb < p.n) dst[cb] = acc[rb][cb][v];
-                    }
+                    for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
                 }
+                if ((full_m && full_n) || row < p.m) store_lane<CB>(dst, o, lane_vec, col, p.n, nt);
             }
         }
     }

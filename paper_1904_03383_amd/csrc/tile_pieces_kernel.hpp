@@ -347,7 +347,8 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     typedef typename vec_of<CB>::type cvec;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;
     const int col = n0 + wn * WN + li * CB;
-    const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
+    const bool lane_vec = col + CB <= p.n;
+    const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -361,13 +362,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
                 for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
             }
             float *dst = out + (int64_t)row * ldo + col;
-            if (vec_c) {
-                if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(dst), o, p.splits == 1);
-            } else if (row < p.m) {   // C not aligned for vectors (or n not a multiple of CB): element by element
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    if (col + cb < p.n) dst[cb] = vec_get(o, cb);
-            }
+            if (full_tile || row < p.m) store_lane<CB>(dst, o, lane_vec, col, p.n, nt);
         }
     }
 }

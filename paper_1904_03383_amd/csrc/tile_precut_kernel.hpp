@@ -8,7 +8,7 @@
 // cutting once per element instead of once per workgroup that uses it costs 6 bytes of workspace per
 // operand element and two bandwidth-bound passes, and takes 264 of the ~380 non-MFMA instructions per
 // K tile out of the loop.  The passes pad every tile with zeros, so m, n and k are arbitrary here and A
-// and B need no alignment; C is stored with 16-byte vectors when its rows allow it, else element by element.
+// and B need no alignment, nor does C.
 //
 // Workspace image.  A: [problem][tile row tm][K tile kt] blocks of 3 * (BK/8) * BM 16-byte entries,
 // entry (piece q, k chunk c, row r) at (q * BK/8 + c) * BM + r, holding the piece-q bf16 values of
@@ -34,7 +34,7 @@ constexpr int precut_lds_bytes() {
 // One workgroup per (problem, tile row, K tile), in that order in a 1-D grid: BM rows x BK columns of A
 // -> one block of the image.
 // Thread slots (row, k chunk): 8 consecutive k of one row.  rs / cs: element strides between rows and
-// along k (cs == 1 and `vec` set: 16-byte loads).
+// along k (cs == 1 and `vec` set: 16-byte loads, at any 4-byte alignment).
 template <int BM, int BK>
 __global__ void __launch_bounds__(256) cut_a_kernel(const float *A, int64_t rs, int64_t cs, int64_t strideA, int m, int k,
                                                     int tiles_m, int ktiles, int vec, u32x4 *planes) {
@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(256) cut_a_kernel(const float *A, int64_t rs, 
         const int gr = tm * BM + row, gk = kt * BK + kc * 8;
         float x[8];
         if (vec && gr < m && gk + 8 <= k) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(src + (int64_t)gr * rs + gk);
+            const f32x4_a4 *q = reinterpret_cast<const f32x4_a4 *>(src + (int64_t)gr * rs + gk);
             const f32x4 lo = q[0], hi = q[1];
 #pragma unroll
             for (int e = 0; e < 4; ++e) { x[e] = lo[e]; x[4 + e] = hi[e]; }
@@ -82,7 +82,7 @@ __global__ void __launch_bounds__(256) cut_b_kernel(const float *B, int64_t rs, 
         f32x4 raw[8];
         if (vec && gk + 8 <= k && gc + 4 <= n) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) raw[r] = *reinterpret_cast<const f32x4 *>(src + (int64_t)(gk + r) * rs + gc);
+            for (int r = 0; r < 8; ++r) raw[r] = *reinterpret_cast<const f32x4_a4 *>(src + (int64_t)(gk + r) * rs + gc);
         } else {
 #pragma unroll
             for (int r = 0; r < 8; ++r)
@@ -278,9 +278,8 @@ sgemm_tile_precut_kernel(const GemmParams p) {
     typedef typename vec_of<CB>::type cvec;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;
     const int col = n0 + wn * WN + li * CB;
-    // CB-float stores need aligned destination rows and n a multiple of CB (C: host flag; a split-K partial
-    // has rows of n floats); otherwise element by element
-    const bool vec_c = p.n % CB == 0 && (p.splits > 1 || (p.flags & kFlagVecC) != 0);
+    const bool lane_vec = col + CB <= p.n;
+    const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -290,13 +289,7 @@ sgemm_tile_precut_kernel(const GemmParams p) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) o[cb] = acc_hi[rb][cb][v] + acc_lo[rb][cb][v];
             float *dst = out + (int64_t)row * ldo + col;
-            if (vec_c) {
-                if (full_tile || (row < p.m && col < p.n)) store_result(reinterpret_cast<cvec *>(dst), o, p.splits == 1);
-            } else if (row < p.m) {
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    if (col + cb < p.n) dst[cb] = o[cb];
-            }
+            if (full_tile || row < p.m) store_lane<CB>(dst, o, lane_vec, col, p.n, nt);
         }
     }
 }

@@ -240,6 +240,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
             ldo = p.ldc;
         }
         const int col = tn * BN + wn * WN + li * CB;
+        const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -253,7 +254,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
                 }
-                store_result(reinterpret_cast<bvec *>(dst), o, p.splits == 1);
+                store_result(dst, o, nt);
             }
         }
     }

@@ -614,11 +614,12 @@ def test_unaligned_and_odd_operands_are_copied_when_the_workspace_has_room():
     say("aligned copies of A and B, element stores for C")
     ws = torch.empty(1 << 22, device="cuda")
     cases = [  # (m, n, k, pads (lda-k, ldb-n, ldc-n), offsets (A, B, C), expected suffix)
-        (517, 771, 333, (0, 0, 0), (0, 0, 0), "+alignAB"),      # k and n odd
-        (300, 516, 256, (0, 0, 0), (1, 0, 0), "+alignA"),       # A one float off the grid
-        (300, 518, 256, (0, 0, 0), (0, 0, 0), "+alignB"),       # n not a multiple of 4
-        (384, 512, 256, (4, 3, 0), (0, 0, 0), "+alignB"),       # odd leading dimension of B
-        (384, 512, 256, (0, 0, 1), (0, 0, 3), ""),              # only C off the grid: no copy, element stores
+        (1030, 771, 777, (0, 0, 0), (0, 0, 0), "+alignAB"),     # k and n odd
+        (900, 1028, 512, (0, 0, 0), (1, 0, 0), "+alignA"),      # A one float off the grid
+        (900, 1030, 512, (0, 0, 0), (0, 0, 0), "+alignB"),      # n not a multiple of 4
+        (896, 1024, 512, (4, 3, 0), (0, 0, 0), "+alignB"),      # odd leading dimension of B
+        (896, 1024, 512, (0, 0, 1), (0, 0, 3), ""),             # only C off the grid: no copy, element stores
+        (517, 771, 333, (0, 0, 0), (0, 0, 0), ""),              # too small for copies to pay: the wave kernels take it
     ]
     for m, n, k, pads, offs, suffix in cases:
         a = ig.small_int(381, (1, m, k))
