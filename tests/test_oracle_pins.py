@@ -92,6 +92,15 @@ def test_parity_metrics_definitions():
     neg0 = good.copy()
     neg0[1, 0] = -0.0
     assert oracle.parity_metrics(neg0, c_ref, s)["bit_exact"]
+    # a batch: the whole-batch figure pools all entries, the per-problem figure is the worst single problem
+    c3 = np.stack([c_ref, 10.0 * c_ref])
+    s3 = np.stack([s, 10.0 * s])
+    t3 = c3.astype(np.float32)
+    t3[0, 1, 1] += 0.5                      # problem 0: error 0.5 against a norm of sqrt(21)
+    m = oracle.parity_metrics(t3, c3, s3)
+    assert abs(m["rel_fro"] - 0.5 / np.sqrt(21 + 2100)) < 1e-15
+    assert abs(m["rel_fro_max_problem"] - 0.5 / np.sqrt(21)) < 1e-15
+    assert oracle.parity_metrics(bad, c_ref, s)["rel_fro_max_problem"] == oracle.parity_metrics(bad, c_ref, s)["rel_fro"]
 
 
 # ---- planted mistakes: each must be caught by at least one pin -------------------------

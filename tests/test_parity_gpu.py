@@ -37,7 +37,8 @@ def test_workload_matches_oracle(name):
     a, b = _squeeze(*ig.make_config(name))
     c = run_hip(a, b)
     m = check_against_oracle(c, a, b, what=name)
-    say(f"  config {tg.last_config()}  max_ratio {m['max_ratio']:.2e}  rel_fro {m['rel_fro']:.2e}")
+    say(f"  config {tg.last_config()}  max_ratio {m['max_ratio']:.2e}  rel_fro {m['rel_fro']:.2e}"
+        f"  (worst single problem {m['rel_fro_max_problem']:.2e})")
 
 
 @pytest.mark.parametrize("name", list(ig.CONFIGS))
