@@ -96,6 +96,25 @@ def time_workload(tg, torch, name, steps, warmup, reps_tune, vendor=False):
         blocks_ms.append(ev0.elapsed_time(ev1) / reps)
     res["repeat_stats"] = {"blocks": 10, "calls_per_block": reps, "median_ms": float(np.median(blocks_ms)),
                            "min_ms": float(min(blocks_ms)), "max_ms": float(max(blocks_ms))}
+    if dev_ms < 0.02:
+        # The same calls made straight through the C ABI with the arguments marshalled once (what a C caller
+        # pays per call: the library's host path plus the HIP launch, without the Python binding's checks).
+        lib = tg.load_library()
+        sh = int(stream.cuda_stream)
+        if batch == 1:
+            fn, args = lib.tg_sgemm, (m, n, k, da.data_ptr(), k, db.data_ptr(), n, out.data_ptr(), n, sh)
+        else:
+            fn, args = lib.tg_sgemm_batched, (batch, m, n, k, da.data_ptr(), k, m * k, db.data_ptr(), n, k * n,
+                                              out.data_ptr(), n, m * n, sh)
+        assert out.is_contiguous() and da.is_contiguous() and db.is_contiguous()
+        ok = all(fn(*args) == 0 for _ in range(max(warmup, 1)))
+        ev0.record(stream)
+        for _ in range(steps):
+            fn(*args)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        if ok:
+            res["abi_call_ms_per_step"] = ev0.elapsed_time(ev1) / steps
     if dev_ms < 0.1:
         # Launch-bound workload: per-call time is dominated by the host launch path.  Replay the
         # same calls from a HIP graph to show the device-side rate (reported separately).
@@ -423,6 +442,8 @@ def main():
             parity_ok = parity_ok and r["parity"]["ok"]
             del a2, b2, out2
             extra = f"  (graph replay {r['graph_device_ms_per_step'] * 1e3:.2f} us)" if "graph_device_ms_per_step" in r else ""
+            if "abi_call_ms_per_step" in r:
+                extra += f"  (through the C ABI directly {r['abi_call_ms_per_step'] * 1e3:.2f} us per call)"
             if "torch_matmul_device_ms_per_step" in r:
                 extra += f"  (torch.matmul {r['torch_matmul_device_ms_per_step'] * 1e3:.2f} us)"
             log(f"  {name}: {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.2f} us  {r['device_tflops']:.2f} TFLOP/s{extra}")
