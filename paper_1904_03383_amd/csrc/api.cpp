@@ -54,6 +54,11 @@ struct Config {
     int tail_splits = 1;
 };
 
+// What tg_last_config() reports: the spec string is formatted on demand from the last call's choice.
+thread_local Config t_last_cfg;
+thread_local const char *t_last_tags[2] = {"", ""};   // "+pack..." and "+align..." suffixes (string literals)
+thread_local bool t_last_pending = false;
+
 struct Problem {
     int64_t batch, m, n, k;
     const float *A; int64_t lda, strideA;
@@ -732,11 +737,11 @@ tg_status align_operands(Problem &p, void *&ws, size_t &ws_bytes, hipStream_t s,
 tg_status run(Problem &p, void *stream) {
     tg_status st = validate(p);
     if (st != TG_OK) return st;
-    if (p.batch == 0 || p.m == 0 || p.n == 0) { t_last_config.clear(); return TG_OK; }
+    if (p.batch == 0 || p.m == 0 || p.n == 0) { t_last_config.clear(); t_last_pending = false; return TG_OK; }
     st = check_device();
     if (st != TG_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (p.k == 0) { t_last_config = "zero_fill"; return zero_fill(p, s); }
+    if (p.k == 0) { t_last_config = "zero_fill"; t_last_pending = false; return zero_fill(p, s); }
     void *ws;
     size_t ws_bytes;
     {
@@ -788,7 +793,12 @@ tg_status run(Problem &p, void *stream) {
     }
     if (st != TG_OK) return st;
     st = launch(p, c, ws, s);
-    if (st == TG_OK) t_last_config = spec_of(c) + packed + copied;
+    if (st == TG_OK) {   // formatted only when tg_last_config() asks: a call must not pay for a string it may never show
+        t_last_cfg = c;
+        t_last_tags[0] = packed;
+        t_last_tags[1] = copied.empty() ? "" : (copied == "+alignAB" ? "+alignAB" : (copied == "+alignA" ? "+alignA" : "+alignB"));
+        t_last_pending = true;
+    }
     return st;
 }
 
@@ -1101,6 +1111,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
         g_cache[key_of(p)] = TunedEntry{best, best_us};
     }
     t_last_config = spec_of(best) + copied;
+    t_last_pending = false;
     return TG_OK;
 }
 
@@ -1173,7 +1184,13 @@ tg_status tg_get_config(int64_t batch, int64_t m, int64_t n, int64_t k, char *bu
     return TG_OK;
 }
 
-const char *tg_last_config(void) { return t_last_config.c_str(); }
+const char *tg_last_config(void) {
+    if (t_last_pending) {
+        t_last_config = spec_of(t_last_cfg) + t_last_tags[0] + t_last_tags[1];
+        t_last_pending = false;
+    }
+    return t_last_config.c_str();
+}
 
 int tg_num_candidates(int64_t batch, int64_t m, int64_t n, int64_t k) {
     Problem p;
