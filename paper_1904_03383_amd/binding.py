@@ -82,20 +82,40 @@ def _check(status: int):
         raise TgemmError(status, load_library().tg_last_error().decode())
 
 
+# torch and the few attributes the per-call path needs, looked up once (a call through this binding is
+# launch-bound for small products: every attribute chain dropped from it shows in the per-call time)
+_torch = None
+_Tensor = None
+_f32 = None
+_raw_stream = None
+_cur_dev = None
+
+
+def _torch_mod():
+    global _torch, _Tensor, _f32, _raw_stream, _cur_dev
+    if _torch is None:
+        import torch
+        _Tensor, _f32 = torch.Tensor, torch.float32
+        _raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)   # avoids building a Stream object per call
+        _cur_dev = torch.cuda.current_device
+        _torch = torch
+    return _torch
+
+
 def _stream_handle(stream=None) -> int:
     """hipStream_t of `stream` (a torch.cuda.Stream) or of torch's current stream, as an integer."""
-    import torch
     if stream is not None:
         return int(stream.cuda_stream)
-    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)     # avoids building a Stream object per call
-    if raw is not None:
-        return int(raw(torch.cuda.current_device()))
+    torch = _torch or _torch_mod()
+    if _raw_stream is not None:
+        return int(_raw_stream(_cur_dev()))
     return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _require_f32_cuda(name, t):
-    import torch
-    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or not t.is_cuda:
+    if _torch is None:
+        _torch_mod()
+    if not isinstance(t, _Tensor) or t.dtype is not _f32 or not t.is_cuda:
         raise ValueError(f"{name} must be a float32 tensor in device memory")
 
 
@@ -119,7 +139,7 @@ def _row_major_ld(t, rows, cols, strides) -> int:
 
 def sgemm(a, b, out=None, stream=None):
     """C = A.B for 2-D float32 device tensors a (m,k), b (k,n); returns out (m,n).  -> tg_sgemm"""
-    import torch
+    torch = _torch or _torch_mod()
     _require_f32_cuda("a", a)
     _require_f32_cuda("b", b)
     sa, sb = a.shape, b.shape
@@ -134,7 +154,7 @@ def sgemm(a, b, out=None, stream=None):
         so = out.shape
         if len(so) != 2 or so[0] != m or so[1] != n:
             raise ValueError("out has the wrong shape")
-    st = load_library().tg_sgemm(m, n, k, a.data_ptr(), _row_major_ld(a, m, k, a.stride()),
+    st = (_lib or load_library()).tg_sgemm(m, n, k, a.data_ptr(), _row_major_ld(a, m, k, a.stride()),
                                  b.data_ptr(), _row_major_ld(b, k, n, b.stride()),
                                  out.data_ptr(), _row_major_ld(out, m, n, out.stride()), _stream_handle(stream))
     if st != TG_OK:
