@@ -126,9 +126,11 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
  * Workspace (device memory, caller-owned, 16-byte aligned): split-K partial products (also those of
  * the K-split tail launch of a tail split), packed copies of strided operands, aligned zero-padded copies
  * of unit-stride operands that are off the 16-byte grid or have k or n not a multiple of 4 (made for
- * single products with m, n >= 256 when there is room: m x k and k x n floats, each rounded up to
+ * single products with m, n >= 256 and m * n * k >= 4.2e8 when there is room: m x k and k x n floats, each rounded up to
  * multiples of 4; tg_last_config() then ends in "+alignA", "+alignB" or "+alignAB"; without room the
- * predicated kernels take such operands as they are), and the piece images of the "c" kernels.  Configurations that need it are considered only while a workspace of
+ * predicated kernels take such operands as they are, as do the one-wave-per-tile kernels that smaller products
+ * run on; C is never copied: its rows may start anywhere), and the piece images of the "c" kernels.
+ * Configurations that need it are considered only while a workspace of
  * sufficient size is set (tg_workspace_bytes(...) covers every candidate); otherwise one that needs none is used.
  * Pass (NULL, 0) to remove it.  Calls that use the workspace concurrently on different
  * streams race; give concurrent streams separate processes or no workspace.
