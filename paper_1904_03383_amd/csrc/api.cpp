@@ -355,6 +355,12 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
                                 : "k is not a multiple of the K tile");
         if (p.b_cols() % 4) return no("n is not a multiple of 4");
         if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
+        if (ki.defer) {
+            const int cb = ki.WN / 32;   // floats per store
+            if (c.splits != 1) return no("this variant has no split-K");
+            if ((reinterpret_cast<uintptr_t>(p.C) & (4 * cb - 1)) || p.ldc % cb || (p.batch > 1 && p.strideC % cb))
+                return no("rows of C are not aligned for this variant's stores");
+        }
         // the fast variants address inside a tile with 32-bit element offsets
         if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
             return no("leading dimension too large for the exact-fit kernels");

@@ -11,7 +11,10 @@ namespace tg {
      tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile<BM, BN, BK, WM, WN, L2, EDGE>},
 #define TG_PROW(BM, BN, BK, WM, WN, NAME)                                                       \
     {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, true, false, (BM / WM) * (BN / WN) * 64, \
-     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile_stream<BM, BN, BK, WM, WN, false>},
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile_stream<BM, BN, BK, WM, WN, false, false>},
+#define TG_QROW(BM, BN, BK, WM, WN, NAME)                                                       \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, false, false, true, false, (BM / WM) * (BN / WN) * 64, \
+     tile_lds_bytes<BM, BN, BK, WM, WN>(), &launch_tile_stream<BM, BN, BK, WM, WN, false, true>, 0, false, 0, true},
 
 // (BM, BN, BK, WM, WN, two_level, edge, name)
 #define TG_TILE_LIST(X)                                                     \
@@ -42,9 +45,10 @@ namespace tg {
 
 #define TG_DECL_X(BM, BN, BK, WM, WN, L2, EDGE, NAME) TG_DECL(BM, BN, BK, WM, WN, L2, EDGE)
 TG_TILE_LIST(TG_DECL_X)
-extern template hipError_t launch_tile_stream<128, 128, 16, 64, 64, false>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_tile_stream<128, 128, 32, 64, 64, false>(const GemmParams &, hipStream_t);
-extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_tile_stream<128, 128, 16, 64, 64, false, false>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_tile_stream<128, 128, 32, 64, 64, false, false>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_tile_stream<128, 256, 16, 64, 128, false, false>(const GemmParams &, hipStream_t);
+extern template hipError_t launch_tile_stream<128, 128, 16, 64, 64, false, true>(const GemmParams &, hipStream_t);
 
 // direct-to-LDS variants: (BM, BN, BK, WM, WN, two_level, LDS stages, wave groups along K, name)
 #define TG_DIRECT_LIST(X)                                                   \
@@ -101,6 +105,7 @@ static const KernelInfo kTable[] = {
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")
     TG_PROW(128, 128, 32, 64, 64, "p128x128x32_w64x64")
     TG_PROW(128, 256, 16, 64, 128, "p128x256x16_w64x128")
+    TG_QROW(128, 128, 16, 64, 64, "p128x128x16_w64x64_ds")
     {"wave32", KIND_WAVE, 32, 32, 8, 32, 32, false, true, false, false, 256, 0, &launch_wave32},
     {"wave16", KIND_WAVE, 16, 16, 16, 16, 16, false, true, false, false, 256, 0, &launch_wave16},
     {"wave16x32", KIND_WAVE, 16, 32, 16, 16, 32, false, false, false, false, 256, 0, &launch_wave16w<2>},

@@ -62,6 +62,7 @@ struct KernelInfo {
     int pieces;          // 0: fp32 MFMA; 6 or 9: every fp32 product formed from that many bf16 piece products
     bool precut;         // piece kernel whose operands are cut by separate passes into a workspace image
     int kwaves;          // KIND_WAVE: waves of a workgroup that share one tile, each with its part of K (0 = one wave per tile)
+    bool defer;          // persistent variant that stores a finished tile during the next one: no split-K, aligned rows of C
 };
 
 // Kernel table (registry.cpp).
@@ -74,7 +75,8 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t s);
 
 // Persistent form of the tile kernel: a fixed number of workgroups walk the K tiles of
 // several output tiles as one stream (exact-fit shapes).
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+// DEFER: finished tiles are stored between the MFMAs of the workgroup's next item.
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool DEFER>
 hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s);
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();

@@ -326,7 +326,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     const int col = n0 + wn * WN + li * CB;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;      // workgroup-uniform
     const bool lane_vec = col + CB <= p.n;
-    const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
+    const bool nt = p.splits == 1 && rows_aligned<CB>(out, ldo);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll

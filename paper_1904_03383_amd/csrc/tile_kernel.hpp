@@ -59,7 +59,8 @@ __device__ __forceinline__ void store_result(float *dst, V v, bool nt) {
     else *reinterpret_cast<VA *>(dst) = v;
 }
 
-// Whether the CB-float groups of this lane are naturally aligned in every row of the destination.
+// Whether every lane's CB-float groups are naturally aligned in every row of the destination that starts at
+// `first` (a lane's column is a multiple of CB, so this is the same for all lanes: a scalar condition).
 template <int CB>
 __device__ __forceinline__ bool rows_aligned(const float *first, int64_t ld) {
     return (reinterpret_cast<uintptr_t>(first) & (4 * CB - 1)) == 0 && ld % CB == 0;
@@ -466,7 +467,7 @@ sgemm_tile_kernel(const GemmParams p) {
         const int col = n0 + wn * WN + li * CB;
         const bool final_c = p.splits == 1;
         const bool lane_vec = col + CB <= p.n;
-        const bool nt = final_c && rows_aligned<CB>(out + col, ldo);
+        const bool nt = final_c && rows_aligned<CB>(out, ldo);
     #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
     #pragma unroll

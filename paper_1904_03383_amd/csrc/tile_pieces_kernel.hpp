@@ -348,7 +348,7 @@ sgemm_tile_pieces_kernel(const GemmParams p) {
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;
     const int col = n0 + wn * WN + li * CB;
     const bool lane_vec = col + CB <= p.n;
-    const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
+    const bool nt = p.splits == 1 && rows_aligned<CB>(out, ldo);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll

@@ -16,8 +16,12 @@
 
 namespace tg {
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
-__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (min_waves_per_simd<BM, BN, BK, WM, WN, TWO_LEVEL>()))
+// DEFER: a finished output tile is not stored at once; it waits in a second register set and its stores are
+// issued one by one between the MFMAs of the first K tile of the workgroup's next item, so that no wave ever
+// spends a phase doing nothing but stores (the last item of a workgroup is stored at the end as usual).
+// These variants write C only (no split-K) and need its rows naturally aligned for their CB-float stores.
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool DEFER>
+__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64, (min_waves_per_simd<BM, BN, BK, WM, WN, TWO_LEVEL || DEFER>()))
 sgemm_tile_stream_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -146,9 +150,136 @@ sgemm_tile_stream_kernel(const GemmParams p) {
                         a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
     };
 
+    // The waiting tile (DEFER): its values, this lane's address of row 0 of its wave tile, and how to store it.
+    f32x16 prev[DEFER ? RB : 1][DEFER ? CB : 1];
+    float *prev_base = nullptr;
+    int64_t prev_ldo = 0;
+    bool have_prev = false;
+    // Stores rows v = 8 * part .. 8 * part + 7 of every 32-row block of the waiting tile (RB * 8 stores).
+    auto store_prev = [&](int part) {
+#pragma unroll
+        for (int rb = 0; rb < (DEFER ? RB : 0); ++rb) {
+#pragma unroll
+            for (int vv = 0; vv < 8; ++vv) {
+                const int v = 8 * part + vv;
+                float *dst = prev_base + (int64_t)(rb * 32 + 8 * (v / 4) + (v % 4)) * prev_ldo;
+                bvec o;
+                if constexpr (CB == 1) {
+                    o = prev[rb][0][v];
+                } else {
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) o[cb] = prev[rb][cb][v];
+                }
+                store_result(dst, o, true);
+            }
+        }
+    };
+    constexpr int PART_STORES = RB * 8;
+
     constexpr int N_MFMA = 4 * RB * CB;
     constexpr int N_ST = A_LD + B_LD;
     constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
+
+    // One K tile of the stream (see tile_kernel.hpp for the order of operations inside a tile).  With the drain
+    // tag the stores of the waiting tile go out between its MFMAs, half with the LDS writes, half with the loads.
+    int stage = 0;
+    // Single steps of a K tile, for the drain form below, where the order is written out instruction by instruction
+    // (a sched_group_barrier pattern cannot place the stores: their address arithmetic is not in its vocabulary).
+    auto mfma_one = [&](int set, int j) {   // j enumerates (t, rb, cb) in the order of mfma_octet
+        const int t = j / (RB * CB), rb = (j / CB) % RB, cb = j % CB;
+        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+    };
+    auto lds_write_one = [&](int st, int i) {
+        if (i < A_LD) *reinterpret_cast<f32x4 *>(As + st * A_STAGE + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
+        else *reinterpret_cast<f32x4 *>(Bs + st * B_STAGE + b_row[i - A_LD] * LDB_S + b_col[i - A_LD]) = b_reg[i - A_LD];
+    };
+    auto load_one = [&](int i) {
+        if (i < A_LD) a_reg[i] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i]);
+        else b_reg[i - A_LD] = *reinterpret_cast<const f32x4 *>(Bg + b_off[i - A_LD]);
+    };
+    auto advance_cursor = [&]() {
+        if (ld_left > 1) {
+            --ld_left;
+            Ag += BK;
+            Bg += (int64_t)BK * p.ldb;
+        } else if (ld_work + step < total_work) {
+            ld_work += step;
+            seek(ld_work);
+        }
+    };
+    auto store_prev_one = [&](int part, int sidx) {
+        const int rb = sidx / 8, v = 8 * part + sidx % 8;
+        float *dst = prev_base + (int64_t)(rb * 32 + 8 * (v / 4) + (v % 4)) * prev_ldo;
+        bvec o;
+        if constexpr (CB == 1) {
+            o = prev[DEFER ? rb : 0][0][v];
+        } else {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) o[cb] = prev[DEFER ? rb : 0][cb][v];
+        }
+        store_result(dst, o, true);   // (DEFER variants: C only, rows naturally aligned: checked on the host)
+    };
+
+    // One K tile of the stream (see tile_kernel.hpp for the order of operations inside a tile).  With the drain
+    // tag the stores of the waiting tile go out between its MFMAs, half with the LDS writes, half with the loads.
+    auto tile_body = [&](auto drain_tag) {
+        constexpr bool DRAIN = decltype(drain_tag)::value;
+#pragma unroll
+        for (int o = 0; o < NO - 2; ++o) {
+            read_frags(stage, o + 1, (o + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_octet(o & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        read_frags(stage, NO - 1, (NO - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (DRAIN) {
+#pragma unroll
+            for (int j = 0; j < N_MFMA; ++j) {
+                mfma_one((NO - 2) & 1, j);
+                if (j % MFMA_PER_ST == MFMA_PER_ST - 1 && j / MFMA_PER_ST < N_ST) lds_write_one(stage ^ 1, j / MFMA_PER_ST);
+#pragma unroll
+                for (int q = j * PART_STORES / N_MFMA; q < (j + 1) * PART_STORES / N_MFMA; ++q) store_prev_one(0, q);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = N_MFMA / MFMA_PER_ST; i < N_ST; ++i) lds_write_one(stage ^ 1, i);
+        } else {
+            mfma_octet((NO - 2) & 1);
+            store_lds(stage ^ 1);
+#pragma unroll
+            for (int i = 0; i < N_ST; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // LDS write
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        read_frags(stage ^ 1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (DRAIN) {
+#pragma unroll
+            for (int j = 0; j < N_MFMA; ++j) {
+                if (j % MFMA_PER_ST == 0 && j / MFMA_PER_ST < N_ST) load_one(j / MFMA_PER_ST);
+                mfma_one((NO - 1) & 1, j);
+#pragma unroll
+                for (int q = j * PART_STORES / N_MFMA; q < (j + 1) * PART_STORES / N_MFMA; ++q) store_prev_one(1, q);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = N_MFMA / MFMA_PER_ST; i < N_ST; ++i) load_one(i);
+            advance_cursor();
+        } else {
+            load_next();
+            mfma_octet((NO - 1) & 1);
+#pragma unroll
+            for (int i = 0; i < N_ST; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global load
+                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
     // ---- start of the stream --------------------------------------------------------------------
     seek(ld_work);
@@ -157,7 +288,6 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     __syncthreads();
     read_frags(0, 0, 0);
     load_next();
-    int stage = 0;
 
     for (unsigned work = blockIdx.x; work < total_work; work += step) {
         int slice, tm, tn, prob, kb, ke;
@@ -191,34 +321,12 @@ sgemm_tile_stream_kernel(const GemmParams p) {
                 ++since_flush;
             }
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int o = 0; o < NO - 2; ++o) {
-                read_frags(stage, o + 1, (o + 1) & 1);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_octet(o & 1);
-                __builtin_amdgcn_sched_barrier(0);
+            if (DEFER && have_prev && kt == kb) {   // wave-uniform
+                tile_body(std::true_type());
+                have_prev = false;
+            } else {
+                tile_body(std::false_type());
             }
-            read_frags(stage, NO - 1, (NO - 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_octet((NO - 2) & 1);
-            store_lds(stage ^ 1);
-#pragma unroll
-            for (int i = 0; i < N_ST; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);             // LDS write
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            read_frags(stage ^ 1, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_next();
-            mfma_octet((NO - 1) & 1);
-#pragma unroll
-            for (int i = 0; i < N_ST; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global load
-                __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
-            }
-            __builtin_amdgcn_sched_barrier(0);
             stage ^= 1;
         }
         if constexpr (TWO_LEVEL) {
@@ -240,31 +348,46 @@ sgemm_tile_stream_kernel(const GemmParams p) {
             ldo = p.ldc;
         }
         const int col = tn * BN + wn * WN + li * CB;
-        const bool nt = p.splits == 1 && rows_aligned<CB>(out + col, ldo);
+        const bool nt = p.splits == 1 && rows_aligned<CB>(out, ldo);
+        if constexpr (DEFER) {
+            // (a tile still waiting here had no successor K tile to ride on: cannot happen, every item has one)
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+            for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = tm * BM + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                float *dst = out + (int64_t)row * ldo + col;
-                bvec o;
-                if constexpr (CB == 1) {
-                    o = acc[rb][0][v];
-                } else {
+                for (int cb = 0; cb < CB; ++cb) prev[rb][cb] = acc[rb][cb];
+            prev_base = out + (int64_t)(tm * BM + wm * WM + 4 * h) * ldo + col;
+            prev_ldo = ldo;
+            have_prev = true;
+        } else {
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+            for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = tm * BM + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                    float *dst = out + (int64_t)row * ldo + col;
+                    bvec o;
+                    if constexpr (CB == 1) {
+                        o = acc[rb][0][v];
+                    } else {
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) o[cb] = acc[rb][cb][v];
+                    }
+                    store_result(dst, o, nt);
                 }
-                store_result(dst, o, nt);
             }
         }
     }
+    if (DEFER && have_prev) {   // the workgroup's last item
+        store_prev(0);
+        store_prev(1);
+    }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, bool DEFER>
 hipError_t launch_tile_stream(const GemmParams &p, hipStream_t s) {
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     constexpr int lds_used = tile_lds_bytes<BM, BN, BK, WM, WN>();
-    auto kern = sgemm_tile_stream_kernel<BM, BN, BK, WM, WN, TWO_LEVEL>;
+    auto kern = sgemm_tile_stream_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, DEFER>;
     int lds = lds_used;
     if (p.max_blocks_per_cu > 0) {
         const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;
