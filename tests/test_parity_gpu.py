@@ -116,7 +116,10 @@ def test_each_kernel_variant(dist):
 
 
 @pytest.mark.parametrize("spec", ["p128x128x16_w64x64:p1", "p128x128x32_w64x64:p2:o2", "p128x128x32_w64x64:p3:g3",
-                                  "p128x128x16_w64x64:s2:p1"])
+                                  "p128x128x16_w64x64:s2:p1",
+                                  # deferred stores: every workgroup has several items, so tiles are stored during
+                                  # the next item's first K tile (and the last one at the end)
+                                  "p128x128x16_w64x64_ds:p1", "p128x128x16_w64x64_ds:p2:o2", "p128x128x16_w64x64_ds:p3:g3"])
 def test_persistent_launch(spec):
     """Fewer workgroups than tiles: every workgroup loops over several tiles."""
     import torch
@@ -127,6 +130,25 @@ def test_persistent_launch(spec):
     a, b = ig.make_operands(1, m, n, k, "int", 313, 314)
     tg.force_config(spec)
     check_against_oracle(run_hip(a[0], b[0]), a[0], b[0], exact=True, what=spec)
+
+
+def test_deferred_store_variant_says_what_it_cannot_take():
+    import torch
+    m, n, k = 256, 256, 64
+    a, b = ig.make_operands(1, m, n, k, "int", 315, 316)
+    da, db = to_dev(a[0]), to_dev(b[0])
+    ws = torch.empty(4 * m * n, dtype=torch.float32, device="cuda")
+    tg.set_workspace(ws)
+    tg.force_config("p128x128x16_w64x64_ds:s2:p1")
+    with pytest.raises(tg.TgemmError, match="no split-K"):
+        tg.sgemm(da, db)
+    buf = torch.empty(m * n + 1, device="cuda")
+    tg.force_config("p128x128x16_w64x64_ds:p1")
+    with pytest.raises(tg.TgemmError, match="rows of C are not aligned"):
+        tg.sgemm(da, db, out=buf[1:].view(m, n))
+    out = tg.sgemm(da, db)   # a fresh, aligned C: accepted
+    torch.cuda.synchronize()
+    check_against_oracle(out.cpu().numpy(), a[0], b[0], exact=True, what="deferred stores, aligned C")
 
 
 @pytest.mark.parametrize("group", [1, 3, 8, 64])
