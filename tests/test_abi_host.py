@@ -177,6 +177,11 @@ def test_force_config_grammar_and_get_config(lib):
     try:
         with pytest.raises(tg.TgemmError, match="not valid here"):
             tg.get_config(1, 1000, 1024, 1024)           # the persistent variants walk whole tiles only
+        tg.force_config("p128x128x16_w64x64_ds:p2")
+        assert tg.get_config(1, 4096, 4096, 128) == "p128x128x16_w64x64_ds:s1:g8:p2"
+        tg.force_config("p128x128x16_w64x64_ds:s2:p2")
+        with pytest.raises(tg.TgemmError, match="no split-K"):
+            tg.get_config(1, 1024, 1024, 1024)           # the deferred-store variant writes C only
     finally:
         tg.force_config(None)
     buf = ctypes.create_string_buffer(4)
