@@ -162,6 +162,20 @@ def sgemm(a, b, out=None, stream=None):
     return out
 
 
+def _elem_strides(t):
+    """(row stride, column stride) in elements of a 2-D view, for tg_sgemm_strided.
+
+    A dimension of extent > 1 must have a positive stride: an expanded (stride 0) view has no element-stride
+    form, and passing 1 in its place would make the library read past the tensor's storage."""
+    for d in (0, 1):
+        if t.shape[d] > 1 and t.stride(d) < 1:
+            raise ValueError("operands must have positive strides along every dimension of extent > 1 "
+                             "(expanded or broadcast views are not supported: materialise them first)")
+    rs = int(t.stride(0)) if t.shape[0] > 1 else 1
+    cs = int(t.stride(1)) if t.shape[1] > 1 else 1
+    return rs, cs
+
+
 def sgemm_strided(a, b, out=None, stream=None):
     """C = A.B for 2-D float32 device tensors with any positive strides (views such as a[:, ::32] or a.T).
 
@@ -180,12 +194,8 @@ def sgemm_strided(a, b, out=None, stream=None):
     if tuple(out.shape) != (m, n):
         raise ValueError("out has the wrong shape")
 
-    def strides(t):
-        rs = int(t.stride(0)) if t.shape[0] > 1 else 1
-        cs = int(t.stride(1)) if t.shape[1] > 1 else 1
-        return max(rs, 1), max(cs, 1)
-    rsa, csa = strides(a)
-    rsb, csb = strides(b)
+    rsa, csa = _elem_strides(a)
+    rsb, csb = _elem_strides(b)
     if csa == 1:
         rsa = max(rsa, k, 1)
     if csb == 1:

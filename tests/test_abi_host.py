@@ -240,7 +240,21 @@ def test_binding_refuses_non_device_tensors():
         tg.sgemm_batched(a[None], a[None])
 
 
-def test_header_is_plain_c_and_every_entry_point_links(tmp_path):
+def test_strided_binding_refuses_views_without_positive_strides():
+    """An expanded view (stride 0) has no element-stride form; turning the 0 into 1 would read past its storage."""
+    import torch
+    from paper_1904_03383_amd import binding
+    v = torch.zeros(8)
+    with pytest.raises(ValueError, match="positive strides"):
+        binding._elem_strides(v.expand(5, 8))          # strides (0, 1)
+    with pytest.raises(ValueError, match="positive strides"):
+        binding._elem_strides(v[:, None].expand(8, 5))  # strides (1, 0)
+    assert binding._elem_strides(torch.zeros(6, 64)[:, ::32]) == (64, 32)
+    assert binding._elem_strides(torch.zeros(6, 4).T) == (1, 4)
+    assert binding._elem_strides(v.expand(1, 8)) == (1, 1)   # extent 1: its stride is never used
+
+
+def test_header_is_plain_c_and_every_entry_point_links(tmp_path, may_spawn):
     """gcc -std=c99 program that includes only tgemm.h, links libtgemm.so and calls each entry point's error path."""
     import os
     import subprocess
@@ -276,7 +290,7 @@ def test_tune_cli_shape_parser():
             parse_shape(bad)
 
 
-def test_host_logic_survives_random_sizes_specs_and_cache_files(tmp_path):
+def test_host_logic_survives_random_sizes_specs_and_cache_files(tmp_path, may_spawn):
     """tests/c_abi/host_fuzz.c: 40000 random shapes through the chooser, 20000 random specs, 300 random cache files."""
     import subprocess
     exe = tmp_path / "host_fuzz"

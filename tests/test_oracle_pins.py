@@ -206,7 +206,7 @@ def test_axpy_pins_reject_planted_mistake(idx):
 
 # ---- sanitizer build ------------------------------------------------------------------------------
 
-def test_oracle_c_under_address_and_ub_sanitizers(tmp_path):
+def test_oracle_c_under_address_and_ub_sanitizers(tmp_path, may_spawn):
     """oracle.c compiled with -fsanitize=address,undefined and run on closed-form cases (threads, strides, row subsets)."""
     import pathlib
     import subprocess
