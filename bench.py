@@ -214,53 +214,73 @@ def time_axpy(tg, torch, steps, warmup):
             "bound": "hbm", "parity_ok": ok, "cpu_oracle_seconds": cpu_s, "cpu_oracle_gbs": nbytes / cpu_s / 1e9, "cpu_cores": 1}
 
 
-def time_strided(tg, torch, steps, warmup, restore_ws):
-    """Strided matmul of Sec. 5.2: 1024^3 with consecutive elements of A stored 32 apart (tg_sgemm_strided).
+def time_layout(tg, torch, name, m, n, k, layout_a, layout_b, steps, warmup, restore_ws, packed_kernel=None):
+    """One product through tg_sgemm_strided with operands that are not plain row-major: layout 'N' plain, 'T' stored
+    transposed (column-major), 'S32' element stride 32 along the rows (the strided matmul of Sec. 5.2).
 
-    Timed twice: with a workspace (A gathered once into a packed copy, then the unit-stride kernels:
-    the figure reported) and without one (the predicated kernels gather on the fly)."""
+    The figure reported is without a workspace: the operands are read as they lie by the kernel variants with fused
+    gather / transposing loaders.  With `packed_kernel`, the packing path is timed too, for comparison: a workspace is
+    set and that plain kernel forced, so every non-plain operand is first copied by the packing pass."""
     from paper_1904_03383_amd import inputgen as ig
     from oracle import oracle
-    m = n = k = 1024
-    a_store = ig.uniform(3003, (m, k * 32))
-    b = ig.uniform(3004, (k, n))
-    da = torch.from_numpy(a_store).to("cuda")[:, ::32]
-    db = torch.from_numpy(b).to("cuda")
+
+    def operand(seed, rows, cols, layout):
+        if layout == "T":
+            store = ig.uniform(seed, (cols, rows))
+            return np.ascontiguousarray(store.T), torch.from_numpy(store).to("cuda").T
+        if layout.startswith("S"):
+            cs = int(layout[1:])
+            store = ig.uniform(seed, (rows, cols * cs))
+            return np.ascontiguousarray(store[:, ::cs]), torch.from_numpy(store).to("cuda")[:, ::cs]
+        store = ig.uniform(seed, (rows, cols))
+        return store, torch.from_numpy(store).to("cuda")
+
+    a, da = operand(3003, m, k, layout_a)
+    b, db = operand(3004, k, n, layout_b)
     out = torch.empty((m, n), device="cuda")
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
-    rows = list(range(0, m, 16))
-    a = np.ascontiguousarray(a_store[:, ::32])
+    rows = sorted(set(int(r) for r in np.linspace(0, m - 1, num=64)))
     c_ref, s_abs = oracle.sgemm_f64(a, b, rows=rows, want_abs=True)
 
-    def timed():
+    def timed(reps):
         out.fill_(float("nan"))
         for _ in range(warmup):
             tg.sgemm_strided(da, db, out=out)
         cfg = tg.last_config()
         torch.cuda.synchronize()
         ev0.record(torch.cuda.current_stream())
-        for _ in range(steps):
+        for _ in range(reps):
             tg.sgemm_strided(da, db, out=out)
         ev1.record(torch.cuda.current_stream())
         torch.cuda.synchronize()
         par = oracle.parity_metrics(out.cpu().numpy()[rows], c_ref, s_abs)
         ok = bool(par["max_ratio"] <= ELEM_TOL and par["rel_fro"] <= FRO_TOL and par["finite"])
-        return ev0.elapsed_time(ev1) / steps, cfg, ok
+        return ev0.elapsed_time(ev1) / reps, cfg, ok
 
-    tg.set_workspace(None)
-    gather_ms, gather_cfg, gather_ok = timed()
-    ws = torch.empty(max(tg.strided_workspace_bytes(m, n, k, 32, 1) // 4, 4), dtype=torch.float32, device="cuda")
-    tg.set_workspace(ws)
-    dev_ms, cfg, ok = timed()
-    tg.set_workspace(restore_ws)
     flops = 2.0 * m * n * k
-    return {"workload": "strided_1024_csa32", "m": m, "n": n, "k": k, "tile_config": cfg, "device_ms_per_step": dev_ms,
-            "flops": flops, "device_tflops": flops / (dev_ms * 1e-3) / 1e12,
-            "frac_mfma_peak": flops / (dev_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, "bound": "mfma",
-            "parity_ok": ok and gather_ok,
-            "no_workspace": {"tile_config": gather_cfg, "device_ms_per_step": gather_ms,
-                             "device_tflops": flops / (gather_ms * 1e-3) / 1e12}}
+    reps = max(5, min(steps, int(50.0 / (flops / 100e12 * 1e3)) + 1))     # about 50 ms of work
+    tg.set_workspace(None)
+    dev_ms, cfg, ok = timed(reps)
+    res = {"workload": name, "m": m, "n": n, "k": k, "layout_a": layout_a, "layout_b": layout_b, "workspace": False,
+           "tile_config": cfg, "device_ms_per_step": dev_ms, "flops": flops, "device_tflops": flops / (dev_ms * 1e-3) / 1e12,
+           "frac_mfma_peak": flops / (dev_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, "bound": "mfma", "parity_ok": ok}
+    if packed_kernel:
+        csa = 1 if layout_a == "N" else 32
+        csb = 1 if layout_b == "N" else 32
+        ws = torch.empty(max(tg.strided_workspace_bytes(m, n, k, csa, csb) // 4, 4), dtype=torch.float32, device="cuda")
+        tg.set_workspace(ws)
+        tg.force_config(packed_kernel)
+        try:
+            p_ms, p_cfg, p_ok = timed(reps)
+        finally:
+            tg.force_config(None)
+        res["packed_with_workspace"] = {"tile_config": p_cfg, "device_ms_per_step": p_ms,
+                                        "device_tflops": flops / (p_ms * 1e-3) / 1e12}
+        res["parity_ok"] = ok and p_ok
+        del ws
+    tg.set_workspace(restore_ws)
+    return res
 
 
 def time_pieces(tg, torch, steps, warmup, reps_tune, restore_ws):
@@ -301,7 +321,6 @@ def time_pieces(tg, torch, steps, warmup, reps_tune, restore_ws):
     par = parity_on_rows(a, b, out, rows)
     res = {"workload": name + " in math mode BF16_PIECES (opt-in)", "batch": batch, "m": m, "n": n, "k": k, "dist": dist,
            "tile_config": cfg, "device_ms_per_step": dev_ms, "device_tflops": flops / (dev_ms * 1e-3) / 1e12,
-           "frac_mfma_peak": flops / (dev_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
            "piece_products_per_product": pieces,
            "parity": {"rows_checked": len(rows), "max_ratio": par["max_ratio"], "rel_fro": par["rel_fro"],
                       "ok": bool(par["finite"] and par["zero_ok"] and par["max_ratio"] <= ELEM_TOL and par["rel_fro"] <= FRO_TOL)}}
@@ -454,11 +473,23 @@ def main():
         log(f"  axpy n=2^26: {r['device_ms_per_step'] * 1e3:.1f} us  {r['algorithmic_gbs']:.0f} GB/s  "
             f"({r['frac_hbm_peak'] * 100:.1f}% of HBM peak)  parity_ok={r['parity_ok']}")
         others.append(r)
-        r = time_strided(tg, torch, min(args.steps, 100), min(args.warmup, 10), ws)
-        log(f"  strided matmul 1024^3 (A element stride 32): {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.1f} us  "
-            f"{r['device_tflops']:.2f} TFLOP/s  parity_ok={r['parity_ok']}  (no workspace: {r['no_workspace']['tile_config']} "
-            f"{r['no_workspace']['device_ms_per_step'] * 1e3:.1f} us)")
-        others.append(r)
+        # strided matmul (Sec. 5.2) and transposed layouts through tg_sgemm_strided, no workspace
+        layouts = [("strided_1024_csa32", 1024, 1024, 1024, "S32", "N", "d64x64x32_w32x32"),
+                   ("AT_B_1024", 1024, 1024, 1024, "T", "N", "d64x64x32_w32x32"),
+                   ("A_BT_1024", 1024, 1024, 1024, "N", "T", "d64x64x32_w32x32"),
+                   ("AT_BT_1024", 1024, 1024, 1024, "T", "T", None),
+                   ("AT_B_4096", 4096, 4096, 4096, "T", "N", "t128x256x32_w64x128_acc2"),
+                   ("A_BT_4096", 4096, 4096, 4096, "N", "T", None)]
+        for lname, lm, ln, lk, la, lb, packed_kernel in layouts:
+            r = time_layout(tg, torch, lname, lm, ln, lk, la, lb, min(args.steps, 100), min(args.warmup, 10), ws, packed_kernel)
+            extra = ""
+            if "packed_with_workspace" in r:
+                pw = r["packed_with_workspace"]
+                extra = f"  (packing pass + {pw['tile_config']}: {pw['device_ms_per_step'] * 1e3:.1f} us)"
+            log(f"  {lname} (A:{la} B:{lb}, no workspace): {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.1f} us  "
+                f"{r['device_tflops']:.2f} TFLOP/s  parity_ok={r['parity_ok']}{extra}")
+            parity_ok = parity_ok and r["parity_ok"]
+            others.append(r)
 
     if not args.no_others:
         r = time_pieces(tg, torch, args.steps, args.warmup, args.tune_reps, ws)
@@ -480,10 +511,21 @@ def main():
         log("copy calibration: one elementwise kernel, 256 MiB read + 256 MiB written")
         del src, dst
 
-    traffic = None
+    # HBM traffic of the dominant kernel per launch comes from committed rocprofv3 counter runs (FETCH_SIZE and
+    # WRITE_SIZE cannot be read from inside this process): profiles/hbm_traffic.json lists, per workload, the tile
+    # configurations it was measured at.  The figure is only reported when this run timed one of exactly those.
+    traffic, traffic_note = None, None
     tfile = ROOT / "profiles" / "hbm_traffic.json"
     if tfile.exists():
-        traffic = json.loads(tfile.read_text()).get(args.workload, {}).get("bytes_per_launch")
+        entries = json.loads(tfile.read_text()).get(args.workload, [])
+        entries = [entries] if isinstance(entries, dict) else entries
+        match = [e for e in entries if e.get("tile_config") == head["tile_config"]]
+        if match:
+            traffic = match[0].get("bytes_per_launch")
+            traffic_note = f"rocprofv3 FETCH_SIZE + WRITE_SIZE at {head['tile_config']}, profiles/hbm_traffic.json"
+        elif entries:
+            traffic_note = ("not measured at the configuration timed here (" + head["tile_config"] + "); profiles/hbm_traffic.json has "
+                            + ", ".join(f"{e.get('tile_config')}: {e.get('bytes_per_launch', 0) / 1e6:.1f} MB" for e in entries))
 
     if head["bound"] == "mfma":
         roof = {"bound": "mfma", "achieved": head["device_tflops"], "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
@@ -491,6 +533,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": head["algorithmic_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": head["frac_hbm_peak"], "traffic": traffic}
+    roof["traffic_note"] = traffic_note
     roof["kernel"] = head["tile_config"]
     roof["avg_launch_ms"] = head["device_ms_per_step"]
 

@@ -82,11 +82,20 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
  * A column-major C is obtained by computing C^T = B^T.A^T: swap the operands and exchange
  * each one's two strides.  All strides are in elements and must be >= 1 (ldc >= n); the
  * operands may not overlap C.  With csa == csb == 1 this is tg_sgemm(lda = rsa, ldb = rsb).
- * Otherwise, when a workspace of tg_strided_workspace_bytes(...) is set, each operand with a
- * non-unit stride that more than one tile row or column would fetch is first gathered into a
- * packed row-major copy in the workspace (one pass, every element fetched once) and the
- * unit-stride kernels multiply the copies; tg_last_config() then ends in "+packA", "+packB" or
- * "+packAB".  Without that room the predicated kernels gather the operands element by element.
+ * Otherwise the operands are read as they lie wherever a kernel variant for their layout exists (k a
+ * multiple of 32 and, for a plain B, n a multiple of 4): a transposed operand on the 16-byte grid (A with
+ * rsa == 1, csa % 4 == 0, m % 4 == 0; B with rsb == 1, csb % 4 == 0; 16-byte aligned bases) is loaded along
+ * its unit-stride axis ("_ta" / "_tb" in tg_last_config()) and costs the same as the plain product; any
+ * other strides are gathered element by element straight into the kernel's staging memory, several K
+ * tiles ahead ("_ga" / "_gb"): no workspace and no separate pass are involved.  An element-strided
+ * operand costs a cache-line request per element and tile that uses it, so the paper's case (1024^3,
+ * csa = 32: 128 MiB of lines behind a 4 MiB operand) runs at about 2.5 times the plain product's time.
+ * Problems those variants do not take (other k, a transposed operand off the 16-byte grid): when a
+ * workspace of tg_strided_workspace_bytes(...) is set, each operand with a non-unit stride that more than
+ * one tile row or column would fetch is first gathered into a packed row-major copy in the workspace (one
+ * pass, every element fetched once) and the unit-stride kernels multiply the copies; tg_last_config()
+ * then ends in "+packA", "+packB" or "+packAB".  Without that room the predicated kernels gather the
+ * operands element by element.
  */
 tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k,
                            const float *A, int64_t rsa, int64_t csa,

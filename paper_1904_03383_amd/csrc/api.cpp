@@ -68,8 +68,23 @@ struct Problem {
                     // (C's alignment only decides between vector and element stores)
     int64_t csa = 1, csb = 1;   // element strides along k of A / along n of B (strided entry point)
     int64_t nb = 0;             // columns of B the exact-fit kernels may fetch (0: n); n rounded up to 4 for a padded copy
+    bool a_al = true, b_al = true;   // base (and batch stride) of A / B on the 16-byte grid (set by validate)
     int64_t b_cols() const { return nb ? nb : n; }
     bool unit() const { return csa == 1 && csb == 1; }
+    // Can a kernel that reads A / B in this operand mode take the operand as it lies?  (KernelInfo::amode, bmode:
+    // 0 plain with 16-byte rows, 1 transposed with 16-byte rows, 2 any element strides)
+    bool a_fits(int mode) const {
+        if (mode == 0) return csa == 1 && a_al && lda % 4 == 0;
+        if (mode == 1) return lda == 1 && csa % 4 == 0 && a_al && m % 4 == 0;
+        return true;
+    }
+    bool b_fits(int mode) const {
+        if (mode == 0) return csb == 1 && b_al && ldb % 4 == 0;
+        if (mode == 1) return ldb == 1 && csb % 4 == 0 && b_al;
+        return true;
+    }
+    int a_class() const { return a_fits(0) ? 0 : (a_fits(1) ? 1 : 2); }
+    int b_class() const { return b_fits(0) ? 0 : (b_fits(1) ? 1 : 2); }
 };
 
 typedef std::tuple<int64_t, int64_t, int64_t, int64_t, int> ShapeKey;
@@ -208,8 +223,9 @@ tg_status validate(Problem &p) {
     if (p.m > INT32_MAX || p.n > INT32_MAX || p.k > INT32_MAX || p.batch > INT32_MAX)
         return fail(TG_ERR_UNSUPPORTED, "a dimension exceeds 2^31-1");
     auto a16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-    p.aligned = a16(p.A) && a16(p.B) && p.lda % 4 == 0 && p.ldb % 4 == 0 &&
-                (p.batch <= 1 || (p.strideA % 4 == 0 && p.strideB % 4 == 0)) && p.unit();
+    p.a_al = a16(p.A) && (p.batch <= 1 || p.strideA % 4 == 0);
+    p.b_al = a16(p.B) && (p.batch <= 1 || p.strideB % 4 == 0);
+    p.aligned = p.a_fits(0) && p.b_fits(0);
     return TG_OK;
 }
 
@@ -251,6 +267,11 @@ int64_t sat_mul(std::initializer_list<int64_t> f) {
     for (int64_t x : f)
         if (mul_ovf(r, x, &r)) return INT64_MAX;
     return r;
+}
+
+int64_t sat_add(int64_t a, int64_t b) {
+    int64_t r;
+    return add_ovf(a, b, &r) ? INT64_MAX : r;
 }
 
 size_t ws_need(const Problem &p, int splits) {
@@ -347,13 +368,17 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
         if (sat_mul({p.batch, ceil_div(p.k, ki.BK), std::max(ceil_div(p.m, ki.BM), ceil_div(p.n, ki.BN))}) > INT32_MAX)
             return no("too many workgroups");
     } else if (!ki.edge) {
-        if (!p.aligned) return no("operands are not 16-byte aligned");
+        if (ki.amode == 0 && ki.bmode == 0) {
+            if (!p.aligned) return no("operands are not 16-byte aligned");
+        } else if (!p.a_fits(ki.amode) || !p.b_fits(ki.bmode)) {
+            return no("the operands do not lie as this variant reads them (plain / transposed with 16-byte aligned rows / strided)");
+        }
         // K must fill whole tiles; ragged m and n are handled by re-reading the last row / vector
         // and masking the stores (the persistent variants walk exact tiles only)
         if (p.k % ki.BK && !(ki.k_tail && p.k % 4 == 0 && p.k >= ki.BK))
             return no(ki.k_tail ? "k is neither a multiple of the K tile nor (a multiple of 4 and at least one K tile)"
                                 : "k is not a multiple of the K tile");
-        if (p.b_cols() % 4) return no("n is not a multiple of 4");
+        if (ki.bmode == 0 && p.b_cols() % 4) return no("n is not a multiple of 4");
         if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
         if (ki.defer) {
             const int cb = ki.WN / 32;   // floats per store
@@ -362,8 +387,13 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
                 return no("rows of C are not aligned for this variant's stores");
         }
         // the fast variants address inside a tile with 32-bit element offsets
-        if ((ki.BM - 1) * p.lda + ki.BK >= INT32_MAX || (ki.BK - 1) * p.ldb + ki.BN >= INT32_MAX)
-            return no("leading dimension too large for the exact-fit kernels");
+        {
+            const int64_t span_a = ki.amode == 1 ? sat_add(sat_mul({ki.BK - 1, p.csa}), ki.BM)
+                                                 : sat_add(sat_mul({ki.BM - 1, p.lda}), sat_mul({ki.BK, p.csa}));
+            const int64_t span_b = ki.bmode == 1 ? sat_add(sat_mul({ki.BN - 1, p.csb}), ki.BK)
+                                                 : sat_add(sat_mul({ki.BK - 1, p.ldb}), sat_mul({ki.BN, p.csb}));
+            if (span_a >= INT32_MAX || span_b >= INT32_MAX) return no("leading dimension too large for the exact-fit kernels");
+        }
         // (the bf16-piece kernels form 32-bit byte offsets)
         if (ki.pieces && ((ki.BM - 1) * p.lda + ki.BK >= (1 << 30) || (ki.BK - 1) * p.ldb + ki.BN >= (1 << 30)))
             return no("leading dimension too large for the exact-fit kernels");
@@ -480,7 +510,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     // the 32-wide and 32-tall tiles are for skinny products; on others they re-fetch the long operand too often
     if ((ki.BN <= 32 && p.n > 32) || (ki.BM <= 32 && p.m > 32)) eff *= 0.9;
     if (ki.persistent) eff *= p.k <= 256 ? 1.0 : 0.95;
-    if (!p.unit()) eff *= 0.5;
+    if (!p.unit() && ki.edge) eff *= 0.5;
+    // (wave tiles of 16 rows on the 16x16x4 instruction: 1024^3 with plain operands 35 us against 27 us for 32x128 tiles)
+    if (ki.WM < 32) eff *= 0.8;
+    // transposed operands read as they lie cost a few more LDS reads per MFMA
+    if (ki.amode == 1) eff *= 0.985;
+    if (ki.bmode == 1) eff *= 0.985;
     // a tile of which at most a quarter is real output (tiny problems of a batch): the waves
     // that hold only padding still take their share of the loads, the barrier and the MFMA pipe
     if (p.m * 2 <= ki.BM && p.n * 2 <= ki.BN) eff *= 0.8;
@@ -497,6 +532,28 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     // 1 us: the first K tile's trip through LDS and the epilogue, which the wave kernels do not have (a sweep of
     // 30 small and mid-size shapes: the model's first choice then averages 5 % above the best measured candidate)
     double t = launch + 1e-6 + per_cu * block_flops / cu_rate;
+    // A gathered operand: every element costs a line request (its own cache line when the stride is large) in every tile
+    // that fetches it.  Measured with hardware counters on 1024^3 with A at element stride 32 (requests per CU, average
+    // latency per request, time): a CU's L1 keeps about a hundred line requests in flight at 450 cycles (L2 hit) to 1400
+    // cycles (miss) each, which comes to about 1.3 ns per request and CU (64x64 tiles: 74 K requests per CU, 93 us;
+    // 128x128: 132 K, 164 us); and the distinct lines arrive from the fabric at about 2.3 TB/s however the tiles are cut
+    // (32x128: 61 us, 16x256: 57 us, for 128 MiB of lines).
+    if (ki.amode == 2 || ki.bmode == 2) {
+        const double line_a = std::min(4.0 * p.csa, 128.0), line_b = std::min(4.0 * p.csb, 128.0);
+        const double tm = (double)ceil_div(p.m, ki.BM), tn = (double)ceil_div(p.n, ki.BN);
+        // line requests of one workgroup: per element of a gathered operand, per 128 bytes of a plain one
+        const double req_a = ki.amode == 2 ? (double)ki.BM * p.k * (line_a / 128.0 > 0.25 ? 1.0 : 4.0 * line_a / 128.0) : (double)ki.BM * p.k / 32.0;
+        const double req_b = ki.bmode == 2 ? (double)ki.BN * p.k * (line_b / 128.0 > 0.25 ? 1.0 : 4.0 * line_b / 128.0) : (double)ki.BN * p.k / 32.0;
+        double lines = 0;
+        if (ki.amode == 2) lines += p.batch * (double)p.m * p.k * line_a;
+        if (ki.bmode == 2) lines += p.batch * (double)p.k * p.n * line_b;
+        // (16-row tiles: best while every workgroup is resident at once, 1024^3 57 us against 61 us for 32x128; with
+        // several rounds per CU they measured about twice the time per request, 2048^3 523 us against 434 us)
+        const double per_req = ki.BM <= 16 && per_cu > 1 ? 2.7e-9 : 1.3e-9;
+        t = std::max(t, launch + 1e-6 + per_cu * (req_a + req_b) / splits * per_req);
+        t = std::max(t, launch + 1e-6 + lines / 2.3e12);
+        (void)tm; (void)tn;
+    }
     if (splits > 1) t += 4e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
     if (ki.precut) t += 6e-6 + 10.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n) / (kPeakHbm * 0.6);
     return t;
@@ -515,7 +572,12 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             if (!config_valid(p, c, ws_bytes)) continue;
             const KernelInfo &kinfo = tg::kernel(ki);
             if (kinfo.pieces && g_math != TG_MATH_BF16_PIECES) continue;   // only on request
-            if (kinfo.kind == tg::KIND_TILE && kinfo.two_level) {
+            // a variant that gathers or reads a transposed operand is offered for operands that lie that way (it is
+            // valid, and can be forced, for anything it can read: a gather takes plain rows too, only slower)
+            if ((kinfo.amode || kinfo.bmode) && (kinfo.amode != p.a_class() || kinfo.bmode != p.b_class())) continue;
+            if (kinfo.amode == 2) c.group = 1;            // a gathered A: the tiles that share a row panel of A run side by side
+            else if (kinfo.bmode == 2) c.group = 64;      // a gathered B: those that share a column panel of B
+            if (kinfo.kind == tg::KIND_TILE && kinfo.two_level && kinfo.amode == 0 && kinfo.bmode == 0) {
                 // second-level accumulators only cost registers when the K range is short
                 int sp, per;
                 split_plan(kinfo, p.k, s, &sp, &per);
@@ -582,8 +644,12 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
     return out;
 }
 
-// Shape class of a problem: operand layout (0 unaligned, 1 aligned, 2 element-strided) + 4 x math mode.
-ShapeKey key_of(const Problem &p) { return ShapeKey(p.batch, p.m, p.n, p.k, (p.aligned ? 1 : (p.unit() ? 0 : 2)) + 4 * g_math); }
+// Shape class of a problem: operand layout (0 unit strides off the 16-byte grid, 1 aligned, 2 + 3 * class of A + class of B
+// for transposed / element-strided operands: 0 plain, 1 transposed and aligned, 2 anything else) + 16 x math mode.
+ShapeKey key_of(const Problem &p) {
+    const int layout = p.aligned ? 1 : (p.unit() ? 0 : 2 + 3 * p.a_class() + p.b_class());
+    return ShapeKey(p.batch, p.m, p.n, p.k, layout + 16 * g_math);
+}
 
 // forced > tuned > heuristic.  Caller holds g_mutex.
 tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
@@ -630,10 +696,11 @@ void choose_xcd_split(const KernelInfo &ki, const Problem &p, GemmParams &g) {
     for (int xm = 1; xm <= 8; xm *= 2) {
         const int xn = 8 / xm;
         if (g.tiles_m % xm || g.tiles_n % xn) continue;
-        const int64_t cost = (int64_t)(g.tiles_m / xm) * ki.BM + (int64_t)(g.tiles_n / xn) * ki.BN;
+        // (an element of a gathered operand costs a whole cache line, or its share of one)
+        const int64_t wa = ki.amode == 2 ? std::min<int64_t>(p.csa, 32) : 1, wb = ki.bmode == 2 ? std::min<int64_t>(p.csb, 32) : 1;
+        const int64_t cost = (int64_t)(g.tiles_m / xm) * ki.BM * wa + (int64_t)(g.tiles_n / xn) * ki.BN * wb;
         if (cost < best) { best = cost; g.xcd_m = xm; g.xcd_n = xn; }
     }
-    (void)p;
 }
 
 tg_status launch(const Problem &p, const Config &c, void *ws, hipStream_t stream) {
@@ -759,8 +826,23 @@ tg_status run(Problem &p, void *stream) {
     // operand once into a packed row-major copy and multiply that with the unit-stride kernels
     // (a strided element costs a whole cache line per fetch; the tile kernels would fetch it once
     // per tile column or row).  Without room the predicated kernels gather on the fly.
+    // A variant that reads the operands as they lie (transposed: 16-byte loads along the other axis; element
+    // strides: 4-byte gathers straight into LDS, several K tiles ahead) needs neither the workspace nor a second
+    // pass: when the choice for the problem as it stands is such a variant, nothing is packed.
+    // (Not for an operand that would have to be gathered across its unit-stride axis, i.e. a transposed operand off
+    // the 16-byte grid: the gather's lanes run along k of A / n of B, so there it touches a line per element where
+    // the packing pass reads whole lines; such an operand is packed when there is room.)
     const char *packed = "";
-    if (!p.unit() && p.batch == 1) {
+    bool fused = false;
+    if (!p.unit()) {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        read_env_once();
+        Config c0;
+        if (g_forced) fused = config_valid(p, g_force_cfg, ws_bytes) && !tg::kernel(g_force_cfg.kernel).edge;
+        else fused = choose(p, ws_bytes, &c0) == TG_OK && !tg::kernel(c0.kernel).edge &&
+                     !(p.a_class() == 2 && p.lda < p.csa) && !(p.b_class() == 2 && p.ldb < p.csb);
+    }
+    if (!p.unit() && p.batch == 1 && !fused) {
         const bool want_a = p.csa != 1 && p.n > kPackMinReuse, want_b = p.csb != 1 && p.m > kPackMinReuse;
         const size_t need_a = want_a ? pack_bytes(p.m, p.k) : 0, need_b = want_b ? pack_bytes(p.k, p.n) : 0;
         if ((want_a || want_b) && need_a + need_b <= ws_bytes &&
@@ -1239,7 +1321,7 @@ tg_status tg_save_tune_cache(const char *path) {
     if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
     FILE *f = fopen(path, "w");
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
-    fprintf(f, "tgemm-tune-cache 4 gfx950\n");
+    fprintf(f, "tgemm-tune-cache 5 gfx950\n");
     std::lock_guard<std::mutex> lk(g_mutex);
     for (const auto &kv : g_cache) {
         const ShapeKey &k = kv.first;
@@ -1258,13 +1340,14 @@ tg_status tg_load_tune_cache(const char *path) {
     if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
     char head[64] = {0}, arch[32] = {0};
     int ver = 0;
-    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || (ver != 3 && ver != 4) ||
+    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || (ver < 3 || ver > 5) ||
         strcmp(arch, "gfx950") != 0) {
         fclose(f);
-        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3 or 4)");
+        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3 to 5)");
     }
     std::lock_guard<std::mutex> lk(g_mutex);
-    // one entry per line; version 4 added the two tail-split fields before the time
+    // one entry per line; version 4 added the two tail-split fields before the time, version 5 widened the
+    // layout class (the math mode moved from 4 x to 16 x)
     char line[512];
     while (fgets(line, sizeof line, f)) {
         long long b, m, n, k;
@@ -1289,6 +1372,7 @@ tg_status tg_load_tune_cache(const char *path) {
         c.tail_splits = tail_splits;
         // entry from another build or a damaged line: ignore
         if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0 || persist < 0 || tail < 0 || tail_splits < 1) continue;
+        if (ver < 5) al = al % 4 + 16 * (al / 4);
         g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
     }
     fclose(f);

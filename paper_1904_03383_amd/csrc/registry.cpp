@@ -74,6 +74,49 @@ extern template hipError_t launch_tile_stream<128, 128, 16, 64, 64, false, true>
      NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, KG>},
 TG_DIRECT_LIST(TG_DDECL)
 
+// direct-to-LDS variants that read transposed or element-strided operands as they lie ("_ta"/"_tb": A / B given
+// transposed; "_ga"/"_gb": any element strides, gathered with 4-byte loads):
+// (BM, BN, BK, WM, WN, two_level, LDS stages, A mode, B mode, name)
+#define TG_MODE_LIST(X)                                                          \
+    X(64, 64, 32, 32, 32, true, 4, 2, 0, "d64x64x32_w32x32_acc2_st4_ga")         \
+    X(32, 128, 32, 32, 32, true, 4, 2, 0, "d32x128x32_w32x32_acc2_st4_ga")       \
+    X(128, 128, 32, 64, 64, true, 3, 2, 0, "d128x128x32_w64x64_acc2_st3_ga")     \
+    X(128, 256, 32, 64, 128, true, 3, 2, 0, "d128x256x32_w64x128_acc2_st3_ga")   \
+    X(64, 64, 32, 32, 32, true, 2, 1, 0, "d64x64x32_w32x32_acc2_ta")             \
+    X(128, 128, 32, 64, 64, true, 2, 1, 0, "d128x128x32_w64x64_acc2_ta")         \
+    X(128, 256, 32, 64, 128, true, 2, 1, 0, "d128x256x32_w64x128_acc2_ta")       \
+    X(64, 64, 32, 32, 32, true, 2, 0, 1, "d64x64x32_w32x32_acc2_tb")             \
+    X(128, 128, 32, 64, 64, true, 2, 0, 1, "d128x128x32_w64x64_acc2_tb")         \
+    X(128, 256, 32, 64, 128, true, 2, 0, 1, "d128x256x32_w64x128_acc2_tb")       \
+    X(64, 64, 32, 32, 32, true, 2, 1, 1, "d64x64x32_w32x32_acc2_ta_tb")          \
+    X(128, 128, 32, 64, 64, true, 2, 1, 1, "d128x128x32_w64x64_acc2_ta_tb")      \
+    X(128, 256, 32, 64, 128, true, 2, 1, 1, "d128x256x32_w64x128_acc2_ta_tb")    \
+    X(64, 64, 32, 32, 32, true, 4, 0, 2, "d64x64x32_w32x32_acc2_st4_gb")         \
+    X(128, 128, 32, 64, 64, true, 3, 0, 2, "d128x128x32_w64x64_acc2_st3_gb")     \
+    X(64, 64, 32, 32, 32, true, 4, 2, 2, "d64x64x32_w32x32_acc2_st4_ga_gb")      \
+    X(128, 128, 32, 64, 64, true, 3, 2, 2, "d128x128x32_w64x64_acc2_st3_ga_gb")  \
+    X(64, 64, 32, 32, 32, true, 4, 2, 1, "d64x64x32_w32x32_acc2_st4_ga_tb")      \
+    X(128, 128, 32, 64, 64, true, 3, 2, 1, "d128x128x32_w64x64_acc2_st3_ga_tb")  \
+    X(64, 64, 32, 32, 32, true, 4, 1, 2, "d64x64x32_w32x32_acc2_st4_ta_gb")      \
+    X(128, 128, 32, 64, 64, true, 3, 1, 2, "d128x128x32_w64x64_acc2_st3_ta_gb")
+#define TG_MDECL(BM, BN, BK, WM, WN, L2, NS, AM, BMD, NAME) \
+    extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, 1, AM, BMD>(const GemmParams &, hipStream_t);
+#define TG_MROW(BM, BN, BK, WM, WN, L2, NS, AM, BMD, NAME)                                      \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, false, (BM / WM) * (BN / WN) * 64,  \
+     NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, 1, AM, BMD>, 0, false, 0, false, AM, BMD},
+TG_MODE_LIST(TG_MDECL)
+// 16-row tiles on v_mfma_f32_16x16x4_f32, for a gathered A: each element of A is a cache line of its own, fetched once
+// per tile column, so the widest tile that still fills the chip wins (1024 x 1024: 16 x 256 tiles are 256 workgroups)
+#define TG_MI16_LIST(X)                                                          \
+    X(16, 256, 32, 16, 64, true, 4, 2, 0, "d16x256x32_w16x64_acc2_st4_ga")       \
+    X(16, 256, 32, 16, 64, true, 3, 2, 0, "d16x256x32_w16x64_acc2_st3_ga")
+#define TG_M16DECL(BM, BN, BK, WM, WN, L2, NS, AM, BMD, NAME) \
+    extern template hipError_t launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, 1, AM, BMD, 16>(const GemmParams &, hipStream_t);
+#define TG_M16ROW(BM, BN, BK, WM, WN, L2, NS, AM, BMD, NAME)                                    \
+    {NAME, KIND_TILE, BM, BN, BK, WM, WN, L2, false, false, false, (BM / WM) * (BN / WN) * 64,  \
+     NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, 1, AM, BMD, 16>, 0, false, 0, false, AM, BMD},
+TG_MI16_LIST(TG_M16DECL)
+
 // bf16-piece variants: (BM, BN, BK, WM, WN, piece products, name)
 #define TG_PIECES_LIST(X)                                                   \
     X(128, 256, 32, 64, 128, 6, "e128x256x32_w64x128_x6")                   \
@@ -100,6 +143,8 @@ TG_PRECUT_LIST(TG_CDECL)
 static const KernelInfo kTable[] = {
     TG_TILE_LIST(TG_ROW)
     TG_DIRECT_LIST(TG_DROW)
+    TG_MODE_LIST(TG_MROW)
+    TG_MI16_LIST(TG_M16ROW)
     TG_PIECES_LIST(TG_EROW)
     TG_PRECUT_LIST(TG_CROW)
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")

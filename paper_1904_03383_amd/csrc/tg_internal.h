@@ -20,7 +20,7 @@ struct GemmParams {
     void *planes;         // piece images of A and B written by the cutting passes (kernels that cut ahead), else nullptr
     int64_t lda, ldb, ldc;
     int64_t csa, csb;     // element strides along k of A and along n of B (1 except for the strided entry point;
-                          // only the predicated kernels honour values other than 1)
+                          // honoured by the predicated kernels and by the direct-to-LDS kernels with operand modes 1, 2)
     int64_t strideA, strideB, strideC;
     int m, n, k;
     int nb;               // columns of B the exact-fit kernels may fetch: n, or n rounded up to a multiple of 4 when
@@ -63,6 +63,8 @@ struct KernelInfo {
     bool precut;         // piece kernel whose operands are cut by separate passes into a workspace image
     int kwaves;          // KIND_WAVE: waves of a workgroup that share one tile, each with its part of K (0 = one wave per tile)
     bool defer;          // persistent variant that stores a finished tile during the next one: no split-K, aligned rows of C
+    int amode, bmode;    // how the kernel reads A / B: 0 as the plain product has them (A k-contiguous, B n-contiguous,
+                         // 16-byte aligned rows), 1 transposed (A m-contiguous, B k-contiguous, aligned), 2 any element strides
 };
 
 // Kernel table (registry.cpp).
@@ -82,8 +84,10 @@ template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes();
 
 // Same, with operand tiles loaded global -> LDS directly into a ring of NS stages (aligned operands, k % 32 == 0, n % 4 == 0);
-// KG wave groups share each wave tile, every group taking 1/KG of each K tile.
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
+// KG wave groups share each wave tile, every group taking 1/KG of each K tile.  AM / BMD: operand modes of A and B
+// (KernelInfo::amode / bmode): transposed and element-strided operands are read as they lie, without a separate pass.
+// MI: edge of the matrix instruction's block, 32 (v_mfma_f32_32x32x2_f32) or 16 (v_mfma_f32_16x16x4_f32: 16-row tiles).
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG, int AM = 0, int BMD = 0, int MI = 32>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s);
 
 // Workgroup-tile kernel on the bf16 matrix pipe: operands cut into three bf16 pieces each, NP piece

@@ -22,6 +22,24 @@
 //    1024^3 one workgroup per CU) then runs two waves per SIMD.  Measured at 1024^3 it only
 //    matches the one-group kernel (21.6 us against 21.9 us): the waits it could cover are not
 //    what limits that shape.
+//
+// Operand modes (AM for A, BMD for B): the strided matmul and the transposed layouts of Sec. 5.2 fused
+// into the loader, so that no separate gather / transpose pass is needed.
+//  * mode 0: the operand as the plain product has it (A row-major with k contiguous, B row-major with n
+//    contiguous), described above.
+//  * mode 1: the operand is given transposed.  A with unit stride along m (element (i, p) at A[i + p*csa]):
+//    its tile is loaded like a B tile, k-major rows of BM floats, no permutation; a lane owns the RB
+//    adjacent rows RB*i .. RB*i+RB-1 of its wave tile (row RB*i+rb in block rb), so an A fragment for
+//    one k is one RB*4-byte LDS read.  B with unit stride along k (element (p, j) at B[p + j*csb]): its
+//    tile is loaded like an A tile, one LDS row of BK floats per column with the chunk permutation, and
+//    LDS row cb*32+i of a wave's slab holds column CB*i+cb, so the fragment reads are the conflict-free
+//    ones of A while a lane still owns CB adjacent columns of C.
+//  * mode 2: arbitrary element strides (element (i, p) of A at A[i*rsa + p*csa], (p, j) of B at
+//    B[p*rsb + j*csb]): every lane of a 4-byte direct load fetches one element, its own cache line if the
+//    stride is large, into the LDS layout of mode 0.  Nothing is staged in registers, so with NS stages
+//    NS-1 K tiles of gathered lines are in flight per workgroup, which is what a gather needs: its
+//    latency is that of HBM, not of L2.
+// Modes other than 0 exist only in this kernel; k must still be a multiple of BK.
 #pragma once
 
 #include "tile_kernel.hpp"
@@ -46,6 +64,23 @@ constexpr int direct_lds_bytes() {
     return NS * (BM * BK + BK * BN) * (int)sizeof(float);
 }
 
+// The two fp32 matrix instructions.  v_mfma_f32_32x32x2_f32: lane l (i = l % 32, h = l / 32) supplies A[i][k = h]
+// and B[k = h][j = i], result register v (of 16) holds row 8*(v/4) + 4*h + v%4, column i.  v_mfma_f32_16x16x4_f32:
+// lane l (i = l % 16, h = l / 16) supplies A[i][k = h] and B[k = h][j = i], result register v (of 4) holds row
+// 4*h + v, column i.  Either way a lane fetches the four consecutive k values 4*h .. 4*h+3 of a step of 4 * (64 / MI)
+// k values at once and feeds element t to the t-th of four instructions.
+template <int MI> struct mfma_shape;
+template <> struct mfma_shape<32> {
+    typedef f32x16 acc_t;
+    static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ int row_of(int v, int h) { return 8 * (v / 4) + 4 * h + (v % 4); }
+};
+template <> struct mfma_shape<16> {
+    typedef f32x4 acc_t;
+    static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ int row_of(int v, int h) { return 4 * h + v; }
+};
+
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL>
 constexpr int direct_min_waves() {
     constexpr int acc = (WM * WN / 64) * (TWO_LEVEL ? 2 : 1);
@@ -54,40 +89,61 @@ constexpr int direct_min_waves() {
 }
 
 // One K tile on its way: instruction i of a wave fills LDS floats [slot*256, slot*256+256) of
-// the stage, slot = i * NWAVES + wave.  a_stage / b_stage are float offsets into the
+// the stage (64 floats for a gathered operand), slot = i * NWAVES + wave.  a_stage / b_stage are float offsets into the
 // __shared__ array.  The builtin wants address-space-qualified pointers, hence the explicit
 // casts (without them the host pass drops the kernel without a diagnostic).
+// (A_EL / B_EL floats per lane and instruction: 4, or 1 for a gathered operand.  The size operand of the
+// builtin must be a literal, hence the two wrappers.)
+template <int EL>
+__device__ __forceinline__ void direct_load(const float *g, float *l);
+template <>
+__device__ __forceinline__ void direct_load<4>(const float *g, float *l) {
+    __builtin_amdgcn_global_load_lds((glb_float *)g, (lds_float *)l, 16, 0, 0);
+}
+template <>
+__device__ __forceinline__ void direct_load<1>(const float *g, float *l) {
+    __builtin_amdgcn_global_load_lds((glb_float *)g, (lds_float *)l, 4, 0, 0);
+}
 #define TG_ISSUE_DIRECT_LOADS(a_stage, b_stage)                                                          \
     do {                                                                                                 \
         _Pragma("unroll") for (int i_ = 0; i_ < A_LD; ++i_)                                              \
-            __builtin_amdgcn_global_load_lds((glb_float *)(Ag + a_off[i_]), (lds_float *)(smem + (a_stage) + (i_ * NWAVES + wave) * 256), 16, 0, 0); \
+            direct_load<A_EL>(Ag + a_off[i_], smem + (a_stage) + (i_ * NWAVES + wave) * (64 * A_EL));    \
         _Pragma("unroll") for (int i_ = 0; i_ < B_LD; ++i_)                                              \
-            __builtin_amdgcn_global_load_lds((glb_float *)(Bg + b_off[i_]), (lds_float *)(smem + (b_stage) + (i_ * NWAVES + wave) * 256), 16, 0, 0); \
+            direct_load<B_EL>(Bg + b_off[i_], smem + (b_stage) + (i_ * NWAVES + wave) * (64 * B_EL));    \
     } while (0)
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG, int AM, int BMD, int MI>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG, (KG > 1 ? 2 : direct_min_waves<BM, BN, BK, WM, WN, TWO_LEVEL>()))
 sgemm_tile_direct_kernel(const GemmParams p) {
     constexpr int WAVES_N = BN / WN;
     constexpr int TILE_WAVES = (BM / WM) * (BN / WN);       // waves that cover the output tile once
     constexpr int NWAVES = TILE_WAVES * KG;
     constexpr int NT = NWAVES * 64;
-    constexpr int RB = WM / 32, CB = WN / 32;
+    static_assert(MI == 32 || MI == 16, "32x32x2 or 16x16x4 matrix instructions");
+    constexpr int RB = WM / MI, CB = WN / MI;                // blocks of one instruction per wave tile
+    constexpr int KSTEP = 4 * (64 / MI);                     // k values of one fragment fetch: an octet (MI = 32) or 16
+    constexpr int NV = MI * MI / 64;                         // results per lane and block
+    typedef mfma_shape<MI> shape;
+    typedef typename shape::acc_t accv;
     constexpr int A_STAGE = BM * BK, B_STAGE = BK * BN;      // floats, unpadded
-    constexpr int A_LD = BM * BK / 4 / NT, B_LD = BK * BN / 4 / NT;
-    constexpr int NO = BK / 8 / KG;                         // octets of a K tile per wave
+    constexpr int A_EL = AM == 2 ? 1 : 4, B_EL = BMD == 2 ? 1 : 4;   // floats per lane of one load instruction
+    constexpr int A_LD = BM * BK / A_EL / NT, B_LD = BK * BN / B_EL / NT;
+    constexpr int NO = BK / KSTEP / KG;                     // fragment steps ("octets" below) of a K tile per wave
+    static_assert(AM >= 0 && AM <= 2 && BMD >= 0 && BMD <= 2, "operand modes");
     static_assert(KG == 1 || KG == 2, "one or two wave groups along K");
     static_assert(KG == 1 || (KG - 1) * BM * BN <= NS * (BM * BK + BK * BN), "the group sum reuses the stage area");
-    static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
-    static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 32, 64 or 128");
+    static_assert(BM % WM == 0 && BN % WN == 0 && WM % MI == 0 && WN % MI == 0, "tile shape");
+    static_assert(CB == 1 || CB == 2 || CB == 4, "wave tile width must be 1, 2 or 4 blocks");
     static_assert(BK == 32, "BK must be 32");
     static_assert(NO >= 2 && NO % 2 == 0, "fragment sets alternate per octet");
-    static_assert((BM * BK / 4) % NT == 0 && (BK * BN / 4) % NT == 0 && A_LD >= 1 && B_LD >= 1,
+    static_assert((BM * BK / A_EL) % NT == 0 && (BK * BN / B_EL) % NT == 0 && A_LD >= 1 && B_LD >= 1,
                   "tile loads must divide evenly over the workgroup");
-    static_assert(BN % 4 == 0 && (256 % BK) == 0, "one load instruction covers whole chunks and rows");
+    static_assert(BN % 4 == 0 && BM % 4 == 0 && (256 % BK) == 0, "one load instruction covers whole chunks and rows");
     static_assert(NS >= 2 && NS <= 4, "two to four LDS stages");
     static_assert((NS - 2) * (A_LD + B_LD) <= 63, "outstanding loads must fit the vmcnt field");
+    static_assert(RB == 1 || RB == 2 || RB == 4, "wave tile height must be 1, 2 or 4 blocks");
     typedef typename vec_of<CB>::type bvec;
+    typedef typename vec_of<RB>::type avec;
 
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float *As = smem;
@@ -95,7 +151,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 31, h = lane >> 5;
+    const int li = lane % MI, h = lane / MI;
     const int kg = wave / TILE_WAVES, tw = wave % TILE_WAVES;   // K group, wave inside the tile
     const int wm = tw / WAVES_N, wn = tw % WAVES_N;
     const int o_base = kg * NO;
@@ -113,59 +169,106 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     const int kt_end = kt_stop < kt_total ? kt_stop : kt_total;
 
     // Tile origins are wave-uniform and advance per K tile; per-lane offsets are fixed.
-    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * BK * p.ldb + n0;
+    // (lda, ldb: row strides of A and B; csa, csb: their element strides along k and along n.)
+    const int64_t a_step = AM == 0 ? (int64_t)BK : (int64_t)BK * p.csa;
+    const int64_t b_step = BMD == 1 ? (int64_t)BK : (int64_t)BK * p.ldb;
+    const float *Ag = p.A + (int64_t)prob * p.strideA + (int64_t)m0 * p.lda + (int64_t)kt_begin * a_step;
+    const float *Bg = p.B + (int64_t)prob * p.strideB + (int64_t)kt_begin * b_step + (int64_t)n0 * (BMD == 0 ? 1 : p.csb);
 
     // Load instruction i of this wave fills LDS floats [slot*256, slot*256 + 256) of a stage,
-    // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3.
+    // slot = i * NWAVES + wave; lane l supplies floats slot*256 + 4l .. +3 (a gathered operand:
+    // [slot*64, slot*64 + 64), lane l the float slot*64 + l).
     unsigned a_off[A_LD], b_off[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the A stage
-        const int row = pos / BK;
-        const int q = (pos % BK) / 4;                          // chunk position inside the row
-        // ragged last tile row: LDS rows past the end of A are filled from its last row (in bounds;
-        // what they produce is never stored)
-        const int src_row = row < p.m - 1 - m0 ? row : p.m - 1 - m0;
-        a_off[i] = (unsigned)src_row * (unsigned)p.lda + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+        const int pos = ((i * NWAVES + wave) * 64 + lane) * A_EL;   // float index inside the A stage
+        if constexpr (AM == 1) {
+            // k-major stage: row pos / BM is one k, BM consecutive m.  Ragged last tile row: vectors past
+            // the end of A re-read its last one (m % 4 == 0; in bounds, what they produce is never stored)
+            const int c = pos % BM < p.m - 4 - m0 ? pos % BM : p.m - 4 - m0;
+            a_off[i] = (unsigned)(pos / BM) * (unsigned)p.csa + (unsigned)c;
+        } else {
+            const int row = pos / BK;
+            const int q = (pos % BK) / 4;                      // chunk position inside the row
+            // ragged last tile row: LDS rows past the end of A are filled from its last row (in bounds;
+            // what they produce is never stored)
+            const int src_row = row < p.m - 1 - m0 ? row : p.m - 1 - m0;
+            const int src_k = (q ^ a_swizzle<BK>(row)) * 4 + (AM == 2 ? pos % 4 : 0);
+            a_off[i] = (unsigned)src_row * (unsigned)p.lda + (unsigned)src_k * (AM == 2 ? (unsigned)p.csa : 1u);
+        }
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        const int pos = (i * NWAVES + wave) * 256 + lane * 4;   // float index inside the B stage
-        // ragged last tile column: vectors past the end of B re-read its last one (n % 4 == 0)
-        const int c = pos % BN < p.nb - 4 - n0 ? pos % BN : p.nb - 4 - n0;
-        b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c;
+        const int pos = ((i * NWAVES + wave) * 64 + lane) * B_EL;   // float index inside the B stage
+        if constexpr (BMD == 1) {
+            // one LDS row of BK floats per column, chunks permuted as in A's stage; LDS row cb*MI+i of a
+            // wave's slab holds column CB*i+cb.  Columns past the end of B re-read its last one.
+            const int row = pos / BK;
+            const int q = (pos % BK) / 4;
+            const int col = (row / WN) * WN + (row % MI) * CB + (row % WN) / MI;
+            const int src_col = col < p.n - 1 - n0 ? col : p.n - 1 - n0;
+            b_off[i] = (unsigned)src_col * (unsigned)p.csb + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+        } else if constexpr (BMD == 2) {
+            const int c = pos % BN < p.n - 1 - n0 ? pos % BN : p.n - 1 - n0;
+            b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c * (unsigned)p.csb;
+        } else {
+            // ragged last tile column: vectors past the end of B re-read its last one (n % 4 == 0)
+            const int c = pos % BN < p.nb - 4 - n0 ? pos % BN : p.nb - 4 - n0;
+            b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c;
+        }
     }
-    const int64_t b_step = (int64_t)BK * p.ldb;
 
-    f32x16 acc[RB][CB];
-    f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
+    accv acc[RB][CB];
+    accv total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
-            acc[rb][cb] = (f32x16)(0.0f);
-            if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
+            acc[rb][cb] = (accv)(0.0f);
+            if constexpr (TWO_LEVEL) total[rb][cb] = (accv)(0.0f);
         }
 
-    // Fragment addressing.  A: row r = wm*WM + rb*32 + li, chunk 2*o + h at position
-    // (2*o + h) ^ swz(r); rb*32 does not change swz (it only looks at the low four row bits).
+    // Fragment addressing.  A (modes 0, 2): row r = wm*WM + rb*MI + li, chunk (KSTEP/4)*o + h at position
+    // ((KSTEP/4)*o + h) ^ swz(r); rb*MI does not change swz (it only looks at the low four row bits).
+    // A (mode 1): k-major stage, the lane's RB adjacent rows of k = KSTEP*o + 4*h + t.
+    // B (modes 0, 2): k-major stage, the lane's CB adjacent columns.  B (mode 1): as A in mode 0.
     const int a_row = wm * WM + li;
-    const int a_swz = a_swizzle<BK>(a_row);
-    const int b_frag_off = (h * 4) * BN + wn * WN + li * CB;
+    const int a_swz = a_swizzle<BK>(a_row);                  // == a_swizzle(li): also B's rows in mode 1
+    const int a_frag_off = AM == 1 ? (h * 4) * BM + wm * WM + li * RB : a_row * BK;
+    const int b_frag_off = BMD == 1 ? (wn * WN + li) * BK : (h * 4) * BN + wn * WN + li * CB;
 
-    f32x4 a_frag[2][RB];
-    bvec b_frag[2][4];
+    // a_frag[set][rb][t] (modes 0, 2) or a_fragT[set][t][rb] (mode 1); b_frag[set][t][cb] (modes 0, 2) or
+    // b_fragT[set][cb][t] (mode 1)
+    f32x4 a_frag[2][AM == 1 ? 1 : RB];
+    avec a_fragT[2][AM == 1 ? 4 : 1];
+    bvec b_frag[2][BMD == 1 ? 1 : 4];
+    f32x4 b_fragT[2][BMD == 1 ? CB : 1];
+    constexpr int N_FRAG_RD = (AM == 1 ? 4 : RB) + (BMD == 1 ? CB : 4);   // LDS reads of one octet
 
     auto read_frags = [&](int stage, int o, int set) {
-        const float *as = As + stage * A_STAGE + a_row * BK + (((2 * (o_base + o) + h) ^ a_swz) * 4);
-        const float *bs = Bs + stage * B_STAGE + b_frag_off + (o_base + o) * 8 * BN;
+        const int chunk = (((KSTEP / 4) * (o_base + o) + h) ^ a_swz) * 4;
+        if constexpr (AM == 1) {
+            const float *as = As + stage * A_STAGE + a_frag_off + (o_base + o) * KSTEP * BM;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * BK);
+            for (int t = 0; t < 4; ++t)
+                a_fragT[set][t] = *reinterpret_cast<const avec *>(as + t * BM);
+        } else {
+            const float *as = As + stage * A_STAGE + a_frag_off + chunk;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
+            for (int rb = 0; rb < RB; ++rb)
+                a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * MI * BK);
+        }
+        if constexpr (BMD == 1) {
+            const float *bs = Bs + stage * B_STAGE + b_frag_off + chunk;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                b_fragT[set][cb] = *reinterpret_cast<const f32x4 *>(bs + cb * MI * BK);
+        } else {
+            const float *bs = Bs + stage * B_STAGE + b_frag_off + (o_base + o) * KSTEP * BN;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                b_frag[set][t] = *reinterpret_cast<const bvec *>(bs + t * BN);
+        }
     };
 
     auto mfma_octet = [&](int set) {
@@ -174,9 +277,14 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                        a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
+                for (int cb = 0; cb < CB; ++cb) {
+                    float av, bv;
+                    if constexpr (AM == 1) av = vec_get(a_fragT[set][t], rb);
+                    else av = a_frag[set][rb][t];
+                    if constexpr (BMD == 1) bv = b_fragT[set][cb][t];
+                    else bv = vec_get(b_frag[set][t], cb);
+                    acc[rb][cb] = shape::mfma(av, bv, acc[rb][cb]);
+                }
     };
 
     int since_flush = 0;
@@ -189,7 +297,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb) {
                         total[rb][cb] += acc[rb][cb];
-                        acc[rb][cb] = (f32x16)(0.0f);
+                        acc[rb][cb] = (accv)(0.0f);
                         __builtin_amdgcn_sched_barrier(0);
                     }
             }
@@ -220,7 +328,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
             TG_ISSUE_DIRECT_LOADS(st * A_STAGE, NS * A_STAGE + st * B_STAGE);
             if (to_load > 1) {
                 --to_load;
-                Ag += BK;
+                Ag += a_step;
                 Bg += b_step;
             }
         }
@@ -242,11 +350,11 @@ sgemm_tile_direct_kernel(const GemmParams p) {
             TG_ISSUE_DIRECT_LOADS(fill * A_STAGE, NS * A_STAGE + fill * B_STAGE);
             if (to_load > 1) {
                 --to_load;
-                Ag += BK;
+                Ag += a_step;
                 Bg += b_step;
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);         // LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x100, N_FRAG_RD, 0);      // LDS reads
 #pragma unroll
             for (int i = 0; i < N_LD; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // global -> LDS load
@@ -259,7 +367,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
                 mfma_octet(o & 1);
                 read_frags(stage, o + 1, (o + 1) & 1);
                 __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, N_FRAG_RD, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -269,7 +377,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
             mfma_octet((NO - 1) & 1);
             read_frags(next, 0, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, RB + 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, N_FRAG_RD, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA, 0);
             __builtin_amdgcn_sched_barrier(0);
             fill = stage;
@@ -289,7 +397,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     if constexpr (KG > 1) {
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
-        constexpr int PER_WAVE = RB * CB * 16 * 64;
+        constexpr int PER_WAVE = RB * CB * NV * 64;
         if (kg > 0) {
             float *dst = smem + ((kg - 1) * TILE_WAVES + tw) * PER_WAVE + lane;
 #pragma unroll
@@ -297,7 +405,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) dst[((rb * CB + cb) * 16 + v) * 64] = acc[rb][cb][v];
+                    for (int v = 0; v < NV; ++v) dst[((rb * CB + cb) * NV + v) * 64] = acc[rb][cb][v];
         }
         __syncthreads();
         if (kg > 0) return;
@@ -309,7 +417,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[rb][cb][v] += src[((rb * CB + cb) * 16 + v) * 64];
+                    for (int v = 0; v < NV; ++v) acc[rb][cb][v] += src[((rb * CB + cb) * NV + v) * 64];
         }
     }
 
@@ -330,8 +438,10 @@ sgemm_tile_direct_kernel(const GemmParams p) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+        for (int v = 0; v < NV; ++v) {
+            // (a transposed A: block rb holds the rows RB*i + rb of the wave tile, i the row inside the block)
+            const int in_block = shape::row_of(v, h);
+            const int row = m0 + wm * WM + (AM == 1 ? in_block * RB + rb : rb * MI + in_block);
             float *dst = out + (int64_t)row * ldo + col;
             bvec o;
             if constexpr (CB == 1) {
@@ -345,12 +455,12 @@ sgemm_tile_direct_kernel(const GemmParams p) {
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG>
+template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG, int AM, int BMD, int MI>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s) {
     constexpr int threads = (BM / WM) * (BN / WN) * 64 * KG;
     constexpr int lds_used = direct_lds_bytes<BM, BN, BK, NS>();
     static_assert(lds_used <= kLdsPerCU, "stages exceed the LDS of a CU");
-    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, NS, KG>;
+    auto kern = sgemm_tile_direct_kernel<BM, BN, BK, WM, WN, TWO_LEVEL, NS, KG, AM, BMD, MI>;
     int lds = lds_used;
     if (p.max_blocks_per_cu > 0) {
         const int share = (kLdsPerCU / p.max_blocks_per_cu) & ~1023;

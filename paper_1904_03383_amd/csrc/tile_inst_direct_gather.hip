@@ -1,0 +1,9 @@
+// Explicit instantiations: direct-to-LDS variants that gather an element-strided A (strided matmul of Sec. 5.2).
+// <BM, BN, BK, WM, WN, two_level, LDS stages, wave groups along K, A mode, B mode>
+#include "tile_direct_kernel.hpp"
+namespace tg {
+template hipError_t launch_tile_direct<64, 64, 32, 32, 32, true, 4, 1, 2, 0>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_direct<32, 128, 32, 32, 32, true, 4, 1, 2, 0>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_direct<128, 128, 32, 64, 64, true, 3, 1, 2, 0>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_direct<128, 256, 32, 64, 128, true, 3, 1, 2, 0>(const GemmParams &, hipStream_t);
+}  // namespace tg

@@ -203,8 +203,9 @@ def test_tune_cache_file_round_trip(tmp_path, lib):
         tg.save_tune_cache(out)
         text = out.read_text().splitlines()
         assert tg.get_config(1, 512, 512, 512) == "p128x128x32_w64x64:s1:g2:o2:p3"
-        # written in the current format (version 4: two tail-split fields before the time); version 3 files load
-        assert text[0] == "tgemm-tune-cache 4 gfx950" and len(text) == 3
+        # written in the current format (version 5: two tail-split fields before the time, 16 x math mode in the
+        # layout class); version 3 and 4 files load
+        assert text[0] == "tgemm-tune-cache 5 gfx950" and len(text) == 3
         assert text[1].startswith("1 512 512 512 1 p128x128x32_w64x64 1 2 2 3 0 1 ")
         assert text[2].startswith("1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 0 0 1 ")
         v4 = tmp_path / "v4.txt"
@@ -461,8 +462,8 @@ def test_tail_split_grammar_validity_and_candidates(lib):
 
 
 def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):
-    """A cache file holds the math mode in the shape class (4 x mode + layout class): an entry tuned in the
-    piece mode is used only there."""
+    """A cache file holds the math mode in the shape class (16 x mode + layout class; 4 x mode in files of
+    versions 3 and 4, converted on loading): an entry tuned in the piece mode is used only there."""
     f = tmp_path / "cache.txt"
     f.write_text("tgemm-tune-cache 3 gfx950\n"
                  "1 4096 4096 4096 1 t128x256x32_w64x128_acc2 1 4 0 0 975.0\n"
@@ -475,7 +476,7 @@ def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):
         out = tmp_path / "again.txt"
         tg.save_tune_cache(out)
         lines = sorted(out.read_text().splitlines()[1:])
-        assert [l.split()[4:6] for l in lines] == [["1", "t128x256x32_w64x128_acc2"], ["5", "e128x256x32_w64x128_x9"]]
+        assert [l.split()[4:6] for l in lines] == [["1", "t128x256x32_w64x128_acc2"], ["17", "e128x256x32_w64x128_x9"]]
     finally:
         tg.set_math(tg.MATH_FP32_MFMA)
         tg.clear_tune_cache()

@@ -1,0 +1,147 @@
+"""GPU parity of the kernel variants that read transposed or element-strided operands as they lie (no
+workspace, no separate gather / transpose pass): the paper's strided matmul (Sec. 5.2: 1024^3 with
+consecutive elements of A 32 apart) and its transposed layouts, through tg_sgemm_strided.  Every variant
+is forced by name on shapes that span several tiles with ragged last tiles, and on a long K (second
+accumulation level); the automatic choice is checked to take them.  Same bar as the plain product: per
+element 1e-5 * sum|a||b|, relative Frobenius 1e-6, integer-valued inputs bit exact."""
+import re
+
+import numpy as np
+import pytest
+
+import paper_1904_03383_amd as tg
+from paper_1904_03383_amd import inputgen as ig
+
+from gpu_common import check_against_oracle, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _clean_library_state():
+    tg.force_config(None)
+    tg.set_workspace(None)
+    yield
+    tg.force_config(None)
+    tg.set_workspace(None)
+
+
+def _mode_variants():
+    return [n for n in tg.kernel_names() if re.search(r"_(ta|tb|ga|gb)(_|$)", n)]
+
+
+def _tile(name):
+    bm, bn, bk = (int(x) for x in re.match(r"[a-z](\d+)x(\d+)x(\d+)_", name).groups())
+    return bm, bn, bk
+
+
+def _operand(gen, seed, rows, cols, layout, stride=3):
+    """(host view, device view) of a rows x cols operand: 'N' row-major, 'T' stored transposed with 16-byte
+    aligned columns, 'S' element stride `stride` along its rows (and a row stride that is no multiple of it)."""
+    if layout == "T":
+        ld = (rows + 3) // 4 * 4 + 4
+        store = gen(seed, (cols, ld))
+        return store[:, :rows].T, to_dev(store)[:, :rows].T
+    if layout == "S":
+        store = gen(seed, (rows, cols * stride + 5))
+        return store[:, :cols * stride:stride], to_dev(store)[:, :cols * stride:stride]
+    store = gen(seed, (rows, cols))
+    return store, to_dev(store)
+
+
+def _layouts_of(name):
+    la = "T" if "_ta" in name else ("S" if "_ga" in name else "N")
+    lb = "T" if "_tb" in name else ("S" if "_gb" in name else "N")
+    return la, lb
+
+
+def _run(da, db, m, n):
+    import torch
+    out = torch.full((m, n), float("nan"), device="cuda")
+    tg.sgemm_strided(da, db, out=out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def test_variant_list_is_not_empty():
+    names = _mode_variants()
+    assert len(names) >= 12 and any("_ga" in n for n in names) and any("_ta_tb" in n for n in names)
+
+
+@pytest.mark.parametrize("name", [pytest.param(n, id=n) for n in (
+    # listed literally so that collection does not need the library; checked against the table below
+    "d64x64x32_w32x32_acc2_st4_ga", "d32x128x32_w32x32_acc2_st4_ga", "d128x128x32_w64x64_acc2_st3_ga",
+    "d128x256x32_w64x128_acc2_st3_ga", "d64x64x32_w32x32_acc2_ta", "d128x128x32_w64x64_acc2_ta",
+    "d128x256x32_w64x128_acc2_ta", "d64x64x32_w32x32_acc2_tb", "d128x128x32_w64x64_acc2_tb",
+    "d128x256x32_w64x128_acc2_tb", "d64x64x32_w32x32_acc2_ta_tb", "d128x128x32_w64x64_acc2_ta_tb",
+    "d128x256x32_w64x128_acc2_ta_tb", "d64x64x32_w32x32_acc2_st4_gb", "d128x128x32_w64x64_acc2_st3_gb",
+    "d64x64x32_w32x32_acc2_st4_ga_gb", "d128x128x32_w64x64_acc2_st3_ga_gb", "d64x64x32_w32x32_acc2_st4_ga_tb",
+    "d128x128x32_w64x64_acc2_st3_ga_tb", "d64x64x32_w32x32_acc2_st4_ta_gb", "d128x128x32_w64x64_acc2_st3_ta_gb",
+    "d16x256x32_w16x64_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga")])
+def test_every_variant_forced(name):
+    assert name in _mode_variants()
+    bm, bn, bk = _tile(name)
+    la, lb = _layouts_of(name)
+    # several tiles with ragged last ones (a transposed A needs m % 4 == 0, a plain B n % 4 == 0; the others take
+    # anything), K of a few tiles (fewer than the LDS ring is deep for one of them), and one long K
+    m_odd = 0 if la == "T" else 1
+    n_odd = 0 if lb == "N" else 1
+    shapes = [(2 * bm + 40 + m_odd, bn + 36 + n_odd, 5 * bk), (bm + 4, 2 * bn, bk), (bm, bn, 65 * bk)]
+    for (m, n, k) in shapes:
+        for dist in ("normal", "int"):
+            say(f"forced {name} {m}x{n}x{k} A:{la} B:{lb} {dist}")
+            gen = ig.normal if dist == "normal" else ig.small_int
+            a_np, da = _operand(gen, 701, m, k, la)
+            b_np, db = _operand(gen, 702, k, n, lb, stride=5)
+            tg.force_config(name)
+            c = _run(da, db, m, n)
+            assert tg.last_config().startswith(name) and "+pack" not in tg.last_config()
+            check_against_oracle(c, np.ascontiguousarray(a_np), np.ascontiguousarray(b_np), exact=(dist == "int"),
+                                 what=f"{name} {m}x{n}x{k} {dist}")
+
+
+def test_paper_strided_matmul_1024_is_fused_without_a_workspace():
+    """matmul 1024x1024x1024 with A's consecutive elements 32 apart (Sec. 5.2): gathered inside the product kernel."""
+    m = n = k = 1024
+    for dist in ("uniform", "int"):
+        say(f"fused strided matmul 1024^3, A element stride 32, {dist}")
+        gen = ig.uniform if dist == "uniform" else ig.small_int
+        a_store = gen(711, (m, k * 32))
+        b = gen(712, (k, n))
+        c = _run(to_dev(a_store)[:, ::32], to_dev(b), m, n)
+        cfg = tg.last_config()
+        assert "_ga" in cfg and "_edge" not in cfg and "+pack" not in cfg, cfg
+        check_against_oracle(c, np.ascontiguousarray(a_store[:, ::32]), b, exact=(dist == "int"), what="fused strided 1024^3 " + dist)
+
+
+@pytest.mark.parametrize("layout", ["A^T", "B^T", "A^T B^T"])
+@pytest.mark.parametrize("shape", [(1024, 1024, 1024), (512, 768, 2048), (260, 132, 96)], ids=str)
+def test_transposed_layouts_are_read_as_they_lie(layout, shape):
+    m, n, k = shape
+    la = "T" if "A^T" in layout else "N"
+    lb = "T" if "B^T" in layout else "N"
+    for dist in ("normal", "int"):
+        say(f"fused transposed {layout} {shape} {dist}")
+        gen = ig.normal if dist == "normal" else ig.small_int
+        a_np, da = _operand(gen, 721, m, k, la)
+        b_np, db = _operand(gen, 722, k, n, lb)
+        c = _run(da, db, m, n)
+        cfg = tg.last_config()
+        want = ("_ta" if la == "T" else "") + ("_tb" if lb == "T" else "")
+        assert want in cfg and "_edge" not in cfg and "+pack" not in cfg, cfg
+        check_against_oracle(c, np.ascontiguousarray(a_np), np.ascontiguousarray(b_np), exact=(dist == "int"),
+                             what=f"{layout} {shape} {dist}")
+
+
+def test_fused_variant_is_preferred_to_packing_when_a_workspace_is_set():
+    import torch
+    say("fused A^T with a workspace set")
+    m, n, k = 512, 512, 256
+    ws = torch.full((tg.strided_workspace_bytes(m, n, k, 7, 1) // 4,), float("nan"), device="cuda")
+    tg.set_workspace(ws)
+    a_np, da = _operand(ig.small_int, 731, m, k, "T")
+    b = ig.small_int(732, (k, n))
+    c = _run(da, to_dev(b), m, n)
+    assert "_ta" in tg.last_config() and "+pack" not in tg.last_config(), tg.last_config()
+    check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=True, what="fused with workspace")
+    del ws

@@ -44,7 +44,7 @@ def test_calls_are_ordered_on_a_side_stream():
     assert torch.equal(twice, out * 2.0) and torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("case", ["sgemm", "batched", "k0", "saxpy", "strided_packed", "split_k", "pieces", "pieces_cut_ahead"])
+@pytest.mark.parametrize("case", ["sgemm", "batched", "k0", "saxpy", "strided_packed", "strided_fused", "split_k", "pieces", "pieces_cut_ahead"])
 def test_graph_capture_replays_match_eager(case):
     """Every entry point captured into a HIP graph; each of several replays (with eager work and
     synchronisation in between, inputs changed before each) must equal the eager result."""
@@ -67,11 +67,16 @@ def test_graph_capture_replays_match_eager(case):
         x, y = to_dev(ig.uniform(715, (100003,))), to_dev(ig.uniform(716, (100003,)))
         out = torch.empty_like(x)
         fn = lambda: tg.saxpy(0.75, x, y, out=out)
-    elif case == "strided_packed":
+    elif case == "strided_packed":                # k no multiple of 32: packing pass + plain kernel, two launches
+        xs, y = to_dev(ig.small_int(717, (256, 100 * 3))), to_dev(ig.small_int(718, (100, 256)))
+        x = xs[:, ::3]
+        ws = torch.empty(tg.strided_workspace_bytes(256, 256, 100, 3, 1) // 4 + 4, device="cuda")
+        tg.set_workspace(ws)
+        out = torch.empty((256, 256), device="cuda")
+        fn = lambda: tg.sgemm_strided(x, y, out=out)
+    elif case == "strided_fused":                 # gathered inside the product kernel
         xs, y = to_dev(ig.small_int(717, (256, 128 * 3))), to_dev(ig.small_int(718, (128, 256)))
         x = xs[:, ::3]
-        ws = torch.empty(tg.strided_workspace_bytes(256, 256, 128, 3, 1) // 4 + 4, device="cuda")
-        tg.set_workspace(ws)
         out = torch.empty((256, 256), device="cuda")
         fn = lambda: tg.sgemm_strided(x, y, out=out)
     elif case == "pieces":
@@ -97,6 +102,8 @@ def test_graph_capture_replays_match_eager(case):
     torch.cuda.synchronize()
     if case == "strided_packed":
         assert tg.last_config().endswith("+packA")
+    if case == "strided_fused":
+        assert "_ga" in tg.last_config() and "+pack" not in tg.last_config()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         fn()

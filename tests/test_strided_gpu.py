@@ -40,8 +40,13 @@ def test_paper_strided_matmul_1024_stride_32():
         b = gen(602, (k, n))
         a = a_store[:, ::32]
         c = _run(to_dev(a_store)[:, ::32], to_dev(b), m, n)
-        assert "_edge" in tg.last_config()
+        assert "_ga" in tg.last_config() and "+pack" not in tg.last_config()      # gathered inside the product kernel
         check_against_oracle(c, np.ascontiguousarray(a), b, exact=(dist == "int"), what="strided 1024^3 " + dist)
+        tg.force_config("t64x64x16_w32x32_edge")                                   # and through the predicated kernel
+        c = _run(to_dev(a_store)[:, ::32], to_dev(b), m, n)
+        assert "_edge" in tg.last_config()
+        tg.force_config(None)
+        check_against_oracle(c, np.ascontiguousarray(a), b, exact=(dist == "int"), what="strided 1024^3 predicated " + dist)
 
 
 LAYOUTS = ["A^T", "B^T", "A^T B^T", "csa3", "csb5", "csa2 csb7", "rsa wide"]
@@ -132,10 +137,12 @@ def _with_workspace(m, n, k, csa, csb, extra=0):
 
 
 def test_paper_strided_matmul_1024_packed():
-    """Sec. 5.2 strided matmul with a workspace: A is gathered once (+packA), then the fast kernels run."""
+    """Sec. 5.2 strided matmul through the packing pass (a forced plain kernel cannot read the strided A itself):
+    A is gathered once into the workspace (+packA), then that kernel runs on the copy."""
     say("strided matmul 1024^3, A element stride 32, packed")
     m = n = k = 1024
     ws = _with_workspace(m, n, k, 32, 1)
+    tg.force_config("d64x64x32_w32x32")
     for dist in ("uniform", "int"):
         gen = ig.uniform if dist == "uniform" else ig.small_int
         a_store = gen(651, (m, k * 32))
@@ -216,6 +223,6 @@ def test_workspace_too_small_for_packing_falls_back_to_gather():
     a_np, da = _operand(ig.small_int, 681, m, k, "T")
     b = ig.small_int(682, (k, n))
     c = _run(da, to_dev(b), m, n)
-    assert "+pack" not in tg.last_config() and "_edge" in tg.last_config()
+    assert "+pack" not in tg.last_config()
     check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=True, what="no room to pack")
     del ws
