@@ -104,6 +104,32 @@ tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k,
                            void *stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, serving loops and
+ * harnesses with a no-allocation rule) and therefore have no workspace to hand to tg_set_workspace:
+ * the split-K form of tg_sgemm (same product, same arguments, same accuracy) with the partial products
+ * kept in a device array of TG_STATIC_SCRATCH_BYTES that is part of the library's code object (every
+ * GPU the library runs on holds it from the first load until the process ends).  The call allocates
+ * and frees nothing, on the host side of the GPU runtime or through any library.
+ * K is cut into two or more ranges (the count the cost model ranks first for this shape: split-K pays
+ * for few output tiles with a long K, e.g. 256 x 256 x 4096), every range's product is written to the
+ * array by one launch, and a second kernel adds them in range order (deterministic, no atomics) into C.
+ * A configuration set by tg_force_config is used if it is a split (":s<n>", n >= 2) of an fp32 tile kernel.
+ * Limits and errors (all detected before any launch): 2 * m * n * 4 bytes must not exceed
+ * TG_STATIC_SCRATCH_BYTES, else TG_ERR_WORKSPACE; a problem that no split fits (K shorter than two K
+ * tiles per range, or an output that already fills the chip) returns TG_ERR_UNSUPPORTED: use tg_sgemm.
+ * Argument checks, m == 0 / n == 0 / k == 0 and tg_last_config() behave as for tg_sgemm.
+ * Every entry of the part of the array a call uses is written before it is read, so nothing has to
+ * start at zero and the last call's contents do no harm.  All calls on one GPU share that GPU's array:
+ * two calls that overlap in time on one GPU (different streams or host threads) race.
+ */
+#define TG_STATIC_SCRATCH_BYTES (32u << 20)
+tg_status tg_sgemm_splitk_static(int64_t m, int64_t n, int64_t k,
+                                 const float *A, int64_t lda,
+                                 const float *B, int64_t ldb,
+                                 float *C, int64_t ldc,
+                                 void *stream);
+
+/*
  * z[i] = alpha * x[i] + y[i] for 0 <= i < n (Sec. 5.2 "axpy": z = alpha.x + y, the paper's
  * bandwidth-bound kernel, n = 2^26 there).  x, y, z are device pointers to n contiguous
  * floats; z may be the same pointer as y or x (in-place), partial overlap is undefined.

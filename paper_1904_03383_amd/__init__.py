@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     set_workspace,
     sgemm,
     sgemm_batched,
+    sgemm_splitk_static,
     sgemm_strided,
     tune,
     version,

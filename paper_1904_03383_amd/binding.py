@@ -21,6 +21,7 @@ STATUS_NAMES = {0: "TG_OK", 1: "TG_ERR_INVALID_ARG", 2: "TG_ERR_UNSUPPORTED", 3:
 _i64, _p, _sz, _int, _cstr = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_char_p
 SIGNATURES = {
     "tg_sgemm": (_int, [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _i64, _p]),
+    "tg_sgemm_splitk_static": (_int, [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _i64, _p]),
     "tg_sgemm_batched": (_int, [_i64, _i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p]),
     "tg_sgemm_strided": (_int, [_i64, _i64, _i64, _p, _i64, _i64, _p, _i64, _i64, _p, _i64, _p]),
     "tg_saxpy": (_int, [_i64, ctypes.c_float, _p, _p, _p, _p]),
@@ -174,6 +175,33 @@ def _elem_strides(t):
     rs = int(t.stride(0)) if t.shape[0] > 1 else 1
     cs = int(t.stride(1)) if t.shape[1] > 1 else 1
     return rs, cs
+
+
+STATIC_SCRATCH_BYTES = 32 << 20   # TG_STATIC_SCRATCH_BYTES
+
+
+def sgemm_splitk_static(a, b, out=None, stream=None):
+    """C = A.B as a split-K product whose partials live in the library's own fixed device array: the entry
+    point for callers that cannot allocate (the binding itself allocates `out` only when none is given).
+    -> tg_sgemm_splitk_static"""
+    torch = _torch or _torch_mod()
+    _require_f32_cuda("a", a)
+    _require_f32_cuda("b", b)
+    sa, sb = a.shape, b.shape
+    if len(sa) != 2 or len(sb) != 2 or sa[1] != sb[0]:
+        raise ValueError(f"shape mismatch: {tuple(sa)} x {tuple(sb)}")
+    m, k = sa
+    n = sb[1]
+    if out is None:
+        out = torch.empty((m, n), dtype=torch.float32, device=a.device)
+    else:
+        _require_f32_cuda("out", out)
+        if tuple(out.shape) != (m, n):
+            raise ValueError("out has the wrong shape")
+    _check((_lib or load_library()).tg_sgemm_splitk_static(
+        m, n, k, a.data_ptr(), _row_major_ld(a, m, k, a.stride()), b.data_ptr(), _row_major_ld(b, k, n, b.stride()),
+        out.data_ptr(), _row_major_ld(out, m, n, out.stride()), _stream_handle(stream)))
+    return out
 
 
 def sgemm_strided(a, b, out=None, stream=None):

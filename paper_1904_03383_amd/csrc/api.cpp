@@ -890,6 +890,70 @@ tg_status run(Problem &p, void *stream) {
     return st;
 }
 
+// tg_sgemm_splitk_static: the split-K form of the product for callers that cannot allocate.  The partial
+// products live in the library's fixed-size device array instead of a caller workspace; nothing here (or
+// below it) allocates or frees device memory.  The configuration is the split-K candidate (two or more K
+// ranges, one launch plus the reduction) that the cost model ranks first for a workspace of that size,
+// memoised per shape class; a forced configuration is honoured when it is such a split.
+std::map<ShapeKey, Config> g_static_choice;
+
+bool static_split_ok(const Config &c) {
+    const KernelInfo &ki = tg::kernel(c.kernel);
+    return c.splits >= 2 && c.tail == 0 && ki.kind == tg::KIND_TILE && !ki.precut && !ki.pieces;
+}
+
+tg_status run_splitk_static(Problem &p, void *stream) {
+    tg_status st = validate(p);
+    if (st != TG_OK) return st;
+    if (p.batch == 0 || p.m == 0 || p.n == 0) { t_last_config.clear(); t_last_pending = false; return TG_OK; }
+    // two partial products are the least a split needs: sizes beyond that are refused before any GPU call
+    if (ws_need(p, 2) > tg::kStaticScratchBytes)
+        return fail(TG_ERR_WORKSPACE, "problem too large for the static scratch: 2 * m * n * 4 bytes = " +
+                                          std::to_string(ws_need(p, 2)) + " exceeds " + std::to_string(tg::kStaticScratchBytes));
+    st = check_device();
+    if (st != TG_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (p.k == 0) { t_last_config = "zero_fill"; t_last_pending = false; return zero_fill(p, s); }
+    void *ws = nullptr;
+    const hipError_t e = tg::static_scratch(&ws);
+    if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("address of the static scratch: ") + hipGetErrorString(e));
+    Config c;
+    {
+        std::lock_guard<std::mutex> lk(g_mutex);
+        read_env_once();
+        if (g_forced) {
+            std::string why;
+            if (!config_valid(p, g_force_cfg, tg::kStaticScratchBytes, &why))
+                return fail(ws_total(p, g_force_cfg) > tg::kStaticScratchBytes ? TG_ERR_WORKSPACE : TG_ERR_INVALID_ARG,
+                            "forced configuration " + spec_of(g_force_cfg) + " is not valid here: " + why);
+            if (!static_split_ok(g_force_cfg))
+                return fail(TG_ERR_INVALID_ARG, "forced configuration " + spec_of(g_force_cfg) + " is not a plain split-K of an fp32 tile kernel");
+            c = g_force_cfg;
+        } else {
+            auto hit = g_static_choice.find(key_of(p));
+            if (hit != g_static_choice.end() && config_valid(p, hit->second, tg::kStaticScratchBytes)) {
+                c = hit->second;
+            } else {
+                bool found = false;
+                for (const Config &cand : candidates(p, tg::kStaticScratchBytes))   // cheapest by the cost model first
+                    if (static_split_ok(cand)) { c = cand; found = true; break; }
+                if (!found)
+                    return fail(TG_ERR_UNSUPPORTED, "no split-K configuration fits this problem (K shorter than two K tiles per "
+                                                    "range, or the tile grid already fills the chip): use tg_sgemm");
+                if (g_static_choice.size() >= 4096) g_static_choice.clear();
+                g_static_choice[key_of(p)] = c;
+            }
+        }
+    }
+    st = launch(p, c, ws, s);
+    if (st == TG_OK) {
+        t_last_cfg = c;
+        t_last_tags[0] = t_last_tags[1] = "";
+        t_last_pending = true;
+    }
+    return st;
+}
+
 // The timing tuner behind tg_tune: one object per call.
 //   1. sweep: every candidate (sorted by the cost model) is timed briefly; one whose lower bound
 //      already exceeds the best time seen is skipped (the branch-and-bound cut of Sec. 5.1 of
@@ -1147,6 +1211,12 @@ tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k, const float *A, int6
     p.csa = csa;
     p.csb = csb;
     return run(p, stream);
+}
+
+tg_status tg_sgemm_splitk_static(int64_t m, int64_t n, int64_t k, const float *A, int64_t lda, const float *B, int64_t ldb,
+                                 float *C, int64_t ldc, void *stream) {
+    Problem p{1, m, n, k, A, lda, 0, B, ldb, 0, C, ldc, 0, false};
+    return run_splitk_static(p, stream);
 }
 
 tg_status tg_saxpy(int64_t n, float alpha, const float *x, const float *y, float *z, void *stream) {

@@ -124,6 +124,10 @@ hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int
 // dst[r * ld + c] = src[r * rs + c] (r < rows, c < cols), +0.0 elsewhere on rows_out x ld: aligned, zero-padded copy.
 hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, float *dst, int64_t ld, int rows_out, hipStream_t s);
 
+// Device address, on the current device, of the library's fixed-size scratch array (static_scratch.hip).
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+hipError_t static_scratch(void **ptr);
+
 constexpr int kLdsPerCU = 160 * 1024;  // gfx950
 
 // Raises a kernel's dynamic LDS limit to the whole LDS of a CU, once per device (`done` holds one

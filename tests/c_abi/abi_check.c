@@ -24,6 +24,12 @@ int main(void)
     CHECK(tg_sgemm(-1, 1, 1, fake, 1, fake, 1, fake, 1, NULL) == TG_ERR_INVALID_ARG);
     CHECK(strstr(tg_last_error(), "negative") != NULL);
     CHECK(tg_sgemm(0, 8, 8, NULL, 8, NULL, 8, NULL, 8, NULL) == TG_OK);
+    CHECK(tg_sgemm_splitk_static(-1, 1, 1, fake, 1, fake, 1, fake, 1, NULL) == TG_ERR_INVALID_ARG);
+    CHECK(tg_sgemm_splitk_static(0, 8, 8, NULL, 8, NULL, 8, NULL, 8, NULL) == TG_OK);
+    /* 2 * m * n * 4 bytes beyond the static scratch: refused before any GPU call */
+    CHECK(tg_sgemm_splitk_static(4096, 4096, 4096, fake, 4096, fake, 4096, fake, 4096, NULL) == TG_ERR_WORKSPACE);
+    CHECK(strstr(tg_last_error(), "static scratch") != NULL);
+    CHECK(TG_STATIC_SCRATCH_BYTES == 32u * 1024 * 1024);
     CHECK(tg_sgemm_batched(2, 4, 4, 4, fake, 4, 16, fake, 4, 16, fake, 4, 8, NULL) == TG_ERR_INVALID_ARG);
     CHECK(tg_sgemm_strided(4, 4, 4, fake, 4, 0, fake, 4, 1, fake, 4, NULL) == TG_ERR_INVALID_ARG);
     CHECK(tg_saxpy(-5, 1.0f, fake, fake, fake, NULL) == TG_ERR_INVALID_ARG);
