@@ -500,6 +500,9 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     eff *= ki.BK >= 32 ? 1.0 : 0.985;
     // (direct-to-LDS loads: ~1 % ahead on the large tiles, 4-10 % on 64x64 tiles with k >= 256, behind on 128x128)
     if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? 1.01 : (ki.WM * ki.WN == 32 * 32 ? 1.04 : 0.97);
+    // (32x32 wave tiles with the fragments of a whole K tile fetched one tile ahead: 1024^3 20.0 us against 21.7 us;
+    // K tiles of 64 in that form: 21.0 us)
+    if (strstr(ki.name, "_tf")) eff *= ki.BK > 32 ? 1.03 : 1.08;
     if (ki.name[0] == 'd') {
         // deeper rings and wave groups along K are there for the tuner to try; untuned, the plain form goes first
         // (a ring deeper than the K range only adds loads: 1536x1536x64 11.3 us against 9.2 us)
@@ -533,26 +536,25 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     // 30 small and mid-size shapes: the model's first choice then averages 5 % above the best measured candidate)
     double t = launch + 1e-6 + per_cu * block_flops / cu_rate;
     // A gathered operand: every element costs a line request (its own cache line when the stride is large) in every tile
-    // that fetches it.  Measured with hardware counters on 1024^3 with A at element stride 32 (requests per CU, average
-    // latency per request, time): a CU's L1 keeps about a hundred line requests in flight at 450 cycles (L2 hit) to 1400
-    // cycles (miss) each, which comes to about 1.3 ns per request and CU (64x64 tiles: 74 K requests per CU, 93 us;
-    // 128x128: 132 K, 164 us); and the distinct lines arrive from the fabric at about 2.3 TB/s however the tiles are cut
-    // (32x128: 61 us, 16x256: 57 us, for 128 MiB of lines).
+    // that fetches it.  Measured with hardware counters on 1024^3 with A at element stride 32: a CU's L1 keeps about a
+    // hundred line requests in flight at 450 cycles (L2 hit) to 1400 cycles (miss) each, which comes to about 1.1 ns
+    // per request and CU (64x64 tiles: 70 K requests per CU, 78 us; 128x128: 132 K, 164 us), and the distinct lines
+    // arrive from the fabric at about 3.2 TB/s however the tiles are cut (128 MiB of lines: 16x256 tiles 44 us,
+    // 32x128 tiles 50 us); the two overlap for the most part.
     if (ki.amode == 2 || ki.bmode == 2) {
         const double line_a = std::min(4.0 * p.csa, 128.0), line_b = std::min(4.0 * p.csb, 128.0);
-        const double tm = (double)ceil_div(p.m, ki.BM), tn = (double)ceil_div(p.n, ki.BN);
-        // line requests of one workgroup: per element of a gathered operand, per 128 bytes of a plain one
+        // line requests of one workgroup: per element of a gathered operand (four elements share a request when they
+        // share a 16-byte piece of a line), per 128 bytes of a plain one
         const double req_a = ki.amode == 2 ? (double)ki.BM * p.k * (line_a / 128.0 > 0.25 ? 1.0 : 4.0 * line_a / 128.0) : (double)ki.BM * p.k / 32.0;
         const double req_b = ki.bmode == 2 ? (double)ki.BN * p.k * (line_b / 128.0 > 0.25 ? 1.0 : 4.0 * line_b / 128.0) : (double)ki.BN * p.k / 32.0;
         double lines = 0;
         if (ki.amode == 2) lines += p.batch * (double)p.m * p.k * line_a;
         if (ki.bmode == 2) lines += p.batch * (double)p.k * p.n * line_b;
-        // (16-row tiles: best while every workgroup is resident at once, 1024^3 57 us against 61 us for 32x128; with
-        // several rounds per CU they measured about twice the time per request, 2048^3 523 us against 434 us)
-        const double per_req = ki.BM <= 16 && per_cu > 1 ? 2.7e-9 : 1.3e-9;
-        t = std::max(t, launch + 1e-6 + per_cu * (req_a + req_b) / splits * per_req);
-        t = std::max(t, launch + 1e-6 + lines / 2.3e12);
-        (void)tm; (void)tn;
+        // (16-row tiles: best while every workgroup is resident at once; with several rounds per CU they measured
+        // about twice the time per request, 2048^3 523 us against 434 us for 32x128 tiles)
+        const double per_req = ki.BM <= 16 && per_cu > 1 ? 2.4e-9 : 1.12e-9;
+        const double t_req = per_cu * (req_a + req_b) / splits * per_req, t_lines = lines / 3.2e12;
+        t = std::max(t, launch + 1e-6 + std::max(t_req, t_lines) + 0.25 * std::min(t_req, t_lines));
     }
     if (splits > 1) t += 4e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
     if (ki.precut) t += 6e-6 + 10.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n) / (kPeakHbm * 0.6);

@@ -117,6 +117,25 @@ TG_MODE_LIST(TG_MDECL)
      NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, 1, AM, BMD, 16>, 0, false, 0, false, AM, BMD},
 TG_MI16_LIST(TG_M16DECL)
 
+// direct-to-LDS variants for 32x32 wave tiles with tile-granular fragment prefetch:
+// (BM, BN, BK, two_level, LDS stages, A mode, B mode, name)
+#define TG_DEEP_LIST(X)                                                     \
+    X(64, 64, 32, false, 2, 0, 0, "d64x64x32_w32x32_tf")                    \
+    X(64, 64, 32, true, 2, 0, 0, "d64x64x32_w32x32_acc2_tf")                \
+    X(64, 64, 64, false, 2, 0, 0, "d64x64x64_w32x32_tf")                    \
+    X(64, 64, 64, true, 2, 0, 0, "d64x64x64_w32x32_acc2_tf")                \
+    X(64, 64, 32, true, 2, 1, 0, "d64x64x32_w32x32_acc2_tf_ta")             \
+    X(64, 64, 32, true, 2, 0, 1, "d64x64x32_w32x32_acc2_tf_tb")             \
+    X(64, 64, 32, true, 2, 1, 1, "d64x64x32_w32x32_acc2_tf_ta_tb")          \
+    X(64, 64, 32, true, 2, 2, 0, "d64x64x32_w32x32_acc2_tf_ga")             \
+    X(64, 64, 32, true, 2, 0, 2, "d64x64x32_w32x32_acc2_tf_gb")
+#define TG_FDECL(BM, BN, BK, L2, NS, AM, BMD, NAME) \
+    extern template hipError_t launch_tile_deep<BM, BN, BK, NS, L2, AM, BMD>(const GemmParams &, hipStream_t);
+#define TG_FROW(BM, BN, BK, L2, NS, AM, BMD, NAME)                                              \
+    {NAME, KIND_TILE, BM, BN, BK, 32, 32, L2, false, false, false, (BM / 32) * (BN / 32) * 64, \
+     NS * (BM * BK + BK * BN) * 4, &launch_tile_deep<BM, BN, BK, NS, L2, AM, BMD>, 0, false, 0, false, AM, BMD},
+TG_DEEP_LIST(TG_FDECL)
+
 // bf16-piece variants: (BM, BN, BK, WM, WN, piece products, name)
 #define TG_PIECES_LIST(X)                                                   \
     X(128, 256, 32, 64, 128, 6, "e128x256x32_w64x128_x6")                   \
@@ -143,6 +162,7 @@ TG_PRECUT_LIST(TG_CDECL)
 static const KernelInfo kTable[] = {
     TG_TILE_LIST(TG_ROW)
     TG_DIRECT_LIST(TG_DROW)
+    TG_DEEP_LIST(TG_FROW)
     TG_MODE_LIST(TG_MROW)
     TG_MI16_LIST(TG_M16ROW)
     TG_PIECES_LIST(TG_EROW)

@@ -90,6 +90,11 @@ constexpr int tile_lds_bytes();
 template <int BM, int BN, int BK, int WM, int WN, bool TWO_LEVEL, int NS, int KG, int AM = 0, int BMD = 0, int MI = 32>
 hipError_t launch_tile_direct(const GemmParams &p, hipStream_t s);
 
+// Direct-to-LDS kernel for 32x32 wave tiles that fetches the fragments of a whole K tile one tile ahead
+// (aligned operands, k % BK == 0, n % 4 == 0; operand modes AM / BMD as for launch_tile_direct).
+template <int BM, int BN, int BK, int NS, bool TWO_LEVEL, int AM = 0, int BMD = 0>
+hipError_t launch_tile_deep(const GemmParams &p, hipStream_t s);
+
 // Workgroup-tile kernel on the bf16 matrix pipe: operands cut into three bf16 pieces each, NP piece
 // products per fp32 product (aligned operands, k % BK == 0, n % 4 == 0).
 template <int BM, int BN, int BK, int WM, int WN, int NP>

@@ -55,8 +55,11 @@ typedef __attribute__((address_space(1))) const float glb_float;
 // accesses may be grouped over banks.
 template <int BK>
 __device__ __forceinline__ int a_swizzle(int row) {
-    static_assert(BK == 32, "the chunk permutation is laid out for rows of 8 chunks");
-    return (row & 6) | ((row ^ (row >> 3)) & 1);
+    static_assert(BK == 32 || BK == 64, "the chunk permutation is laid out for rows of 8 or 16 chunks");
+    // (rows of 64 floats all start in bank 0: the low three bits of the row spread eight consecutive rows over the
+    // eight 16-byte bank groups)
+    if constexpr (BK == 64) return row & 7;
+    else return (row & 6) | ((row ^ (row >> 3)) & 1);
 }
 
 template <int BM, int BN, int BK, int NS>
@@ -305,13 +308,17 @@ sgemm_tile_direct_kernel(const GemmParams p) {
         }
     };
 
-    // s_waitcnt that allows kOutstanding vector-memory operations to stay in flight and leaves
-    // the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4,
-    // lgkmcnt 11:8).
+    // s_waitcnt that allows kOutstanding vector-memory operations to stay in flight and waits for every LDS
+    // operation of the wave (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
     constexpr int N_MFMA = 4 * RB * CB;
     constexpr int N_LD = A_LD + B_LD;
     constexpr int kOutstanding = (NS - 2) * N_LD;
-    constexpr int kWaitTile = 0x0F70 | (kOutstanding & 15) | ((kOutstanding >> 4) << 14);
+    // The barriers of the K loop are the bare instruction behind this wait, not __syncthreads(): the fence that
+    // comes with the latter makes the compiler wait for every load in flight (vmcnt(0)) before each barrier, which
+    // empties a ring of more than two stages at every K tile.  What the barrier has to order is covered by the
+    // wait: a direct load counts as done (vmcnt) when its data is in LDS, and the wave's own LDS reads have
+    // returned (lgkmcnt(0)) before it lets the others overwrite the stage they came from.
+    constexpr int kWaitTile = 0x0070 | (kOutstanding & 15) | ((kOutstanding >> 4) << 14);
     constexpr int MFMA_PER_LD = (N_MFMA - 2) / N_LD > 0 ? (N_MFMA - 2) / N_LD : 1;
 
     // K loop over an NS-stage ring in LDS.  During tile t (stage t % NS) the loads of tile
@@ -333,7 +340,7 @@ sgemm_tile_direct_kernel(const GemmParams p) {
             }
         }
         __builtin_amdgcn_s_waitcnt(kWaitTile);
-        __syncthreads();
+        __builtin_amdgcn_s_barrier();
         read_frags(0, 0, 0);
         int stage = 0, fill = NS - 1;               // stage being multiplied / stage being filled
         for (int kt = kt_begin; kt < kt_end; ++kt) {
@@ -372,8 +379,8 @@ sgemm_tile_direct_kernel(const GemmParams p) {
                 __builtin_amdgcn_sched_barrier(0);
             }
             const int next = stage + 1 == NS ? 0 : stage + 1;
-            __builtin_amdgcn_s_waitcnt(kWaitTile);   // this wave's share of the next tile is in LDS
-            __syncthreads();                         // everyone's is; stage `stage` is free
+            __builtin_amdgcn_s_waitcnt(kWaitTile);   // this wave's share of the next tile is in LDS, its own LDS reads are back
+            __builtin_amdgcn_s_barrier();            // everyone's is; stage `stage` is free
             mfma_octet((NO - 1) & 1);
             read_frags(next, 0, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);

@@ -84,6 +84,20 @@ __device__ __forceinline__ void store_lane(float *dst, V o, bool lane_vec, int c
     }
 }
 
+// Row of the A tile that load slot f (one 16-byte vector; BK/4 consecutive slots make a row) fetches and
+// writes to LDS.  With BK = 32 eight consecutive lanes fill one padded LDS row, 32 consecutive banks.  With
+// BK = 16 they fill two rows, and at a row pitch of 20 floats the rows r and r+1 overlap in four banks (a
+// 2-way conflict on every ds_write_b128 of A: 16.9 % of the LDS cycles in the hardware counters); rows r
+// and r+4 do not (20*4 = 80 = 16 mod 32).  So within each group of eight rows the slots take the rows in
+// the order 0, 4, 1, 5, 2, 6, 3, 7.  No padding alone can do this: the second row would have to start 16
+// banks after the first, i.e. at a pitch of 16 mod 32, where the fragment reads of 8 rows collide.
+template <int BK>
+__device__ __forceinline__ int a_slot_row(int f) {
+    const int r = f / (BK / 4);
+    if constexpr (BK == 16) return (r & ~7) | ((r & 1) << 2) | ((r & 7) >> 1);
+    else return r;
+}
+
 // Workgroup id -> (slice, tile row, tile column);  slice = problem * splits + split.
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn, and each XCD has its own
 // 4 MB L2.  So that the workgroups resident on one XCD share operand panels:
@@ -204,7 +218,7 @@ sgemm_tile_kernel(const GemmParams p) {
     #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             const int f = tid + i * NT;
-            a_row[i] = f / (BK / 4);
+            a_row[i] = a_slot_row<BK>(f);
             a_k[i] = (f % (BK / 4)) * 4;
             // exact-fit variants on a ragged last tile row: rows past the end re-read the last row
             // (in bounds; what they produce is never stored)

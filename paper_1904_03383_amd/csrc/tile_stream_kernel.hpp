@@ -56,7 +56,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         const int f = tid + i * NT;
-        a_row[i] = f / (BK / 4);
+        a_row[i] = a_slot_row<BK>(f);
         a_k[i] = (f % (BK / 4)) * 4;
         a_off[i] = (unsigned)a_row[i] * (unsigned)p.lda + (unsigned)a_k[i];
     }

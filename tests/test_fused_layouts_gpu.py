@@ -77,7 +77,9 @@ def test_variant_list_is_not_empty():
     "d128x256x32_w64x128_acc2_ta_tb", "d64x64x32_w32x32_acc2_st4_gb", "d128x128x32_w64x64_acc2_st3_gb",
     "d64x64x32_w32x32_acc2_st4_ga_gb", "d128x128x32_w64x64_acc2_st3_ga_gb", "d64x64x32_w32x32_acc2_st4_ga_tb",
     "d128x128x32_w64x64_acc2_st3_ga_tb", "d64x64x32_w32x32_acc2_st4_ta_gb", "d128x128x32_w64x64_acc2_st3_ta_gb",
-    "d16x256x32_w16x64_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga")])
+    "d16x256x32_w16x64_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga",
+    "d64x64x32_w32x32_acc2_tf_ta", "d64x64x32_w32x32_acc2_tf_tb", "d64x64x32_w32x32_acc2_tf_ta_tb",
+    "d64x64x32_w32x32_acc2_tf_ga", "d64x64x32_w32x32_acc2_tf_gb")])
 def test_every_variant_forced(name):
     assert name in _mode_variants()
     bm, bn, bk = _tile(name)
