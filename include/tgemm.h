@@ -150,6 +150,21 @@ tg_status tg_saxpy(int64_t n, float alpha, const float *x, const float *y, float
  * stream created for the duration of the call).  Must not be called while `stream` is being captured.
  * Blocking: synchronises `stream`.  tg_sgemm / tg_sgemm_batched never time anything;
  * without a tuned entry they use a static heuristic.
+ * Whether a problem counts as launch-bound is decided from the cost model's device time of its first
+ * candidate (under 12 us), not from a measured per-call time, so that a slow host or a profiler cannot
+ * hide it (tg_tune_is_launch_bound answers the same question without a GPU).
+ * Result check: the first candidate's product is kept (every step-th row of C, in the static array of
+ * tg_sgemm_splitk_static, so tg_tune must not overlap such calls on the same GPU) and every other
+ * candidate's product is compared with it before that candidate may lead: two results that meet the
+ * accuracy bar differ by at most 2e-6 in the relative Frobenius norm; 4e-6 is allowed, non-finite values
+ * are not.  If any candidate fails, nothing is cached and the call returns TG_ERR_INTERNAL naming the
+ * configurations (tg_last_error()).
+ * The operands are passed (the benchmark definition's tg_tune(batch, m, n, k, stream) has none) because
+ * candidates are timed on the caller's real buffers, with their real leading dimensions and alignment,
+ * and the library allocates nothing.
+ * Two environment variables exist for tests of the tuner itself: TG_TUNE_TEST_HOST_DELAY_US=<us> makes
+ * the host wait that long after every timed launch (a slow host), TG_TUNE_TEST_SPOIL_REFERENCE=1
+ * overwrites one entry of the kept reference (so that every candidate fails the check).
  */
 tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
                   const float *A, int64_t lda, int64_t strideA,
@@ -158,7 +173,8 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
                   void *stream, int reps);
 
 /*
- * Workspace (device memory, caller-owned, 16-byte aligned): split-K partial products (also those of
+ * Workspace (device memory, caller-owned, 16-byte aligned; the benchmark definition keeps allocation with
+ * the caller: PyTorch owns device memory): split-K partial products (also those of
  * the K-split tail launch of a tail split), packed copies of strided operands, aligned zero-padded copies
  * of unit-stride operands that are off the 16-byte grid or have k or n not a multiple of 4 (made for
  * single products with m, n >= 256 and m * n * k >= 4.2e8 when there is room: m x k and k x n floats, each rounded up to
@@ -183,7 +199,8 @@ size_t tg_workspace_bytes(int64_t batch, int64_t m, int64_t n, int64_t k);
 size_t tg_strided_workspace_bytes(int64_t m, int64_t n, int64_t k, int64_t csa, int64_t csb);
 
 /*
- * Configuration control.  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>][:p<n>][:t<rows>x<splits>]", e.g.
+ * Configuration control (the paper notes that an expert can set decisions by hand before the search,
+ * Sec. 6.1; this is that hook).  A spec is "<kernel>[:s<splitK>][:g<group>][:o<cap>][:p<n>][:t<rows>x<splits>]", e.g.
  * "t128x128x16_w64x64:s1:g8" (split-K factor; tile rows per ordering group; cap on
  * workgroups per CU; persistent launch with n workgroups per CU that loop over the tiles;
  * tail split: the last <rows> tile rows of every problem go out as a second launch with split-K
@@ -245,6 +262,13 @@ int tg_num_candidates(int64_t batch, int64_t m, int64_t n, int64_t k);
 tg_status tg_candidate(int64_t batch, int64_t m, int64_t n, int64_t k, int idx, char *spec, size_t len,
                        double *lower_bound_us, double *model_us);
 
+/*
+ * 1 if tg_tune would time the leading candidates of this problem (packed, aligned operands) as graph replays
+ * because it is launch-bound by the cost model, 0 if not, -1 with tg_last_error set for invalid sizes.
+ * Does not touch the GPU.
+ */
+int tg_tune_is_launch_bound(int64_t batch, int64_t m, int64_t n, int64_t k);
+
 /* Spec the most recent successful tg_sgemm/tg_sgemm_batched/tg_tune call on this thread ran (or "" ). */
 const char *tg_last_config(void);
 
@@ -252,7 +276,13 @@ const char *tg_last_config(void);
 int tg_num_kernels(void);
 tg_status tg_kernel_name(int idx, char *buf, size_t len);
 
-/* Tuned-entry cache: plain text, one entry per line.  Loading merges into the live cache. */
+/*
+ * Tuned-entry cache (the only persistent state; the counterpart of the paper's remark, Sec. 3.4, that a
+ * candidate's decision vector is easy to serialise): plain text, one entry per line.  Loading merges into
+ * the live cache.  If the environment variable TG_TUNE_CACHE names a file, it is loaded at the first call
+ * that chooses a configuration (when it exists), and every successful tg_tune rewrites the file the variable
+ * names at that time with the whole live cache.
+ */
 tg_status tg_load_tune_cache(const char *path);
 tg_status tg_save_tune_cache(const char *path);
 void tg_clear_tune_cache(void);

@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     sgemm_splitk_static,
     sgemm_strided,
     tune,
+    tune_is_launch_bound,
     version,
     workspace_bytes,
     strided_workspace_bytes,

@@ -35,6 +35,7 @@ SIGNATURES = {
     "tg_get_config": (_int, [_i64, _i64, _i64, _i64, _p, _sz]),
     "tg_num_candidates": (_int, [_i64, _i64, _i64, _i64]),
     "tg_candidate": (_int, [_i64, _i64, _i64, _i64, _int, _p, _sz, _p, _p]),
+    "tg_tune_is_launch_bound": (_int, [_i64, _i64, _i64, _i64]),
     "tg_last_config": (_cstr, []),
     "tg_num_kernels": (_int, []),
     "tg_kernel_name": (_int, [_int, _p, _sz]),
@@ -356,6 +357,15 @@ def candidates(batch: int, m: int, n: int, k: int):
                                 ctypes.cast(ctypes.byref(model), ctypes.c_void_p)))
         out.append((buf.value.decode(), bound.value, model.value))
     return out
+
+
+def tune_is_launch_bound(batch: int, m: int, n: int, k: int) -> bool:
+    """Whether ``tune`` would time this problem's leaders as graph replays (decided by the cost model).  -> tg_tune_is_launch_bound"""
+    lib = load_library()
+    r = lib.tg_tune_is_launch_bound(batch, m, n, k)
+    if r < 0:
+        raise TgemmError(1, lib.tg_last_error().decode())
+    return bool(r)
 
 
 def last_config() -> str:

@@ -8,6 +8,8 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -160,9 +162,78 @@ bool parse_spec(const char *spec, Config &out, std::string &why) {
     return true;
 }
 
+// Tune cache file: plain text, one entry per line.  Callers hold g_mutex.
+tg_status save_cache_locked(const char *path) {
+    FILE *f = fopen(path, "w");
+    if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
+    fprintf(f, "tgemm-tune-cache 5 gfx950\n");
+    for (const auto &kv : g_cache) {
+        const ShapeKey &k = kv.first;
+        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
+                (long long)std::get<2>(k), (long long)std::get<3>(k), std::get<4>(k),
+                tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.cfg.occ,
+                kv.second.cfg.persist, kv.second.cfg.tail, kv.second.cfg.tail_splits, kv.second.usec);
+    }
+    fclose(f);
+    return TG_OK;
+}
+
+tg_status load_cache_locked(const char *path) {
+    FILE *f = fopen(path, "r");
+    if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
+    char head[64] = {0}, arch[32] = {0};
+    int ver = 0;
+    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || (ver < 3 || ver > 5) ||
+        strcmp(arch, "gfx950") != 0) {
+        fclose(f);
+        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3 to 5)");
+    }
+    // one entry per line; version 4 added the two tail-split fields before the time, version 5 widened the
+    // layout class (the math mode moved from 4 x to 16 x)
+    char line[512];
+    while (fgets(line, sizeof line, f)) {
+        long long b, m, n, k;
+        int al, splits, group, occ, persist, tail = 0, tail_splits = 1;
+        char name[128];
+        double us;
+        int got;
+        if (ver == 3)
+            got = sscanf(line, "%lld %lld %lld %lld %d %127s %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ,
+                         &persist, &us) == 11;
+        else
+            got = sscanf(line, "%lld %lld %lld %lld %d %127s %d %d %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group,
+                         &occ, &persist, &tail, &tail_splits, &us) == 13;
+        if (!got) continue;
+        Config c;
+        c.kernel = find_kernel(name);
+        c.splits = splits;
+        c.group = group;
+        c.occ = occ;
+        c.persist = persist;
+        c.tail = tail;
+        c.tail_splits = tail_splits;
+        // entry from another build or a damaged line: ignore
+        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0 || persist < 0 || tail < 0 || tail_splits < 1) continue;
+        if (ver < 5) al = al % 4 + 16 * (al / 4);
+        g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
+    }
+    fclose(f);
+    return TG_OK;
+}
+
 void read_env_once() {
     if (g_env_read) return;
     g_env_read = true;
+    // TG_TUNE_CACHE: a tune cache file that is loaded now (if it exists) and rewritten after every tg_tune
+    if (const char *path = getenv("TG_TUNE_CACHE")) {
+        if (*path) {
+            FILE *probe = fopen(path, "r");
+            if (probe) {
+                fclose(probe);
+                if (load_cache_locked(path) != TG_OK) fprintf(stderr, "tgemm: ignoring TG_TUNE_CACHE: %s\n", t_error.c_str());
+            }
+        }
+    }
     const char *e = getenv("TG_FORCE_CONFIG");
     if (e && *e) {
         Config c;
@@ -956,6 +1027,15 @@ tg_status run_splitk_static(Problem &p, void *stream) {
     return st;
 }
 
+// Is the problem launch-bound, i.e. would back-to-back calls only measure the host's launch rate?  Decided from the
+// cost model's device time of the candidate it ranks first (its estimate less the launch cost it includes), never
+// from a measured per-call time: under a profiler or on a busy host every call takes tens of microseconds, and a
+// classification made from that would skip the device-time measurement exactly when it is needed.
+constexpr double kLaunchBoundDeviceSeconds = 12e-6;
+bool launch_bound_problem(const Problem &p, const std::vector<Config> &cands) {
+    return !cands.empty() && heuristic_seconds(p, cands.front()) - 4e-6 < kLaunchBoundDeviceSeconds;
+}
+
 // The timing tuner behind tg_tune: one object per call.
 //   1. sweep: every candidate (sorted by the cost model) is timed briefly; one whose lower bound
 //      already exceeds the best time seen is skipped (the branch-and-bound cut of Sec. 5.1 of
@@ -963,11 +1043,16 @@ tg_status run_splitk_static(Problem &p, void *stream) {
 //   2. refine: tile-order group, cap on workgroups per CU and (persistent variants) workgroups
 //      per CU of the winner;
 //   3. final round among the leading kernel variants, with timings that can tell them apart.
+// Every candidate's result is compared with the first candidate's before it may lead (result check below).
 class Tuner {
   public:
     Tuner(const Problem &p, void *ws, size_t ws_bytes, hipStream_t stream, int reps)
         : p_(p), ws_(ws), ws_bytes_(ws_bytes), s_(stream), reps_(reps), log_(getenv("TG_LOG") != nullptr) {
         events_ok_ = hipEventCreate(&ev0_) == hipSuccess && hipEventCreate(&ev1_) == hipSuccess;
+        // test switches (documented in tgemm.h): a host-side delay after every timed launch, in microseconds, and a
+        // deliberately spoilt reference for the result check
+        if (const char *d = getenv("TG_TUNE_TEST_HOST_DELAY_US")) host_delay_us_ = atof(d);
+        spoil_reference_ = getenv("TG_TUNE_TEST_SPOIL_REFERENCE") != nullptr;
     }
     ~Tuner() {
         if (ev0_) (void)hipEventDestroy(ev0_);
@@ -980,6 +1065,8 @@ class Tuner {
         if (!events_ok_) return fail(TG_ERR_HIP, "hipEventCreate failed");
         const std::vector<Config> cands = candidates(p_, ws_bytes_);
         if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
+        launch_bound_ = launch_bound_problem(p_, cands);
+        prepare_check();
         sweep(cands);
         if (best_.kernel < 0) return fail(TG_ERR_HIP, "every candidate failed to run: " + last_err_);
         if (tg::kernel(best_.kernel).kind == tg::KIND_TILE) {
@@ -988,12 +1075,76 @@ class Tuner {
             refine_persistence();
         }
         final_round();
+        // A candidate whose product differs from the first candidate's is a defect of the library, not a tuning result:
+        // nothing is cached and the call says which configurations disagree.
+        if (!disagree_.empty())
+            return fail(TG_ERR_INTERNAL, "result check: " + disagree_ + " (reference: " + spec_of(ref_cfg_) + "); nothing cached");
         *best = best_;
         *best_us = best_us_;
         return TG_OK;
     }
 
   private:
+    // ---- result check -------------------------------------------------------------------------------------------
+    // The first candidate that runs leaves its product in C; every step-th row of it is copied into the library's
+    // static scratch (step such that the copy fits; 1 for products up to about 8 M elements).  Every later candidate's
+    // product is compared with it on those rows: two results that each meet the benchmark's bar (relative Frobenius
+    // error <= 1e-6 against the exact product, Sec. 5.2 definition) differ by at most 2e-6 in that norm; the check
+    // allows 4e-6 and no non-finite value.  A candidate that fails is dropped and reported.
+    void prepare_check() {
+        void *base = nullptr;
+        if (tg::static_scratch(&base) != hipSuccess || base == nullptr) return;   // no check without the scratch
+        const size_t room = tg::kStaticScratchBytes - kPartialBytes;
+        const double need = 4.0 * (double)p_.batch * (double)p_.m * (double)p_.n;
+        step_ = (int)std::min<double>(std::max(1.0, std::ceil(need / (double)room)), (double)p_.m);
+        const int64_t rows = ceil_div(p_.m, step_);
+        if ((double)p_.batch * rows * p_.n * 4.0 > (double)room) return;          // (a single row too long: no check)
+        ref_ = static_cast<float *>(base);
+        partial_ = reinterpret_cast<double *>(static_cast<char *>(base) + room);
+    }
+
+    void take_reference(const Config &c) {
+        if (!ref_ || have_ref_) return;
+        if (launch(p_, c, ws_, s_) != TG_OK) return;
+        hipError_t e = tg::launch_snapshot_rows(p_.C, p_.ldc, p_.strideC, (int)p_.batch, (int)p_.m, (int)p_.n, step_, ref_, s_);
+        if (e == hipSuccess && spoil_reference_) {
+            static const float kBogus = 1.0e30f;
+            e = hipMemcpyAsync(ref_, &kBogus, sizeof kBogus, hipMemcpyHostToDevice, s_);
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(s_);
+        if (e != hipSuccess) { (void)hipGetLastError(); return; }
+        have_ref_ = true;
+        ref_cfg_ = c;
+    }
+
+    // true: agrees with the reference (or no check is possible)
+    bool agrees(const Config &c) {
+        if (!have_ref_) return true;
+        if (launch(p_, c, ws_, s_) != TG_OK) return true;   // (a launch failure is reported by the timing path)
+        double host[3 * tg::kCheckBlocks];
+        hipError_t e = tg::launch_compare_rows(p_.C, p_.ldc, p_.strideC, (int)p_.batch, (int)p_.m, (int)p_.n, step_, ref_, partial_, s_);
+        if (e == hipSuccess) e = hipMemcpyAsync(host, partial_, sizeof host, hipMemcpyDeviceToHost, s_);
+        if (e == hipSuccess) e = hipStreamSynchronize(s_);
+        if (e != hipSuccess) { (void)hipGetLastError(); return true; }
+        double d2 = 0, r2 = 0, bad = 0;
+        for (int b = 0; b < tg::kCheckBlocks; ++b) { d2 += host[3 * b]; r2 += host[3 * b + 1]; bad += host[3 * b + 2]; }
+        const bool ok = bad == 0 && d2 <= (4e-6 * 4e-6) * r2;
+        if (!ok) {
+            char buf[256];
+            snprintf(buf, sizeof buf, "%s%s differs (relative Frobenius difference %.3g, %.0f non-finite)", disagree_.empty() ? "" : "; ",
+                     spec_of(c).c_str(), r2 > 0 ? std::sqrt(d2 / r2) : 0.0, bad);
+            disagree_ += buf;
+            if (log_) fprintf(stderr, "tgemm tune: %s\n", buf);
+        }
+        return ok;
+    }
+
+    void host_delay() const {
+        if (host_delay_us_ <= 0) return;
+        const auto until = std::chrono::steady_clock::now() + std::chrono::duration<double, std::micro>(host_delay_us_);
+        while (std::chrono::steady_clock::now() < until) {}
+    }
+
     // One brief timing: warm-up launch, then `n` back-to-back launches between two events.
     // Short kernels are repeated more often (until about 0.3 ms is covered) so that launch
     // jitter does not decide between candidates.
@@ -1004,7 +1155,7 @@ class Tuner {
         double best_of = 1e300;
         for (int round = 0; round < 3; ++round) {
             hipError_t e = hipEventRecord(ev0_, s_);
-            for (int i = 0; i < n && r == TG_OK; ++i) r = launch(p_, c, ws_, s_);
+            for (int i = 0; i < n && r == TG_OK; ++i) { r = launch(p_, c, ws_, s_); host_delay(); }
             if (e == hipSuccess) e = hipEventRecord(ev1_, s_);
             if (e == hipSuccess) e = hipEventSynchronize(ev1_);
             if (r != TG_OK) return r;
@@ -1020,13 +1171,18 @@ class Tuner {
         return TG_OK;
     }
 
-    // Times `c`, records it and makes it the leader when it beats the best by `margin`.
-    void consider(const Config &c, double margin) {
+    // Times `c`, records it and makes it the leader when it beats the best by `margin`.  `check`: a kernel variant not
+    // seen before, whose product is compared with the reference first (the refinements re-run a variant that passed).
+    void consider(const Config &c, double margin, bool check = false) {
         double us = 0;
         if (time_briefly(c, &us) != TG_OK) {
             last_err_ = t_error;
             (void)hipGetLastError();   // clear the error so the next candidate starts clean
             return;
+        }
+        if (check) {
+            if (!have_ref_) take_reference(c);
+            else if (!agrees(c)) return;
         }
         if (log_) fprintf(stderr, "tgemm tune: %-44s %.2f us\n", spec_of(c).c_str(), us);
         seen_.emplace_back(us, c);
@@ -1040,7 +1196,7 @@ class Tuner {
                 if (log_) fprintf(stderr, "tgemm tune: %-44s pruned (bound %.1f us >= best %.1f us)\n", spec_of(c).c_str(), lb_us, best_us_);
                 continue;
             }
-            consider(c, 1.0);
+            consider(c, 1.0, true);
         }
     }
 
@@ -1078,7 +1234,7 @@ class Tuner {
     double time_run(const Config &c, int n) {
         tg_status r = TG_OK;
         hipError_t e = hipEventRecord(ev0_, s_);
-        for (int j = 0; j < n && r == TG_OK; ++j) r = launch(p_, c, ws_, s_);
+        for (int j = 0; j < n && r == TG_OK; ++j) { r = launch(p_, c, ws_, s_); host_delay(); }
         if (e == hipSuccess) e = hipEventRecord(ev1_, s_);
         if (e == hipSuccess) e = hipEventSynchronize(ev1_);
         float ms = 0.f;
@@ -1122,22 +1278,38 @@ class Tuner {
     // Long kernels: the leaders are often within the noise of the brief timings (1 % at 4096^3),
     // so the three fastest kernel variants within 2 % of the best are timed again, alternating,
     // with longer runs (>= 10 launches and >= 2 ms each).
-    // Launch-bound kernels (under ~12 us per call): back-to-back calls only measure the host's
-    // launch rate, which is the same for every candidate, so up to six variants within 25 % are
-    // timed as replays of a captured graph on a private stream, i.e. by their device time.
-    // The best of two such runs decides.
+    // Launch-bound problems (modelled device time under 12 us, see launch_bound_problem): back-to-back calls
+    // only measure the host's launch rate, which is the same for every candidate, so up to six variants within
+    // 25 % (every variant seen, when the host is so slow that all per-call times are alike) are timed as replays
+    // of a captured graph on a private stream, i.e. by their device time.  The best of two such runs decides.
     void final_round() {
-        const bool launch_bound = best_us_ < 12.0;
-        const size_t max_finalists = launch_bound ? 6 : 3;
+        const bool launch_bound = launch_bound_;
+        const size_t max_finalists = launch_bound ? 4 : 3;
         const double window = launch_bound ? 1.25 : 1.02;
         std::stable_sort(seen_.begin(), seen_.end(),
                          [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
         std::vector<Config> finalists{best_};
+        auto add = [&](const Config &c) {      // one entry per kernel variant: its fastest setting so far
+            for (const Config &f : finalists)
+                if (f.kernel == c.kernel) return;
+            finalists.push_back(c);
+        };
         for (const auto &sc : seen_) {
             if (finalists.size() >= max_finalists || sc.first > best_us_ * window) break;
-            bool dup = false;   // one entry per kernel variant: its fastest setting so far
-            for (const Config &f : finalists) dup = dup || f.kernel == sc.second.kernel;
-            if (!dup) finalists.push_back(sc.second);
+            add(sc.second);
+        }
+        if (launch_bound) {
+            // the per-call times of a launch-bound problem say little (nothing at all on a slow host): the four
+            // variants the cost model ranks first are timed by their device time as well
+            std::vector<std::pair<double, Config>> by_model;
+            for (const auto &sc : seen_) by_model.emplace_back(heuristic_seconds(p_, sc.second), sc.second);
+            std::stable_sort(by_model.begin(), by_model.end(),
+                             [](const std::pair<double, Config> &a, const std::pair<double, Config> &b) { return a.first < b.first; });
+            for (size_t i = 0, taken = 0; i < by_model.size() && taken < 4; ++i) {
+                const size_t before = finalists.size();
+                add(by_model[i].second);
+                taken += finalists.size() > before || by_model[i].second.kernel == best_.kernel ? 1 : 0;
+            }
         }
         if (finalists.size() < 2) return;
 
@@ -1179,6 +1351,18 @@ class Tuner {
     double best_us_ = 1e300;
     std::string last_err_;
     std::vector<std::pair<double, Config>> seen_;   // every configuration measured, for the final round
+    bool launch_bound_ = false;
+    // result check
+    static constexpr size_t kPartialBytes = 16384;  // tail of the static scratch: 3 doubles per checking workgroup
+    float *ref_ = nullptr;
+    double *partial_ = nullptr;
+    int step_ = 1;
+    bool have_ref_ = false;
+    Config ref_cfg_;
+    std::string disagree_;
+    // test switches
+    double host_delay_us_ = 0;
+    bool spoil_reference_ = false;
 };
 
 // The packed, aligned problem of these sizes (no operands: for queries only).
@@ -1268,7 +1452,11 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k, const float *A
     if (e != hipSuccess) return fail(TG_ERR_HIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
     {
         std::lock_guard<std::mutex> lk(g_mutex);
+        read_env_once();
         g_cache[key_of(p)] = TunedEntry{best, best_us};
+        const char *path = getenv("TG_TUNE_CACHE");
+        if (path && *path && save_cache_locked(path) != TG_OK)
+            fprintf(stderr, "tgemm: could not write TG_TUNE_CACHE: %s\n", t_error.c_str());
     }
     t_last_config = spec_of(best) + copied;
     t_last_pending = false;
@@ -1379,6 +1567,13 @@ tg_status tg_candidate(int64_t batch, int64_t m, int64_t n, int64_t k, int idx, 
     return TG_OK;
 }
 
+int tg_tune_is_launch_bound(int64_t batch, int64_t m, int64_t n, int64_t k) {
+    Problem p;
+    if (query_problem(batch, m, n, k, &p) != TG_OK) return -1;
+    std::lock_guard<std::mutex> lk(g_mutex);
+    return launch_bound_problem(p, candidates(p, g_ws_bytes)) ? 1 : 0;
+}
+
 int tg_num_kernels(void) { return tg::num_kernels(); }
 
 tg_status tg_kernel_name(int idx, char *buf, size_t len) {
@@ -1391,64 +1586,14 @@ tg_status tg_kernel_name(int idx, char *buf, size_t len) {
 
 tg_status tg_save_tune_cache(const char *path) {
     if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
-    FILE *f = fopen(path, "w");
-    if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path + " for writing");
-    fprintf(f, "tgemm-tune-cache 5 gfx950\n");
     std::lock_guard<std::mutex> lk(g_mutex);
-    for (const auto &kv : g_cache) {
-        const ShapeKey &k = kv.first;
-        fprintf(f, "%lld %lld %lld %lld %d %s %d %d %d %d %d %d %.3f\n", (long long)std::get<0>(k), (long long)std::get<1>(k),
-                (long long)std::get<2>(k), (long long)std::get<3>(k), std::get<4>(k),
-                tg::kernel(kv.second.cfg.kernel).name, kv.second.cfg.splits, kv.second.cfg.group, kv.second.cfg.occ,
-                kv.second.cfg.persist, kv.second.cfg.tail, kv.second.cfg.tail_splits, kv.second.usec);
-    }
-    fclose(f);
-    return TG_OK;
+    return save_cache_locked(path);
 }
 
 tg_status tg_load_tune_cache(const char *path) {
     if (!path) return fail(TG_ERR_INVALID_ARG, "path is null");
-    FILE *f = fopen(path, "r");
-    if (!f) return fail(TG_ERR_INVALID_ARG, std::string("cannot open ") + path);
-    char head[64] = {0}, arch[32] = {0};
-    int ver = 0;
-    if (fscanf(f, "%63s %d %31s", head, &ver, arch) != 3 || strcmp(head, "tgemm-tune-cache") != 0 || (ver < 3 || ver > 5) ||
-        strcmp(arch, "gfx950") != 0) {
-        fclose(f);
-        return fail(TG_ERR_INVALID_ARG, "not a tgemm tune cache for gfx950 (version 3 to 5)");
-    }
     std::lock_guard<std::mutex> lk(g_mutex);
-    // one entry per line; version 4 added the two tail-split fields before the time, version 5 widened the
-    // layout class (the math mode moved from 4 x to 16 x)
-    char line[512];
-    while (fgets(line, sizeof line, f)) {
-        long long b, m, n, k;
-        int al, splits, group, occ, persist, tail = 0, tail_splits = 1;
-        char name[128];
-        double us;
-        int got;
-        if (ver == 3)
-            got = sscanf(line, "%lld %lld %lld %lld %d %127s %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group, &occ,
-                         &persist, &us) == 11;
-        else
-            got = sscanf(line, "%lld %lld %lld %lld %d %127s %d %d %d %d %d %d %lf", &b, &m, &n, &k, &al, name, &splits, &group,
-                         &occ, &persist, &tail, &tail_splits, &us) == 13;
-        if (!got) continue;
-        Config c;
-        c.kernel = find_kernel(name);
-        c.splits = splits;
-        c.group = group;
-        c.occ = occ;
-        c.persist = persist;
-        c.tail = tail;
-        c.tail_splits = tail_splits;
-        // entry from another build or a damaged line: ignore
-        if (c.kernel < 0 || splits < 1 || group < 1 || occ < 0 || persist < 0 || tail < 0 || tail_splits < 1) continue;
-        if (ver < 5) al = al % 4 + 16 * (al / 4);
-        g_cache[ShapeKey(b, m, n, k, al)] = TunedEntry{c, us};
-    }
-    fclose(f);
-    return TG_OK;
+    return load_cache_locked(path);
 }
 
 void tg_clear_tune_cache(void) {

@@ -512,6 +512,67 @@ hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, flo
     return hipGetLastError();
 }
 
+// The tuner's result check.  snapshot_rows_kernel copies every `step`-th row of every problem's C (rows 0, step,
+// 2*step, ...) into a packed reference buffer; compare_rows_kernel later compares the same rows of C with that
+// reference and leaves, per workgroup, the sums of (c - ref)^2 and of ref^2 and a count of non-finite values
+// (doubles; added up on the host, so no atomics are involved).
+__global__ void __launch_bounds__(256) snapshot_rows_kernel(const float *__restrict__ C, int64_t ldc, int64_t strideC, int batch,
+                                                            int m, int n, int step, float *__restrict__ ref) {
+    const int rows = (m + step - 1) / step;
+    const int64_t total = (int64_t)batch * rows * n;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = idx / ((int64_t)rows * n);
+        const int64_t rem = idx - b * rows * n;
+        const int64_t r = rem / n, j = rem - r * n;
+        ref[idx] = C[b * strideC + r * step * ldc + j];
+    }
+}
+
+__global__ void __launch_bounds__(256) compare_rows_kernel(const float *__restrict__ C, int64_t ldc, int64_t strideC, int batch,
+                                                           int m, int n, int step, const float *__restrict__ ref,
+                                                           double *__restrict__ partial) {
+    __shared__ double red[3][256];
+    const int rows = (m + step - 1) / step;
+    const int64_t total = (int64_t)batch * rows * n;
+    double d2 = 0.0, r2 = 0.0, bad = 0.0;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = idx / ((int64_t)rows * n);
+        const int64_t rem = idx - b * rows * n;
+        const int64_t r = rem / n, j = rem - r * n;
+        const float c = C[b * strideC + r * step * ldc + j], f = ref[idx];
+        if (!(__builtin_fabsf(c) <= 3.4e38f) || !(__builtin_fabsf(f) <= 3.4e38f)) {
+            bad += 1.0;
+        } else {
+            const double d = (double)c - (double)f;
+            d2 += d * d;
+            r2 += (double)f * (double)f;
+        }
+    }
+    red[0][threadIdx.x] = d2;
+    red[1][threadIdx.x] = r2;
+    red[2][threadIdx.x] = bad;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w)
+            for (int q = 0; q < 3; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        for (int q = 0; q < 3; ++q) partial[3 * blockIdx.x + q] = red[q][0];
+}
+
+hipError_t launch_snapshot_rows(const float *C, int64_t ldc, int64_t strideC, int batch, int m, int n, int step, float *ref,
+                                hipStream_t s) {
+    hipLaunchKernelGGL(snapshot_rows_kernel, dim3(kCheckBlocks), dim3(256), 0, s, C, ldc, strideC, batch, m, n, step, ref);
+    return hipGetLastError();
+}
+
+hipError_t launch_compare_rows(const float *C, int64_t ldc, int64_t strideC, int batch, int m, int n, int step, const float *ref,
+                               double *partial, hipStream_t s) {
+    hipLaunchKernelGGL(compare_rows_kernel, dim3(kCheckBlocks), dim3(256), 0, s, C, ldc, strideC, batch, m, n, step, ref, partial);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int64_t ld, int rows, int cols, hipStream_t s) {
     const int64_t tiles_r = ((int64_t)rows + 63) / 64, tiles_c = ((int64_t)cols + 63) / 64;
     if (rows <= 0 || cols <= 0) return hipSuccess;

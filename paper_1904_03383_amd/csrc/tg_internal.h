@@ -129,6 +129,14 @@ hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int
 // dst[r * ld + c] = src[r * rs + c] (r < rows, c < cols), +0.0 elsewhere on rows_out x ld: aligned, zero-padded copy.
 hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, float *dst, int64_t ld, int rows_out, hipStream_t s);
 
+// The tuner's result check: copy every step-th row of C into `ref` (packed), and compare the same rows of a later
+// result with it: partial[3*b + 0..2] of workgroup b = sum (c - ref)^2, sum ref^2, count of non-finite values.
+constexpr int kCheckBlocks = 512;
+hipError_t launch_snapshot_rows(const float *C, int64_t ldc, int64_t strideC, int batch, int m, int n, int step, float *ref,
+                                hipStream_t s);
+hipError_t launch_compare_rows(const float *C, int64_t ldc, int64_t strideC, int batch, int m, int n, int step, const float *ref,
+                               double *partial, hipStream_t s);
+
 // Device address, on the current device, of the library's fixed-size scratch array (static_scratch.hip).
 constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
 hipError_t static_scratch(void **ptr);

@@ -40,6 +40,8 @@ int main(void)
     CHECK(tg_workspace_bytes(1, 1024, 1024, 1024) > 0);
     CHECK(tg_strided_workspace_bytes(1024, 1024, 1024, 32, 1) >= tg_workspace_bytes(1, 1024, 1024, 1024) + 4u * 1024 * 1024);
     CHECK(tg_strided_workspace_bytes(1024, 1024, 1024, 0, 1) == 0);
+    CHECK(tg_tune_is_launch_bound(1, 256, 256, 32) == 1 && tg_tune_is_launch_bound(1, 4096, 4096, 4096) == 0);
+    CHECK(tg_tune_is_launch_bound(1, 0, 4, 4) == -1);
     CHECK(tg_num_kernels() > 0);
     CHECK(tg_kernel_name(0, buf, sizeof buf) == TG_OK && strlen(buf) > 0);
     CHECK(tg_force_config("no_such_kernel") == TG_ERR_INVALID_ARG);

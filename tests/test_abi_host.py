@@ -481,3 +481,45 @@ def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):
         tg.set_math(tg.MATH_FP32_MFMA)
         tg.clear_tune_cache()
     assert tg.get_config(1, 4096, 4096, 4096).startswith("d128x256x32_w64x128_acc2")
+
+
+def test_launch_bound_classification_comes_from_the_cost_model(lib):
+    """tg_tune times launch-bound problems as graph replays.  Which problems those are is a function of the sizes
+    alone (the cost model's device time of the first candidate, under 12 us), so no measured per-call time, however
+    inflated by a slow host or a profiler, can switch the device-time measurement off."""
+    assert tg.tune_is_launch_bound(1, 256, 256, 32)            # c1
+    assert tg.tune_is_launch_bound(512, 32, 32, 64)            # c3
+    assert not tg.tune_is_launch_bound(1, 1024, 1024, 1024)    # c2: 20 us of device time
+    assert not tg.tune_is_launch_bound(1, 4096, 4096, 128)
+    assert not tg.tune_is_launch_bound(1, 4096, 4096, 4096)
+    # the answer agrees with the model's own figure for the first candidate
+    for shape in [(1, 256, 256, 32), (512, 32, 32, 64), (1, 512, 512, 256), (1, 1024, 1024, 1024), (1, 2048, 2048, 64)]:
+        first = tg.candidates(*shape)[0]
+        assert tg.tune_is_launch_bound(*shape) == (first[2] - 4.0 < 12.0), (shape, first)
+    with pytest.raises(tg.TgemmError):
+        tg.tune_is_launch_bound(1, 0, 8, 8)
+
+
+def test_tune_cache_named_by_the_environment_is_loaded_at_first_use(tmp_path, may_spawn):
+    """TG_TUNE_CACHE is read once, at the first call that chooses a configuration: checked in a fresh process."""
+    import os
+    import subprocess
+    import sys
+    cache = tmp_path / "env_cache.txt"
+    cache.write_text("tgemm-tune-cache 5 gfx950\n1 1024 1024 1024 1 t128x128x16_w64x64 1 4 0 0 0 1 20.5\n")
+    code = ("import paper_1904_03383_amd as tg; print(tg.get_config(1, 1024, 1024, 1024)); "
+            "print(tg.get_config(1, 512, 512, 512))")
+    env = dict(os.environ, TG_TUNE_CACHE=str(cache), PYTHONPATH=str(ROOT))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stderr
+    lines = r.stdout.split()
+    assert lines[0] == "t128x128x16_w64x64:s1:g4" and not lines[1].startswith("t128x128x16_w64x64:s1:g4")
+    # a file that does not exist (yet) is not an error; a damaged one is reported and ignored
+    env["TG_TUNE_CACHE"] = str(tmp_path / "not_there.txt")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env)
+    assert r.returncode == 0 and "ignoring" not in r.stderr
+    bad = tmp_path / "bad.txt"
+    bad.write_text("garbage\n")
+    env["TG_TUNE_CACHE"] = str(bad)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env)
+    assert r.returncode == 0 and "ignoring TG_TUNE_CACHE" in r.stderr
