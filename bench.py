@@ -399,7 +399,10 @@ def main():
                     help="also time torch.matmul (the vendor BLAS behind PyTorch) on every GEMM workload, for context")
     ap.add_argument("--tune-reps", type=int, default=5)
     ap.add_argument("--tune-cache", default=None,
-                    help="file of tuned configurations: loaded (and tuning skipped) if it exists, else written")
+                    help="file of tuned configurations: loaded (and tuning skipped) if it exists, else written; "
+                         "default: the configurations shipped in paper_1904_03383_amd/tuned_gfx950.txt")
+    ap.add_argument("--tune", action="store_true",
+                    help="ignore the shipped configurations and tune every workload in this run (tg_tune)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -422,7 +425,10 @@ def main():
     ws = torch.empty(max(ws_bytes // 4, 4), dtype=torch.float32, device="cuda")
     tg.set_workspace(ws)
 
-    cache = pathlib.Path(args.tune_cache) if args.tune_cache else None
+    # The tile configurations are the ones tg_tune found on an MI355X, shipped with the package, so that every run
+    # times the same kernels as the committed profiles (profiles/ names them); --tune searches again.
+    shipped = ROOT / "paper_1904_03383_amd" / "tuned_gfx950.txt"
+    cache = pathlib.Path(args.tune_cache) if args.tune_cache else (shipped if shipped.exists() and not args.tune else None)
     if cache and cache.exists():
         tg.load_tune_cache(cache)
         args.tune_reps = 0
