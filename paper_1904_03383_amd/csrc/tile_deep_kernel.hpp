@@ -12,7 +12,9 @@
 // right after the barrier that publishes tile t+1 it issues the LDS reads of tile t+1 into one set (20 for
 // BK = 32) while it multiplies tile t out of the other, BK/2 MFMAs that depend on none of those reads.
 // BK = 64 halves the number of barriers per product at twice the registers and LDS (measured no gain at
-// 1024^3: 21.0 us against 20.0 us; kept for the tuner).  A deeper ring (NS = 3) measured 20.4 us.
+// 1024^3: 21.0 us against 20.0 us; kept for the tuner).  A deeper ring (NS = 3) measured 20.4 us, and two waves per
+// wave tile, each with half of every K tile and the sums joined through LDS at the end, 20.5 us (the two waves of a
+// SIMD then meet the same barrier together, so neither covers the other's wait).
 //
 // Order of one K tile t (stage t % NS holds it; its fragments are already in registers):
 //   wait: this wave's share of tile t+1 has landed, and its fragment reads of tile t have come back;
