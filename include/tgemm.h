@@ -90,12 +90,16 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
  * tiles ahead ("_ga" / "_gb"): no workspace and no separate pass are involved.  An element-strided
  * operand costs a cache-line request per element and tile that uses it, so the paper's case (1024^3,
  * csa = 32: 128 MiB of lines behind a 4 MiB operand) runs at about 2.5 times the plain product's time.
- * Problems those variants do not take (other k, a transposed operand off the 16-byte grid): when a
- * workspace of tg_strided_workspace_bytes(...) is set, each operand with a non-unit stride that more than
- * one tile row or column would fetch is first gathered into a packed row-major copy in the workspace (one
- * pass, every element fetched once) and the unit-stride kernels multiply the copies; tg_last_config()
- * then ends in "+packA", "+packB" or "+packAB".  Without that room the predicated kernels gather the
- * operands element by element.
+ * The other form: when a workspace of tg_strided_workspace_bytes(...) is set, each operand with a non-unit
+ * stride that more than one tile row or column would fetch can first be gathered into a packed row-major
+ * copy in the workspace (one pass, every element fetched once), and the unit-stride kernels multiply the
+ * copies; tg_last_config() then ends in "+packA", "+packB" or "+packAB".  It is used for problems the
+ * reading variants do not take (other k, a transposed operand off the 16-byte grid), and for
+ * element-strided operands when the cost model puts the two passes ahead of the gather, which it does once
+ * the strided operand is fetched over several rounds of tiles (2048 x 2048 x 512 at csa = 32: 64 us against
+ * 88 us; the paper's 1024^3 stays with the gather, 45 us against 50 us).  Transposed operands on the
+ * 16-byte grid are never packed.  Without room for the copies the reading variants are used wherever they
+ * apply, and the predicated kernels gather element by element otherwise.
  */
 tg_status tg_sgemm_strided(int64_t m, int64_t n, int64_t k,
                            const float *A, int64_t rsa, int64_t csa,

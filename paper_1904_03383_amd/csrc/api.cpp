@@ -608,24 +608,33 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     double t = launch + 1e-6 + per_cu * block_flops / cu_rate;
     // A gathered operand: every element costs a line request (its own cache line when the stride is large) in every tile
     // that fetches it.  Measured with hardware counters on 1024^3 with A at element stride 32: a CU's L1 keeps about a
-    // hundred line requests in flight at 450 cycles (L2 hit) to 1400 cycles (miss) each, which comes to about 1.1 ns
-    // per request and CU (64x64 tiles: 70 K requests per CU, 78 us; 128x128: 132 K, 164 us), and the distinct lines
-    // arrive from the fabric at about 3.2 TB/s however the tiles are cut (128 MiB of lines: 16x256 tiles 44 us,
-    // 32x128 tiles 50 us); the two overlap for the most part.
+    // hundred line requests in flight at 450 cycles (L2 hit) to 1400 cycles (miss) each, which comes to 1.1 - 1.5 ns
+    // per request and CU, and the distinct lines arrive from the fabric on top of that unless every workgroup is
+    // resident at once on tiles of few rows, where the two overlap for the most part.  Constants from sweeps of all
+    // gathering variants (us, stride 32: 1024^3 16x256 45, 32x128 51, 64x64 77, 128x128 162; 2048^3 431, 409, 794, 543;
+    // 4096x1024x1024 227, 229, 418, 288; 1024x4096x1024 167, 173, 269, 183; stride 16, 1536^3: 144, 125, 178, 179;
+    // stride 4, 3072^3: 674, 542, 605, 644).
     if (ki.amode == 2 || ki.bmode == 2) {
         const double line_a = std::min(4.0 * p.csa, 128.0), line_b = std::min(4.0 * p.csb, 128.0);
-        // line requests of one workgroup: per element of a gathered operand (four elements share a request when they
-        // share a 16-byte piece of a line), per 128 bytes of a plain one
-        const double req_a = ki.amode == 2 ? (double)ki.BM * p.k * (line_a / 128.0 > 0.25 ? 1.0 : 4.0 * line_a / 128.0) : (double)ki.BM * p.k / 32.0;
-        const double req_b = ki.bmode == 2 ? (double)ki.BN * p.k * (line_b / 128.0 > 0.25 ? 1.0 : 4.0 * line_b / 128.0) : (double)ki.BN * p.k / 32.0;
+        // line requests per element of a gathered operand: neighbours in one line share a request, down to a floor
+        // that the 4-byte loads themselves set (a quarter of a wave per cycle whatever the addresses)
+        auto per_element = [](double line) { return std::max(line / 128.0, line >= 32.0 ? 0.5 : (line >= 16.0 ? 0.35 : 0.25)); };
+        // line requests of one workgroup: per element of a gathered operand, per 128 bytes of a plain one
+        const double req_a = ki.amode == 2 ? (double)ki.BM * p.k * per_element(line_a) : (double)ki.BM * p.k / 32.0;
+        const double req_b = ki.bmode == 2 ? (double)ki.BN * p.k * per_element(line_b) : (double)ki.BN * p.k / 32.0;
         double lines = 0;
         if (ki.amode == 2) lines += p.batch * (double)p.m * p.k * line_a;
         if (ki.bmode == 2) lines += p.batch * (double)p.k * p.n * line_b;
-        // (16-row tiles: best while every workgroup is resident at once; with several rounds per CU they measured
-        // about twice the time per request, 2048^3 523 us against 434 us for 32x128 tiles)
-        const double per_req = ki.BM <= 16 && per_cu > 1 ? 2.4e-9 : 1.12e-9;
-        const double t_req = per_cu * (req_a + req_b) / splits * per_req, t_lines = lines / 3.2e12;
-        t = std::max(t, launch + 1e-6 + std::max(t_req, t_lines) + 0.25 * std::min(t_req, t_lines));
+        // tiles of few rows of a gathered A (and a plain B): more requests in flight per line of output, and their
+        // misses stream at nearly the memory rate
+        const bool few_rows = ki.amode == 2 && ki.bmode != 2 && ki.BM <= 32;
+        const double per_req = few_rows ? (ki.BM <= 16 ? 1.5e-9 : 1.15e-9) : 1.12e-9;
+        const double t_req = per_cu * (req_a + req_b) / splits * per_req, t_lines = lines / (few_rows ? 6e12 : 3.2e12);
+        const bool overlapped = per_cu <= 1 && few_rows;
+        const double t_gather = launch + 1e-6 + (overlapped ? std::max(t_req, t_lines) + 0.25 * std::min(t_req, t_lines) : t_req + t_lines);
+        // (over several rounds the waits of the gather and the products overlap only in part: 4096^3 at stride 8 with
+        // 128x256 tiles takes 1350 us where the product alone takes 975 us)
+        t = std::max(t, t_gather) + (overlapped ? 0.0 : 0.35 * std::min(t, t_gather));
     }
     if (splits > 1) t += 4e-6 + 2.0 * 4.0 * p.batch * splits * (double)p.m * p.n / (kPeakHbm * 0.5);
     if (ki.precut) t += 6e-6 + 10.0 * p.batch * ((double)p.m * p.k + (double)p.k * p.n) / (kPeakHbm * 0.6);
@@ -724,6 +733,17 @@ ShapeKey key_of(const Problem &p) {
     return ShapeKey(p.batch, p.m, p.n, p.k, layout + 16 * g_math);
 }
 
+// Element strides of gathered operands by the share of a cache line that an element costs: 0 not gathered or
+// unit stride, then strides 2, 3-4, 5-8, 9-16, 17 and more (a line per element).  8 x A's + B's.
+int stride_signature(const Problem &p) {
+    auto bucket = [](int64_t cs) {
+        int b = 0;
+        while (b < 5 && (int64_t(1) << b) < cs) ++b;
+        return b;
+    };
+    return 8 * (p.a_class() == 2 ? bucket(p.csa) : 0) + (p.b_class() == 2 ? bucket(p.csb) : 0);
+}
+
 // forced > tuned > heuristic.  Caller holds g_mutex.
 tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
     read_env_once();
@@ -745,7 +765,10 @@ tg_status choose(const Problem &p, size_t ws_bytes, Config *out) {
     }
     // Ranking the candidates costs some 10 us; the outcome depends only on the shape class and on
     // the workspace size, so it is kept (a call must not spend longer choosing than launching).
-    const auto hkey = std::make_pair(key_of(p), ws_bytes);
+    // (for a gathered operand the ranking also depends on how far apart its elements lie)
+    ShapeKey shape = key_of(p);
+    std::get<4>(shape) += 256 * stride_signature(p);
+    const auto hkey = std::make_pair(shape, ws_bytes);
     auto hit = g_heuristic_choice.find(hkey);
     if (hit != g_heuristic_choice.end() && config_valid(p, hit->second, ws_bytes)) {
         *out = hit->second;
@@ -880,6 +903,38 @@ tg_status align_operands(Problem &p, void *&ws, size_t &ws_bytes, hipStream_t s,
     return validate(p);   // the alignment class of the copies
 }
 
+// Time of the packing pass over a rows x cols operand (seconds): it reads whole lines along whichever axis has the
+// smaller stride (64 x 64 tiles through LDS), so an element costs min(4 x that stride, 128) bytes of line traffic,
+// and it writes 4 bytes.  Measured: 1024 x 1024 at element stride 32 (128 MiB of lines) 26 us.
+double pack_seconds(int64_t rows, int64_t cols, int64_t rs, int64_t cs) {
+    const double line = std::min<double>(4.0 * std::min(rs, cs), 128.0);
+    const double elems = (double)rows * cols;
+    return 2.5e-6 + std::max(elems * line / 5.5e12, elems * 8.0 / 4e12);
+}
+
+// A gathering variant asks for every element of the strided operand once per tile that uses it; the packing pass
+// asks once in all and leaves a unit-stride problem.  With room for the copies the cost model says which is faster
+// (1024^3 with A at element stride 32: fused 44 us, packed 50 us; 2048^3: fused 434 us, packed 230 us); the fused
+// form, which leaves the workspace alone, keeps a margin that covers the model's error on both.  Caller holds g_mutex.
+bool packing_is_faster(const Problem &p, const Config &fused_cfg, void *ws, size_t ws_bytes) {
+    const bool want_a = p.csa != 1 && p.n > kPackMinReuse, want_b = p.csb != 1 && p.m > kPackMinReuse;
+    const size_t need_a = want_a ? pack_bytes(p.m, p.k) : 0, need_b = want_b ? pack_bytes(p.k, p.n) : 0;
+    if (!(want_a || want_b) || ws == nullptr || need_a + need_b > ws_bytes) return false;
+    Problem q = p;
+    double t = 0;
+    if (want_a) {
+        t += pack_seconds(p.m, p.k, p.lda, p.csa);
+        q.A = static_cast<const float *>(ws); q.lda = pack_ld(p.k); q.csa = 1;
+    }
+    if (want_b) {
+        t += pack_seconds(p.k, p.n, p.ldb, p.csb);
+        q.B = reinterpret_cast<const float *>(static_cast<char *>(ws) + need_a); q.ldb = pack_ld(p.n); q.csb = 1;
+    }
+    Config c;
+    if (validate(q) != TG_OK || choose(q, ws_bytes - need_a - need_b, &c) != TG_OK) return false;
+    return t + heuristic_seconds(q, c) < 0.95 * heuristic_seconds(p, fused_cfg);
+}
+
 tg_status run(Problem &p, void *stream) {
     tg_status st = validate(p);
     if (st != TG_OK) return st;
@@ -914,6 +969,8 @@ tg_status run(Problem &p, void *stream) {
         if (g_forced) fused = config_valid(p, g_force_cfg, ws_bytes) && !tg::kernel(g_force_cfg.kernel).edge;
         else fused = choose(p, ws_bytes, &c0) == TG_OK && !tg::kernel(c0.kernel).edge &&
                      !(p.a_class() == 2 && p.lda < p.csa) && !(p.b_class() == 2 && p.ldb < p.csb);
+        if (fused && !g_forced && p.batch == 1 && (tg::kernel(c0.kernel).amode == 2 || tg::kernel(c0.kernel).bmode == 2))
+            fused = !packing_is_faster(p, c0, ws, ws_bytes);
     }
     if (!p.unit() && p.batch == 1 && !fused) {
         const bool want_a = p.csa != 1 && p.n > kPackMinReuse, want_b = p.csb != 1 && p.m > kPackMinReuse;

@@ -226,3 +226,25 @@ def test_workspace_too_small_for_packing_falls_back_to_gather():
     assert "+pack" not in tg.last_config()
     check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=True, what="no room to pack")
     del ws
+
+
+def test_with_room_to_pack_the_cost_model_picks_between_gathering_and_packing():
+    """A gather asks for each strided element once per tile that uses it, the packing pass once in all: with a
+    workspace the paper's 1024^3 (every workgroup resident at once on 16-row tiles) stays fused, while a product whose
+    strided operand is re-fetched over several rounds is packed first (2048x2048x512 at stride 32: 64 us packed
+    against 88 us gathered).  Both must still match the oracle on sampled rows."""
+    import torch
+    for (m, n, k, want_pack) in ((1024, 1024, 1024, False), (2048, 2048, 512, True)):
+        say(f"strided {m}x{n}x{k}, A element stride 32, workspace set: {'packed' if want_pack else 'fused'}")
+        ws = _with_workspace(m, n, k, 32, 1, extra=tg.workspace_bytes(1, m, n, k))
+        a_store = ig.small_int(691, (m, k * 32))
+        b = ig.small_int(692, (k, n))
+        c = _run(to_dev(a_store)[:, ::32], to_dev(b), m, n)
+        cfg = tg.last_config()
+        assert ("+packA" in cfg) == want_pack and "_edge" not in cfg, cfg
+        assert want_pack or "_ga" in cfg, cfg
+        rows = np.arange(0, m, 37)
+        a = np.ascontiguousarray(a_store[:, ::32])
+        check_against_oracle(c[rows], a[rows], b, exact=True, what=f"strided {m}x{n}x{k} with workspace")
+        tg.set_workspace(None)
+        del ws
