@@ -293,6 +293,9 @@ void tg_clear_tune_cache(void);
 
 const char *tg_status_string(tg_status s);
 const char *tg_last_error(void);
+/* 100 * major + minor.  The debug flavour of the library (libtgemm_poison.so, compiled with TG_POISON_LDS: every
+ * kernel overwrites an LDS stage with NaN once it has given it up and before it is refilled, so that a read of
+ * stale staging memory shows as NaN in C instead of as plausible numbers) reports 1000000 more. */
 int tg_version(void);
 
 #ifdef __cplusplus

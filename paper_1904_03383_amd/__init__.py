@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     last_config,
     library_path,
     load_library,
+    open_library,
+    poison_library_path,
     load_tune_cache,
     save_tune_cache,
     saxpy,

@@ -79,6 +79,25 @@ def load_library():
     return _lib
 
 
+def poison_library_path() -> pathlib.Path:
+    return _LIB_PATH.with_name("libtgemm_poison.so")
+
+
+def open_library(path):
+    """A second, independent instance of the library (e.g. the debug flavour at poison_library_path()), with the
+    argument types set; the functions of this module keep using the one load_library() returns."""
+    path = pathlib.Path(path)
+    if not path.exists():
+        raise FileNotFoundError(f"{path} is missing: build it with `python -m paper_1904_03383_amd.build --poison`")
+    import torch  # noqa: F401  (see load_library)
+    lib = ctypes.CDLL(str(path))
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
 def _check(status: int):
     if status != TG_OK:
         raise TgemmError(status, load_library().tg_last_error().decode())

@@ -2,6 +2,8 @@
 
     python -m paper_1904_03383_amd.build            # rebuild what changed
     python -m paper_1904_03383_amd.build --force    # rebuild everything
+    python -m paper_1904_03383_amd.build --poison   # also the debug flavour libtgemm_poison.so (TG_POISON_LDS:
+                                                    # LDS stages are overwritten with NaN once they are given up)
 """
 from __future__ import annotations
 
@@ -15,6 +17,8 @@ PKG = pathlib.Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libtgemm.so"
+OBJ_POISON = PKG / "_build_poison"
+LIB_POISON = PKG / "libtgemm_poison.so"
 
 ARCH = "gfx950"
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
@@ -39,24 +43,28 @@ def _headers_mtime() -> float:
     return max(h.stat().st_mtime for h in hdrs)
 
 
-def _compile(src: pathlib.Path, force: bool, hdr_mtime: float) -> pathlib.Path:
-    obj = OBJ / (src.name + ".o")
+def _compile(src: pathlib.Path, force: bool, hdr_mtime: float, objdir: pathlib.Path = OBJ, defines=()) -> pathlib.Path:
+    obj = objdir / (src.name + ".o")
     if not force and obj.exists() and obj.stat().st_mtime > max(src.stat().st_mtime, hdr_mtime):
         return obj
-    cmd = [_hipcc()] + HIP_FLAGS + ["-c", str(src), "-o", str(obj)]
+    cmd = [_hipcc()] + HIP_FLAGS + [f"-D{d}" for d in defines] + ["-c", str(src), "-o", str(obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"{' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
     return obj
 
 
-def build(force: bool = False, jobs: int | None = None) -> pathlib.Path:
-    OBJ.mkdir(exist_ok=True)
+def build(force: bool = False, jobs: int | None = None, poison: bool = False) -> pathlib.Path:
+    """Compile and link the library; with poison=True the debug flavour (its own object folder and file name)."""
+    objdir = OBJ_POISON if poison else OBJ
+    LIB = LIB_POISON if poison else globals()["LIB"]
+    defines = ("TG_POISON_LDS",) if poison else ()
+    objdir.mkdir(exist_ok=True)
     srcs = sources()
     hdr_mtime = _headers_mtime()
     jobs = jobs or min(8, len(srcs), os.cpu_count() or 1)
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force, hdr_mtime), srcs))
+        objs = list(ex.map(lambda s: _compile(s, force, hdr_mtime, objdir, defines), srcs))
     if force or not LIB.exists() or LIB.stat().st_mtime < max(o.stat().st_mtime for o in objs):
         # The library needs libamdhip64.so.7 by soname: inside a PyTorch process it binds to the
         # runtime torch has already loaded (the binding imports torch first; two HIP runtimes in
@@ -70,3 +78,5 @@ def build(force: bool = False, jobs: int | None = None) -> pathlib.Path:
 
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))
+    if "--poison" in sys.argv:
+        print(build(force="--force" in sys.argv, poison=True))

@@ -171,6 +171,7 @@ sgemm_tile_deep_kernel(const GemmParams p) {
     if (kt_begin < kt_end) {
         int to_issue = kt_end - kt_begin;           // tiles not requested yet
         auto issue = [&](int stage) {
+            TG_POISON_DIRECT(stage * A_STAGE, NS * A_STAGE + stage * B_STAGE);   // (debug flavour only)
 #pragma unroll
             for (int i = 0; i < A_LD; ++i)
                 direct_load<A_EL>(Ag + a_off[i], smem + stage * A_STAGE + (i * NWAVES + wave) * (64 * A_EL));

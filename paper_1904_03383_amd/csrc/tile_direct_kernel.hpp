@@ -107,8 +107,30 @@ template <>
 __device__ __forceinline__ void direct_load<1>(const float *g, float *l) {
     __builtin_amdgcn_global_load_lds((glb_float *)g, (lds_float *)l, 4, 0, 0);
 }
+// Debug flavour of the library (compiled with TG_POISON_LDS): before a stage is refilled, every lane overwrites
+// the slots that its own loads are about to fill with NaN and waits for those writes.  A kernel that read a
+// stage after giving it up, or before its loads had landed, then returns NaN instead of stale but plausible
+// numbers.
+#ifdef TG_POISON_LDS
+template <int EL>
+__device__ __forceinline__ void poison_slot(float *slot, int lane) {
+    if constexpr (EL == 4) *reinterpret_cast<f32x4 *>(slot + lane * 4) = (f32x4)(__builtin_nanf(""));
+    else slot[lane] = __builtin_nanf("");
+}
+#define TG_POISON_DIRECT(a_stage, b_stage)                                                               \
+    do {                                                                                                 \
+        _Pragma("unroll") for (int i_ = 0; i_ < A_LD; ++i_)                                              \
+            poison_slot<A_EL>(smem + (a_stage) + (i_ * NWAVES + wave) * (64 * A_EL), lane);              \
+        _Pragma("unroll") for (int i_ = 0; i_ < B_LD; ++i_)                                              \
+            poison_slot<B_EL>(smem + (b_stage) + (i_ * NWAVES + wave) * (64 * B_EL), lane);              \
+        __builtin_amdgcn_s_waitcnt(0xC07F);   /* lgkmcnt(0) */                                           \
+    } while (0)
+#else
+#define TG_POISON_DIRECT(a_stage, b_stage) do { } while (0)
+#endif
 #define TG_ISSUE_DIRECT_LOADS(a_stage, b_stage)                                                          \
     do {                                                                                                 \
+        TG_POISON_DIRECT(a_stage, b_stage);                                                              \
         _Pragma("unroll") for (int i_ = 0; i_ < A_LD; ++i_)                                              \
             direct_load<A_EL>(Ag + a_off[i_], smem + (a_stage) + (i_ * NWAVES + wave) * (64 * A_EL));    \
         _Pragma("unroll") for (int i_ = 0; i_ < B_LD; ++i_)                                              \

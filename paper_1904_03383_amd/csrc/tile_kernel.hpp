@@ -324,6 +324,23 @@ sgemm_tile_kernel(const GemmParams p) {
             for (int i = 0; i < B_LD; ++i)
                 *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = b_reg[i];
         };
+        // Debug flavour of the library (compiled with TG_POISON_LDS): once a stage has been given up (the barrier after
+        // which nobody reads it), every lane overwrites the slots it will fill next with NaN.  A kernel that read a stage
+        // after giving it up, or before it was complete, then returns NaN instead of stale but plausible numbers.
+        auto poison_lds = [&](int stage) {
+#ifdef TG_POISON_LDS
+            float *as = As + stage * A_STAGE;
+            float *bs = Bs + stage * B_STAGE;
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i)
+                *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = (f32x4)(__builtin_nanf(""));
+#pragma unroll
+            for (int i = 0; i < B_LD; ++i)
+                *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = (f32x4)(__builtin_nanf(""));
+#else
+            (void)stage;
+#endif
+        };
 
         f32x16 acc[RB][CB];
         f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
@@ -437,6 +454,7 @@ sgemm_tile_kernel(const GemmParams p) {
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 __syncthreads();
+                poison_lds(stage);            // (debug flavour only: nothing reads this stage any more)
                 read_frags(stage ^ 1, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 {

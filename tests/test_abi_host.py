@@ -273,7 +273,7 @@ def test_header_is_plain_c_and_every_entry_point_links(tmp_path, may_spawn):
 def test_product_package_does_not_import_the_oracle():
     pkg = ROOT / "paper_1904_03383_amd"
     for f in list(pkg.rglob("*.py")) + list(pkg.rglob("*.hip")) + list(pkg.rglob("*.cpp")) + list(pkg.rglob("*.h*")):
-        if "_build" in f.parts:
+        if any(part.startswith("_build") for part in f.parts):
             continue
         text = f.read_text()
         assert "oracle" not in text.lower().replace("oracle's tests", ""), f
@@ -523,3 +523,19 @@ def test_tune_cache_named_by_the_environment_is_loaded_at_first_use(tmp_path, ma
     env["TG_TUNE_CACHE"] = str(bad)
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env)
     assert r.returncode == 0 and "ignoring TG_TUNE_CACHE" in r.stderr
+
+
+def test_the_poison_flavour_really_writes_into_lds(tmp_path, may_spawn):
+    """The direct-to-LDS kernels fill LDS by loads only: the release build of one of them holds no LDS write at all,
+    the TG_POISON_LDS build must (the NaN it puts into every stage before the stage is refilled)."""
+    import subprocess
+    from paper_1904_03383_amd import build as lib_build
+    src = ROOT / "paper_1904_03383_amd" / "csrc" / "tile_inst_deep.hip"
+    counts = {}
+    for flavour, defs in (("release", []), ("poison", ["-DTG_POISON_LDS"])):
+        out = tmp_path / f"{flavour}.s"
+        cmd = [lib_build._hipcc()] + lib_build.HIP_FLAGS + defs + ["--cuda-device-only", "-S", str(src), "-o", str(out)]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+        counts[flavour] = len(re.findall(r"^\s*ds_write", out.read_text(), flags=re.M))
+    assert counts["release"] == 0 and counts["poison"] >= 8, counts
