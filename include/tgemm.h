@@ -30,6 +30,9 @@
  * Accuracy.  fp32 multiply-add on the matrix cores, fp32 accumulation; for k > 1024 the
  * running sums are folded into a second accumulator every 1024 terms so that the
  * relative Frobenius error stays below 1e-6 at k = 4096 (measured 5.7e-7; 1.15e-6 without).
+ * The first-level sums stay 1024 terms long however long k is; on normal(0,1) operands the error
+ * measures 5.8e-7 at k = 16384, 5.9e-7 at k = 65536 and 6.6e-7 at k = 262144, the longest k tested
+ * against the fp64 reference; the 1e-6 bar is stated for k <= 262144.
  */
 #ifndef TGEMM_H
 #define TGEMM_H
