@@ -457,13 +457,14 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
             if ((reinterpret_cast<uintptr_t>(p.C) & (4 * cb - 1)) || p.ldc % cb || (p.batch > 1 && p.strideC % cb))
                 return no("rows of C are not aligned for this variant's stores");
         }
-        // the fast variants address inside a tile with 32-bit element offsets
+        // the fast variants address inside a tile with 32-bit offsets
         {
             const int64_t span_a = ki.amode == 1 ? sat_add(sat_mul({ki.BK - 1, p.csa}), ki.BM)
                                                  : sat_add(sat_mul({ki.BM - 1, p.lda}), sat_mul({ki.BK, p.csa}));
             const int64_t span_b = ki.bmode == 1 ? sat_add(sat_mul({ki.BN - 1, p.csb}), ki.BK)
                                                  : sat_add(sat_mul({ki.BK - 1, p.ldb}), sat_mul({ki.BN, p.csb}));
-            if (span_a >= INT32_MAX || span_b >= INT32_MAX) return no("leading dimension too large for the exact-fit kernels");
+            // (element offsets inside a tile are kept as 32-bit byte offsets)
+            if (span_a >= (1 << 30) || span_b >= (1 << 30)) return no("leading dimension too large for the exact-fit kernels");
         }
         // (the bf16-piece kernels form 32-bit byte offsets)
         if (ki.pieces && ((ki.BM - 1) * p.lda + ki.BK >= (1 << 30) || (ki.BK - 1) * p.ldb + ki.BN >= (1 << 30)))

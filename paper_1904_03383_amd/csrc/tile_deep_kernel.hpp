@@ -40,6 +40,10 @@
 
 namespace tg {
 
+__device__ __forceinline__ const float *byte_offset(const float *base, unsigned bytes) {
+    return reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + bytes);
+}
+
 template <int BM, int BN, int BK, int NS, bool TWO_LEVEL, int AM, int BMD>
 __global__ void __launch_bounds__((BM / 32) * (BN / 32) * 64, (BK > 32 ? 1 : 2))
 sgemm_tile_deep_kernel(const GemmParams p) {
@@ -86,20 +90,22 @@ sgemm_tile_deep_kernel(const GemmParams p) {
 
     // Load slots as in the direct kernel: instruction i of a wave fills LDS floats [slot*256, slot*256+256)
     // of a stage (64 floats for a gathered operand), slot = i * NWAVES + wave; rows, columns and vectors past a
-    // ragged edge re-read the last valid one.
+    // ragged edge re-read the last valid one.  The per-lane offsets are kept in bytes, 32 bits wide (the host
+    // checks that a tile's footprint stays below 4 GiB), so that a load is the wave-uniform tile origin plus a
+    // 32-bit lane offset and needs no address arithmetic in the loop.
     unsigned a_off[A_LD], b_off[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         const int pos = ((i * NWAVES + wave) * 64 + lane) * A_EL;
         if constexpr (AM == 1) {                      // k-major stage: row pos / BM is one k, BM consecutive m
             const int c = pos % BM < p.m - 4 - m0 ? pos % BM : p.m - 4 - m0;
-            a_off[i] = (unsigned)(pos / BM) * (unsigned)p.csa + (unsigned)c;
+            a_off[i] = 4u * ((unsigned)(pos / BM) * (unsigned)p.csa + (unsigned)c);
         } else {
             const int row = pos / BK;
             const int q = (pos % BK) / 4;
             const int src_row = row < p.m - 1 - m0 ? row : p.m - 1 - m0;
             const int src_k = (q ^ a_swizzle<BK>(row)) * 4 + (AM == 2 ? pos % 4 : 0);
-            a_off[i] = (unsigned)src_row * (unsigned)p.lda + (unsigned)src_k * (AM == 2 ? (unsigned)p.csa : 1u);
+            a_off[i] = 4u * ((unsigned)src_row * (unsigned)p.lda + (unsigned)src_k * (AM == 2 ? (unsigned)p.csa : 1u));
         }
     }
 #pragma unroll
@@ -109,13 +115,13 @@ sgemm_tile_deep_kernel(const GemmParams p) {
             const int row = pos / BK;
             const int q = (pos % BK) / 4;
             const int src_col = row < p.n - 1 - n0 ? row : p.n - 1 - n0;
-            b_off[i] = (unsigned)src_col * (unsigned)p.csb + (unsigned)((q ^ a_swizzle<BK>(row)) * 4);
+            b_off[i] = 4u * ((unsigned)src_col * (unsigned)p.csb + (unsigned)((q ^ a_swizzle<BK>(row)) * 4));
         } else if constexpr (BMD == 2) {
             const int c = pos % BN < p.n - 1 - n0 ? pos % BN : p.n - 1 - n0;
-            b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c * (unsigned)p.csb;
+            b_off[i] = 4u * ((unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c * (unsigned)p.csb);
         } else {
             const int c = pos % BN < p.nb - 4 - n0 ? pos % BN : p.nb - 4 - n0;
-            b_off[i] = (unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c;
+            b_off[i] = 4u * ((unsigned)(pos / BN) * (unsigned)p.ldb + (unsigned)c);
         }
     }
 
@@ -174,10 +180,10 @@ sgemm_tile_deep_kernel(const GemmParams p) {
             TG_POISON_DIRECT(stage * A_STAGE, NS * A_STAGE + stage * B_STAGE);   // (debug flavour only)
 #pragma unroll
             for (int i = 0; i < A_LD; ++i)
-                direct_load<A_EL>(Ag + a_off[i], smem + stage * A_STAGE + (i * NWAVES + wave) * (64 * A_EL));
+                direct_load<A_EL>(byte_offset(Ag, a_off[i]), smem + stage * A_STAGE + (i * NWAVES + wave) * (64 * A_EL));
 #pragma unroll
             for (int i = 0; i < B_LD; ++i)
-                direct_load<B_EL>(Bg + b_off[i], smem + NS * A_STAGE + stage * B_STAGE + (i * NWAVES + wave) * (64 * B_EL));
+                direct_load<B_EL>(byte_offset(Bg, b_off[i]), smem + NS * A_STAGE + stage * B_STAGE + (i * NWAVES + wave) * (64 * B_EL));
             --to_issue;
             Ag += a_step;
             Bg += b_step;
@@ -200,14 +206,17 @@ sgemm_tile_deep_kernel(const GemmParams p) {
             if (NS > 2 && more) __builtin_amdgcn_s_waitcnt(kWaitSteady);
             else __builtin_amdgcn_s_waitcnt(kWaitAll);
             __builtin_amdgcn_s_barrier();
-            const int next = stage + 1 == NS ? 0 : stage + 1;
+            // (a ring of two: the stage of a tile is the register set of its fragments, a constant of this instance
+            // of the step, and every LDS address of the tile is a register plus an immediate)
+            const int cur_stage = NS == 2 ? cur : stage;
+            const int next = NS == 2 ? nxt : (stage + 1 == NS ? 0 : stage + 1);
             // the first MFMA goes ahead of everything: the loads of the tile ahead (a block of its own, not issued
             // once the K range is exhausted) and the LDS reads go out in its shadow and in that of the following
             // ones, which do not depend on them
             // (measured at 1024^3, alternating in one process: 20.0 us this way, 20.4 us with the loads ahead of the
             // first MFMA, 21.7 us for the kernel that fetches fragments octet by octet)
             mfma_range(cur, 0, 1);
-            if (more) issue(stage);
+            if (more) issue(cur_stage);
             read_tile(next, nxt);
             mfma_range(cur, 1, 4 * NO);
 #pragma unroll
