@@ -199,7 +199,7 @@ sgemm_tile_kernel(const GemmParams p) {
 
         // Tile origins are wave-uniform (kept in scalar registers and advanced per K tile); each
         // thread adds fixed offsets for its slots.  Fast variants use 32-bit offsets (the host
-        // checks that a tile spans fewer than 2^31 elements), predicated ones 64-bit.
+        // checks that a tile spans fewer than 2^30 elements), predicated ones 64-bit.
         // (csa, csb: element strides along k of A / along n of B, honoured by the predicated variants)
         const int64_t csa = EDGE ? p.csa : 1, csb = EDGE ? p.csb : 1;
         // Exact-fit variants with k not a multiple of BK: the k % BK leftover elements form K tile 0,
@@ -224,6 +224,7 @@ sgemm_tile_kernel(const GemmParams p) {
             // (in bounds; what they produce is never stored)
             const int r = EDGE ? a_row[i] : (a_row[i] < p.m - 1 - m0 ? a_row[i] : p.m - 1 - m0);
             a_off[i] = (off_t)r * (off_t)p.lda + (off_t)a_k[i] * (off_t)csa;
+            if constexpr (!EDGE) a_off[i] *= 4;      // exact-fit variants: in bytes (see at_bytes)
         }
     #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
@@ -233,9 +234,19 @@ sgemm_tile_kernel(const GemmParams p) {
             // ... and on a ragged last tile column, vectors past the end re-read the last one (n % 4 == 0)
             const int c = EDGE ? b_col[i] : (b_col[i] < p.nb - 4 - n0 ? b_col[i] : p.nb - 4 - n0);
             b_off[i] = (off_t)b_row[i] * (off_t)p.ldb + (off_t)c * (off_t)csb;
+            if constexpr (!EDGE) b_off[i] *= 4;
         }
 
         f32x4 a_reg[A_LD], b_reg[B_LD];
+        // Exact-fit variants keep the lane offsets in bytes, 32 bits wide (the host checks that a tile's footprint
+        // stays below 2^30 elements): a load is then the wave-uniform tile origin in scalar registers plus a 32-bit
+        // vector offset, with no 64-bit address arithmetic and no second register per offset.
+        // (The empty asm keeps the widening of the offset next to the load: hoisted out of the K loop as a 64-bit
+        // value it would hide from instruction selection that the offset is a 32-bit one.)
+        auto at_bytes = [](const float *base, unsigned bytes) {
+            asm volatile("" : "+v"(bytes));
+            return reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + bytes);
+        };
 
         // Fetch K tile `kt` (absolute index) into the staging registers.  The pointers then move
         // on to the next tile only if `advance` is set, so that asking again for the last tile of
@@ -250,9 +261,9 @@ sgemm_tile_kernel(const GemmParams p) {
             const bool full_k = EDGE && (kt + 1) * BK <= p.k;
     #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const float *src = Ag + a_off[i];
+                const float *src = EDGE ? Ag + a_off[i] : nullptr;
                 if constexpr (!EDGE) {
-                    a_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                    a_reg[i] = *at_bytes(Ag, (unsigned)a_off[i]);
                 } else if (full_m && full_k) {
                     if (vec_a) {
                         a_reg[i] = *reinterpret_cast<const f32x4_a4 *>(src);
@@ -273,9 +284,9 @@ sgemm_tile_kernel(const GemmParams p) {
             }
     #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const float *src = Bg + b_off[i];
+                const float *src = EDGE ? Bg + b_off[i] : nullptr;
                 if constexpr (!EDGE) {
-                    b_reg[i] = *reinterpret_cast<const f32x4 *>(src);
+                    b_reg[i] = *at_bytes(Bg, (unsigned)b_off[i]);
                 } else if (full_n && full_k) {
                     if (vec_b) {
                         b_reg[i] = *reinterpret_cast<const f32x4_a4 *>(src);
@@ -304,25 +315,29 @@ sgemm_tile_kernel(const GemmParams p) {
         auto load_global_tail = [&](bool advance) {
     #pragma unroll
             for (int i = 0; i < A_LD; ++i)
-                a_reg[i] = a_k[i] < tail ? *reinterpret_cast<const f32x4 *>(Ag + a_off[i]) : (f32x4)(0.0f);
+                a_reg[i] = a_k[i] < tail ? *at_bytes(Ag, (unsigned)a_off[i]) : (f32x4)(0.0f);
     #pragma unroll
             for (int i = 0; i < B_LD; ++i)
-                b_reg[i] = b_row[i] < tail ? *reinterpret_cast<const f32x4 *>(Bg + b_off[i]) : (f32x4)(0.0f);
+                b_reg[i] = b_row[i] < tail ? *at_bytes(Bg, (unsigned)b_off[i]) : (f32x4)(0.0f);
             if (advance) {
                 Ag += tail;
                 Bg += (int64_t)tail * p.ldb;
             }
         };
 
+        // (slot i of a thread lies a fixed number of rows below its slot 0: one address register per operand and
+        // immediates, instead of an address computed per slot and tile)
+        constexpr int A_SLOT_ROWS = NT / (BK / 4), B_SLOT_ROWS = NT / (BN / 4);
+        static_assert(NT % (BK / 4) == 0 && A_SLOT_ROWS % 8 == 0 && NT % (BN / 4) == 0, "slots of a thread are whole rows apart");
         auto store_lds = [&](int stage) {
-            float *as = As + stage * A_STAGE;
-            float *bs = Bs + stage * B_STAGE;
-    #pragma unroll
+            float *as = As + stage * A_STAGE + a_row[0] * LDA_S + a_k[0];
+            float *bs = Bs + stage * B_STAGE + b_row[0] * LDB_S + b_col[0];
+#pragma unroll
             for (int i = 0; i < A_LD; ++i)
-                *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
-    #pragma unroll
+                *reinterpret_cast<f32x4 *>(as + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
+#pragma unroll
             for (int i = 0; i < B_LD; ++i)
-                *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = b_reg[i];
+                *reinterpret_cast<f32x4 *>(bs + i * B_SLOT_ROWS * LDB_S) = b_reg[i];
         };
         // Debug flavour of the library (compiled with TG_POISON_LDS): once a stage has been given up (the barrier after
         // which nobody reads it), every lane overwrites the slots it will fill next with NaN.  A kernel that read a stage

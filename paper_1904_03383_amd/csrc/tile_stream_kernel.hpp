@@ -109,15 +109,19 @@ sgemm_tile_stream_kernel(const GemmParams p) {
         }
     };
 
+    // (slot i of a thread lies a fixed number of rows below its slot 0: one address register per operand and
+    // immediates, instead of an address computed per slot and tile)
+    constexpr int A_SLOT_ROWS = NT / (BK / 4), B_SLOT_ROWS = NT / (BN / 4);
+    static_assert(NT % (BK / 4) == 0 && A_SLOT_ROWS % 8 == 0 && NT % (BN / 4) == 0, "slots of a thread are whole rows apart");
     auto store_lds = [&](int stage) {
-        float *as = As + stage * A_STAGE;
-        float *bs = Bs + stage * B_STAGE;
+        float *as = As + stage * A_STAGE + a_row[0] * LDA_S + a_k[0];
+        float *bs = Bs + stage * B_STAGE + b_row[0] * LDB_S + b_col[0];
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
-            *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
+            *reinterpret_cast<f32x4 *>(as + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
-            *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = b_reg[i];
+            *reinterpret_cast<f32x4 *>(bs + i * B_SLOT_ROWS * LDB_S) = b_reg[i];
     };
     // Debug flavour of the library (compiled with TG_POISON_LDS): once a stage has been given up (the barrier after
     // which nobody reads it), every lane overwrites the slots it will fill next with NaN.  A kernel that read a stage
@@ -207,8 +211,8 @@ sgemm_tile_stream_kernel(const GemmParams p) {
         acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
     };
     auto lds_write_one = [&](int st, int i) {
-        if (i < A_LD) *reinterpret_cast<f32x4 *>(As + st * A_STAGE + a_row[i] * LDA_S + a_k[i]) = a_reg[i];
-        else *reinterpret_cast<f32x4 *>(Bs + st * B_STAGE + b_row[i - A_LD] * LDB_S + b_col[i - A_LD]) = b_reg[i - A_LD];
+        if (i < A_LD) *reinterpret_cast<f32x4 *>(As + st * A_STAGE + a_row[0] * LDA_S + a_k[0] + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
+        else *reinterpret_cast<f32x4 *>(Bs + st * B_STAGE + b_row[0] * LDB_S + b_col[0] + (i - A_LD) * B_SLOT_ROWS * LDB_S) = b_reg[i - A_LD];
     };
     auto load_one = [&](int i) {
         if (i < A_LD) a_reg[i] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i]);
