@@ -91,6 +91,16 @@ __device__ __forceinline__ void store_lane(float *dst, V o, bool lane_vec, int c
 // and r+4 do not (20*4 = 80 = 16 mod 32).  So within each group of eight rows the slots take the rows in
 // the order 0, 4, 1, 5, 2, 6, 3, 7.  No padding alone can do this: the second row would have to start 16
 // banks after the first, i.e. at a pitch of 16 mod 32, where the fragment reads of 8 rows collide.
+// Address of a 16-byte vector at a 32-bit byte offset from a wave-uniform origin.  The exact-fit variants keep their
+// lane offsets that way (the host checks that a tile's footprint stays below 2^30 elements): a load is then the tile
+// origin in scalar registers plus a 32-bit vector offset, with no 64-bit address arithmetic and no second register
+// per offset.  (The empty asm keeps the widening of the offset next to the load: hoisted out of the K loop as a
+// 64-bit value it would hide from instruction selection that the offset is a 32-bit one.)
+__device__ __forceinline__ const f32x4 *at_bytes(const float *base, unsigned bytes) {
+    asm volatile("" : "+v"(bytes));
+    return reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + bytes);
+}
+
 template <int BK>
 __device__ __forceinline__ int a_slot_row(int f) {
     const int r = f / (BK / 4);
@@ -238,16 +248,6 @@ sgemm_tile_kernel(const GemmParams p) {
         }
 
         f32x4 a_reg[A_LD], b_reg[B_LD];
-        // Exact-fit variants keep the lane offsets in bytes, 32 bits wide (the host checks that a tile's footprint
-        // stays below 2^30 elements): a load is then the wave-uniform tile origin in scalar registers plus a 32-bit
-        // vector offset, with no 64-bit address arithmetic and no second register per offset.
-        // (The empty asm keeps the widening of the offset next to the load: hoisted out of the K loop as a 64-bit
-        // value it would hide from instruction selection that the offset is a 32-bit one.)
-        auto at_bytes = [](const float *base, unsigned bytes) {
-            asm volatile("" : "+v"(bytes));
-            return reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + bytes);
-        };
-
         // Fetch K tile `kt` (absolute index) into the staging registers.  The pointers then move
         // on to the next tile only if `advance` is set, so that asking again for the last tile of
         // the range (when nothing is left to prefetch) stays inside the matrices.

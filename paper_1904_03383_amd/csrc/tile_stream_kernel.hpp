@@ -58,14 +58,14 @@ sgemm_tile_stream_kernel(const GemmParams p) {
         const int f = tid + i * NT;
         a_row[i] = a_slot_row<BK>(f);
         a_k[i] = (f % (BK / 4)) * 4;
-        a_off[i] = (unsigned)a_row[i] * (unsigned)p.lda + (unsigned)a_k[i];
+        a_off[i] = 4u * ((unsigned)a_row[i] * (unsigned)p.lda + (unsigned)a_k[i]);     // in bytes (see at_bytes)
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
         const int f = tid + i * NT;
         b_row[i] = f / (BN / 4);
         b_col[i] = (f % (BN / 4)) * 4;
-        b_off[i] = (unsigned)b_row[i] * (unsigned)p.ldb + (unsigned)b_col[i];
+        b_off[i] = 4u * ((unsigned)b_row[i] * (unsigned)p.ldb + (unsigned)b_col[i]);
     }
 
     // K range of a work item (slice = problem * splits + split).
@@ -96,9 +96,9 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     // and keeps the loop body uniform).
     auto load_next = [&]() {
 #pragma unroll
-        for (int i = 0; i < A_LD; ++i) a_reg[i] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i]);
+        for (int i = 0; i < A_LD; ++i) a_reg[i] = *at_bytes(Ag, a_off[i]);
 #pragma unroll
-        for (int i = 0; i < B_LD; ++i) b_reg[i] = *reinterpret_cast<const f32x4 *>(Bg + b_off[i]);
+        for (int i = 0; i < B_LD; ++i) b_reg[i] = *at_bytes(Bg, b_off[i]);
         if (ld_left > 1) {
             --ld_left;
             Ag += BK;
@@ -215,8 +215,8 @@ sgemm_tile_stream_kernel(const GemmParams p) {
         else *reinterpret_cast<f32x4 *>(Bs + st * B_STAGE + b_row[0] * LDB_S + b_col[0] + (i - A_LD) * B_SLOT_ROWS * LDB_S) = b_reg[i - A_LD];
     };
     auto load_one = [&](int i) {
-        if (i < A_LD) a_reg[i] = *reinterpret_cast<const f32x4 *>(Ag + a_off[i]);
-        else b_reg[i - A_LD] = *reinterpret_cast<const f32x4 *>(Bg + b_off[i - A_LD]);
+        if (i < A_LD) a_reg[i] = *at_bytes(Ag, a_off[i]);
+        else b_reg[i - A_LD] = *at_bytes(Bg, b_off[i - A_LD]);
     };
     auto advance_cursor = [&]() {
         if (ld_left > 1) {
