@@ -158,9 +158,19 @@ inline hipError_t allow_full_lds(const void *kernel, std::atomic<uint64_t> &done
 constexpr int kLdsPadA = 4;  // floats added to each A row in LDS (conflict-free b128 reads)
 constexpr int kLdsPadB = 8;  // floats added to each B row in LDS
 
+// The two LDS stages of the register-staged kernels: A then B of a stage side by side, the second stage right
+// after the first.
+template <int BM, int BN, int BK>
+constexpr int tile_stage_floats() {
+    return BM * (BK + kLdsPadA) + BK * (BN + kLdsPadB);
+}
+template <int BM, int BN, int BK>
+constexpr int tile_stage_pitch() {
+    return tile_stage_floats<BM, BN, BK>();
+}
 template <int BM, int BN, int BK, int WM, int WN>
 constexpr int tile_lds_bytes() {
-    return 2 * (BM * (BK + kLdsPadA) + BK * (BN + kLdsPadB)) * (int)sizeof(float);
+    return (tile_stage_pitch<BM, BN, BK>() + tile_stage_floats<BM, BN, BK>()) * (int)sizeof(float);
 }
 
 }  // namespace tg

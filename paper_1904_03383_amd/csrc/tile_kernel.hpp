@@ -184,9 +184,15 @@ sgemm_tile_kernel(const GemmParams p) {
                   "tile loads must divide evenly over the workgroup");
     typedef typename vec_of<CB>::type bvec;
 
+    // LDS: stage 0 at float 0, stage 1 at float PITCH; inside a stage A, then B.  Every LDS address a thread uses
+    // is kept as a 32-bit LDS address into the stage it currently refers to and moves to the other stage with one
+    // addition per K tile (of +-PITCH, a scalar that changes sign per tile): no stage index, no multiplication, no
+    // address rebuilt per access.
+    constexpr unsigned PITCH_BYTES = 4u * tile_stage_pitch<BM, BN, BK>();
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    float *As = smem;
-    float *Bs = smem + 2 * A_STAGE;
+    typedef __attribute__((address_space(3))) float lds_space_float;
+    const unsigned lds_base = (unsigned)(uintptr_t)(lds_space_float *)smem;
+    auto lds = [](unsigned addr) { return (float *)(lds_space_float *)(uintptr_t)addr; };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -329,9 +335,11 @@ sgemm_tile_kernel(const GemmParams p) {
         // immediates, instead of an address computed per slot and tile)
         constexpr int A_SLOT_ROWS = NT / (BK / 4), B_SLOT_ROWS = NT / (BN / 4);
         static_assert(NT % (BK / 4) == 0 && A_SLOT_ROWS % 8 == 0 && NT % (BN / 4) == 0, "slots of a thread are whole rows apart");
-        auto store_lds = [&](int stage) {
-            float *as = As + stage * A_STAGE + a_row[0] * LDA_S + a_k[0];
-            float *bs = Bs + stage * B_STAGE + b_row[0] * LDB_S + b_col[0];
+        unsigned wr_a = lds_base + 4u * (a_row[0] * LDA_S + a_k[0]);      // this thread's slot 0 in the stage being filled
+        unsigned wr_b = lds_base + 4u * (A_STAGE + b_row[0] * LDB_S + b_col[0]);
+        auto store_lds = [&]() {
+            float *as = lds(wr_a);
+            float *bs = lds(wr_b);
 #pragma unroll
             for (int i = 0; i < A_LD; ++i)
                 *reinterpret_cast<f32x4 *>(as + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
@@ -342,18 +350,16 @@ sgemm_tile_kernel(const GemmParams p) {
         // Debug flavour of the library (compiled with TG_POISON_LDS): once a stage has been given up (the barrier after
         // which nobody reads it), every lane overwrites the slots it will fill next with NaN.  A kernel that read a stage
         // after giving it up, or before it was complete, then returns NaN instead of stale but plausible numbers.
-        auto poison_lds = [&](int stage) {
+        auto poison_lds = [&]() {
 #ifdef TG_POISON_LDS
-            float *as = As + stage * A_STAGE;
-            float *bs = Bs + stage * B_STAGE;
+            float *as = lds(wr_a);
+            float *bs = lds(wr_b);
 #pragma unroll
             for (int i = 0; i < A_LD; ++i)
-                *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = (f32x4)(__builtin_nanf(""));
+                *reinterpret_cast<f32x4 *>(as + i * A_SLOT_ROWS * LDA_S) = (f32x4)(__builtin_nanf(""));
 #pragma unroll
             for (int i = 0; i < B_LD; ++i)
-                *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = (f32x4)(__builtin_nanf(""));
-#else
-            (void)stage;
+                *reinterpret_cast<f32x4 *>(bs + i * B_SLOT_ROWS * LDB_S) = (f32x4)(__builtin_nanf(""));
 #endif
         };
 
@@ -367,8 +373,16 @@ sgemm_tile_kernel(const GemmParams p) {
                 if constexpr (TWO_LEVEL) total[rb][cb] = (f32x16)(0.0f);
             }
 
-        const int a_frag_off = (wm * WM + li) * LDA_S + h * 4;
-        const int b_frag_off = (h * 4) * LDB_S + wn * WN + li * CB;
+        unsigned rd_a = lds_base + 4u * ((wm * WM + li) * LDA_S + h * 4); // this lane's fragments in the stage being multiplied
+        unsigned rd_b = lds_base + 4u * (A_STAGE + (h * 4) * LDB_S + wn * WN + li * CB);
+        unsigned to_other = PITCH_BYTES;            // what takes the read addresses to the other stage (and the write addresses back)
+        auto other_stage = [&]() {
+            rd_a += to_other;
+            rd_b += to_other;
+            to_other = 0u - to_other;
+            wr_a += to_other;
+            wr_b += to_other;
+        };
 
         // Operand fragments of two consecutive k-octets: while the MFMAs of octet o run from
         // one set, the LDS reads of octet o+1 fill the other.
@@ -377,9 +391,9 @@ sgemm_tile_kernel(const GemmParams p) {
         f32x4 a_frag[2][RB];
         bvec b_frag[2][4];
 
-        auto read_frags = [&](int stage, int o, int set) {
-            const float *as = As + stage * A_STAGE + a_frag_off + o * 8;
-            const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * LDB_S;
+        auto read_frags = [&](int o, int set) {
+            const float *as = lds(rd_a) + o * 8;
+            const float *bs = lds(rd_b) + o * 8 * LDB_S;
     #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S);
@@ -440,28 +454,29 @@ sgemm_tile_kernel(const GemmParams p) {
             const int last = kt_end - 1;
             if (!EDGE && tail != 0 && kt_begin == 0) load_global_tail(kt_begin < last);
             else load_global(kt_begin, kt_begin < last);
-            store_lds(0);
+            store_lds();                  // stage 0
             __syncthreads();
-            read_frags(0, 0, 0);
+            read_frags(0, 0);
+            wr_a += PITCH_BYTES;          // the next tile is staged in stage 1
+            wr_b += PITCH_BYTES;
             {
                 const int nl = kt_begin + 1 < last ? kt_begin + 1 : last;
                 load_global(nl, nl < last);
             }
-            int stage = 0;
             for (int kt = kt_begin; kt < last; ++kt) {
                 maybe_flush();                // (at the top, so the loop body below stays one block)
                 __builtin_amdgcn_sched_barrier(0);
     #pragma unroll
                 for (int o = 0; o < NO - 2; ++o) {
-                    read_frags(stage, o + 1, (o + 1) & 1);
+                    read_frags(o + 1, (o + 1) & 1);
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_octet(o & 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                read_frags(stage, NO - 1, (NO - 1) & 1);
+                read_frags(NO - 1, (NO - 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_octet((NO - 2) & 1);
-                store_lds(stage ^ 1);
+                store_lds();
     #pragma unroll
                 for (int i = 0; i < N_ST; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
@@ -469,8 +484,9 @@ sgemm_tile_kernel(const GemmParams p) {
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 __syncthreads();
-                poison_lds(stage);            // (debug flavour only: nothing reads this stage any more)
-                read_frags(stage ^ 1, 0, 0);
+                other_stage();                // the stage just completed is multiplied next, the one just left is filled next
+                poison_lds();                 // (debug flavour only: nothing reads that stage any more)
+                read_frags(0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 {
                     const int nl = kt + 2 < last ? kt + 2 : last;
@@ -483,11 +499,10 @@ sgemm_tile_kernel(const GemmParams p) {
                     __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                stage ^= 1;
             }
     #pragma unroll
             for (int o = 0; o < NO - 1; ++o) {
-                read_frags(stage, o + 1, (o + 1) & 1);
+                read_frags(o + 1, (o + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_octet(o & 1);
                 __builtin_amdgcn_sched_barrier(0);
