@@ -37,9 +37,13 @@ sgemm_tile_stream_kernel(const GemmParams p) {
                   "tile loads must divide evenly over the workgroup");
     typedef typename vec_of<CB>::type bvec;
 
+    // LDS as in tile_kernel.hpp: stage 0 then stage 1, A then B inside a stage; every LDS address of a thread is a
+    // running 32-bit LDS address that one addition per K tile moves to the other stage.
+    constexpr unsigned PITCH_BYTES = 4u * tile_stage_pitch<BM, BN, BK>();
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    float *As = smem;
-    float *Bs = smem + 2 * A_STAGE;
+    typedef __attribute__((address_space(3))) float lds_space_float;
+    const unsigned lds_base = (unsigned)(uintptr_t)(lds_space_float *)smem;
+    auto lds = [](unsigned addr) { return (float *)(lds_space_float *)(uintptr_t)addr; };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -113,9 +117,11 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     // immediates, instead of an address computed per slot and tile)
     constexpr int A_SLOT_ROWS = NT / (BK / 4), B_SLOT_ROWS = NT / (BN / 4);
     static_assert(NT % (BK / 4) == 0 && A_SLOT_ROWS % 8 == 0 && NT % (BN / 4) == 0, "slots of a thread are whole rows apart");
-    auto store_lds = [&](int stage) {
-        float *as = As + stage * A_STAGE + a_row[0] * LDA_S + a_k[0];
-        float *bs = Bs + stage * B_STAGE + b_row[0] * LDB_S + b_col[0];
+    unsigned wr_a = lds_base + 4u * (a_row[0] * LDA_S + a_k[0]);      // this thread's slot 0 in the stage being filled
+    unsigned wr_b = lds_base + 4u * (A_STAGE + b_row[0] * LDB_S + b_col[0]);
+    auto store_lds = [&]() {
+        float *as = lds(wr_a);
+        float *bs = lds(wr_b);
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
             *reinterpret_cast<f32x4 *>(as + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
@@ -126,32 +132,38 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     // Debug flavour of the library (compiled with TG_POISON_LDS): once a stage has been given up (the barrier after
     // which nobody reads it), every lane overwrites the slots it will fill next with NaN.  A kernel that read a stage
     // after giving it up, or before it was complete, then returns NaN instead of stale but plausible numbers.
-    auto poison_lds = [&](int stage) {
+    auto poison_lds = [&]() {
 #ifdef TG_POISON_LDS
-        float *as = As + stage * A_STAGE;
-        float *bs = Bs + stage * B_STAGE;
+        float *as = lds(wr_a);
+        float *bs = lds(wr_b);
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
-            *reinterpret_cast<f32x4 *>(as + a_row[i] * LDA_S + a_k[i]) = (f32x4)(__builtin_nanf(""));
+            *reinterpret_cast<f32x4 *>(as + i * A_SLOT_ROWS * LDA_S) = (f32x4)(__builtin_nanf(""));
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
-            *reinterpret_cast<f32x4 *>(bs + b_row[i] * LDB_S + b_col[i]) = (f32x4)(__builtin_nanf(""));
-#else
-        (void)stage;
+            *reinterpret_cast<f32x4 *>(bs + i * B_SLOT_ROWS * LDB_S) = (f32x4)(__builtin_nanf(""));
 #endif
     };
 
     // ---- compute side -------------------------------------------------------------------------
     f32x16 acc[RB][CB];
     f32x16 total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? CB : 1];
-    const int a_frag_off = (wm * WM + li) * LDA_S + h * 4;
-    const int b_frag_off = (h * 4) * LDB_S + wn * WN + li * CB;
+    unsigned rd_a = lds_base + 4u * ((wm * WM + li) * LDA_S + h * 4); // this lane's fragments in the stage being multiplied
+    unsigned rd_b = lds_base + 4u * (A_STAGE + (h * 4) * LDB_S + wn * WN + li * CB);
+    unsigned to_other = PITCH_BYTES;            // what takes the read addresses to the other stage (and the write addresses back)
+    auto other_stage = [&]() {
+        rd_a += to_other;
+        rd_b += to_other;
+        to_other = 0u - to_other;
+        wr_a += to_other;
+        wr_b += to_other;
+    };
     f32x4 a_frag[2][RB];
     bvec b_frag[2][4];
 
-    auto read_frags = [&](int stage, int o, int set) {
-        const float *as = As + stage * A_STAGE + a_frag_off + o * 8;
-        const float *bs = Bs + stage * B_STAGE + b_frag_off + o * 8 * LDB_S;
+    auto read_frags = [&](int o, int set) {
+        const float *as = lds(rd_a) + o * 8;
+        const float *bs = lds(rd_b) + o * 8 * LDB_S;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
             a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(as + rb * 32 * LDA_S);
@@ -203,16 +215,15 @@ sgemm_tile_stream_kernel(const GemmParams p) {
 
     // One K tile of the stream (see tile_kernel.hpp for the order of operations inside a tile).  With the drain
     // tag the stores of the waiting tile go out between its MFMAs, half with the LDS writes, half with the loads.
-    int stage = 0;
     // Single steps of a K tile, for the drain form below, where the order is written out instruction by instruction
     // (a sched_group_barrier pattern cannot place the stores: their address arithmetic is not in its vocabulary).
     auto mfma_one = [&](int set, int j) {   // j enumerates (t, rb, cb) in the order of mfma_octet
         const int t = j / (RB * CB), rb = (j / CB) % RB, cb = j % CB;
         acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
     };
-    auto lds_write_one = [&](int st, int i) {
-        if (i < A_LD) *reinterpret_cast<f32x4 *>(As + st * A_STAGE + a_row[0] * LDA_S + a_k[0] + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
-        else *reinterpret_cast<f32x4 *>(Bs + st * B_STAGE + b_row[0] * LDB_S + b_col[0] + (i - A_LD) * B_SLOT_ROWS * LDB_S) = b_reg[i - A_LD];
+    auto lds_write_one = [&](int i) {
+        if (i < A_LD) *reinterpret_cast<f32x4 *>(lds(wr_a) + i * A_SLOT_ROWS * LDA_S) = a_reg[i];
+        else *reinterpret_cast<f32x4 *>(lds(wr_b) + (i - A_LD) * B_SLOT_ROWS * LDB_S) = b_reg[i - A_LD];
     };
     auto load_one = [&](int i) {
         if (i < A_LD) a_reg[i] = *at_bytes(Ag, a_off[i]);
@@ -247,27 +258,27 @@ sgemm_tile_stream_kernel(const GemmParams p) {
         constexpr bool DRAIN = decltype(drain_tag)::value;
 #pragma unroll
         for (int o = 0; o < NO - 2; ++o) {
-            read_frags(stage, o + 1, (o + 1) & 1);
+            read_frags(o + 1, (o + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
             mfma_octet(o & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        read_frags(stage, NO - 1, (NO - 1) & 1);
+        read_frags(NO - 1, (NO - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (DRAIN) {
 #pragma unroll
             for (int j = 0; j < N_MFMA; ++j) {
                 mfma_one((NO - 2) & 1, j);
-                if (j % MFMA_PER_ST == MFMA_PER_ST - 1 && j / MFMA_PER_ST < N_ST) lds_write_one(stage ^ 1, j / MFMA_PER_ST);
+                if (j % MFMA_PER_ST == MFMA_PER_ST - 1 && j / MFMA_PER_ST < N_ST) lds_write_one(j / MFMA_PER_ST);
 #pragma unroll
                 for (int q = j * PART_STORES / N_MFMA; q < (j + 1) * PART_STORES / N_MFMA; ++q) store_prev_one(0, q);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int i = N_MFMA / MFMA_PER_ST; i < N_ST; ++i) lds_write_one(stage ^ 1, i);
+            for (int i = N_MFMA / MFMA_PER_ST; i < N_ST; ++i) lds_write_one(i);
         } else {
             mfma_octet((NO - 2) & 1);
-            store_lds(stage ^ 1);
+            store_lds();
 #pragma unroll
             for (int i = 0; i < N_ST; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_ST, 0);   // MFMA
@@ -276,8 +287,9 @@ sgemm_tile_stream_kernel(const GemmParams p) {
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        poison_lds(stage);                    // (debug flavour only: nothing reads this stage any more)
-        read_frags(stage ^ 1, 0, 0);
+        other_stage();                        // the stage just completed is multiplied next, the one just left is filled next
+        poison_lds();                         // (debug flavour only: nothing reads that stage any more)
+        read_frags(0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (DRAIN) {
 #pragma unroll
@@ -306,9 +318,11 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     // ---- start of the stream --------------------------------------------------------------------
     seek(ld_work);
     load_next();
-    store_lds(0);
+    store_lds();                              // stage 0
     __syncthreads();
-    read_frags(0, 0, 0);
+    read_frags(0, 0);
+    wr_a += PITCH_BYTES;                      // the next tile is staged in stage 1
+    wr_b += PITCH_BYTES;
     load_next();
 
     for (unsigned work = blockIdx.x; work < total_work; work += step) {
@@ -349,7 +363,6 @@ sgemm_tile_stream_kernel(const GemmParams p) {
             } else {
                 tile_body(std::false_type());
             }
-            stage ^= 1;
         }
         if constexpr (TWO_LEVEL) {
 #pragma unroll
