@@ -40,10 +40,6 @@
 
 namespace tg {
 
-__device__ __forceinline__ const float *byte_offset(const float *base, unsigned bytes) {
-    return reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + bytes);
-}
-
 template <int BM, int BN, int BK, int NS, bool TWO_LEVEL, int AM, int BMD>
 __global__ void __launch_bounds__((BM / 32) * (BN / 32) * 64, (BK > 32 ? 1 : 2))
 sgemm_tile_deep_kernel(const GemmParams p) {
