@@ -94,9 +94,10 @@ __device__ __forceinline__ void store_lane(float *dst, V o, bool lane_vec, int c
 // Address of a 16-byte vector at a 32-bit byte offset from a wave-uniform origin.  The exact-fit variants keep their
 // lane offsets that way (the host checks that a tile's footprint stays below 2^30 elements): a load is then the tile
 // origin in scalar registers plus a 32-bit vector offset, with no 64-bit address arithmetic and no second register
-// per offset.  (The empty asm keeps the widening of the offset next to the load: hoisted out of the K loop as a
-// 64-bit value it would hide from instruction selection that the offset is a 32-bit one.)
-__device__ __forceinline__ const f32x4 *at_bytes(const float *base, unsigned bytes) {
+// per offset.  (The empty asm passes the offset through unchanged, in place: it keeps the widening of the offset
+// next to the load; hoisted out of the K loop as a 64-bit value it would hide from instruction selection that the
+// offset is a 32-bit one.)
+__device__ __forceinline__ const f32x4 *at_bytes(const float *base, unsigned &bytes) {
     asm volatile("" : "+v"(bytes));
     return reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + bytes);
 }
@@ -269,7 +270,7 @@ sgemm_tile_kernel(const GemmParams p) {
             for (int i = 0; i < A_LD; ++i) {
                 const float *src = EDGE ? Ag + a_off[i] : nullptr;
                 if constexpr (!EDGE) {
-                    a_reg[i] = *at_bytes(Ag, (unsigned)a_off[i]);
+                    a_reg[i] = *at_bytes(Ag, a_off[i]);
                 } else if (full_m && full_k) {
                     if (vec_a) {
                         a_reg[i] = *reinterpret_cast<const f32x4_a4 *>(src);
@@ -292,7 +293,7 @@ sgemm_tile_kernel(const GemmParams p) {
             for (int i = 0; i < B_LD; ++i) {
                 const float *src = EDGE ? Bg + b_off[i] : nullptr;
                 if constexpr (!EDGE) {
-                    b_reg[i] = *at_bytes(Bg, (unsigned)b_off[i]);
+                    b_reg[i] = *at_bytes(Bg, b_off[i]);
                 } else if (full_n && full_k) {
                     if (vec_b) {
                         b_reg[i] = *reinterpret_cast<const f32x4_a4 *>(src);
@@ -319,12 +320,14 @@ sgemm_tile_kernel(const GemmParams p) {
 
         // K tile 0 of a k that leaves a remainder: only its first `tail` columns of A / rows of B exist.
         auto load_global_tail = [&](bool advance) {
+            if constexpr (!EDGE) {
     #pragma unroll
-            for (int i = 0; i < A_LD; ++i)
-                a_reg[i] = a_k[i] < tail ? *at_bytes(Ag, (unsigned)a_off[i]) : (f32x4)(0.0f);
+                for (int i = 0; i < A_LD; ++i)
+                    a_reg[i] = a_k[i] < tail ? *at_bytes(Ag, a_off[i]) : (f32x4)(0.0f);
     #pragma unroll
-            for (int i = 0; i < B_LD; ++i)
-                b_reg[i] = b_row[i] < tail ? *at_bytes(Bg, (unsigned)b_off[i]) : (f32x4)(0.0f);
+                for (int i = 0; i < B_LD; ++i)
+                    b_reg[i] = b_row[i] < tail ? *at_bytes(Bg, b_off[i]) : (f32x4)(0.0f);
+            }
             if (advance) {
                 Ag += tail;
                 Bg += (int64_t)tail * p.ldb;
@@ -447,6 +450,9 @@ sgemm_tile_kernel(const GemmParams p) {
         // scheduler would otherwise undo to save registers.
         // One barrier per K tile is enough: stage s^1 was last read before the previous barrier,
         // and stage s is not overwritten before the next one.
+        // s_waitcnt encodings (gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all ones = not waited for)
+        constexpr int kWaitLoads = 0x0F70;           // vmcnt(0)
+        constexpr int kWaitOlderReads = 0xC07F | ((RB + 4) << 8);   // lgkmcnt(the reads of one octet): everything older has returned
         constexpr int N_MFMA = 4 * RB * CB;          // MFMAs of one octet
         constexpr int N_ST = A_LD + B_LD;            // LDS writes / global loads of one tile
         constexpr int MFMA_PER_ST = N_MFMA / N_ST > 0 ? N_MFMA / N_ST : 1;
@@ -470,11 +476,13 @@ sgemm_tile_kernel(const GemmParams p) {
                 for (int o = 0; o < NO - 2; ++o) {
                     read_frags(o + 1, (o + 1) & 1);
                     __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_s_waitcnt(kWaitOlderReads);   // one wait per octet instead of one per fragment
                     mfma_octet(o & 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 read_frags(NO - 1, (NO - 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(kWaitLoads & kWaitOlderReads);   // one wait for the staged tile instead of one per LDS write
                 mfma_octet((NO - 2) & 1);
                 store_lds();
     #pragma unroll
