@@ -99,13 +99,13 @@ constexpr int direct_min_waves() {
 // builtin must be a literal, hence the two wrappers.)
 // A float address at a 32-bit byte offset from a wave-uniform origin (lane offsets are kept that way, see
 // at_bytes in tile_kernel.hpp: the load then takes the origin from scalar registers and a 32-bit vector offset).
-__device__ __forceinline__ const float *byte_offset(const float *base, unsigned bytes) {
-    asm volatile("" : "+v"(bytes));
+__device__ __forceinline__ const float *byte_offset(const float *base, unsigned &bytes) {
+    asm volatile("" : "+v"(bytes));     // (in place: the offset passes through unchanged)
     return reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + bytes);
 }
 // lane offset in bytes (LEAN) or in elements
 template <bool LEAN>
-__device__ __forceinline__ const float *lane_address(const float *base, unsigned off) {
+__device__ __forceinline__ const float *lane_address(const float *base, unsigned &off) {
     if constexpr (LEAN) return byte_offset(base, off);
     else return base + off;
 }

@@ -254,17 +254,22 @@ sgemm_tile_stream_kernel(const GemmParams p) {
 
     // One K tile of the stream (see tile_kernel.hpp for the order of operations inside a tile).  With the drain
     // tag the stores of the waiting tile go out between its MFMAs, half with the LDS writes, half with the loads.
+    // s_waitcnt encodings (gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all ones = not waited for)
+    constexpr int kWaitLoads = 0x0F70;           // vmcnt(0)
+    constexpr int kWaitOlderReads = 0xC07F | ((RB + 4) << 8);   // lgkmcnt(the reads of one octet): everything older has returned
     auto tile_body = [&](auto drain_tag) {
         constexpr bool DRAIN = decltype(drain_tag)::value;
 #pragma unroll
         for (int o = 0; o < NO - 2; ++o) {
             read_frags(o + 1, (o + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderReads);   // one wait per octet instead of one per fragment
             mfma_octet(o & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         read_frags(NO - 1, (NO - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWaitLoads & kWaitOlderReads);   // and one for the staged tile instead of one per LDS write
         if constexpr (DRAIN) {
 #pragma unroll
             for (int j = 0; j < N_MFMA; ++j) {
