@@ -263,14 +263,22 @@ sgemm_tile_deep_kernel(const GemmParams p) {
         out = p.C + (int64_t)prob * p.strideC;
         ldo = p.ldc;
     }
+    // Result register v of a lane is row 8 (v / 4) + v % 4 + 4 h of the wave's block, column li: the part that
+    // depends on v is wave-uniform (a scalar row origin per store), the lane's part one 32-bit byte offset for all
+    // sixteen stores (the host checks ldc < 2^27 for these kernels), so a store needs no vector address arithmetic.
     const int col = n0 + wn * 32 + li;
     const bool full_tile = m0 + BM <= p.m && n0 + BN <= p.n;      // workgroup-uniform
     const bool nt = p.splits == 1;
+    float *block = out + (int64_t)(m0 + wm * 32) * ldo + n0 + wn * 32;
+    unsigned lane_bytes = 4u * ((unsigned)(4 * h) * (unsigned)ldo + (unsigned)li);
     if (col < p.n) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-            if (full_tile || row < p.m) store_result(out + (int64_t)row * ldo + col, acc[v], nt);
+            const int r = 8 * (v / 4) + (v % 4);
+            const int row = m0 + wm * 32 + r + 4 * h;
+            asm volatile("" : "+v"(lane_bytes));    // (keeps the widening of the offset next to the store, see at_bytes)
+            float *dst = reinterpret_cast<float *>(reinterpret_cast<char *>(block + (int64_t)r * ldo) + lane_bytes);
+            if (full_tile || row < p.m) store_result(dst, acc[v], nt);
         }
     }
 }

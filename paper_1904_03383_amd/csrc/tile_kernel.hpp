@@ -84,13 +84,6 @@ __device__ __forceinline__ void store_lane(float *dst, V o, bool lane_vec, int c
     }
 }
 
-// Row of the A tile that load slot f (one 16-byte vector; BK/4 consecutive slots make a row) fetches and
-// writes to LDS.  With BK = 32 eight consecutive lanes fill one padded LDS row, 32 consecutive banks.  With
-// BK = 16 they fill two rows, and at a row pitch of 20 floats the rows r and r+1 overlap in four banks (a
-// 2-way conflict on every ds_write_b128 of A: 16.9 % of the LDS cycles in the hardware counters); rows r
-// and r+4 do not (20*4 = 80 = 16 mod 32).  So within each group of eight rows the slots take the rows in
-// the order 0, 4, 1, 5, 2, 6, 3, 7.  No padding alone can do this: the second row would have to start 16
-// banks after the first, i.e. at a pitch of 16 mod 32, where the fragment reads of 8 rows collide.
 // Address of a 16-byte vector at a 32-bit byte offset from a wave-uniform origin.  The exact-fit variants keep their
 // lane offsets that way (the host checks that a tile's footprint stays below 2^30 elements): a load is then the tile
 // origin in scalar registers plus a 32-bit vector offset, with no 64-bit address arithmetic and no second register
@@ -102,6 +95,13 @@ __device__ __forceinline__ const f32x4 *at_bytes(const float *base, unsigned &by
     return reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + bytes);
 }
 
+// Row of the A tile that load slot f (one 16-byte vector; BK/4 consecutive slots make a row) fetches and
+// writes to LDS.  With BK = 32 eight consecutive lanes fill one padded LDS row, 32 consecutive banks.  With
+// BK = 16 they fill two rows, and at a row pitch of 20 floats the rows r and r+1 overlap in four banks (a
+// 2-way conflict on every ds_write_b128 of A: 16.9 % of the LDS cycles in the hardware counters); rows r
+// and r+4 do not (20*4 = 80 = 16 mod 32).  So within each group of eight rows the slots take the rows in
+// the order 0, 4, 1, 5, 2, 6, 3, 7.  No padding alone can do this: the second row would have to start 16
+// banks after the first, i.e. at a pitch of 16 mod 32, where the fragment reads of 8 rows collide.
 template <int BK>
 __device__ __forceinline__ int a_slot_row(int f) {
     const int r = f / (BK / 4);
