@@ -46,7 +46,8 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     auto lds = [](unsigned addr) { return (float *)(lds_space_float *)(uintptr_t)addr; };
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: what depends only on the wave stays scalar
     const int li = lane & 31, h = lane >> 5;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
@@ -183,9 +184,17 @@ sgemm_tile_stream_kernel(const GemmParams p) {
                         a_frag[set][rb][t], vec_get(b_frag[set][t], cb), acc[rb][cb], 0, 0, 0);
     };
 
-    // The waiting tile (DEFER): its values, this lane's address of row 0 of its wave tile, and how to store it.
+    // A result row of a lane is row r = 32 rb + 8 (v / 4) + v % 4 (+ 4 h) of its wave tile: the origin of row r is
+    // wave-uniform (scalar registers), the lane's part (4 h rows down, its column) one 32-bit byte offset for all
+    // its stores (the host checks ldc < 2^27 for these kernels), so a store needs no vector address arithmetic.
+    auto result_at = [&](float *wave_tile, int64_t ld, int r, unsigned &lane_bytes) {
+        asm volatile("" : "+v"(lane_bytes));    // (keeps the widening of the offset next to the store, see at_bytes)
+        return reinterpret_cast<float *>(reinterpret_cast<char *>(wave_tile + (int64_t)r * ld) + lane_bytes);
+    };
+    // The waiting tile (DEFER): its values, the origin of its wave tile, this lane's offset in it, and its row stride.
     f32x16 prev[DEFER ? RB : 1][DEFER ? CB : 1];
-    float *prev_base = nullptr;
+    float *prev_tile = nullptr;
+    unsigned prev_lane = 0;
     int64_t prev_ldo = 0;
     bool have_prev = false;
     // Stores rows v = 8 * part .. 8 * part + 7 of every 32-row block of the waiting tile (RB * 8 stores).
@@ -195,7 +204,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
 #pragma unroll
             for (int vv = 0; vv < 8; ++vv) {
                 const int v = 8 * part + vv;
-                float *dst = prev_base + (int64_t)(rb * 32 + 8 * (v / 4) + (v % 4)) * prev_ldo;
+                float *dst = result_at(prev_tile, prev_ldo, rb * 32 + 8 * (v / 4) + (v % 4), prev_lane);
                 bvec o;
                 if constexpr (CB == 1) {
                     o = prev[rb][0][v];
@@ -241,7 +250,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
     };
     auto store_prev_one = [&](int part, int sidx) {
         const int rb = sidx / 8, v = 8 * part + sidx % 8;
-        float *dst = prev_base + (int64_t)(rb * 32 + 8 * (v / 4) + (v % 4)) * prev_ldo;
+        float *dst = result_at(prev_tile, prev_ldo, rb * 32 + 8 * (v / 4) + (v % 4), prev_lane);
         bvec o;
         if constexpr (CB == 1) {
             o = prev[DEFER ? rb : 0][0][v];
@@ -387,15 +396,17 @@ sgemm_tile_stream_kernel(const GemmParams p) {
             out = p.C + (int64_t)prob * p.strideC;
             ldo = p.ldc;
         }
-        const int col = tn * BN + wn * WN + li * CB;
         const bool nt = p.splits == 1 && rows_aligned<CB>(out, ldo);
+        float *wave_tile = out + (int64_t)(tm * BM + wm * WM) * ldo + tn * BN + wn * WN;
+        unsigned lane_bytes = 4u * ((unsigned)(4 * h) * (unsigned)ldo + (unsigned)(li * CB));
         if constexpr (DEFER) {
             // (a tile still waiting here had no successor K tile to ride on: cannot happen, every item has one)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) prev[rb][cb] = acc[rb][cb];
-            prev_base = out + (int64_t)(tm * BM + wm * WM + 4 * h) * ldo + col;
+            prev_tile = wave_tile;
+            prev_lane = lane_bytes;
             prev_ldo = ldo;
             have_prev = true;
         } else {
@@ -403,8 +414,7 @@ sgemm_tile_stream_kernel(const GemmParams p) {
             for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = tm * BM + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                    float *dst = out + (int64_t)row * ldo + col;
+                    float *dst = result_at(wave_tile, ldo, rb * 32 + 8 * (v / 4) + (v % 4), lane_bytes);
                     bvec o;
                     if constexpr (CB == 1) {
                         o = acc[rb][0][v];
