@@ -466,9 +466,8 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
             // (element offsets inside a tile are kept as 32-bit byte offsets)
             if (span_a >= (1 << 30) || span_b >= (1 << 30)) return no("leading dimension too large for the exact-fit kernels");
         }
-        // (the whole-tile-prefetch and the persistent kernels address the rows of a lane's results with a 32-bit byte offset)
-        if ((strstr(ki.name, "_tf") || ki.persistent) && (p.ldc >= (1 << 27) || p.n >= (1 << 27)))
-            return no("leading dimension of C too large for this variant");
+        // (the rows of a lane's results are addressed with a 32-bit byte offset)
+        if (p.ldc >= (1 << 27) || p.n >= (1 << 27)) return no("leading dimension of C too large for the exact-fit kernels");
         // (the bf16-piece kernels form 32-bit byte offsets)
         if (ki.pieces && ((ki.BM - 1) * p.lda + ki.BK >= (1 << 30) || (ki.BK - 1) * p.ldb + ki.BN >= (1 << 30)))
             return no("leading dimension too large for the exact-fit kernels");

@@ -196,7 +196,8 @@ sgemm_tile_kernel(const GemmParams p) {
     auto lds = [](unsigned addr) { return (float *)(lds_space_float *)(uintptr_t)addr; };
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: what depends only on the wave stays scalar
     const int li = lane & 31, h = lane >> 5;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
@@ -538,12 +539,23 @@ sgemm_tile_kernel(const GemmParams p) {
         const bool final_c = p.splits == 1;
         const bool lane_vec = col + CB <= p.n;
         const bool nt = final_c && rows_aligned<CB>(out, ldo);
+        float *wave_tile = out + (int64_t)(m0 + wm * WM) * ldo + n0 + wn * WN;
+        unsigned lane_bytes = 4u * ((unsigned)(4 * h) * (unsigned)ldo + (unsigned)(li * CB));
     #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
     #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * WM + rb * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                float *dst = out + (int64_t)row * ldo + col;
+                const int r = rb * 32 + 8 * (v / 4) + (v % 4);
+                const int row = m0 + wm * WM + r + 4 * h;
+                float *dst;
+                if constexpr (EDGE) {
+                    dst = out + (int64_t)row * ldo + col;
+                } else {
+                    // (the origin of row r of the wave tile is wave-uniform, the lane's part one 32-bit byte offset for
+                    // all its stores: the host checks ldc < 2^27 for the exact-fit variants; see at_bytes for the asm)
+                    asm volatile("" : "+v"(lane_bytes));
+                    dst = reinterpret_cast<float *>(reinterpret_cast<char *>(wave_tile + (int64_t)r * ldo) + lane_bytes);
+                }
                 bvec o;
                 if constexpr (CB == 1) {
                     o = acc[rb][0][v];
