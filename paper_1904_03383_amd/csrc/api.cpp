@@ -570,10 +570,18 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     // (measured on MI355X: K tiles of 32 beat 16 by ~1 %, direct-to-LDS loads win by ~1 % on
     // the large tiles, persistent variants only pay for short K; element-strided operands
     // cost the predicated kernels another factor of about two)
-    double eff = 1.0 / (1.0 + 12.0 / ki.WM + 12.0 / ki.WN) * (ki.edge ? 0.75 : 1.0) * (ki.two_level ? 0.97 : 1.0);
+    // (constants refitted after the K loops lost a third of their non-MFMA instructions: the register-staged kernels
+    // gained most, small wave tiles lost less to large ones than before; sweep of 24 shapes, first choice against the
+    // best of the model's ten first)
+    double eff = 1.0 / (1.0 + 6.0 / ki.WM + 6.0 / ki.WN) * (ki.edge ? 0.75 : 1.0) * (ki.two_level ? 0.97 : 1.0);
     eff *= ki.BK >= 32 ? 1.0 : 0.985;
-    // (direct-to-LDS loads: ~1 % ahead on the large tiles, 4-10 % on 64x64 tiles with k >= 256, behind on 128x128)
-    if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? 1.01 : (ki.WM * ki.WN == 32 * 32 ? 1.04 : 0.97);
+    // (direct-to-LDS loads: 2 % behind the register-staged kernels on the large tiles, ahead on 64x64 tiles with
+    // k >= 256, behind on 128x128; the 128x128 wave tile, 256 accumulator registers, a further 7 % behind)
+    if (ki.name[0] == 'd') eff *= ki.WM * ki.WN > 64 * 64 ? (ki.WM * ki.WN >= 128 * 128 ? 0.92 : 0.985) : (ki.WM * ki.WN == 32 * 32 ? 1.04 : 0.97);
+    // two workgroups resident per CU cover each other's barrier and load waits (4096^3 on 128x128 tiles with a second
+    // accumulator level: 94 % of the MFMA rate, against 86 % at 2048^3 where every CU holds one)
+    if (ki.kind == tg::KIND_TILE && !ki.persistent && 2 * ki.lds_bytes <= kLdsPerCU && ki.WM * ki.WN <= 64 * 64 && blocks >= 2.0 * kNumCUs)
+        eff *= 1.05;
     // (32x32 wave tiles with the fragments of a whole K tile fetched one tile ahead: 1024^3 20.0 us against 21.7 us;
     // K tiles of 64 in that form: 21.0 us)
     if (strstr(ki.name, "_tf")) eff *= ki.BK > 32 ? 1.03 : 1.08;
@@ -608,7 +616,10 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     const double cu_rate = std::min(ki.threads / 64, 4) * kSimdFlops * eff;
     // 1 us: the first K tile's trip through LDS and the epilogue, which the wave kernels do not have (a sweep of
     // 30 small and mid-size shapes: the model's first choice then averages 5 % above the best measured candidate)
-    double t = launch + 1e-6 + per_cu * block_flops / cu_rate;
+    // (the first K tile of a workgroup is fetched and staged before anything is multiplied: half a tile's worth of its
+    // time shows on short K ranges, 4096x4096x128 with K tiles of 32 43 us against 40 us with tiles of 16)
+    const double fill = 1.0 + 0.5 * ki.BK / (double)std::min<int64_t>((int64_t)per * ki.BK, p.k);
+    double t = launch + 1e-6 + per_cu * block_flops / cu_rate * fill;
     // A gathered operand: every element costs a line request (its own cache line when the stride is large) in every tile
     // that fetches it.  Measured with hardware counters on 1024^3 with A at element stride 32: a CU's L1 keeps about a
     // hundred line requests in flight at 450 cycles (L2 hit) to 1400 cycles (miss) each, which comes to 1.1 - 1.5 ns

@@ -480,7 +480,8 @@ def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):
     finally:
         tg.set_math(tg.MATH_FP32_MFMA)
         tg.clear_tune_cache()
-    assert tg.get_config(1, 4096, 4096, 4096).startswith("d128x256x32_w64x128_acc2")
+    # nothing tuned any more: the heuristic answers, with a kernel that has the second accumulation level K = 4096 needs
+    assert "_acc2:s1:g8" in tg.get_config(1, 4096, 4096, 4096)
 
 
 def test_launch_bound_classification_comes_from_the_cost_model(lib):
