@@ -673,3 +673,31 @@ def test_unaligned_and_odd_operands_are_copied_when_the_workspace_has_room():
             mask = torch.ones_like(cflat, dtype=torch.bool)
             torch.as_strided(mask, (1, m, n), dc.stride(), offs[2]).fill_(False)
             assert bool((cflat[mask] == 7.0).all()), f"{cfg}: stores outside the output"
+
+
+# ---- lane offsets beyond 2^31 bytes: the exact-fit kernels keep them as unsigned 32-bit byte offsets ----------------
+
+@pytest.mark.parametrize("spec", ["t128x128x16_w64x64", "t128x256x32_w64x128_acc2", "p128x128x16_w64x64_ds:p1",
+                                  "d64x64x32_w32x32_tf", "d128x128x32_w64x64", "d128x256x32_w64x128_acc2"])
+def test_leading_dimensions_that_put_a_tile_row_beyond_2_gib(spec):
+    """A with 2^22 floats per row: the last rows of a 128-row tile start 2.1 GB after its origin, beyond the range of
+    a signed 32-bit byte offset and still within the 2^30 elements that the host admits for these kernels; C with a
+    leading dimension of 2^21 likewise stretches the byte offsets of the stores.  (A is a view of a 4 GiB buffer.)"""
+    import torch
+    m, n, k = 256, 256, 64
+    lda, ldc = 1 << 22, 1 << 21
+    say(f"forced {spec} on {m}x{n}x{k} with lda = 2^22, ldc = 2^21")
+    a, b = ig.make_operands(1, m, n, k, "int", 391, 392)
+    a, b = a[0], b[0]
+    big_a = torch.empty(m * lda, dtype=torch.float32, device="cuda")
+    da = big_a.view(m, lda)[:, :k]
+    da.copy_(to_dev(a))
+    big_c = torch.empty(m * ldc, dtype=torch.float32, device="cuda")
+    dc = big_c.view(m, ldc)[:, :n]
+    dc.fill_(float("nan"))
+    tg.force_config(spec)
+    tg.sgemm(da, to_dev(b), out=dc)
+    torch.cuda.synchronize()
+    assert tg.last_config().startswith(spec.split(":")[0]), tg.last_config()
+    check_against_oracle(dc.cpu().numpy(), a, b, exact=True, what=f"{spec} with rows 16 MB apart")
+    del big_a, big_c
