@@ -505,6 +505,7 @@ double lower_bound_seconds(const Problem &p, const Config &c) {
     double t = flops / (kPeakFlops * speed);
     int splits = 1, per = 1;
     int waves_per_block = ki.threads / 64;
+    if (ki.name[0] == 'g') waves_per_block = (ki.BM / ki.WM) * (ki.BN / ki.WN);   // row-panel kernels: the other waves only gather
     double wave_flops;
     int64_t blocks;
     if (ki.kind == tg::KIND_WAVE) {
@@ -565,6 +566,28 @@ double heuristic_seconds(const Problem &p, const Config &c) {
     split_plan(ki, p.k, c.splits, &splits, &per);
     const double blocks = (double)ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * splits * p.batch;
     const double per_cu = std::ceil(blocks / kNumCUs);
+    if (ki.name[0] == 'g') {
+        // Row panels of a gathered A (tile_panel_kernel.hpp).  Measured on MI355X: lines that miss L2 arrive at about
+        // 5e10 lines/s over the whole chip and 2.4e8 per CU (an element asked for again by another column tile costs
+        // about a third of that), B streams through a CU at about 125 GB/s beside the gather and is hidden while the
+        // CU's own request rate is the limit, and the 16x16x4 products overlap with both for the most part
+        // (us, A at element stride 32: 1024^3 16x1024 tiles s1 73, s2 50, s4 42, 16x512 tiles s1 47, s2 37, s4 39;
+        // 4096x1024x1024 145 and 142 at s1; 2048^3 233 and 251 at s2; stride 3, 1024x520x512: 32 / 19 and 18.5 / 16.6).
+        const double k_range = (double)std::min<int64_t>((int64_t)per * ki.BK, p.k);
+        const double line = std::min(4.0 * p.csa, 128.0);
+        const double per_el = std::max(line / 128.0, line >= 32.0 ? 0.5 : (line >= 16.0 ? 0.35 : 0.25));
+        const double tiles_n = (double)ceil_div(p.n, ki.BN);
+        const double miss_share = line / 128.0;          // share of the requests that bring a new line
+        const double req = ki.BM * k_range * per_el * (1.0 + (tiles_n - 1.0) / 3.0) / tiles_n;
+        const double t_cu = per_cu * req * (miss_share + (1.0 - miss_share) / 3.0) / 2.4e8;
+        const double t_chip = p.batch * (double)p.m * p.k * line / 128.0 / 5e10;
+        const double t_b = per_cu * k_range * (double)std::min<int64_t>(ki.BN, p.n) * 4.0 / 1.25e11;
+        const double t_mem = std::max(t_chip + 0.8 * t_b, t_cu);
+        const double t_mfma = per_cu * 2.0 * ki.BM * ki.BN * k_range / (4.0 * kSimdFlops * 0.85);
+        double t = launch + 1e-6 + std::max(t_mem, t_mfma) + 0.2 * std::min(t_mem, t_mfma);
+        if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (splits + 1.0) * (double)p.m * p.n / 5e12;
+        return t;
+    }
     // operand traffic per flop falls with the wave tile; predication and the second
     // accumulator level cost a little
     // (measured on MI355X: K tiles of 32 beat 16 by ~1 %, direct-to-LDS loads win by ~1 % on

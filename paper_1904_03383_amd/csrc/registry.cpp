@@ -117,6 +117,18 @@ TG_MODE_LIST(TG_MDECL)
      NS * (BM * BK + BK * BN) * 4, &launch_tile_direct<BM, BN, BK, WM, WN, L2, NS, 1, AM, BMD, 16>, 0, false, 0, false, AM, BMD},
 TG_MI16_LIST(TG_M16DECL)
 
+// row panels of a gathered A: 16 rows by up to 1024 columns per workgroup, so that an element of A (a cache line of its
+// own at a large stride) is requested once per 1024 columns; with few tile rows a K split fills the chip
+// (compute waves, producer waves, name)
+#define TG_PANEL_LIST(X)                    \
+    X(8, 4, "g16x1024x64_w16x128_acc2_ga")       \
+    X(4, 4, "g16x512x64_w16x128_acc2_ga")
+#define TG_GDECL(NC, NP, NAME) extern template hipError_t launch_tile_panel<NC, NP>(const GemmParams &, hipStream_t);
+#define TG_GROW(NC, NP, NAME)                                                                         \
+    {NAME, KIND_TILE, 16, NC * 128, 64, 16, 128, true, false, false, false, (NC + NP) * 64, 3 * 16 * 68 * 4, \
+     &launch_tile_panel<NC, NP>, 0, false, 0, false, 2, 0},
+TG_PANEL_LIST(TG_GDECL)
+
 // direct-to-LDS variants for 32x32 wave tiles with tile-granular fragment prefetch:
 // (BM, BN, BK, two_level, LDS stages, A mode, B mode, name)
 #define TG_DEEP_LIST(X)                                                     \
@@ -165,6 +177,7 @@ static const KernelInfo kTable[] = {
     TG_DEEP_LIST(TG_FROW)
     TG_MODE_LIST(TG_MROW)
     TG_MI16_LIST(TG_M16ROW)
+    TG_PANEL_LIST(TG_GROW)
     TG_PIECES_LIST(TG_EROW)
     TG_PRECUT_LIST(TG_CROW)
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")

@@ -1,0 +1,229 @@
+// Row-panel SGEMM kernel for a gathered A (the strided matmul of Sec. 5.2 of the paper: consecutive
+// elements of a row of A lie a fixed number of floats apart, so that at a large stride every element
+// is a cache line of its own).  What such a product costs is line requests: every tile that needs an
+// element requests its line again.  This kernel gives a workgroup 16 rows of A and up to 1024 columns
+// of B, so an element is requested once per 1024 columns of the result, and fills the chip through a
+// K split (partial products meet in the split-K reduction) where 16-row panels alone are too few.
+//
+// Roles inside a workgroup (the BLOCK / THREAD mapping of Sec. 4, with the SHARED temporary for A only):
+//  * NP producer waves do nothing but gather.  Per chunk of 64 k each fetches its rows of the panel,
+//    one 4-byte direct-to-LDS load per row (lane l fetches element k0 + l), into a ring of three LDS
+//    stages, two chunks ahead of the product.  Their loads are the only ones they ever wait for, so the
+//    gather queue never drains: a wave that also loaded B would have to wait for its youngest gather
+//    whenever it needs an older B vector (vector-memory results return in order).
+//  * NC compute waves own 16 x 128 of the result each.  B is used by one wave only (a panel has a
+//    single tile row), so it does not go through LDS: per 16-k step a lane fetches two 16-byte vectors
+//    (its 8 adjacent columns) from each of its four k rows into registers, one step ahead of the
+//    MFMAs, and reads its four consecutive k values of A's row with one ds_read_b128.
+//  * One barrier per chunk joins the two roles: the producers arrive when the next chunk has landed,
+//    the compute waves when they are done with the previous one (which frees its stage).
+//
+// v_mfma_f32_16x16x4_f32 operand and result layout: see mfma_shape<16> in tile_direct_kernel.hpp; the
+// k pairing (MFMA t of a step multiplies k = 4h + t) and the ownership of adjacent columns by one lane
+// only reorder the sum and the stores.
+#pragma once
+
+#include "tile_direct_kernel.hpp"
+
+namespace tg {
+
+constexpr int kPanelRows = 16;
+constexpr int kPanelChunk = 64;                    // k per chunk = lanes of one gather instruction
+constexpr int kPanelPitch = kPanelChunk + 4;       // floats per row of a stage: the 16 rows of a fragment read fall in distinct bank groups
+constexpr int kPanelStages = 3;
+constexpr int kPanelStageFloats = kPanelRows * kPanelPitch;
+
+template <int NC, int NP>
+__global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmParams p) {
+    static_assert(kPanelRows % NP == 0, "producer waves share the 16 rows evenly");
+    constexpr int BN = NC * 128;
+    constexpr int ROWS_PER_PRODUCER = kPanelRows / NP;
+    __shared__ __attribute__((aligned(16))) float smem[kPanelStages * kPanelStageFloats];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
+    int slice, tm, tn;
+    map_workgroup(p, total_work, blockIdx.x, slice, tm, tn);
+    const int prob = slice / p.splits, split = slice - prob * p.splits;
+    const int m0 = tm * kPanelRows, n0 = tn * BN;
+    const int ch_total = p.k / kPanelChunk;
+    const int ch_begin = split * p.ktiles_per_split;
+    const int ch_stop = ch_begin + p.ktiles_per_split;
+    const int nch = (ch_stop < ch_total ? ch_stop : ch_total) - ch_begin;   // >= 1: the host plans no empty K range
+    const int64_t k_begin = (int64_t)ch_begin * kPanelChunk;
+
+    if (wave >= NC) {
+        // ---- producer ---------------------------------------------------------------------------------
+        const int pw = wave - NC;
+        const float *row[ROWS_PER_PRODUCER];
+#pragma unroll
+        for (int i = 0; i < ROWS_PER_PRODUCER; ++i) {
+            const int r = pw * ROWS_PER_PRODUCER + i;
+            const int rg = m0 + r < p.m ? m0 + r : p.m - 1;   // rows past the end re-read the last one (never stored)
+            row[i] = p.A + (int64_t)prob * p.strideA + (int64_t)rg * p.lda + k_begin * p.csa;
+        }
+        unsigned lane_bytes = 4u * (unsigned)lane * (unsigned)p.csa;   // (the host checks that a chunk spans < 2^30 elements)
+        const int64_t step = (int64_t)kPanelChunk * p.csa;
+        auto gather = [&](int stage) {
+#pragma unroll
+            for (int i = 0; i < ROWS_PER_PRODUCER; ++i) {
+                const int r = pw * ROWS_PER_PRODUCER + i;
+                direct_load<1>(byte_offset(row[i], lane_bytes), smem + stage * kPanelStageFloats + r * kPanelPitch);
+                row[i] += step;
+            }
+        };
+#ifdef TG_POISON_LDS
+        for (int s = 0; s < kPanelStages; ++s)
+            for (int i = 0; i < ROWS_PER_PRODUCER; ++i)
+                smem[s * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + lane] = __builtin_nanf("");
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+#endif
+        gather(0);
+        if (nch > 1) gather(1);
+        int stage_free = 2;                      // where chunk j + 2 goes
+        for (int j = 0; j < nch; ++j) {
+            // chunk j has landed (the chunk after it may still be on its way)
+            if (j + 1 < nch) __builtin_amdgcn_s_waitcnt(0x0F70 | ROWS_PER_PRODUCER);   // vmcnt(one chunk's loads)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);                                   // vmcnt(0)
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();        // #j: chunk j may be read; nobody reads chunk j - 1 any more
+            __builtin_amdgcn_sched_barrier(0);
+            if (j + 2 < nch) {
+#ifdef TG_POISON_LDS
+                for (int i = 0; i < ROWS_PER_PRODUCER; ++i)
+                    smem[stage_free * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + lane] = __builtin_nanf("");
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+#endif
+                gather(stage_free);
+            }
+            stage_free = stage_free == kPanelStages - 1 ? 0 : stage_free + 1;
+        }
+        return;
+    }
+
+    // ---- compute --------------------------------------------------------------------------------------
+    const int c = lane & 15, g = lane >> 4;
+    const int n0w = n0 + wave * 128;
+    // the lane's two groups of four adjacent columns; a group past the end re-reads the last four columns
+    // (n is a multiple of 4: a group is inside or outside as a whole) and is not stored
+    const int col0 = n0w + 8 * c, col1 = col0 + 4;
+    const int last = p.nb - 4;
+    // B is addressed from a wave-uniform row origin (scalar registers, advanced per step) plus two 32-bit byte offsets
+    // per lane (the host checks that 64 rows of B span fewer than 2^30 elements)
+    const float *Bg = p.B + (int64_t)prob * p.strideB + k_begin * p.ldb;
+    unsigned off0 = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col0 < last ? col0 : last));
+    unsigned off1 = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col1 < last ? col1 : last));
+    const int64_t step_b = 16 * p.ldb;
+    int steps_left = 4 * nch;                    // 16-k steps not yet fetched
+
+    f32x4 bq[2][4][2];
+    // vector i = 2t + q of a step: k row 4g + t, column group q
+    auto fetch_one = [&](int set, int i) {
+        const float *r = Bg + (int64_t)(i / 2) * p.ldb;
+        bq[set][i / 2][i % 2] = *reinterpret_cast<const f32x4 *>(byte_offset(r, i % 2 ? off1 : off0));
+    };
+    // past the end of the K range the last step is fetched again (in bounds, never multiplied): the number of
+    // loads in flight stays the same through the whole loop
+    auto next_step = [&]() {
+        if (steps_left > 1) {
+            --steps_left;
+            Bg += step_b;
+        }
+    };
+
+    // two accumulation levels: every flush_tiles chunks the MFMA accumulators are folded into `total`, which bounds the
+    // length of any single fp32 running sum (as in the other tile kernels)
+    f32x4 acc[8], total[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        acc[e] = (f32x4)(0.0f);
+        total[e] = (f32x4)(0.0f);
+    }
+
+    const float *a_lane = smem + c * kPanelPitch + 4 * g;
+    f32x4 a_frag[2];
+    auto read_a = [&](int stage, int s, int set) {
+        a_frag[set] = *reinterpret_cast<const f32x4 *>(a_lane + stage * kPanelStageFloats + 16 * s);
+    };
+    // A step is eight groups of one load (for the next step, into the other register set) and four independent MFMAs,
+    // written in the order they are to issue and fenced group by group: left alone, the scheduler sinks the loads to
+    // their uses and waits for each in turn.
+    auto chunk = [&](int stage) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();            // #j (see the producer)
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(stage, 0, 0);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                fetch_one((s + 1) & 1, i);
+                if (i == 0 && s < 3) read_a(stage, s + 1, (s + 1) & 1);
+#pragma unroll
+                for (int e = 4 * (i % 2); e < 4 * (i % 2) + 4; ++e)
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][i / 2], bq[s & 1][i / 2][e / 4][e % 4], acc[e], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            next_step();
+        }
+    };
+
+#pragma unroll
+    for (int i = 0; i < 8; ++i) fetch_one(0, i);
+    next_step();
+    int stage = 0, since_flush = 0;
+    for (int j = 0; j < nch; ++j) {
+        if (since_flush == p.flush_tiles) {
+            since_flush = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                total[e] += acc[e];
+                acc[e] = (f32x4)(0.0f);
+            }
+        }
+        ++since_flush;
+        chunk(stage);
+        stage = stage == kPanelStages - 1 ? 0 : stage + 1;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += total[e];
+
+    // Epilogue: registers -> C (or the split-K partial).  Register v of block e: row 4g + v, column 8c + e.
+    float *out;
+    int64_t ldo;
+    if (p.splits > 1) {
+        out = p.ws + (int64_t)slice * p.m * p.n;
+        ldo = p.n;
+    } else {
+        out = p.C + (int64_t)prob * p.strideC;
+        ldo = p.ldc;
+    }
+    const bool nt = p.splits == 1 && rows_aligned<4>(out, ldo);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int r = m0 + 4 * g + v;
+        if (r >= p.m) continue;
+        float *dst = out + (int64_t)r * ldo;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int col = q ? col1 : col0;
+            if (col >= p.n) continue;
+            f32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = acc[4 * q + e][v];
+            store_result(dst + col, o, nt);
+        }
+    }
+}
+
+template <int NC, int NP>
+hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s) {
+    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace tg

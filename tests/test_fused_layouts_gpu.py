@@ -78,6 +78,7 @@ def test_variant_list_is_not_empty():
     "d64x64x32_w32x32_acc2_st4_ga_gb", "d128x128x32_w64x64_acc2_st3_ga_gb", "d64x64x32_w32x32_acc2_st4_ga_tb",
     "d128x128x32_w64x64_acc2_st3_ga_tb", "d64x64x32_w32x32_acc2_st4_ta_gb", "d128x128x32_w64x64_acc2_st3_ta_gb",
     "d16x256x32_w16x64_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga",
+    "g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga",
     "d64x64x32_w32x32_acc2_tf_ta", "d64x64x32_w32x32_acc2_tf_tb", "d64x64x32_w32x32_acc2_tf_ta_tb",
     "d64x64x32_w32x32_acc2_tf_ga", "d64x64x32_w32x32_acc2_tf_gb")])
 def test_every_variant_forced(name):
@@ -147,3 +148,65 @@ def test_fused_variant_is_preferred_to_packing_when_a_workspace_is_set():
     assert "_ta" in tg.last_config() and "+pack" not in tg.last_config(), tg.last_config()
     check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=True, what="fused with workspace")
     del ws
+
+
+PANELS = ["g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga"]
+
+
+@pytest.mark.parametrize("name", PANELS)
+@pytest.mark.parametrize("splits", [2, 3, 4])
+def test_row_panel_variants_with_a_k_split(name, splits):
+    """The row-panel kernels fill the chip through a K split when the panels alone are too few: partial products in
+    the workspace, added by the reduction in a fixed order.  Ragged rows, a partly used last column tile, K ranges
+    of unequal length (13 chunks over 3 or 4 ranges)."""
+    import torch
+    for (m, n, k, stride) in [(1000, 1024, 1024, 32), (73, 1060, 832, 3)]:
+        ws = torch.full((4 * m * n + 64,), float("nan"), device="cuda")
+        tg.set_workspace(ws)
+        for dist in ("normal", "int"):
+            say(f"forced {name}:s{splits} {m}x{n}x{k} A element stride {stride} {dist}")
+            gen = ig.normal if dist == "normal" else ig.small_int
+            a_np, da = _operand(gen, 741, m, k, "S", stride=stride)
+            b = gen(742, (k, n))
+            tg.force_config(f"{name}:s{splits}:g1")
+            c = _run(da, to_dev(b), m, n)
+            assert tg.last_config().startswith(f"{name}:s{splits}"), tg.last_config()
+            check_against_oracle(c, np.ascontiguousarray(a_np), b, exact=(dist == "int"),
+                                 what=f"{name}:s{splits} {m}x{n}x{k} {dist}")
+        tg.set_workspace(None)
+        del ws
+
+
+@pytest.mark.parametrize("name", PANELS)
+def test_row_panel_variants_on_a_batch_of_plain_operands(name):
+    """A gather reads plain rows too: forced on a batch through tg_sgemm_batched (problem strides, padded leading
+    dimensions, rows of C off the 16-byte grid)."""
+    import torch
+    batch, m, n, k = 3, 50, 1028, 192
+    say(f"forced {name} on a batch {batch} x {m}x{n}x{k}")
+    a = ig.small_int(751, (batch, m, k + 4))
+    b = ig.small_int(752, (batch, k, n + 8))
+    out = torch.full((batch, m, n + 1), float("nan"), device="cuda")
+    tg.force_config(name)
+    tg.sgemm_batched(to_dev(a)[:, :, :k], to_dev(b)[:, :, :n], out=out[:, :, :n])
+    torch.cuda.synchronize()
+    assert tg.last_config().startswith(name), tg.last_config()
+    c = out.cpu().numpy()
+    assert np.isnan(c[:, :, n]).all()                     # the padding column of C is not written
+    for i in range(batch):
+        check_against_oracle(c[i, :, :n], np.ascontiguousarray(a[i, :, :k]), np.ascontiguousarray(b[i, :, :n]), exact=True,
+                             what=f"{name} batch problem {i}")
+
+
+def test_tall_strided_product_takes_a_row_panel_without_a_workspace():
+    """4096 x 1024 x 1024 with A at element stride 32: 256 panels of 16 rows fill the chip by themselves, every
+    element of A is requested once, nothing is packed and no workspace is needed."""
+    m, n, k = 4096, 1024, 1024
+    say("automatic choice, 4096x1024x1024 with A at element stride 32, no workspace")
+    a_store = ig.uniform(761, (m, k * 32))
+    b = ig.uniform(762, (k, n))
+    c = _run(to_dev(a_store)[:, ::32], to_dev(b), m, n)
+    cfg = tg.last_config()
+    assert cfg.startswith("g16x") and "+pack" not in cfg, cfg
+    rows = np.arange(0, m, 37)
+    check_against_oracle(c[rows], np.ascontiguousarray(a_store[rows, ::32]), b, what="tall strided product, sampled rows")

@@ -50,12 +50,13 @@ def test_the_flavour_says_what_it_is():
 # one or two variants of every kernel family that stages operands through LDS: register-staged (t), predicated
 # (edge), persistent stream with and without deferred stores (p), direct-to-LDS rings of two to four stages (d),
 # the whole-tile fragment prefetch (tf), gathering and transposed-operand loaders (on plain operands where they
-# can read them)
+# can read them), row panels with producer waves (g)
 SPECS = ["t128x128x16_w64x64", "t128x256x32_w64x128_acc2", "t64x64x32_w32x32", "t64x64x16_w32x32_edge",
          "p128x128x16_w64x64:p1", "p128x128x16_w64x64_ds:p2", "p128x128x32_w64x64:p2",
          "d128x128x32_w64x64", "d128x256x32_w64x128_acc2_st3", "d64x64x32_w32x32_st4", "d64x64x32_w32x32_k2",
          "d64x64x32_w32x32_tf", "d64x64x64_w32x32_acc2_tf", "d256x256x32_w128x128",
-         "d64x64x32_w32x32_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga", "d64x64x32_w32x32_acc2_tf_gb"]
+         "d64x64x32_w32x32_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga", "d64x64x32_w32x32_acc2_tf_gb",
+         "g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga"]
 
 
 @pytest.mark.parametrize("spec", SPECS)
