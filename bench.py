@@ -297,6 +297,17 @@ def time_layout(tg, torch, name, m, n, k, layout_a, layout_b, steps, warmup, res
                                         "device_tflops": flops / (p_ms * 1e-3) / 1e12}
         res["parity_ok"] = ok and p_ok
         del ws
+        if csa != 1 or csb != 1:
+            # the library's own choice with room for packed copies and for split-K partial products (a gathered A:
+            # row panels with a K split)
+            ws = torch.empty(max((tg.strided_workspace_bytes(m, n, k, csa, csb) + tg.workspace_bytes(1, m, n, k)) // 4, 4),
+                             dtype=torch.float32, device="cuda")
+            tg.set_workspace(ws)
+            a_ms, a_cfg, a_ok = timed(reps)
+            res["auto_with_workspace"] = {"tile_config": a_cfg, "device_ms_per_step": a_ms,
+                                          "device_tflops": flops / (a_ms * 1e-3) / 1e12}
+            res["parity_ok"] = res["parity_ok"] and a_ok
+            del ws
     tg.set_workspace(restore_ws)
     return res
 
@@ -500,6 +511,7 @@ def main():
         others.append(r)
         # strided matmul (Sec. 5.2) and transposed layouts through tg_sgemm_strided, no workspace
         layouts = [("strided_1024_csa32", 1024, 1024, 1024, "S32", "N", "d64x64x32_w32x32"),
+                   ("strided_4096x1024x1024_csa32", 4096, 1024, 1024, "S32", "N", None),
                    ("AT_B_1024", 1024, 1024, 1024, "T", "N", "d64x64x32_w32x32"),
                    ("A_BT_1024", 1024, 1024, 1024, "N", "T", "d64x64x32_w32x32"),
                    ("AT_BT_1024", 1024, 1024, 1024, "T", "T", None),
@@ -511,6 +523,9 @@ def main():
             if "packed_with_workspace" in r:
                 pw = r["packed_with_workspace"]
                 extra = f"  (packing pass + {pw['tile_config']}: {pw['device_ms_per_step'] * 1e3:.1f} us)"
+            if "auto_with_workspace" in r:
+                aw = r["auto_with_workspace"]
+                extra += f"  (automatic choice with a workspace: {aw['tile_config']} {aw['device_ms_per_step'] * 1e3:.1f} us)"
             log(f"  {lname} (A:{la} B:{lb}, no workspace): {r['tile_config']}  {r['device_ms_per_step'] * 1e3:.1f} us  "
                 f"{r['device_tflops']:.2f} TFLOP/s  parity_ok={r['parity_ok']}{extra}")
             parity_ok = parity_ok and r["parity_ok"]

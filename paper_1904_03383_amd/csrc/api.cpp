@@ -570,9 +570,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // Row panels of a gathered A (tile_panel_kernel.hpp).  Measured on MI355X: lines that miss L2 arrive at about
         // 5e10 lines/s over the whole chip and 2.4e8 per CU (an element asked for again by another column tile costs
         // about a third of that), B streams through a CU at about 125 GB/s beside the gather and is hidden while the
-        // CU's own request rate is the limit, and the 16x16x4 products overlap with both for the most part
-        // (us, A at element stride 32: 1024^3 16x1024 tiles s1 73, s2 50, s4 42, 16x512 tiles s1 47, s2 37, s4 39;
-        // 4096x1024x1024 145 and 142 at s1; 2048^3 233 and 251 at s2; stride 3, 1024x520x512: 32 / 19 and 18.5 / 16.6).
+        // CU's own request rate is the limit; where the gather is much the longer part the 16x16x4 products hide behind
+        // it, from parity on the producers wait for free stages and half of the shorter part shows; a K range of few
+        // chunks pays its pipeline fill; a K split pays the partial products' way out and back.
+        // (us, A at element stride 32, 16x1024 / 16x512 / 32x512 / 32x1024 panels: 1024^3 s2 51 38 52 79, s4 43 40 42 56;
+        // 2048^3 s1 224 244 229 -, s2 238 249 246 200; 4096x1024x1024 s1 148 141 134 188; 4096x4096x1024 s1 395 425 438 342;
+        // 8192x512x1024 s1 238 210 187 222; stride 8, 1024^3: s2 40 28 41 69)
         const double k_range = (double)std::min<int64_t>((int64_t)per * ki.BK, p.k);
         const double line = std::min(4.0 * p.csa, 128.0);
         const double per_el = std::max(line / 128.0, line >= 32.0 ? 0.5 : (line >= 16.0 ? 0.35 : 0.25));
@@ -584,8 +587,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double t_b = per_cu * k_range * (double)std::min<int64_t>(ki.BN, p.n) * 4.0 / 1.25e11;
         const double t_mem = std::max(t_chip + 0.8 * t_b, t_cu);
         const double t_mfma = per_cu * 2.0 * ki.BM * ki.BN * k_range / (4.0 * kSimdFlops * 0.85);
-        double t = launch + 1e-6 + std::max(t_mem, t_mfma) + 0.2 * std::min(t_mem, t_mfma);
-        if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (splits + 1.0) * (double)p.m * p.n / 5e12;
+        const double fill = 1.0 + ki.BK / k_range;
+        // (share of the shorter part that shows: 0.15 while the products are well below the gather, 0.5 from parity on)
+        const double ratio = t_mfma / std::max(t_mem, 1e-9);
+        const double shown = 0.15 + 0.35 * std::min(1.0, std::max(0.0, (ratio - 0.6) / 0.4));
+        double t = launch + 1e-6 + (std::max(t_mem, t_mfma) + shown * std::min(t_mem, t_mfma)) * fill;
+        if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (2.0 * splits + 1.0) * (double)p.m * p.n / 5e12;
         return t;
     }
     // operand traffic per flop falls with the wave tile; predication and the second

@@ -31,13 +31,16 @@ constexpr int kPanelRows = 16;
 constexpr int kPanelChunk = 64;                    // k per chunk = lanes of one gather instruction
 constexpr int kPanelPitch = kPanelChunk + 4;       // floats per row of a stage: the 16 rows of a fragment read fall in distinct bank groups
 constexpr int kPanelStages = 3;
-constexpr int kPanelStageFloats = kPanelRows * kPanelPitch;
 
-template <int NC, int NP>
+// NC compute waves, NP producer waves, RB blocks of 16 rows per panel (every compute wave owns 16 * RB x 128 of the
+// result and uses a B vector RB times), TWO_LEVEL: second accumulation level for K ranges beyond 1024.
+template <int NC, int NP, int RB, bool TWO_LEVEL>
 __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmParams p) {
-    static_assert(kPanelRows % NP == 0, "producer waves share the 16 rows evenly");
+    constexpr int BM = kPanelRows * RB;
+    static_assert(BM % NP == 0, "producer waves share the rows evenly");
     constexpr int BN = NC * 128;
-    constexpr int ROWS_PER_PRODUCER = kPanelRows / NP;
+    constexpr int ROWS_PER_PRODUCER = BM / NP;
+    constexpr int kPanelStageFloats = BM * kPanelPitch;
     __shared__ __attribute__((aligned(16))) float smem[kPanelStages * kPanelStageFloats];
 
     const int tid = threadIdx.x;
@@ -48,7 +51,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     int slice, tm, tn;
     map_workgroup(p, total_work, blockIdx.x, slice, tm, tn);
     const int prob = slice / p.splits, split = slice - prob * p.splits;
-    const int m0 = tm * kPanelRows, n0 = tn * BN;
+    const int m0 = tm * BM, n0 = tn * BN;
     const int ch_total = p.k / kPanelChunk;
     const int ch_begin = split * p.ktiles_per_split;
     const int ch_stop = ch_begin + p.ktiles_per_split;
@@ -136,19 +139,23 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 
     // two accumulation levels: every flush_tiles chunks the MFMA accumulators are folded into `total`, which bounds the
     // length of any single fp32 running sum (as in the other tile kernels)
-    f32x4 acc[8], total[8];
+    f32x4 acc[RB][8], total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? 8 : 1];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        acc[e] = (f32x4)(0.0f);
-        total[e] = (f32x4)(0.0f);
-    }
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            acc[rb][e] = (f32x4)(0.0f);
+            if constexpr (TWO_LEVEL) total[rb][e] = (f32x4)(0.0f);
+        }
 
     const float *a_lane = smem + c * kPanelPitch + 4 * g;
-    f32x4 a_frag[2];
+    f32x4 a_frag[2][RB];
     auto read_a = [&](int stage, int s, int set) {
-        a_frag[set] = *reinterpret_cast<const f32x4 *>(a_lane + stage * kPanelStageFloats + 16 * s);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(a_lane + stage * kPanelStageFloats + rb * 16 * kPanelPitch + 16 * s);
     };
-    // A step is eight groups of one load (for the next step, into the other register set) and four independent MFMAs,
+    // A step is eight groups of one load (for the next step, into the other register set) and 4 * RB independent MFMAs,
     // written in the order they are to issue and fenced group by group: left alone, the scheduler sinks the loads to
     // their uses and waits for each in turn.
     auto chunk = [&](int stage) {
@@ -163,8 +170,11 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
                 fetch_one((s + 1) & 1, i);
                 if (i == 0 && s < 3) read_a(stage, s + 1, (s + 1) & 1);
 #pragma unroll
-                for (int e = 4 * (i % 2); e < 4 * (i % 2) + 4; ++e)
-                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][i / 2], bq[s & 1][i / 2][e / 4][e % 4], acc[e], 0, 0, 0);
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int e = 4 * (i % 2); e < 4 * (i % 2) + 4; ++e)
+                        acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][rb][i / 2], bq[s & 1][i / 2][e / 4][e % 4],
+                                                                          acc[rb][e], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
             next_step();
@@ -176,20 +186,28 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     next_step();
     int stage = 0, since_flush = 0;
     for (int j = 0; j < nch; ++j) {
-        if (since_flush == p.flush_tiles) {
-            since_flush = 0;
+        if constexpr (TWO_LEVEL) {
+            if (since_flush == p.flush_tiles) {
+                since_flush = 0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                total[e] += acc[e];
-                acc[e] = (f32x4)(0.0f);
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        total[rb][e] += acc[rb][e];
+                        acc[rb][e] = (f32x4)(0.0f);
+                    }
             }
+            ++since_flush;
         }
-        ++since_flush;
         chunk(stage);
         stage = stage == kPanelStages - 1 ? 0 : stage + 1;
     }
+    if constexpr (TWO_LEVEL) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] += total[e];
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[rb][e] += total[rb][e];
+    }
 
     // Epilogue: registers -> C (or the split-K partial).  Register v of block e: row 4g + v, column 8c + e.
     float *out;
@@ -203,26 +221,29 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     }
     const bool nt = p.splits == 1 && rows_aligned<4>(out, ldo);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int r = m0 + 4 * g + v;
-        if (r >= p.m) continue;
-        float *dst = out + (int64_t)r * ldo;
+    for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int col = q ? col1 : col0;
-            if (col >= p.n) continue;
-            f32x4 o;
+        for (int v = 0; v < 4; ++v) {
+            const int r = m0 + 16 * rb + 4 * g + v;
+            if (r >= p.m) continue;
+            float *dst = out + (int64_t)r * ldo;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = acc[4 * q + e][v];
-            store_result(dst + col, o, nt);
+            for (int q = 0; q < 2; ++q) {
+                const int col = q ? col1 : col0;
+                if (col >= p.n) continue;
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = acc[rb][4 * q + e][v];
+                store_result(dst + col, o, nt);
+            }
         }
     }
 }
 
-template <int NC, int NP>
+template <int NC, int NP, int RB, bool TWO_LEVEL>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s) {
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
-    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
+    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, TWO_LEVEL>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
     return hipGetLastError();
 }
 
