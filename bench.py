@@ -297,7 +297,7 @@ def time_layout(tg, torch, name, m, n, k, layout_a, layout_b, steps, warmup, res
                                         "device_tflops": flops / (p_ms * 1e-3) / 1e12}
         res["parity_ok"] = ok and p_ok
         del ws
-        if csa != 1 or csb != 1:
+        if layout_a.startswith("S") or layout_b.startswith("S"):
             # the library's own choice with room for packed copies and for split-K partial products (a gathered A:
             # row panels with a K split)
             ws = torch.empty(max((tg.strided_workspace_bytes(m, n, k, csa, csb) + tg.workspace_bytes(1, m, n, k)) // 4, 4),

@@ -93,14 +93,19 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
  * tiles ahead ("_ga" / "_gb"): no workspace and no separate pass are involved.  An element-strided
  * operand costs a cache-line request per element and tile that uses it, so the paper's case (1024^3,
  * csa = 32: 128 MiB of lines behind a 4 MiB operand) runs at about 2.5 times the plain product's time.
+ * A strided A with a plain B (k a multiple of 64) is also taken by row-panel variants ("g16x..." / "g32x..."):
+ * a workgroup owns 16 or 32 rows of A and 512 or 1024 columns of B, so an element is requested once or
+ * twice in all; they are chosen where such panels fill the chip by themselves (4096 x 1024 x 1024 at
+ * csa = 32: 133 us against 227 us on tiles) or, with a workspace for the partial products, through a K
+ * split (the paper's 1024^3: 37-39 us against 43-46 us without a workspace).
  * The other form: when a workspace of tg_strided_workspace_bytes(...) is set, each operand with a non-unit
  * stride that more than one tile row or column would fetch can first be gathered into a packed row-major
  * copy in the workspace (one pass, every element fetched once), and the unit-stride kernels multiply the
  * copies; tg_last_config() then ends in "+packA", "+packB" or "+packAB".  It is used for problems the
  * reading variants do not take (other k, a transposed operand off the 16-byte grid), and for
- * element-strided operands when the cost model puts the two passes ahead of the gather, which it does once
- * the strided operand is fetched over several rounds of tiles (2048 x 2048 x 512 at csa = 32: 64 us against
- * 88 us; the paper's 1024^3 stays with the gather, 45 us against 50 us).  Transposed operands on the
+ * element-strided operands when the cost model puts the two passes ahead of the gather, which it does where
+ * no variant gathers sparingly: a strided B fetched by many tile rows (1024^3 at csb = 32: 48 us against
+ * 78 us), a strided A with a k that the row panels do not take.  Transposed operands on the
  * 16-byte grid are never packed.  Without room for the copies the reading variants are used wherever they
  * apply, and the predicated kernels gather element by element otherwise.
  */
