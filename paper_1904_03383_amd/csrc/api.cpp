@@ -570,9 +570,8 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // Row panels of a gathered A (tile_panel_kernel.hpp).  Measured on MI355X: lines that miss L2 arrive at about
         // 5e10 lines/s over the whole chip and 2.4e8 per CU (an element asked for again by another column tile costs
         // about a third of that), B streams through a CU at about 125 GB/s beside the gather and is hidden while the
-        // CU's own request rate is the limit; where the gather is much the longer part the 16x16x4 products hide behind
-        // it, from parity on the producers wait for free stages and half of the shorter part shows; a K range of few
-        // chunks pays its pipeline fill; a K split pays the partial products' way out and back.
+        // CU's own request rate is the limit; the 16x16x4 products run at 93 % of the MFMA rate (1024^3 at stride 2:
+        // 21 us in all); a K range of few chunks pays its pipeline fill; a K split pays the partial products' way out and back.
         // (us, A at element stride 32, 16x1024 / 16x512 / 32x512 / 32x1024 panels: 1024^3 s2 51 38 52 79, s4 43 40 42 56;
         // 2048^3 s1 224 244 229 -, s2 238 249 246 200; 4096x1024x1024 s1 148 141 134 188; 4096x4096x1024 s1 395 425 438 342;
         // 8192x512x1024 s1 238 210 187 222; stride 8, 1024^3: s2 40 28 41 69)
@@ -585,13 +584,22 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double t_cu = per_cu * req * (miss_share + (1.0 - miss_share) / 3.0) / 2.4e8;
         const double t_chip = p.batch * (double)p.m * p.k * line / 128.0 / 5e10;
         const double t_b = per_cu * k_range * (double)std::min<int64_t>(ki.BN, p.n) * 4.0 / 1.25e11;
-        const double t_mem = std::max(t_chip + 0.8 * t_b, t_cu);
-        const double t_mfma = per_cu * 2.0 * ki.BM * ki.BN * k_range / (4.0 * kSimdFlops * 0.85);
+        const double t_gather = std::max(t_chip, t_cu);
+        const double t_mem = std::max(t_chip + 0.8 * t_b, t_cu);      // B's line requests take slots from the gather
+        // (64-column wave tiles: twice the compute waves per SIMD, 2 - 5 % ahead of 128-column ones on every shape swept)
+        const double t_mfma = per_cu * 2.0 * ki.BM * ki.BN * k_range / (4.0 * kSimdFlops * (ki.WN == 64 ? 0.95 : 0.93));
+        const double t_comp = std::max(t_mfma, t_b);                  // B is fetched by the compute waves, behind their MFMAs
         const double fill = 1.0 + ki.BK / k_range;
-        // (share of the shorter part that shows: 0.15 while the products are well below the gather, 0.5 from parity on)
-        const double ratio = t_mfma / std::max(t_mem, 1e-9);
-        const double shown = 0.15 + 0.35 * std::min(1.0, std::max(0.0, (ratio - 0.6) / 0.4));
-        double t = launch + 1e-6 + (std::max(t_mem, t_mfma) + shown * std::min(t_mem, t_mfma)) * fill;
+        // (what shows of the shorter part: half of the gather where the products are longer; where the gather is, 15 % of
+        // the products when they are far shorter and up to 70 % near parity, where the two roles keep waiting for each other)
+        double body;
+        if (t_mem >= t_comp) {
+            const double l = std::log(t_comp / std::max(t_mem, 1e-9));
+            body = t_mem + (0.15 + 0.55 * std::exp(-l * l / (2.0 * 0.35 * 0.35))) * t_comp;
+        } else {
+            body = t_comp + 0.5 * t_gather + 0.25 * std::max(0.0, t_mem - t_gather);
+        }
+        double t = launch + 1e-6 + body * fill;
         if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (2.0 * splits + 1.0) * (double)p.m * p.n / 5e12;
         return t;
     }

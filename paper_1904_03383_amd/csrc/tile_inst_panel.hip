@@ -1,9 +1,12 @@
-// Explicit instantiations: row-panel variants for a gathered A (16 or 32 rows x 128 columns per compute wave).
-// <compute waves, producer waves, 16-row blocks, two_level>
+// Explicit instantiations: row-panel variants for a gathered A.
+// <compute waves, producer waves, 16-row blocks, column groups per lane, two_level>
 #include "tile_panel_kernel.hpp"
 namespace tg {
-template hipError_t launch_tile_panel<8, 4, 1, true>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<4, 4, 1, true>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<4, 4, 2, true>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<8, 4, 2, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 1, 2, true>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 1, 2, true>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 2, 2, true>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 2, false>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 1, true>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 1, 1, true>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 1, 1, true>(const GemmParams &, hipStream_t);
 }  // namespace tg

@@ -11,10 +11,10 @@
 //    stages, two chunks ahead of the product.  Their loads are the only ones they ever wait for, so the
 //    gather queue never drains: a wave that also loaded B would have to wait for its youngest gather
 //    whenever it needs an older B vector (vector-memory results return in order).
-//  * NC compute waves own 16 x 128 of the result each.  B is used by one wave only (a panel has a
-//    single tile row), so it does not go through LDS: per 16-k step a lane fetches two 16-byte vectors
-//    (its 8 adjacent columns) from each of its four k rows into registers, one step ahead of the
-//    MFMAs, and reads its four consecutive k values of A's row with one ds_read_b128.
+//  * NC compute waves own 16 or 32 rows x 64 or 128 columns of the result each.  B is used by one wave
+//    only (a panel has a single tile row), so it does not go through LDS: per 16-k step a lane fetches one
+//    or two 16-byte vectors (its 4 or 8 adjacent columns) from each of its four k rows into registers, one
+//    step ahead of the MFMAs, and reads its four consecutive k values of A's row with one ds_read_b128.
 //  * One barrier per chunk joins the two roles: the producers arrive when the next chunk has landed,
 //    the compute waves when they are done with the previous one (which frees its stage).
 //
@@ -29,16 +29,20 @@ namespace tg {
 
 constexpr int kPanelRows = 16;
 constexpr int kPanelChunk = 64;                    // k per chunk = lanes of one gather instruction
-constexpr int kPanelPitch = kPanelChunk + 4;       // floats per row of a stage: the 16 rows of a fragment read fall in distinct bank groups
+constexpr int kPanelPitch = kPanelChunk + 8;       // floats per row of a stage (measured: 0 bank-conflict cycles on the fragment reads; +4 and +20: half of the LDS cycles)
 constexpr int kPanelStages = 3;
 
-// NC compute waves, NP producer waves, RB blocks of 16 rows per panel (every compute wave owns 16 * RB x 128 of the
-// result and uses a B vector RB times), TWO_LEVEL: second accumulation level for K ranges beyond 1024.
-template <int NC, int NP, int RB, bool TWO_LEVEL>
+// NC compute waves, NP producer waves, RB blocks of 16 rows per panel, NQ groups of four adjacent columns per lane
+// (every compute wave owns 16 * RB x 64 * NQ of the result and uses a B vector RB times), TWO_LEVEL: second
+// accumulation level for K ranges beyond 1024.
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL>
 __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmParams p) {
     constexpr int BM = kPanelRows * RB;
     static_assert(BM % NP == 0, "producer waves share the rows evenly");
-    constexpr int BN = NC * 128;
+    static_assert(NQ == 1 || NQ == 2, "a lane owns four or eight adjacent columns");
+    constexpr int WN = 64 * NQ, BN = NC * WN;
+    constexpr int NE = 4 * NQ;                   // accumulator blocks (of 16 x 16) per row block = columns per lane
+    constexpr int NLD = 4 * NQ;                  // B vectors per lane and 16-k step
     constexpr int ROWS_PER_PRODUCER = BM / NP;
     constexpr int kPanelStageFloats = BM * kPanelPitch;
     __shared__ __attribute__((aligned(16))) float smem[kPanelStages * kPanelStageFloats];
@@ -109,24 +113,28 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 
     // ---- compute --------------------------------------------------------------------------------------
     const int c = lane & 15, g = lane >> 4;
-    const int n0w = n0 + wave * 128;
-    // the lane's two groups of four adjacent columns; a group past the end re-reads the last four columns
+    const int n0w = n0 + wave * WN;
+    // the lane's NQ groups of four adjacent columns; a group past the end re-reads the last four columns
     // (n is a multiple of 4: a group is inside or outside as a whole) and is not stored
-    const int col0 = n0w + 8 * c, col1 = col0 + 4;
     const int last = p.nb - 4;
-    // B is addressed from a wave-uniform row origin (scalar registers, advanced per step) plus two 32-bit byte offsets
-    // per lane (the host checks that 64 rows of B span fewer than 2^30 elements)
+    // B is addressed from a wave-uniform row origin (scalar registers, advanced per step) plus one 32-bit byte offset
+    // per lane and column group (the host checks that 64 rows of B span fewer than 2^30 elements)
     const float *Bg = p.B + (int64_t)prob * p.strideB + k_begin * p.ldb;
-    unsigned off0 = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col0 < last ? col0 : last));
-    unsigned off1 = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col1 < last ? col1 : last));
+    int col[NQ];
+    unsigned off[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        col[q] = n0w + 4 * NQ * c + 4 * q;
+        off[q] = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col[q] < last ? col[q] : last));
+    }
     const int64_t step_b = 16 * p.ldb;
     int steps_left = 4 * nch;                    // 16-k steps not yet fetched
 
-    f32x4 bq[2][4][2];
-    // vector i = 2t + q of a step: k row 4g + t, column group q
+    f32x4 bq[2][4][NQ];
+    // vector i = NQ * t + q of a step: k row 4g + t, column group q
     auto fetch_one = [&](int set, int i) {
-        const float *r = Bg + (int64_t)(i / 2) * p.ldb;
-        bq[set][i / 2][i % 2] = *reinterpret_cast<const f32x4 *>(byte_offset(r, i % 2 ? off1 : off0));
+        const float *r = Bg + (int64_t)(i / NQ) * p.ldb;
+        bq[set][i / NQ][i % NQ] = *reinterpret_cast<const f32x4 *>(byte_offset(r, off[i % NQ]));
     };
     // past the end of the K range the last step is fetched again (in bounds, never multiplied): the number of
     // loads in flight stays the same through the whole loop
@@ -139,11 +147,11 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 
     // two accumulation levels: every flush_tiles chunks the MFMA accumulators are folded into `total`, which bounds the
     // length of any single fp32 running sum (as in the other tile kernels)
-    f32x4 acc[RB][8], total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? 8 : 1];
+    f32x4 acc[RB][NE], total[TWO_LEVEL ? RB : 1][TWO_LEVEL ? NE : 1];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < NE; ++e) {
             acc[rb][e] = (f32x4)(0.0f);
             if constexpr (TWO_LEVEL) total[rb][e] = (f32x4)(0.0f);
         }
@@ -155,7 +163,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         for (int rb = 0; rb < RB; ++rb)
             a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(a_lane + stage * kPanelStageFloats + rb * 16 * kPanelPitch + 16 * s);
     };
-    // A step is eight groups of one load (for the next step, into the other register set) and 4 * RB independent MFMAs,
+    // A step is 4 * NQ groups of one load (for the next step, into the other register set) and 4 * RB independent MFMAs,
     // written in the order they are to issue and fenced group by group: left alone, the scheduler sinks the loads to
     // their uses and waits for each in turn.
     auto chunk = [&](int stage) {
@@ -166,14 +174,14 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < NLD; ++i) {
                 fetch_one((s + 1) & 1, i);
                 if (i == 0 && s < 3) read_a(stage, s + 1, (s + 1) & 1);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                    for (int e = 4 * (i % 2); e < 4 * (i % 2) + 4; ++e)
-                        acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][rb][i / 2], bq[s & 1][i / 2][e / 4][e % 4],
+                    for (int e = 4 * (i % NQ); e < 4 * (i % NQ) + 4; ++e)
+                        acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][rb][i / NQ], bq[s & 1][i / NQ][e / 4][e % 4],
                                                                           acc[rb][e], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -182,7 +190,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     };
 
 #pragma unroll
-    for (int i = 0; i < 8; ++i) fetch_one(0, i);
+    for (int i = 0; i < NLD; ++i) fetch_one(0, i);
     next_step();
     int stage = 0, since_flush = 0;
     for (int j = 0; j < nch; ++j) {
@@ -192,7 +200,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
+                    for (int e = 0; e < NE; ++e) {
                         total[rb][e] += acc[rb][e];
                         acc[rb][e] = (f32x4)(0.0f);
                     }
@@ -206,10 +214,10 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[rb][e] += total[rb][e];
+            for (int e = 0; e < NE; ++e) acc[rb][e] += total[rb][e];
     }
 
-    // Epilogue: registers -> C (or the split-K partial).  Register v of block e: row 4g + v, column 8c + e.
+    // Epilogue: registers -> C (or the split-K partial).  Register v of block e: row 4g + v, column 4 * NQ * c + e.
     float *out;
     int64_t ldo;
     if (p.splits > 1) {
@@ -228,22 +236,21 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
             if (r >= p.m) continue;
             float *dst = out + (int64_t)r * ldo;
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int col = q ? col1 : col0;
-                if (col >= p.n) continue;
+            for (int q = 0; q < NQ; ++q) {
+                if (col[q] >= p.n) continue;
                 f32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = acc[rb][4 * q + e][v];
-                store_result(dst + col, o, nt);
+                store_result(dst + col[q], o, nt);
             }
         }
     }
 }
 
-template <int NC, int NP, int RB, bool TWO_LEVEL>
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s) {
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
-    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, TWO_LEVEL>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
+    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
     return hipGetLastError();
 }
 

@@ -79,6 +79,7 @@ def test_variant_list_is_not_empty():
     "d128x128x32_w64x64_acc2_st3_ga_tb", "d64x64x32_w32x32_acc2_st4_ta_gb", "d128x128x32_w64x64_acc2_st3_ta_gb",
     "d16x256x32_w16x64_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga",
     "g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
+    "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga",
     "d64x64x32_w32x32_acc2_tf_ta", "d64x64x32_w32x32_acc2_tf_tb", "d64x64x32_w32x32_acc2_tf_ta_tb",
     "d64x64x32_w32x32_acc2_tf_ga", "d64x64x32_w32x32_acc2_tf_gb")])
 def test_every_variant_forced(name):
@@ -152,7 +153,8 @@ def test_fused_variant_is_preferred_to_packing_when_a_workspace_is_set():
     del ws
 
 
-PANELS = ["g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga"]
+PANELS = ["g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
+          "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga"]
 
 
 @pytest.mark.parametrize("name", PANELS)
