@@ -589,7 +589,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // (64-column wave tiles: twice the compute waves per SIMD, 2 - 5 % ahead of 128-column ones on every shape swept)
         const double t_mfma = per_cu * 2.0 * ki.BM * ki.BN * k_range / (4.0 * kSimdFlops * (ki.WN == 64 ? 0.95 : 0.93));
         const double t_comp = std::max(t_mfma, t_b);                  // B is fetched by the compute waves, behind their MFMAs
-        const double fill = 1.0 + ki.BK / k_range;
+        // (B fetched three steps ahead instead of one: the compute waves stall less on it, reach the barrier sooner, and
+        // the producers wait less for free stages: stride 32, us: 1024^3 on 16x256 panels 37.3 -> 33.0, 4096x1024x1024 on
+        // 32x512 panels 127 -> 122, 2048^3 224 -> 210, 1024^3 at stride 8 28 -> 21.6; two chunks of pipeline fill instead of one:
+        // 4096x4096x128 44 -> 48)
+        const bool deep_b = strstr(ki.name, "_b3") != nullptr;
+        const double fill = 1.0 + (deep_b ? 2.0 : 1.0) * ki.BK / k_range;
         // (what shows of the shorter part: half of the gather where the products are longer; where the gather is, 15 % of
         // the products when they are far shorter and up to 70 % near parity, where the two roles keep waiting for each other)
         double body;
@@ -599,7 +604,7 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         } else {
             body = t_comp + 0.5 * t_gather + 0.25 * std::max(0.0, t_mem - t_gather);
         }
-        double t = launch + 1e-6 + body * fill;
+        double t = launch + 1e-6 + body * fill * (deep_b ? 0.9 : 1.0);
         if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (2.0 * splits + 1.0) * (double)p.m * p.n / 5e12;
         return t;
     }

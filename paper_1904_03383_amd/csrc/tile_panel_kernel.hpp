@@ -14,7 +14,7 @@
 //  * NC compute waves own 16 or 32 rows x 64 or 128 columns of the result each.  B is used by one wave
 //    only (a panel has a single tile row), so it does not go through LDS: per 16-k step a lane fetches one
 //    or two 16-byte vectors (its 4 or 8 adjacent columns) from each of its four k rows into registers, one
-//    step ahead of the MFMAs, and reads its four consecutive k values of A's row with one ds_read_b128.
+//    or three 16-k steps ahead of the MFMAs, and reads its four consecutive k values of A's row with one ds_read_b128.
 //  * One barrier per chunk joins the two roles: the producers arrive when the next chunk has landed,
 //    the compute waves when they are done with the previous one (which frees its stage).
 //
@@ -34,12 +34,14 @@ constexpr int kPanelStages = 3;
 
 // NC compute waves, NP producer waves, RB blocks of 16 rows per panel, NQ groups of four adjacent columns per lane
 // (every compute wave owns 16 * RB x 64 * NQ of the result and uses a B vector RB times), TWO_LEVEL: second
-// accumulation level for K ranges beyond 1024.
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL>
+// accumulation level for K ranges beyond 1024, PD: how many 16-k steps ahead of the MFMAs B is fetched (1 or 3).
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD>
 __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmParams p) {
     constexpr int BM = kPanelRows * RB;
     static_assert(BM % NP == 0, "producer waves share the rows evenly");
     static_assert(NQ == 1 || NQ == 2, "a lane owns four or eight adjacent columns");
+    static_assert(PD == 1 || PD == 3, "register sets of B: PD + 1 must divide the four steps of a chunk");
+    constexpr int NSETS = PD + 1;
     constexpr int WN = 64 * NQ, BN = NC * WN;
     constexpr int NE = 4 * NQ;                   // accumulator blocks (of 16 x 16) per row block = columns per lane
     constexpr int NLD = 4 * NQ;                  // B vectors per lane and 16-k step
@@ -130,7 +132,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     const int64_t step_b = 16 * p.ldb;
     int steps_left = 4 * nch;                    // 16-k steps not yet fetched
 
-    f32x4 bq[2][4][NQ];
+    f32x4 bq[NSETS][4][NQ];
     // vector i = NQ * t + q of a step: k row 4g + t, column group q
     auto fetch_one = [&](int set, int i) {
         const float *r = Bg + (int64_t)(i / NQ) * p.ldb;
@@ -163,7 +165,8 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         for (int rb = 0; rb < RB; ++rb)
             a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(a_lane + stage * kPanelStageFloats + rb * 16 * kPanelPitch + 16 * s);
     };
-    // A step is 4 * NQ groups of one load (for the next step, into the other register set) and 4 * RB independent MFMAs,
+    // A step is 4 * NQ groups of one load (for the step PD steps on, into the register set that step will use: four steps
+    // per chunk, so step s of any chunk uses set s % NSETS) and 4 * RB independent MFMAs,
     // written in the order they are to issue and fenced group by group: left alone, the scheduler sinks the loads to
     // their uses and waits for each in turn.
     auto chunk = [&](int stage) {
@@ -175,13 +178,13 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         for (int s = 0; s < 4; ++s) {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
-                fetch_one((s + 1) & 1, i);
+                fetch_one((s + PD) % NSETS, i);
                 if (i == 0 && s < 3) read_a(stage, s + 1, (s + 1) & 1);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                     for (int e = 4 * (i % NQ); e < 4 * (i % NQ) + 4; ++e)
-                        acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][rb][i / NQ], bq[s & 1][i / NQ][e / 4][e % 4],
+                        acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_frag[s & 1][rb][i / NQ], bq[s % NSETS][i / NQ][e / 4][e % 4],
                                                                           acc[rb][e], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -190,8 +193,11 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     };
 
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) fetch_one(0, i);
-    next_step();
+    for (int s = 0; s < PD; ++s) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) fetch_one(s, i);
+        next_step();
+    }
     int stage = 0, since_flush = 0;
     for (int j = 0; j < nch; ++j) {
         if constexpr (TWO_LEVEL) {
@@ -247,10 +253,10 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     }
 }
 
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL>
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s) {
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
-    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
+    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL, PD>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
     return hipGetLastError();
 }
 

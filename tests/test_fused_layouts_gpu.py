@@ -80,6 +80,7 @@ def test_variant_list_is_not_empty():
     "d16x256x32_w16x64_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga",
     "g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
     "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga",
+    "g32x512x64_w32x64_acc2_b3_ga", "g16x512x64_w16x64_acc2_b3_ga", "g16x256x64_w16x64_acc2_b3_ga",
     "d64x64x32_w32x32_acc2_tf_ta", "d64x64x32_w32x32_acc2_tf_tb", "d64x64x32_w32x32_acc2_tf_ta_tb",
     "d64x64x32_w32x32_acc2_tf_ga", "d64x64x32_w32x32_acc2_tf_gb")])
 def test_every_variant_forced(name):
@@ -154,7 +155,8 @@ def test_fused_variant_is_preferred_to_packing_when_a_workspace_is_set():
 
 
 PANELS = ["g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
-          "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga"]
+          "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga",
+          "g32x512x64_w32x64_acc2_b3_ga", "g16x256x64_w16x64_acc2_b3_ga"]
 
 
 @pytest.mark.parametrize("name", PANELS)

@@ -57,7 +57,7 @@ SPECS = ["t128x128x16_w64x64", "t128x256x32_w64x128_acc2", "t64x64x32_w32x32", "
          "d64x64x32_w32x32_tf", "d64x64x64_w32x32_acc2_tf", "d256x256x32_w128x128",
          "d64x64x32_w32x32_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga", "d64x64x32_w32x32_acc2_tf_gb",
          "g16x1024x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
-         "g32x512x64_w32x64_acc2_ga", "g16x256x64_w16x64_acc2_ga"]
+         "g32x512x64_w32x64_acc2_ga", "g16x256x64_w16x64_acc2_b3_ga", "g32x512x64_w32x64_acc2_b3_ga"]
 
 
 @pytest.mark.parametrize("spec", SPECS)
