@@ -92,11 +92,11 @@ tg_status tg_sgemm_batched(int64_t batch, int64_t m, int64_t n, int64_t k,
  * other strides are gathered element by element straight into the kernel's staging memory, several K
  * tiles ahead ("_ga" / "_gb"): no workspace and no separate pass are involved.  An element-strided
  * operand costs a cache-line request per element and tile that uses it, so the paper's case (1024^3,
- * csa = 32: 128 MiB of lines behind a 4 MiB operand) runs at about twice the plain product's time.
+ * csa = 32: 128 MiB of lines behind a 4 MiB operand) runs at about 1.8 times the plain product's time.
  * A strided A with a plain B (k a multiple of 64) is taken by row-panel variants ("g16x..." / "g32x..."):
  * a workgroup owns 16 or 32 rows of A and 256 to 1024 columns of B, so an element is requested once per
- * 256 ... 1024 columns, by waves that do nothing else (the paper's 1024^3: 37-39 us; 4096 x 1024 x 1024 at
- * csa = 32: 128 us against 227 us on tiles); with a workspace for partial products they can also split K.
+ * 256 ... 1024 columns, by waves that do nothing else (the paper's 1024^3: 33 us; 4096 x 1024 x 1024 at
+ * csa = 32: 122 us against 227 us on tiles); with a workspace for partial products they can also split K.
  * The other form: when a workspace of tg_strided_workspace_bytes(...) is set, each operand with a non-unit
  * stride that more than one tile row or column would fetch can first be gathered into a packed row-major
  * copy in the workspace (one pass, every element fetched once), and the unit-stride kernels multiply the
