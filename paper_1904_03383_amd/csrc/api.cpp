@@ -605,6 +605,7 @@ double heuristic_seconds(const Problem &p, const Config &c) {
             body = t_comp + 0.5 * t_gather + 0.25 * std::max(0.0, t_mem - t_gather);
         }
         double t = launch + 1e-6 + body * fill * (deep_b ? 0.9 : 1.0);
+        if (p.a_class() == 0) t *= 1.15;     // plain operands: behind the tile kernels until the tuner has timed both
         if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (2.0 * splits + 1.0) * (double)p.m * p.n / 5e12;
         return t;
     }
@@ -713,7 +714,13 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             if (kinfo.pieces && g_math != TG_MATH_BF16_PIECES) continue;   // only on request
             // a variant that gathers or reads a transposed operand is offered for operands that lie that way (it is
             // valid, and can be forced, for anything it can read: a gather takes plain rows too, only slower)
-            if ((kinfo.amode || kinfo.bmode) && (kinfo.amode != p.a_class() || kinfo.bmode != p.b_class())) continue;
+            // (the row-panel kernels are also offered on plain operands, which their 4-byte gather reads as well: measured
+            // on a par with the tile kernels on mid-size products and up to 5 % ahead, 2048^3 120 us against 127 us; the
+            // cost model keeps them behind untuned, the tuner times them.  Only the forms with B three steps ahead,
+            // and only where K is long enough for their pipeline)
+            const bool panel_on_plain = kinfo.name[0] == 'g' && p.a_class() == 0 && p.b_class() == 0 && p.aligned &&
+                                        strstr(kinfo.name, "_b3") && p.k >= 512 && s == 1;
+            if (!panel_on_plain && (kinfo.amode || kinfo.bmode) && (kinfo.amode != p.a_class() || kinfo.bmode != p.b_class())) continue;
             if (kinfo.amode == 2) c.group = 1;            // a gathered A: the tiles that share a row panel of A run side by side
             else if (kinfo.bmode == 2) c.group = 64;      // a gathered B: those that share a column panel of B
             if (kinfo.kind == tg::KIND_TILE && kinfo.two_level && kinfo.amode == 0 && kinfo.bmode == 0) {

@@ -1,15 +1,18 @@
 // Explicit instantiations: row-panel variants for a gathered A.
-// <compute waves, producer waves, 16-row blocks, column groups per lane, two_level, steps of B in flight>
+// <compute waves, producer waves, 16-row blocks, column groups per lane, two_level, steps of B in flight, chunk / 64>
 #include "tile_panel_kernel.hpp"
 namespace tg {
-template hipError_t launch_tile_panel<8, 4, 1, 2, true, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<4, 4, 1, 2, true, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<4, 4, 2, 2, true, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<8, 4, 2, 2, false, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<8, 4, 2, 1, true, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<8, 4, 1, 1, true, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<4, 4, 1, 1, true, 1>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<8, 4, 2, 1, true, 3>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<8, 4, 1, 1, true, 3>(const GemmParams &, hipStream_t);
-template hipError_t launch_tile_panel<4, 4, 1, 1, true, 3>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 1, 2, true, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 1, 2, true, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 2, 2, true, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 2, false, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 1, true, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 1, 1, true, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 1, 1, true, 1, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 1, true, 3, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 1, 1, true, 3, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 1, 1, true, 3, 1>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 1, true, 3, 2>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<4, 4, 1, 1, true, 3, 2>(const GemmParams &, hipStream_t);
+template hipError_t launch_tile_panel<8, 4, 2, 1, true, 3, 4>(const GemmParams &, hipStream_t);
 }  // namespace tg

@@ -6,8 +6,8 @@
 // K split (partial products meet in the split-K reduction) where 16-row panels alone are too few.
 //
 // Roles inside a workgroup (the BLOCK / THREAD mapping of Sec. 4, with the SHARED temporary for A only):
-//  * NP producer waves do nothing but gather.  Per chunk of 64 k each fetches its rows of the panel,
-//    one 4-byte direct-to-LDS load per row (lane l fetches element k0 + l), into a ring of three LDS
+//  * NP producer waves do nothing but gather.  Per chunk of 64, 128 or 256 k each fetches its rows of the panel,
+//    one 4-byte direct-to-LDS load per row and 64 k (lane l fetches element k0 + l), into a ring of three LDS
 //    stages, two chunks ahead of the product.  Their loads are the only ones they ever wait for, so the
 //    gather queue never drains: a wave that also loaded B would have to wait for its youngest gather
 //    whenever it needs an older B vector (vector-memory results return in order).
@@ -28,17 +28,23 @@
 namespace tg {
 
 constexpr int kPanelRows = 16;
-constexpr int kPanelChunk = 64;                    // k per chunk = lanes of one gather instruction
-constexpr int kPanelPitch = kPanelChunk + 8;       // floats per row of a stage (measured: 0 bank-conflict cycles on the fragment reads; +4 and +20: half of the LDS cycles)
+// s_waitcnt operand that waits until at most n vector-memory operations are outstanding and for nothing else
+// (gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all ones = not waited for)
+constexpr int panel_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 constexpr int kPanelStages = 3;
 
 // NC compute waves, NP producer waves, RB blocks of 16 rows per panel, NQ groups of four adjacent columns per lane
 // (every compute wave owns 16 * RB x 64 * NQ of the result and uses a B vector RB times), TWO_LEVEL: second
-// accumulation level for K ranges beyond 1024, PD: how many 16-k steps ahead of the MFMAs B is fetched (1 or 3).
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD>
+// accumulation level for K ranges beyond 1024, PD: how many 16-k steps ahead of the MFMAs B is fetched (1 or 3), CW: k per
+// chunk in units of 64 (the lanes of one gather instruction): a producer fills a row of a chunk with CW instructions.
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD, int CW>
 __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmParams p) {
+    constexpr int kPanelChunk = 64 * CW;
+    constexpr int kPanelPitch = kPanelChunk + 8;       // floats per row of a stage (measured at 72: 0 bank-conflict cycles on the fragment reads; 68 and 84: half of the LDS cycles)
+    constexpr int STEPS = 4 * CW;                      // 16-k steps per chunk
     constexpr int BM = kPanelRows * RB;
     static_assert(BM % NP == 0, "producer waves share the rows evenly");
+    static_assert(BM / NP * CW <= 63, "the gather instructions of one chunk must fit the wait counter");
     static_assert(NQ == 1 || NQ == 2, "a lane owns four or eight adjacent columns");
     static_assert(PD == 1 || PD == 3, "register sets of B: PD + 1 must divide the four steps of a chunk");
     constexpr int NSETS = PD + 1;
@@ -80,14 +86,17 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 #pragma unroll
             for (int i = 0; i < ROWS_PER_PRODUCER; ++i) {
                 const int r = pw * ROWS_PER_PRODUCER + i;
-                direct_load<1>(byte_offset(row[i], lane_bytes), smem + stage * kPanelStageFloats + r * kPanelPitch);
+#pragma unroll
+                for (int w = 0; w < CW; ++w)
+                    direct_load<1>(byte_offset(row[i] + (int64_t)(64 * w) * p.csa, lane_bytes),
+                                   smem + stage * kPanelStageFloats + r * kPanelPitch + 64 * w);
                 row[i] += step;
             }
         };
 #ifdef TG_POISON_LDS
         for (int s = 0; s < kPanelStages; ++s)
             for (int i = 0; i < ROWS_PER_PRODUCER; ++i)
-                smem[s * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + lane] = __builtin_nanf("");
+                for (int w = 0; w < CW; ++w) smem[s * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + 64 * w + lane] = __builtin_nanf("");
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
 #endif
         gather(0);
@@ -95,7 +104,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         int stage_free = 2;                      // where chunk j + 2 goes
         for (int j = 0; j < nch; ++j) {
             // chunk j has landed (the chunk after it may still be on its way)
-            if (j + 1 < nch) __builtin_amdgcn_s_waitcnt(0x0F70 | ROWS_PER_PRODUCER);   // vmcnt(one chunk's loads)
+            if (j + 1 < nch) __builtin_amdgcn_s_waitcnt(panel_vmcnt(ROWS_PER_PRODUCER * CW));   // vmcnt(one chunk's loads)
             else __builtin_amdgcn_s_waitcnt(0x0F70);                                   // vmcnt(0)
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();        // #j: chunk j may be read; nobody reads chunk j - 1 any more
@@ -103,7 +112,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
             if (j + 2 < nch) {
 #ifdef TG_POISON_LDS
                 for (int i = 0; i < ROWS_PER_PRODUCER; ++i)
-                    smem[stage_free * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + lane] = __builtin_nanf("");
+                    for (int w = 0; w < CW; ++w) smem[stage_free * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + 64 * w + lane] = __builtin_nanf("");
                 __builtin_amdgcn_s_waitcnt(0xC07F);
 #endif
                 gather(stage_free);
@@ -130,7 +139,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         off[q] = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col[q] < last ? col[q] : last));
     }
     const int64_t step_b = 16 * p.ldb;
-    int steps_left = 4 * nch;                    // 16-k steps not yet fetched
+    int steps_left = STEPS * nch;                    // 16-k steps not yet fetched
 
     f32x4 bq[NSETS][4][NQ];
     // vector i = NQ * t + q of a step: k row 4g + t, column group q
@@ -165,8 +174,8 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         for (int rb = 0; rb < RB; ++rb)
             a_frag[set][rb] = *reinterpret_cast<const f32x4 *>(a_lane + stage * kPanelStageFloats + rb * 16 * kPanelPitch + 16 * s);
     };
-    // A step is 4 * NQ groups of one load (for the step PD steps on, into the register set that step will use: four steps
-    // per chunk, so step s of any chunk uses set s % NSETS) and 4 * RB independent MFMAs,
+    // A step is 4 * NQ groups of one load (for the step PD steps on, into the register set that step will use: the steps
+    // per chunk are a multiple of the sets, so step s of any chunk uses set s % NSETS) and 4 * RB independent MFMAs,
     // written in the order they are to issue and fenced group by group: left alone, the scheduler sinks the loads to
     // their uses and waits for each in turn.
     auto chunk = [&](int stage) {
@@ -175,11 +184,11 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         __builtin_amdgcn_sched_barrier(0);
         read_a(stage, 0, 0);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < STEPS; ++s) {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 fetch_one((s + PD) % NSETS, i);
-                if (i == 0 && s < 3) read_a(stage, s + 1, (s + 1) & 1);
+                if (i == 0 && s < STEPS - 1) read_a(stage, s + 1, (s + 1) & 1);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -253,10 +262,10 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     }
 }
 
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD>
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD, int CW>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s) {
     const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
-    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL, PD>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
+    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL, PD, CW>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
     return hipGetLastError();
 }
 

@@ -81,6 +81,7 @@ def test_variant_list_is_not_empty():
     "g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
     "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga",
     "g32x512x64_w32x64_acc2_b3_ga", "g16x512x64_w16x64_acc2_b3_ga", "g16x256x64_w16x64_acc2_b3_ga",
+    "g32x512x128_w32x64_acc2_b3_ga", "g16x256x128_w16x64_acc2_b3_ga", "g32x512x256_w32x64_acc2_b3_ga",
     "d64x64x32_w32x32_acc2_tf_ta", "d64x64x32_w32x32_acc2_tf_tb", "d64x64x32_w32x32_acc2_tf_ta_tb",
     "d64x64x32_w32x32_acc2_tf_ga", "d64x64x32_w32x32_acc2_tf_gb")])
 def test_every_variant_forced(name):
@@ -156,7 +157,8 @@ def test_fused_variant_is_preferred_to_packing_when_a_workspace_is_set():
 
 PANELS = ["g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
           "g32x512x64_w32x64_acc2_ga", "g16x512x64_w16x64_acc2_ga", "g16x256x64_w16x64_acc2_ga",
-          "g32x512x64_w32x64_acc2_b3_ga", "g16x256x64_w16x64_acc2_b3_ga"]
+          "g32x512x64_w32x64_acc2_b3_ga", "g16x256x64_w16x64_acc2_b3_ga", "g32x512x128_w32x64_acc2_b3_ga",
+          "g32x512x256_w32x64_acc2_b3_ga"]
 
 
 @pytest.mark.parametrize("name", PANELS)
@@ -164,9 +166,10 @@ PANELS = ["g16x1024x64_w16x128_acc2_ga", "g16x512x64_w16x128_acc2_ga", "g32x512x
 def test_row_panel_variants_with_a_k_split(name, splits):
     """The row-panel kernels fill the chip through a K split when the panels alone are too few: partial products in
     the workspace, added by the reduction in a fixed order.  Ragged rows, a partly used last column tile, K ranges
-    of unequal length (13 chunks over 3 or 4 ranges)."""
+    of unequal length (13 chunks over 2, 3 or 4 ranges)."""
     import torch
-    for (m, n, k, stride) in [(1000, 1024, 1024, 32), (73, 1060, 832, 3)]:
+    bk = _tile(name)[2]
+    for (m, n, k, stride) in [(1000, 1024, max(1024, 8 * bk), 32), (73, 1060, 13 * bk, 3)]:
         ws = torch.full((4 * m * n + 64,), float("nan"), device="cuda")
         tg.set_workspace(ws)
         for dist in ("normal", "int"):
@@ -188,7 +191,7 @@ def test_row_panel_variants_on_a_batch_of_plain_operands(name):
     """A gather reads plain rows too: forced on a batch through tg_sgemm_batched (problem strides, padded leading
     dimensions, rows of C off the 16-byte grid)."""
     import torch
-    batch, m, n, k = 3, 50, 1028, 192
+    batch, m, n, k = 3, 50, 1028, 3 * _tile(name)[2]
     say(f"forced {name} on a batch {batch} x {m}x{n}x{k}")
     a = ig.small_int(751, (batch, m, k + 4))
     b = ig.small_int(752, (batch, k, n + 8))
