@@ -451,6 +451,12 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
                                 : "k is not a multiple of the K tile");
         if (ki.bmode == 0 && p.b_cols() % 4) return no("n is not a multiple of 4");
         if (ki.persistent && (p.m % ki.BM || p.n % ki.BN)) return no("sizes are not multiples of the tile");
+        if (ki.persistent && ki.name[0] == 'g') {
+            // a workgroup walks tiles / workgroups neighbouring column tiles of one row panel
+            const int64_t tiles = (p.m / ki.BM) * (p.n / ki.BN), wgs = (int64_t)c.persist * kNumCUs;
+            if (p.batch != 1 || c.splits != 1) return no("the walking row-panel variants take one problem and one K range");
+            if (tiles % wgs || (p.n / ki.BN) % (tiles / wgs)) return no("the tiles of a row panel do not divide evenly over the workgroups");
+        }
         if (ki.defer) {
             const int cb = ki.WN / 32;   // floats per store
             if (c.splits != 1) return no("this variant has no split-K");
@@ -594,7 +600,9 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // 32x512 panels 127 -> 122, 2048^3 224 -> 210, 1024^3 at stride 8 28 -> 21.6; two chunks of pipeline fill instead of one:
         // 4096x4096x128 44 -> 48)
         const bool deep_b = strstr(ki.name, "_b3") != nullptr;
-        const double fill = 1.0 + (deep_b ? 2.0 : 1.0) * ki.BK / k_range;
+        // (a workgroup that walks several tiles of its row panel fills its pipeline once for all of them)
+        const double walked = ki.persistent && c.persist > 0 ? std::max(1.0, blocks / ((double)c.persist * kNumCUs)) : 1.0;
+        const double fill = 1.0 + (deep_b ? 2.0 : 1.0) * ki.BK / (k_range * walked);
         // (what shows of the shorter part: half of the gather where the products are longer; where the gather is, 15 % of
         // the products when they are far shorter and up to 70 % near parity, where the two roles keep waiting for each other)
         double body;
@@ -708,7 +716,7 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             c.kernel = ki;
             c.splits = s;
             c.group = kDefaultGroup;
-            c.persist = tg::kernel(ki).persistent ? 2 : 0;
+            c.persist = tg::kernel(ki).persistent ? (tg::kernel(ki).name[0] == 'g' ? 1 : 2) : 0;   // workgroups per CU
             if (!config_valid(p, c, ws_bytes)) continue;
             const KernelInfo &kinfo = tg::kernel(ki);
             if (kinfo.pieces && g_math != TG_MATH_BF16_PIECES) continue;   // only on request
@@ -718,8 +726,10 @@ std::vector<Config> candidates(const Problem &p, size_t ws_bytes) {
             // on a par with the tile kernels on mid-size products and up to 5 % ahead, 2048^3 120 us against 127 us; the
             // cost model keeps them behind untuned, the tuner times them.  Only the forms with B three steps ahead,
             // and only where K is long enough for their pipeline)
-            const bool panel_on_plain = kinfo.name[0] == 'g' && p.a_class() == 0 && p.b_class() == 0 && p.aligned &&
-                                        strstr(kinfo.name, "_b3") && p.k >= 512 && s == 1;
+            // (... or, for a short K, the forms in which a workgroup walks along its row panel: 4096x4096x128 37.2 us
+            // against 38.7 us for the best tile kernel)
+            const bool panel_on_plain = kinfo.name[0] == 'g' && p.a_class() == 0 && p.b_class() == 0 && p.aligned && s == 1 &&
+                                        (kinfo.persistent ? p.k <= 512 : (strstr(kinfo.name, "_b3") && p.k >= 512));
             if (!panel_on_plain && (kinfo.amode || kinfo.bmode) && (kinfo.amode != p.a_class() || kinfo.bmode != p.b_class())) continue;
             if (kinfo.amode == 2) c.group = 1;            // a gathered A: the tiles that share a row panel of A run side by side
             else if (kinfo.bmode == 2) c.group = 64;      // a gathered B: those that share a column panel of B
@@ -1295,6 +1305,9 @@ class Tuner {
     // Times `c`, records it and makes it the leader when it beats the best by `margin`.  `check`: a kernel variant not
     // seen before, whose product is compared with the reference first (the refinements re-run a variant that passed).
     void consider(const Config &c, double margin, bool check = false) {
+        // (the refinements vary one parameter of a valid configuration; not every value stays valid: the walking
+        // row-panel variants need the tiles to divide over the workgroups)
+        if (!config_valid(p_, c, ws_bytes_)) return;
         double us = 0;
         if (time_briefly(c, &us) != TG_OK) {
             last_err_ = t_error;

@@ -120,26 +120,34 @@ TG_MI16_LIST(TG_M16DECL)
 // row panels of a gathered A: 16 rows by up to 1024 columns per workgroup, so that an element of A (a cache line of its
 // own at a large stride) is requested once per 1024 columns; with few tile rows a K split fills the chip
 // (compute waves, producer waves, 16-row blocks, column groups of four per lane, two_level, steps of B in flight,
-// k per chunk / 64, name)
+// k per chunk / 64, persistent walk along a row panel, name)
 #define TG_PANEL_LIST(X)                                       \
-    X(8, 4, 1, 2, true, 1, 1, "g16x1024x64_w16x128_acc2_ga")      \
-    X(4, 4, 1, 2, true, 1, 1, "g16x512x64_w16x128_acc2_ga")       \
-    X(4, 4, 2, 2, true, 1, 1, "g32x512x64_w32x128_acc2_ga")       \
-    X(8, 4, 2, 2, false, 1, 1, "g32x1024x64_w32x128_ga")          \
-    X(8, 4, 2, 1, true, 1, 1, "g32x512x64_w32x64_acc2_ga")        \
-    X(8, 4, 1, 1, true, 1, 1, "g16x512x64_w16x64_acc2_ga")        \
-    X(4, 4, 1, 1, true, 1, 1, "g16x256x64_w16x64_acc2_ga")        \
-    X(8, 4, 2, 1, true, 3, 1, "g32x512x64_w32x64_acc2_b3_ga")     \
-    X(8, 4, 1, 1, true, 3, 1, "g16x512x64_w16x64_acc2_b3_ga")     \
-    X(4, 4, 1, 1, true, 3, 1, "g16x256x64_w16x64_acc2_b3_ga")     \
-    X(8, 4, 2, 1, true, 3, 2, "g32x512x128_w32x64_acc2_b3_ga")    \
-    X(4, 4, 1, 1, true, 3, 2, "g16x256x128_w16x64_acc2_b3_ga")    \
-    X(8, 4, 2, 1, true, 3, 4, "g32x512x256_w32x64_acc2_b3_ga")
-#define TG_GDECL(NC, NP, RB, NQ, L2, PD, CW, NAME) \
-    extern template hipError_t launch_tile_panel<NC, NP, RB, NQ, L2, PD, CW>(const GemmParams &, hipStream_t);
-#define TG_GROW(NC, NP, RB, NQ, L2, PD, CW, NAME)                                                                   \
-    {NAME, KIND_TILE, 16 * RB, NC * 64 * NQ, 64 * CW, 16 * RB, 64 * NQ, L2, false, false, false, (NC + NP) * 64, 3 * 16 * RB * (64 * CW + 8) * 4, \
-     &launch_tile_panel<NC, NP, RB, NQ, L2, PD, CW>, 0, false, 0, false, 2, 0},
+    X(8, 4, 1, 2, true, 1, 1, false, "g16x1024x64_w16x128_acc2_ga")      \
+    X(4, 4, 1, 2, true, 1, 1, false, "g16x512x64_w16x128_acc2_ga")       \
+    X(4, 4, 2, 2, true, 1, 1, false, "g32x512x64_w32x128_acc2_ga")       \
+    X(8, 4, 2, 2, false, 1, 1, false, "g32x1024x64_w32x128_ga")          \
+    X(8, 4, 2, 1, true, 1, 1, false, "g32x512x64_w32x64_acc2_ga")        \
+    X(8, 4, 1, 1, true, 1, 1, false, "g16x512x64_w16x64_acc2_ga")        \
+    X(4, 4, 1, 1, true, 1, 1, false, "g16x256x64_w16x64_acc2_ga")        \
+    X(8, 4, 2, 1, true, 3, 1, false, "g32x512x64_w32x64_acc2_b3_ga")     \
+    X(8, 4, 1, 1, true, 3, 1, false, "g16x512x64_w16x64_acc2_b3_ga")     \
+    X(4, 4, 1, 1, true, 3, 1, false, "g16x256x64_w16x64_acc2_b3_ga")     \
+    X(8, 4, 2, 1, true, 3, 2, false, "g32x512x128_w32x64_acc2_b3_ga")    \
+    X(4, 4, 1, 1, true, 3, 2, false, "g16x256x128_w16x64_acc2_b3_ga")    \
+    X(8, 4, 2, 1, true, 3, 4, false, "g32x512x256_w32x64_acc2_b3_ga")    \
+    X(8, 4, 1, 1, true, 1, 1, true, "g16x512x64_w16x64_acc2_rw_ga")      \
+    X(8, 4, 2, 1, true, 1, 1, true, "g32x512x64_w32x64_acc2_rw_ga")      \
+    X(4, 4, 1, 1, true, 1, 1, true, "g16x256x64_w16x64_acc2_rw_ga")      \
+    X(8, 4, 2, 1, true, 3, 2, true, "g32x512x128_w32x64_acc2_b3_rw_ga")  \
+    X(8, 4, 2, 1, false, 1, 1, true, "g32x512x64_w32x64_rw_ga")          \
+    X(8, 4, 2, 1, false, 3, 1, true, "g32x512x64_w32x64_b3_rw_ga")       \
+    X(8, 4, 1, 1, false, 3, 1, true, "g16x512x64_w16x64_b3_rw_ga")       \
+    X(8, 4, 2, 1, true, 3, 1, true, "g32x512x64_w32x64_acc2_b3_rw_ga")
+#define TG_GDECL(NC, NP, RB, NQ, L2, PD, CW, RW, NAME) \
+    extern template hipError_t launch_tile_panel<NC, NP, RB, NQ, L2, PD, CW, RW>(const GemmParams &, hipStream_t);
+#define TG_GROW(NC, NP, RB, NQ, L2, PD, CW, RW, NAME)                                                                   \
+    {NAME, KIND_TILE, 16 * RB, NC * 64 * NQ, 64 * CW, 16 * RB, 64 * NQ, L2, false, RW, false, (NC + NP) * 64, 3 * 16 * RB * (64 * CW + 8) * 4, \
+     &launch_tile_panel<NC, NP, RB, NQ, L2, PD, CW, RW>, 0, false, 0, false, 2, 0},
 TG_PANEL_LIST(TG_GDECL)
 
 // direct-to-LDS variants for 32x32 wave tiles with tile-granular fragment prefetch:

@@ -98,7 +98,7 @@ hipError_t launch_tile_deep(const GemmParams &p, hipStream_t s);
 // Row-panel kernel for a gathered A (any element strides of A; B plain with 16-byte rows, n % 4 == 0, k % (64 * CW) == 0):
 // 16 * RB rows x 64 * NQ * NC columns per workgroup, NC compute waves that read B straight from global memory and NP
 // waves that only gather A into LDS.
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD = 1, int CW = 1>
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD = 1, int CW = 1, bool WALK = false>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s);
 
 // Workgroup-tile kernel on the bf16 matrix pipe: operands cut into three bf16 pieces each, NP piece

@@ -37,7 +37,12 @@ constexpr int kPanelStages = 3;
 // (every compute wave owns 16 * RB x 64 * NQ of the result and uses a B vector RB times), TWO_LEVEL: second
 // accumulation level for K ranges beyond 1024, PD: how many 16-k steps ahead of the MFMAs B is fetched (1 or 3), CW: k per
 // chunk in units of 64 (the lanes of one gather instruction): a producer fills a row of a chunk with CW instructions.
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD, int CW>
+// WALK: persistent launch in which a workgroup owns several neighbouring column tiles of one row panel and takes them one
+// after the other with the chunk pipeline running on across the tile boundaries: while the results of one tile are
+// stored the producers are two chunks into the next and B's prefetch is in its columns (one problem, one K range,
+// whole tiles; the host checks).  For products with a short K, where a workgroup per tile spends as long starting and
+// ending as multiplying.
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD, int CW, bool WALK>
 __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmParams p) {
     constexpr int kPanelChunk = 64 * CW;
     constexpr int kPanelPitch = kPanelChunk + 8;       // floats per row of a stage (measured at 72: 0 bank-conflict cycles on the fragment reads; 68 and 84: half of the LDS cycles)
@@ -61,7 +66,16 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
 
     const unsigned total_work = (unsigned)p.tiles_m * (unsigned)p.tiles_n * (unsigned)p.splits * (unsigned)p.batch;
     int slice, tm, tn;
-    map_workgroup(p, total_work, blockIdx.x, slice, tm, tn);
+    int walk = 1;                                // tiles this workgroup takes
+    if constexpr (WALK) {
+        walk = (int)(total_work / gridDim.x);
+        const unsigned per_row = (unsigned)p.tiles_n / (unsigned)walk;
+        slice = 0;
+        tm = (int)(blockIdx.x / per_row);
+        tn = (int)(blockIdx.x % per_row) * walk;
+    } else {
+        map_workgroup(p, total_work, blockIdx.x, slice, tm, tn);
+    }
     const int prob = slice / p.splits, split = slice - prob * p.splits;
     const int m0 = tm * BM, n0 = tn * BN;
     const int ch_total = p.k / kPanelChunk;
@@ -82,6 +96,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         }
         unsigned lane_bytes = 4u * (unsigned)lane * (unsigned)p.csa;   // (the host checks that a chunk spans < 2^30 elements)
         const int64_t step = (int64_t)kPanelChunk * p.csa;
+        int gathered = 0;                        // chunks of the current tile asked for
         auto gather = [&](int stage) {
 #pragma unroll
             for (int i = 0; i < ROWS_PER_PRODUCER; ++i) {
@@ -92,7 +107,15 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
                                    smem + stage * kPanelStageFloats + r * kPanelPitch + 64 * w);
                 row[i] += step;
             }
+            if constexpr (WALK) {
+                if (++gathered == nch) {         // the next tile of the walk has the same rows of A: back to their start
+                    gathered = 0;
+#pragma unroll
+                    for (int i = 0; i < ROWS_PER_PRODUCER; ++i) row[i] -= (int64_t)nch * step;
+                }
+            }
         };
+        const int chunks = walk * nch;
 #ifdef TG_POISON_LDS
         for (int s = 0; s < kPanelStages; ++s)
             for (int i = 0; i < ROWS_PER_PRODUCER; ++i)
@@ -100,16 +123,16 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
 #endif
         gather(0);
-        if (nch > 1) gather(1);
+        if (chunks > 1) gather(1);
         int stage_free = 2;                      // where chunk j + 2 goes
-        for (int j = 0; j < nch; ++j) {
+        for (int j = 0; j < chunks; ++j) {
             // chunk j has landed (the chunk after it may still be on its way)
-            if (j + 1 < nch) __builtin_amdgcn_s_waitcnt(panel_vmcnt(ROWS_PER_PRODUCER * CW));   // vmcnt(one chunk's loads)
+            if (j + 1 < chunks) __builtin_amdgcn_s_waitcnt(panel_vmcnt(ROWS_PER_PRODUCER * CW));   // vmcnt(one chunk's loads)
             else __builtin_amdgcn_s_waitcnt(0x0F70);                                   // vmcnt(0)
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();        // #j: chunk j may be read; nobody reads chunk j - 1 any more
             __builtin_amdgcn_sched_barrier(0);
-            if (j + 2 < nch) {
+            if (j + 2 < chunks) {
 #ifdef TG_POISON_LDS
                 for (int i = 0; i < ROWS_PER_PRODUCER; ++i)
                     for (int w = 0; w < CW; ++w) smem[stage_free * kPanelStageFloats + (pw * ROWS_PER_PRODUCER + i) * kPanelPitch + 64 * w + lane] = __builtin_nanf("");
@@ -139,7 +162,9 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         off[q] = 4u * ((unsigned)(4 * g) * (unsigned)p.ldb + (unsigned)(col[q] < last ? col[q] : last));
     }
     const int64_t step_b = 16 * p.ldb;
-    int steps_left = STEPS * nch;                    // 16-k steps not yet fetched
+    int steps_left = STEPS * nch * walk;             // 16-k steps not yet fetched
+    int steps_of_tile = STEPS * nch;                 // ... of the tile the prefetch is in
+    const float *const B_first = Bg;
 
     f32x4 bq[NSETS][4][NQ];
     // vector i = NQ * t + q of a step: k row 4g + t, column group q
@@ -152,7 +177,14 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     auto next_step = [&]() {
         if (steps_left > 1) {
             --steps_left;
-            Bg += step_b;
+            if (WALK && --steps_of_tile == 0) {  // on to the next tile of the walk: same K range, the next BN columns
+                steps_of_tile = STEPS * nch;
+                Bg = B_first;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) off[q] += 4u * BN;
+            } else {
+                Bg += step_b;
+            }
         }
     };
 
@@ -207,7 +239,18 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         for (int i = 0; i < NLD; ++i) fetch_one(s, i);
         next_step();
     }
-    int stage = 0, since_flush = 0;
+    int stage = 0;
+    for (int t = 0; t < walk; ++t) {
+    if (WALK && t > 0) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                acc[rb][e] = (f32x4)(0.0f);
+                if constexpr (TWO_LEVEL) total[rb][e] = (f32x4)(0.0f);
+            }
+    }
+    int since_flush = 0;
     for (int j = 0; j < nch; ++j) {
         if constexpr (TWO_LEVEL) {
             if (since_flush == p.flush_tiles) {
@@ -252,20 +295,22 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
             float *dst = out + (int64_t)r * ldo;
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-                if (col[q] >= p.n) continue;
+                const int cq = col[q] + t * BN;
+                if (cq >= p.n) continue;
                 f32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = acc[rb][4 * q + e][v];
-                store_result(dst + col[q], o, nt);
+                store_result(dst + cq, o, nt);
             }
         }
     }
+    }   // tiles of the walk
 }
 
-template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD, int CW>
+template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD, int CW, bool WALK>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s) {
-    const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
-    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL, PD, CW>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
+    const int64_t blocks = WALK ? p.persistent_blocks : (int64_t)p.tiles_m * p.tiles_n * p.splits * p.batch;
+    hipLaunchKernelGGL((sgemm_panel_kernel<NC, NP, RB, NQ, TWO_LEVEL, PD, CW, WALK>), dim3((unsigned)blocks), dim3((NC + NP) * 64), 0, s, p);
     return hipGetLastError();
 }
 

@@ -219,3 +219,38 @@ def test_tall_strided_product_takes_a_row_panel_without_a_workspace():
     assert re.match(r"g(16|32)x", cfg) and "+pack" not in cfg, cfg
     rows = np.arange(0, m, 37)
     check_against_oracle(c[rows], np.ascontiguousarray(a_store[rows, ::32]), b, what="tall strided product, sampled rows")
+
+
+WALKS = [("g32x512x64_w32x64_rw_ga", 1, (4096, 4096, 128)), ("g32x512x64_w32x64_rw_ga", 2, (4096, 4096, 128)),
+         ("g32x512x64_w32x64_acc2_rw_ga", 1, (8192, 2048, 192)), ("g16x512x64_w16x64_acc2_rw_ga", 1, (4096, 4096, 64)),
+         ("g16x256x64_w16x64_acc2_rw_ga", 2, (4096, 1024, 1088)), ("g32x512x64_w32x64_b3_rw_ga", 1, (4096, 2048, 256)),
+         ("g16x512x64_w16x64_b3_rw_ga", 1, (4096, 2048, 128)), ("g32x512x64_w32x64_acc2_b3_rw_ga", 1, (4096, 4096, 128)),
+         ("g32x512x128_w32x64_acc2_b3_rw_ga", 2, (4096, 4096, 256))]
+
+
+@pytest.mark.parametrize("name,per_cu,shape", WALKS, ids=lambda v: v if isinstance(v, str) else str(v))
+def test_row_panel_variants_that_walk_along_their_panel(name, per_cu, shape):
+    """Persistent form for short K: a workgroup takes several neighbouring column tiles of one row panel, the chunk
+    pipeline running on across the tile boundaries.  Plain operands (the shipped 4096x4096x128 configuration is one
+    of these) and a strided A; every element against the oracle."""
+    m, n, k = shape
+    for layout, dist in (("N", "normal"), ("N", "int"), ("S", "int")):
+        say(f"forced {name}:p{per_cu} {m}x{n}x{k} A:{layout} {dist}")
+        gen = ig.normal if dist == "normal" else ig.small_int
+        a_np, da = _operand(gen, 771, m, k, layout, stride=5)
+        b = gen(772, (k, n))
+        tg.force_config(f"{name}:s1:g1:p{per_cu}")
+        c = _run(da, to_dev(b), m, n)
+        assert tg.last_config().startswith(name), tg.last_config()
+        rows = np.arange(0, m, 7)
+        check_against_oracle(c[rows], np.ascontiguousarray(a_np[rows]), b, exact=(dist == "int"), what=f"{name}:p{per_cu} {shape} {layout} {dist}")
+        assert np.isfinite(c).all()
+
+
+def test_walking_variants_refuse_what_they_cannot_divide():
+    import torch
+    a = torch.zeros((4096, 128), device="cuda")
+    b = torch.zeros((128, 1536), device="cuda")      # 128 x 3 tiles of 32 x 512: 384 tiles do not divide over 256 workgroups
+    tg.force_config("g32x512x64_w32x64_rw_ga:s1:g1:p1")
+    with pytest.raises(Exception, match="divide evenly"):
+        tg.sgemm(a, b)
