@@ -1251,6 +1251,13 @@ class Tuner {
     // true: agrees with the reference (or no check is possible)
     bool agrees(const Config &c) {
         if (!have_ref_) return true;
+        // C still holds an earlier candidate's (correct) product: filled with NaN first, so that a candidate which
+        // leaves part of C unwritten cannot pass on what was there
+        for (int64_t b = 0; b < p_.batch; ++b)
+            if (hipMemset2DAsync(p_.C + b * p_.strideC, (size_t)p_.ldc * sizeof(float), 0xFF, (size_t)p_.n * sizeof(float), (size_t)p_.m, s_) != hipSuccess) {
+                (void)hipGetLastError();
+                return true;
+            }
         if (launch(p_, c, ws_, s_) != TG_OK) return true;   // (a launch failure is reported by the timing path)
         double host[3 * tg::kCheckBlocks];
         hipError_t e = tg::launch_compare_rows(p_.C, p_.ldc, p_.strideC, (int)p_.batch, (int)p_.m, (int)p_.n, step_, ref_, partial_, s_);
