@@ -1367,7 +1367,7 @@ class Tuner {
         for (int per_cu = 1; per_cu <= 4 && tg::kernel(base.kernel).persistent; ++per_cu) {
             Config c = base;
             c.persist = per_cu;
-            consider(c, 0.995);
+            consider(c, 0.995, true);   // (checked again: the number of workgroups decides which of them takes which tile)
         }
     }
 
