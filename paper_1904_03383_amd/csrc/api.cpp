@@ -402,6 +402,9 @@ size_t ws_total(const Problem &p, const Config &c) {
     return b == 0 ? a : (a + 255) / 256 * 256 + b;
 }
 
+// Row-panel variants that hold their rows of A in LDS for the whole K range (tile_resident_kernel.hpp).
+bool resident_panel(const KernelInfo &ki) { return ki.name[0] == 'g' && strstr(ki.name, "_res_") != nullptr; }
+
 // Is this configuration usable for this problem?  (static validity filter of the tuner:
 // divisibility, alignment, accumulation depth, LDS capacity, workspace)
 bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::string *why = nullptr) {
@@ -456,6 +459,9 @@ bool config_valid(const Problem &p, const Config &c, size_t ws_bytes, std::strin
             const int64_t tiles = (p.m / ki.BM) * (p.n / ki.BN), wgs = (int64_t)c.persist * kNumCUs;
             if (p.batch != 1 || c.splits != 1) return no("the walking row-panel variants take one problem and one K range");
             if (tiles % wgs || (p.n / ki.BN) % (tiles / wgs)) return no("the tiles of a row panel do not divide evenly over the workgroups");
+            // (the variants that keep their rows of A in LDS over the whole K range: k + 8 floats per row, 64 KB per workgroup)
+            if (resident_panel(ki) && (int64_t)ki.BM * (p.k + 8) * 4 > 64 * 1024)
+                return no("the workgroup's rows of A over the whole K range do not fit its LDS");
         }
         if (ki.defer) {
             const int cb = ki.WN / 32;   // floats per store
@@ -583,6 +589,29 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // 8192x512x1024 s1 238 210 187 222; stride 8, 1024^3: s2 40 28 41 69)
         const double k_range = (double)std::min<int64_t>((int64_t)per * ki.BK, p.k);
         const double line = std::min(4.0 * p.csa, 128.0);
+        if (ki.persistent && (resident_panel(ki) || (p.a_class() == 0 && p.k <= 448))) {
+            // Short K, one walk per workgroup.  A resident in LDS (tile_resident_kernel.hpp): the panel is gathered once per
+            // workgroup, in front of the products and not beside them; from there the waves run at 96.5 % of the MFMA rate
+            // and what shows of C's way out is a twentieth of a microsecond per MB (us, plain operands, measured / this
+            // model: 4096x4096x64 22.1 / 22.0, x128 36.0 / 36.7, x256 64.2 / 66, x448 108.5 / 110; 8192x8192x128 137 / 132;
+            // 2048x2048x128 12.4 / 12.7; 8192x4096x192 98 / 97).  The walking panels that re-gather A per tile behind a
+            // barrier per chunk are about a microsecond behind on the same shapes (4096x4096x128 37.2, x64 22.8, x256 65.7)
+            // and, from k = 512 on, no longer ahead of the tile kernels (4096x4096x512 123 - 126 against 123).
+            const double wgs = std::max(1, c.persist) * (double)kNumCUs;
+            const double wgs_per_row = std::max(1.0, wgs / (double)ceil_div(p.m, ki.BM));
+            const double per_el = std::max(line / 128.0, line >= 32.0 ? 0.5 : (line >= 16.0 ? 0.35 : 0.25));
+            const double miss_share = line / 128.0;
+            const double req = ki.BM * (double)p.k * per_el * (1.0 + (wgs_per_row - 1.0) / 3.0) / wgs_per_row;
+            const double t_cu = std::max(1, c.persist) * req * (miss_share + (1.0 - miss_share) / 3.0) / 2.4e8;
+            const double t_chip = (double)p.m * p.k * line / 128.0 / 5e10;
+            const double t_mfma = 2.0 * (double)p.m * p.n * p.k / (kNumCUs * 4.0 * kSimdFlops * 0.965);
+            double t = launch + std::max(t_chip, t_cu) + t_mfma + 4.0 * (double)p.m * p.n / 20e12;
+            if (!resident_panel(ki)) t = (t + 1.0e-6) * (ki.two_level ? 1.01 : 1.0) + (strstr(ki.name, "_b3") ? 0.3e-6 : 0.0);
+            else t = t * (ki.threads < 1024 ? 1.0 : 1.005) + (strstr(ki.name, "_b3") ? 0.1e-6 : 0.0);
+            // (sixteen waves in one workgroup: on a par on most shapes, 8192x8192x64 97 us against 82 us; three steps of B
+            // ahead: within 2 % either way)
+            return t;
+        }
         const double per_el = std::max(line / 128.0, line >= 32.0 ? 0.5 : (line >= 16.0 ? 0.35 : 0.25));
         const double tiles_n = (double)ceil_div(p.n, ki.BN);
         const double miss_share = line / 128.0;          // share of the requests that bring a new line
@@ -1198,6 +1227,7 @@ class Tuner {
         if (cands.empty()) return fail(TG_ERR_INTERNAL, "no kernel variant is valid for this problem");
         launch_bound_ = launch_bound_problem(p_, cands);
         prepare_check();
+        warm_up(cands);
         sweep(cands);
         if (best_.kernel < 0) return fail(TG_ERR_HIP, "every candidate failed to run: " + last_err_);
         if (tg::kernel(best_.kernel).kind == tg::KIND_TILE) {
@@ -1281,6 +1311,23 @@ class Tuner {
         if (host_delay_us_ <= 0) return;
         const auto until = std::chrono::steady_clock::now() + std::chrono::duration<double, std::micro>(host_delay_us_);
         while (std::chrono::steady_clock::now() < until) {}
+    }
+
+    // An idle GPU takes its time to reach its clock under load (measured on MI355X: the first configuration timed in a
+    // fresh process read 43 us after 50 ms of launches, 37 us later on), and the sweep times the model's favourites
+    // first: they would be the ones to lose.  The first candidate that runs is launched for 0.2 s before anything is timed.
+    void warm_up(const std::vector<Config> &cands) {
+        const auto until = std::chrono::steady_clock::now() + std::chrono::milliseconds(200);
+        for (const Config &c : cands) {
+            if (launch(p_, c, ws_, s_) != TG_OK) { (void)hipGetLastError(); continue; }
+            while (std::chrono::steady_clock::now() < until) {
+                for (int i = 0; i < 16; ++i)
+                    if (launch(p_, c, ws_, s_) != TG_OK) { (void)hipGetLastError(); break; }
+                if (hipStreamSynchronize(s_) != hipSuccess) { (void)hipGetLastError(); break; }
+            }
+            break;
+        }
+        (void)hipStreamSynchronize(s_);
     }
 
     // One brief timing: warm-up launch, then `n` back-to-back launches between two events.

@@ -150,6 +150,19 @@ TG_MI16_LIST(TG_M16DECL)
      &launch_tile_panel<NC, NP, RB, NQ, L2, PD, CW, RW>, 0, false, 0, false, 2, 0},
 TG_PANEL_LIST(TG_GDECL)
 
+// row panels that keep their rows of A in LDS over the whole (short) K range: one barrier per workgroup, persistent walk
+// (waves, 16-row blocks, column groups of four per lane, steps of B in flight, name)
+#define TG_RESIDENT_LIST(X)                                  \
+    X(16, 2, 1, 1, "g32x1024x64_w32x64_res_ga")              \
+    X(8, 2, 1, 1, "g32x512x64_w32x64_res_ga")                \
+    X(8, 2, 1, 3, "g32x512x64_w32x64_b3_res_ga")
+#define TG_RDECL(NC, RB, NQ, PD, NAME) \
+    extern template hipError_t launch_tile_resident<NC, RB, NQ, PD>(const GemmParams &, hipStream_t);
+#define TG_RROW(NC, RB, NQ, PD, NAME)                                                                          \
+    {NAME, KIND_TILE, 16 * RB, NC * 64 * NQ, 64, 16 * RB, 64 * NQ, false, false, true, false, NC * 64, 16 * RB * (128 + 8) * 4, \
+     &launch_tile_resident<NC, RB, NQ, PD>, 0, false, 0, false, 2, 0},
+TG_RESIDENT_LIST(TG_RDECL)
+
 // direct-to-LDS variants for 32x32 wave tiles with tile-granular fragment prefetch:
 // (BM, BN, BK, two_level, LDS stages, A mode, B mode, name)
 #define TG_DEEP_LIST(X)                                                     \
@@ -199,6 +212,7 @@ static const KernelInfo kTable[] = {
     TG_MODE_LIST(TG_MROW)
     TG_MI16_LIST(TG_M16ROW)
     TG_PANEL_LIST(TG_GROW)
+    TG_RESIDENT_LIST(TG_RROW)
     TG_PIECES_LIST(TG_EROW)
     TG_PRECUT_LIST(TG_CROW)
     TG_PROW(128, 128, 16, 64, 64, "p128x128x16_w64x64")

@@ -100,6 +100,8 @@ hipError_t launch_tile_deep(const GemmParams &p, hipStream_t s);
 // waves that only gather A into LDS.
 template <int NC, int NP, int RB, int NQ, bool TWO_LEVEL, int PD = 1, int CW = 1, bool WALK = false>
 hipError_t launch_tile_panel(const GemmParams &p, hipStream_t s);
+template <int NC, int RB, int NQ, int PD>
+hipError_t launch_tile_resident(const GemmParams &p, hipStream_t s);
 
 // Workgroup-tile kernel on the bf16 matrix pipe: operands cut into three bf16 pieces each, NP piece
 // products per fp32 product (aligned operands, k % BK == 0, n % 4 == 0).

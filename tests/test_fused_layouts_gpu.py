@@ -225,7 +225,12 @@ WALKS = [("g32x512x64_w32x64_rw_ga", 1, (4096, 4096, 128)), ("g32x512x64_w32x64_
          ("g32x512x64_w32x64_acc2_rw_ga", 1, (8192, 2048, 192)), ("g16x512x64_w16x64_acc2_rw_ga", 1, (4096, 4096, 64)),
          ("g16x256x64_w16x64_acc2_rw_ga", 2, (4096, 1024, 1088)), ("g32x512x64_w32x64_b3_rw_ga", 1, (4096, 2048, 256)),
          ("g16x512x64_w16x64_b3_rw_ga", 1, (4096, 2048, 128)), ("g32x512x64_w32x64_acc2_b3_rw_ga", 1, (4096, 4096, 128)),
-         ("g32x512x128_w32x64_acc2_b3_rw_ga", 2, (4096, 4096, 256))]
+         ("g32x512x128_w32x64_acc2_b3_rw_ga", 2, (4096, 4096, 256)),
+         # A resident in LDS over the whole K range: one barrier per workgroup, the waves on their own from there
+         ("g32x512x64_w32x64_res_ga", 1, (4096, 4096, 128)), ("g32x512x64_w32x64_res_ga", 2, (4096, 4096, 128)),
+         ("g32x512x64_w32x64_res_ga", 4, (4096, 4096, 64)), ("g32x1024x64_w32x64_res_ga", 1, (4096, 4096, 128)),
+         ("g32x1024x64_w32x64_res_ga", 2, (8192, 2048, 192)), ("g32x512x64_w32x64_b3_res_ga", 1, (2048, 8192, 448)),
+         ("g32x512x64_w32x64_b3_res_ga", 2, (4096, 2048, 64)), ("g32x1024x64_w32x64_res_ga", 1, (4096, 2048, 320))]
 
 
 @pytest.mark.parametrize("name,per_cu,shape", WALKS, ids=lambda v: v if isinstance(v, str) else str(v))
@@ -254,3 +259,14 @@ def test_walking_variants_refuse_what_they_cannot_divide():
     tg.force_config("g32x512x64_w32x64_rw_ga:s1:g1:p1")
     with pytest.raises(Exception, match="divide evenly"):
         tg.sgemm(a, b)
+    # the variants that keep their rows of A in LDS take no K range that does not fit there
+    a = torch.zeros((4096, 512), device="cuda")
+    b = torch.zeros((512, 4096), device="cuda")
+    tg.force_config("g32x512x64_w32x64_res_ga:s1:g1:p1")
+    with pytest.raises(Exception, match="do not fit its LDS"):
+        tg.sgemm(a, b)
+    tg.force_config(None)
+    # ... and a batch or a K split goes to the other variants
+    tg.force_config("g32x512x64_w32x64_res_ga:s2:g1:p1")
+    with pytest.raises(Exception, match="one problem and one K range"):
+        tg.sgemm(torch.zeros((4096, 256), device="cuda"), torch.zeros((256, 4096), device="cuda"))

@@ -104,10 +104,10 @@ def test_each_kernel_variant(dist):
     import torch
     ws = torch.empty(1 << 24, dtype=torch.float32, device="cuda")   # 64 MiB: the piece images of the "c" variants
     for name in tg.kernel_names():
-        if "_ta" in name or "_tb" in name or "_rw_" in name:
+        if "_ta" in name or "_tb" in name or "_rw_" in name or "_res_" in name:
             continue    # variants for transposed operands cannot read plain ones: forced in test_fused_layouts_gpu.py
                         # (the gathering "_ga" / "_gb" variants can, and do so here); the row-panel variants that walk
-                        # along their panel need 256 workgroups' worth of tiles: forced there too
+                        # along their panel (or keep it in LDS) need 256 workgroups' worth of tiles: forced there too
         tg.set_workspace(ws if name.startswith("c") else None)
         batch, m, n, k = _shape_for(name)
         say(f"forced {name} on {m}x{n}x{k} ({dist})")

@@ -60,7 +60,8 @@ SPECS = ["t128x128x16_w64x64", "t128x256x32_w64x128_acc2", "t64x64x32_w32x32", "
          "d64x64x32_w32x32_acc2_st4_ga", "d16x256x32_w16x64_acc2_st3_ga", "d64x64x32_w32x32_acc2_tf_gb",
          "g16x1024x64_w16x128_acc2_ga", "g32x512x64_w32x128_acc2_ga", "g32x1024x64_w32x128_ga",
          "g32x512x64_w32x64_acc2_ga", "g16x256x64_w16x64_acc2_b3_ga", "g32x512x64_w32x64_acc2_b3_ga",
-         "g32x512x128_w32x64_acc2_b3_ga", "g32x512x64_w32x64_rw_ga:p1"]
+         "g32x512x128_w32x64_acc2_b3_ga", "g32x512x64_w32x64_rw_ga:p1", "g32x512x64_w32x64_res_ga:p1",
+         "g32x1024x64_w32x64_res_ga:p1"]
 
 
 @pytest.mark.parametrize("spec", SPECS)
@@ -71,7 +72,7 @@ def test_no_kernel_reads_a_stage_it_has_given_up(spec):
     shapes = [(512, 512, 448)] if persistent else [(300, 260, 448)] + ([(256, 512, 2112)] if "acc2" in spec else [])
     if "_edge" in spec:
         shapes = [(301, 259, 413)]
-    if "_rw_" in spec:         # workgroups that walk two column tiles each
+    if "_rw_" in spec or "_res_" in spec:         # workgroups that walk two column tiles each (one of 1024 columns)
         shapes = [(4096, 2048, 192)]
     if re.match(r"[a-z]\d+x\d+x128_", spec):      # K tiles of 128
         shapes = [(300, 260, 384), (256, 512, 2176)]
