@@ -642,7 +642,21 @@ double heuristic_seconds(const Problem &p, const Config &c) {
             body = t_comp + 0.5 * t_gather + 0.25 * std::max(0.0, t_mem - t_gather);
         }
         double t = launch + 1e-6 + body * fill * (deep_b ? 0.9 : 1.0);
-        if (p.a_class() == 0) t *= 1.15;     // plain operands: behind the tile kernels until the tuner has timed both
+        if (p.a_class() == 0) {
+            // Plain operands.  Where the 32 x 512 panels fill every CU the same number of times and K is long, the deep
+            // chunks run at 96 % of the MFMA rate plus 3.3 us per round of workgroups, which no tile kernel reaches (us, these
+            // panels / the tile kernel chosen before: 2048^3 119.5 / 123, 2048x2048x8192 463 / 499, 4096x4096x2048 469 / 474,
+            // 4096x4096x8192 1837 / 1858, 6144^3 3089 / 3132, 8192^3 7277 / 7348, 1024x4096x2048 120 / 126); with a
+            // partial last round they lose by as much as that round is empty (3072^3 518 / 407, 2048x1024x4096 230 / 126),
+            // and on batches the tile kernels are level or 1 % ahead (64 of 512x512x2048: 503 / 497).
+            // Elsewhere they stay behind the tile kernels until the tuner has timed both.
+            const int64_t blocks_i = ceil_div(p.m, ki.BM) * ceil_div(p.n, ki.BN) * p.batch;
+            if (deep_b && ki.BK >= 128 && ki.BM == 32 && p.b_class() == 0 && p.batch == 1 && splits == 1 && p.k >= 2048 && p.m % ki.BM == 0 &&
+                p.n % ki.BN == 0 && blocks_i % kNumCUs == 0)
+                return launch + (double)(blocks_i / kNumCUs) * 3.25e-6 +
+                       2.0 * p.batch * (double)p.m * p.n * p.k / (kPeakFlops * (ki.BK >= 256 ? 0.961 : 0.959));
+            t *= 1.15;
+        }
         if (splits > 1) t += 2.5e-6 + 4.0 * p.batch * (2.0 * splits + 1.0) * (double)p.m * p.n / 5e12;
         return t;
     }

@@ -166,7 +166,7 @@ def test_force_config_grammar_and_get_config(lib):
     finally:
         tg.force_config(None)
     # heuristic choices (nothing tuned, nothing forced)
-    assert tg.get_config(1, 4096, 4096, 4096).split(":")[0].endswith("_acc2")       # long K: two levels
+    assert "_acc2" in tg.get_config(1, 4096, 4096, 4096).split(":")[0]              # long K: two levels
     assert "acc2" not in tg.get_config(1, 4096, 4096, 128)
     assert tg.get_config(512, 32, 32, 64).startswith("wave")
     assert "_edge" in tg.get_config(1, 1000, 1000, 1001) or tg.get_config(1, 1000, 1000, 1001).startswith("wave")
@@ -481,7 +481,7 @@ def test_tuned_entries_are_kept_per_math_mode(tmp_path, lib):
         tg.set_math(tg.MATH_FP32_MFMA)
         tg.clear_tune_cache()
     # nothing tuned any more: the heuristic answers, with a kernel that has the second accumulation level K = 4096 needs
-    assert "_acc2:s1:g8" in tg.get_config(1, 4096, 4096, 4096)
+    assert "_acc2" in tg.get_config(1, 4096, 4096, 4096).split(":")[0]
 
 
 def test_launch_bound_classification_comes_from_the_cost_model(lib):
