@@ -999,14 +999,17 @@ tg_status align_operands(Problem &p, void *&ws, size_t &ws_bytes, hipStream_t s,
     if (need_a + need_b > ws_bytes || (reinterpret_cast<uintptr_t>(ws) & 15u) != 0) return TG_OK;
     char *w = static_cast<char *>(ws);
     hipError_t e = hipSuccess;
+    if (copy_a && copy_b)       // one launch for both
+        e = tg::launch_pad_copy2(p.A, p.lda, (int)p.m, (int)p.k, reinterpret_cast<float *>(w), k4, (int)p.m,
+                                 p.B, p.ldb, (int)p.k, (int)p.n, reinterpret_cast<float *>(w + need_a), n4, (int)k4, s);
     if (copy_a) {
-        e = tg::launch_pad_copy(p.A, p.lda, (int)p.m, (int)p.k, reinterpret_cast<float *>(w), k4, (int)p.m, s);
+        if (!copy_b) e = tg::launch_pad_copy(p.A, p.lda, (int)p.m, (int)p.k, reinterpret_cast<float *>(w), k4, (int)p.m, s);
         p.A = reinterpret_cast<const float *>(w);
         p.lda = k4;
         w += need_a;
     }
     if (e == hipSuccess && copy_b) {
-        e = tg::launch_pad_copy(p.B, p.ldb, (int)p.k, (int)p.n, reinterpret_cast<float *>(w), n4, (int)k4, s);
+        if (!copy_a) e = tg::launch_pad_copy(p.B, p.ldb, (int)p.k, (int)p.n, reinterpret_cast<float *>(w), n4, (int)k4, s);
         p.B = reinterpret_cast<const float *>(w);
         p.ldb = n4;
         p.nb = n4;

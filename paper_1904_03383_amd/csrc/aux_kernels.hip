@@ -488,27 +488,70 @@ __global__ void __launch_bounds__(256) pack_kernel(const float *__restrict__ src
 
 // dst[r * ld + c] = src[r * rs + c] for r < rows, c < cols, and +0.0 on the rest of rows_out x ld (ld a multiple
 // of 4, dst 16-byte aligned): the aligned, zero-padded copy of an operand whose base, leading dimension or
-// extents keep the exact-fit kernels from using 16-byte loads.  One 16-byte store per thread.
-__global__ void __launch_bounds__(256) pad_copy_kernel(const float *__restrict__ src, int64_t rs, int rows, int cols,
-                                                       float *__restrict__ dst, int64_t ld, int rows_out) {
-    const int64_t vecs = ld / 4;
-    const int64_t total = (int64_t)rows_out * vecs;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+// extents keep the exact-fit kernels from using 16-byte loads.  A workgroup copies 1024 vectors of 16 bytes, a thread
+// four of them: its sixteen 4-byte loads (the source has no alignment to speak of) are all issued before the first
+// store.  (One or four vectors per thread: the same time, 1023^3 28.3 us in all; the launch is what the copy costs.)
+struct PadCopy {
+    const float *src;
+    int64_t rs;
+    int rows, cols;
+    float *dst;
+    int64_t ld;
+    int rows_out;
+};
+constexpr int kPadCopyVecs = 4;                       // per thread
+constexpr int kPadCopyBlock = 256 * kPadCopyVecs;     // per workgroup
+
+__device__ __forceinline__ void pad_copy_block(const PadCopy &d, int64_t block) {
+    const int64_t vecs = d.ld / 4;
+    const int64_t total = (int64_t)d.rows_out * vecs;
+    f32x4 v[kPadCopyVecs];
+    int64_t at[kPadCopyVecs];
+#pragma unroll
+    for (int j = 0; j < kPadCopyVecs; ++j) {
+        const int64_t idx = block * kPadCopyBlock + j * 256 + threadIdx.x;
         const int64_t r = idx / vecs;
         const int c = (int)(idx - r * vecs) * 4;
-        f32x4 v;
+        at[j] = idx < total ? r * d.ld + c : -1;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (r < rows && c + e < cols) ? src[r * rs + c + e] : 0.0f;
-        *reinterpret_cast<f32x4 *>(dst + r * ld + c) = v;
+        for (int e = 0; e < 4; ++e) v[j][e] = (idx < total && r < d.rows && c + e < d.cols) ? d.src[r * d.rs + c + e] : 0.0f;
     }
+#pragma unroll
+    for (int j = 0; j < kPadCopyVecs; ++j)
+        if (at[j] >= 0) *reinterpret_cast<f32x4 *>(d.dst + at[j]) = v[j];
 }
 
+__global__ void __launch_bounds__(256) pad_copy_kernel(const PadCopy d, int64_t blocks) {
+    for (int64_t b = blockIdx.x; b < blocks; b += gridDim.x) pad_copy_block(d, b);
+}
+
+// Both operands in one launch (a launch costs as much as either copy of a mid-size product): the first blocks_a
+// workgroups copy A, the others B.
+__global__ void __launch_bounds__(256) pad_copy2_kernel(const PadCopy a, const PadCopy b, unsigned blocks_a) {
+    if (blockIdx.x < blocks_a) pad_copy_block(a, blockIdx.x);
+    else pad_copy_block(b, blockIdx.x - blocks_a);
+}
+
+static int64_t pad_copy_blocks(int64_t ld, int rows_out) { return ((int64_t)rows_out * (ld / 4) + kPadCopyBlock - 1) / kPadCopyBlock; }
+
 hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, float *dst, int64_t ld, int rows_out, hipStream_t s) {
-    const int64_t items = (int64_t)rows_out * (ld / 4);
-    if (items <= 0) return hipSuccess;
-    int64_t blocks = (items + 255) / 256;
-    if (blocks > INT32_MAX) blocks = INT32_MAX;
-    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, rs, rows, cols, dst, ld, rows_out);
+    const int64_t blocks = pad_copy_blocks(ld, rows_out);
+    if (blocks <= 0) return hipSuccess;
+    const PadCopy d{src, rs, rows, cols, dst, ld, rows_out};
+    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)std::min<int64_t>(blocks, INT32_MAX)), dim3(256), 0, s, d, blocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_copy2(const float *src_a, int64_t rs_a, int rows_a, int cols_a, float *dst_a, int64_t ld_a, int rows_out_a,
+                            const float *src_b, int64_t rs_b, int rows_b, int cols_b, float *dst_b, int64_t ld_b, int rows_out_b,
+                            hipStream_t s) {
+    const int64_t blocks_a = pad_copy_blocks(ld_a, rows_out_a), blocks_b = pad_copy_blocks(ld_b, rows_out_b);
+    if (blocks_a <= 0 || blocks_b <= 0 || blocks_a + blocks_b > INT32_MAX) {     // (one of them empty, or too many for one grid)
+        hipError_t e = launch_pad_copy(src_a, rs_a, rows_a, cols_a, dst_a, ld_a, rows_out_a, s);
+        return e != hipSuccess ? e : launch_pad_copy(src_b, rs_b, rows_b, cols_b, dst_b, ld_b, rows_out_b, s);
+    }
+    const PadCopy a{src_a, rs_a, rows_a, cols_a, dst_a, ld_a, rows_out_a}, b{src_b, rs_b, rows_b, cols_b, dst_b, ld_b, rows_out_b};
+    hipLaunchKernelGGL(pad_copy2_kernel, dim3((unsigned)(blocks_a + blocks_b)), dim3(256), 0, s, a, b, (unsigned)blocks_a);
     return hipGetLastError();
 }
 

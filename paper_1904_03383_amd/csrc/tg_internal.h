@@ -136,6 +136,10 @@ hipError_t launch_pack(const float *src, int64_t rs, int64_t cs, float *dst, int
 
 // dst[r * ld + c] = src[r * rs + c] (r < rows, c < cols), +0.0 elsewhere on rows_out x ld: aligned, zero-padded copy.
 hipError_t launch_pad_copy(const float *src, int64_t rs, int rows, int cols, float *dst, int64_t ld, int rows_out, hipStream_t s);
+// ... of both operands in one launch
+hipError_t launch_pad_copy2(const float *src_a, int64_t rs_a, int rows_a, int cols_a, float *dst_a, int64_t ld_a, int rows_out_a,
+                            const float *src_b, int64_t rs_b, int rows_b, int cols_b, float *dst_b, int64_t ld_b, int rows_out_b,
+                            hipStream_t s);
 
 // The tuner's result check: copy every step-th row of C into `ref` (packed), and compare the same rows of a later
 // result with it: partial[3*b + 0..2] of workgroup b = sum (c - ref)^2, sum ref^2, count of non-finite values.

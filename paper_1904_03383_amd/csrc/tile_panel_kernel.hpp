@@ -149,7 +149,8 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     const int c = lane & 15, g = lane >> 4;
     const int n0w = n0 + wave * WN;
     // the lane's NQ groups of four adjacent columns; a group past the end re-reads the last four columns
-    // (n is a multiple of 4: a group is inside or outside as a whole) and is not stored
+    // (the width that may be fetched, nb, is a multiple of 4: n itself, or n rounded up when B is a padded copy) and
+    // is not stored
     const int last = p.nb - 4;
     // B is addressed from a wave-uniform row origin (scalar registers, advanced per step) plus one 32-bit byte offset
     // per lane and column group (the host checks that 64 rows of B span fewer than 2^30 elements)
@@ -300,7 +301,9 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
                 f32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = acc[rb][4 * q + e][v];
-                store_result(dst + cq, o, nt);
+                // (B may have been fetched from a copy padded to a multiple of 4 columns: the last group of an n that is
+                // not one leaves element by element)
+                store_lane<4>(dst + cq, o, cq + 4 <= p.n, cq, p.n, nt);
             }
         }
     }

@@ -207,6 +207,33 @@ def test_row_panel_variants_on_a_batch_of_plain_operands(name):
                              what=f"{name} batch problem {i}")
 
 
+@pytest.mark.parametrize("name", ["g16x256x64_w16x64_acc2_b3_ga", "g32x512x128_w32x64_acc2_b3_ga", "g32x1024x64_w32x128_ga"])
+def test_row_panel_variants_behind_a_padded_copy_of_b(name):
+    """n not a multiple of 4 with a workspace set: B is fetched from a copy padded to the next multiple of 4 columns,
+    and the last, partial group of four columns of C must leave element by element (a 16-byte store there wrote the
+    first element of the next row: the tuner's result check caught it on 1023 x 1023 x 1023).  Rows of C are packed, so
+    a write past the end of a row would land in the result."""
+    import torch
+    m, n, k = 530, 1023, 1024
+    say(f"forced {name} on {m}x{n}x{k} behind a padded copy of B")
+    a = ig.small_int(781, (m, k))
+    b = ig.small_int(782, (k, n))
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+    out = torch.full((m + 1, n), float("nan"), device="cuda")
+    try:
+        tg.set_workspace(ws)
+        tg.force_config(name)
+        tg.sgemm(to_dev(a), to_dev(b), out=out[:m])
+        torch.cuda.synchronize()
+        cfg = tg.last_config()
+    finally:
+        tg.set_workspace(None)
+    assert cfg.startswith(name) and "+align" in cfg, cfg
+    c = out.cpu().numpy()
+    assert np.isnan(c[m]).all()                           # nothing written behind the last row
+    check_against_oracle(c[:m], a, b, exact=True, what=f"{name} behind a padded B")
+
+
 def test_tall_strided_product_takes_a_row_panel_without_a_workspace():
     """4096 x 1024 x 1024 with A at element stride 32: row panels of 16 or 32 rows fill the chip by themselves, every
     element of A is requested once or twice, nothing is packed and no workspace is needed."""
