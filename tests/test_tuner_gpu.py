@@ -69,6 +69,32 @@ def test_every_candidate_is_checked_against_the_first_one():
     del ws
 
 
+@pytest.mark.parametrize("shape,workspace", [((1023, 1023, 1023), True), ((530, 1023, 1024), True), ((2047, 1025, 515), True),
+                                             ((777, 2222, 333), False), ((1025, 520, 1025), True), ((2048, 2048, 192), False)],
+                         ids=str)
+def test_every_candidate_agrees_on_ragged_shapes(shape, workspace):
+    """The tuner runs every valid variant on the problem and compares each product with the first one's: a tuning that
+    succeeds says that all of them agree.  Ragged sizes, with a workspace (the exact-fit kernels then run on aligned,
+    zero-padded copies: n not a multiple of 4 behind such a copy is how a 16-byte store past the end of a row was
+    found) and without (predicated kernels).  The tuned choice against the oracle."""
+    import torch
+    m, n, k = shape
+    say(f"tune {m}x{n}x{k} {'with' if workspace else 'without'} a workspace: all candidates must agree")
+    a, b = ig.normal(821, (m, k)), ig.normal(822, (k, n))
+    da, db = to_dev(a), to_dev(b)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda") if workspace else None
+    tg.set_workspace(ws)
+    out = torch.full((m + 1, n), float("nan"), device="cuda")
+    tg.tune(da, db, out=out[:m], reps=1)
+    torch.cuda.synchronize()
+    c = out.cpu().numpy()
+    assert np.isnan(c[m]).all()                                    # nothing written behind the last row
+    rows = np.arange(0, m, 5)
+    check_against_oracle(c[rows], a[rows], b, what=f"tuned {tg.last_config()} on {shape}")
+    tg.set_workspace(None)
+    del ws
+
+
 def test_result_check_samples_rows_of_a_large_product():
     """4096 x 4096 x 64: C is 64 MiB, twice the room for the reference, so every other row is compared."""
     import torch
