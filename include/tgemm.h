@@ -189,7 +189,7 @@ tg_status tg_tune(int64_t batch, int64_t m, int64_t n, int64_t k,
  * the K-split tail launch of a tail split), packed copies of strided operands, aligned zero-padded copies
  * of unit-stride operands that are off the 16-byte grid or have k or n not a multiple of 4 (made for
  * single products with m, n >= 256 and m * n * k >= 4.2e8 when there is room: m x k and k x n floats, each rounded up to
- * multiples of 4; tg_last_config() then ends in "+alignA", "+alignB" or "+alignAB"; without room the
+ * multiples of 4 (k to a multiple of 32 when both are copied and k >= 1000); tg_last_config() then ends in "+alignA", "+alignB" or "+alignAB"; without room the
  * predicated kernels take such operands as they are, as do the one-wave-per-tile kernels that smaller products
  * run on; C is never copied: its rows may start anywhere), and the piece images of the "c" kernels.
  * Configurations that need it are considered only while a workspace of
