@@ -597,11 +597,15 @@ double heuristic_seconds(const Problem &p, const Config &c) {
             // 2048x2048x128 12.4 / 12.7; 8192x4096x192 98 / 97).  The walking panels that re-gather A per tile behind a
             // barrier per chunk are about a microsecond behind on the same shapes (4096x4096x128 37.2, x64 22.8, x256 65.7)
             // and, from k = 512 on, no longer ahead of the tile kernels (4096x4096x512 123 - 126 against 123).
+            // (the workgroups of one row panel run on one XCD: the first to ask for a line of A brings it into their L2, the
+            // others find it there at about eight times the rate.  A at stride 32, time of the gather alone, us measured /
+            // this model: 4096x4096x128, two workgroups per panel 8.4 / 9.6; 4096x4096x320, two 21 / 24; 2048x4096x384,
+            // four 13 / 17)
             const double wgs = std::max(1, c.persist) * (double)kNumCUs;
             const double wgs_per_row = std::max(1.0, wgs / (double)ceil_div(p.m, ki.BM));
             const double per_el = std::max(line / 128.0, line >= 32.0 ? 0.5 : (line >= 16.0 ? 0.35 : 0.25));
             const double miss_share = line / 128.0;
-            const double req = ki.BM * (double)p.k * per_el * (1.0 + (wgs_per_row - 1.0) / 3.0) / wgs_per_row;
+            const double req = ki.BM * (double)p.k * per_el * (1.0 + (wgs_per_row - 1.0) / 8.0) / wgs_per_row;
             const double t_cu = std::max(1, c.persist) * req * (miss_share + (1.0 - miss_share) / 3.0) / 2.4e8;
             const double t_chip = (double)p.m * p.k * line / 128.0 / 5e10;
             const double t_mfma = 2.0 * (double)p.m * p.n * p.k / (kNumCUs * 4.0 * kSimdFlops * 0.965);
@@ -617,7 +621,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double miss_share = line / 128.0;          // share of the requests that bring a new line
         const double req = ki.BM * k_range * per_el * (1.0 + (tiles_n - 1.0) / 3.0) / tiles_n;
         const double t_cu = per_cu * req * (miss_share + (1.0 - miss_share) / 3.0) / 2.4e8;
-        const double t_chip = p.batch * (double)p.m * p.k * line / 128.0 / 5e10;
+        // (a workgroup that walks several tiles of its row panel gathers the panel again for each of them, one after the
+        // other: at a large stride the lines have left L2 by then and cross the fabric once per tile, where the tiles of
+        // one-tile workgroups run side by side and share them.  us, A at stride 32, walking / one tile per workgroup:
+        // 4096x4096x128 95 / 61, 2048x2048x256 52 / 26, 4096x4096x320 205 / 113; at stride 2 - 8 the walk wins: 38 / 45)
+        const double walked = ki.persistent && c.persist > 0 ? std::max(1.0, blocks / ((double)c.persist * kNumCUs)) : 1.0;
+        const double t_chip = p.batch * (double)p.m * p.k * line / 128.0 / 5e10 * (1.0 + (walked - 1.0) * line / 128.0);
         const double t_b = per_cu * k_range * (double)std::min<int64_t>(ki.BN, p.n) * 4.0 / 1.25e11;
         const double t_gather = std::max(t_chip, t_cu);
         const double t_mem = std::max(t_chip + 0.8 * t_b, t_cu);      // B's line requests take slots from the gather
@@ -630,7 +639,6 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // 4096x4096x128 44 -> 48)
         const bool deep_b = strstr(ki.name, "_b3") != nullptr;
         // (a workgroup that walks several tiles of its row panel fills its pipeline once for all of them)
-        const double walked = ki.persistent && c.persist > 0 ? std::max(1.0, blocks / ((double)c.persist * kNumCUs)) : 1.0;
         const double fill = 1.0 + (deep_b ? 2.0 : 1.0) * ki.BK / (k_range * walked);
         // (what shows of the shorter part: half of the gather where the products are longer; where the gather is, 15 % of
         // the products when they are far shorter and up to 70 % near parity, where the two roles keep waiting for each other)

@@ -33,6 +33,16 @@ constexpr int kPanelRows = 16;
 constexpr int panel_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 constexpr int kPanelStages = 3;
 
+// Workgroups are dealt to the eight XCDs in turn (workgroup w runs on XCD w % 8, each with an L2 of its own).  The
+// persistent row-panel forms want the workgroups that share a row panel of A on one XCD, so that a strided A crosses
+// the fabric once per panel and not once per XCD that holds one of its workgroups (2048^3 with A at stride 32, four
+// workgroups per panel: 294 us with neighbours on four XCDs, 210 us for the one-tile form, whose order keeps them
+// together): this is the position of workgroup w in an order that lists XCD 0's workgroups first, then XCD 1's, ...
+// (grids that are not a multiple of eight keep their order).
+__device__ __forceinline__ unsigned xcd_major(unsigned w, unsigned grid) {
+    return (grid & 7u) == 0 ? (w & 7u) * (grid >> 3) + (w >> 3) : w;
+}
+
 // NC compute waves, NP producer waves, RB blocks of 16 rows per panel, NQ groups of four adjacent columns per lane
 // (every compute wave owns 16 * RB x 64 * NQ of the result and uses a B vector RB times), TWO_LEVEL: second
 // accumulation level for K ranges beyond 1024, PD: how many 16-k steps ahead of the MFMAs B is fetched (1 or 3), CW: k per
@@ -70,9 +80,10 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
     if constexpr (WALK) {
         walk = (int)(total_work / gridDim.x);
         const unsigned per_row = (unsigned)p.tiles_n / (unsigned)walk;
+        const unsigned id = xcd_major(blockIdx.x, gridDim.x);
         slice = 0;
-        tm = (int)(blockIdx.x / per_row);
-        tn = (int)(blockIdx.x % per_row) * walk;
+        tm = (int)(id / per_row);
+        tn = (int)(id % per_row) * walk;
     } else {
         map_workgroup(p, total_work, blockIdx.x, slice, tm, tn);
     }

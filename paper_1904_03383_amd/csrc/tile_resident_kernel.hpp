@@ -43,8 +43,9 @@ __global__ void __launch_bounds__(NC * 64) sgemm_resident_kernel(const GemmParam
     const unsigned tiles = (unsigned)p.tiles_m * (unsigned)p.tiles_n;
     const int walk = (int)(tiles / gridDim.x);                 // tiles this workgroup takes (the host checks that it divides)
     const unsigned per_row = (unsigned)p.tiles_n / (unsigned)walk;
-    const int tm = (int)(blockIdx.x / per_row);
-    const int tn = (int)(blockIdx.x % per_row) * walk;
+    const unsigned id = xcd_major(blockIdx.x, gridDim.x);   // the workgroups of one row panel on one XCD
+    const int tm = (int)(id / per_row);
+    const int tn = (int)(id % per_row) * walk;
     const int m0 = tm * BM, n0 = tn * BN;
     const int nch = p.k / 64;                                  // runs of four 16-k steps
 
