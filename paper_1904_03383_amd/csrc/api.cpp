@@ -620,7 +620,12 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         const double tiles_n = (double)ceil_div(p.n, ki.BN);
         const double miss_share = line / 128.0;          // share of the requests that bring a new line
         const double req = ki.BM * k_range * per_el * (1.0 + (tiles_n - 1.0) / 3.0) / tiles_n;
-        const double t_cu = per_cu * req * (miss_share + (1.0 - miss_share) / 3.0) / 2.4e8;
+        // (the 2.4e8 requests/s of a CU were measured with all 256 CUs gathering, where they are the chip's line rate
+        // seen from one CU; with fewer workgroups than CUs each gets more of it, up to about 6.5e8: 1024x256x1024 at
+        // stride 32, 64 workgroups of 16384 lines each, 31.6 us in all)
+        const double active = std::min(blocks, (double)kNumCUs);
+        const double cu_rate = std::min(6.5e8, 1.25 * 5e10 / std::max(active, 1.0));
+        const double t_cu = per_cu * req * (miss_share + (1.0 - miss_share) / 3.0) / cu_rate;
         // (a workgroup that walks several tiles of its row panel gathers the panel again for each of them, one after the
         // other: at a large stride the lines have left L2 by then and cross the fabric once per tile, where the tiles of
         // one-tile workgroups run side by side and share them.  us, A at stride 32, walking / one tile per workgroup:
@@ -639,7 +644,9 @@ double heuristic_seconds(const Problem &p, const Config &c) {
         // 4096x4096x128 44 -> 48)
         const bool deep_b = strstr(ki.name, "_b3") != nullptr;
         // (a workgroup that walks several tiles of its row panel fills its pipeline once for all of them)
-        const double fill = 1.0 + (deep_b ? 2.0 : 1.0) * ki.BK / (k_range * walked);
+        // (where the gather is the longer part the fill is mostly gather that has to happen anyway: 1024x1024x256 at
+        // stride 32 11.4 us where a full charge for two chunks said 17.4)
+        const double fill = 1.0 + (t_mem >= t_comp ? 0.25 : 1.0) * (deep_b ? 2.0 : 1.0) * ki.BK / (k_range * walked);
         // (what shows of the shorter part: half of the gather where the products are longer; where the gather is, 15 % of
         // the products when they are far shorter and up to 70 % near parity, where the two roles keep waiting for each other)
         double body;
