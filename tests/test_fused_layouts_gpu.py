@@ -262,9 +262,10 @@ WALKS = [("g32x512x64_w32x64_rw_ga", 1, (4096, 4096, 128)), ("g32x512x64_w32x64_
 
 @pytest.mark.parametrize("name,per_cu,shape", WALKS, ids=lambda v: v if isinstance(v, str) else str(v))
 def test_row_panel_variants_that_walk_along_their_panel(name, per_cu, shape):
-    """Persistent form for short K: a workgroup takes several neighbouring column tiles of one row panel, the chunk
-    pipeline running on across the tile boundaries.  Plain operands (the shipped 4096x4096x128 configuration is one
-    of these) and a strided A; every element against the oracle."""
+    """Persistent forms for short K: a workgroup takes several neighbouring column tiles of one row panel, with the chunk
+    pipeline running on across the tile boundaries, or with its rows of A resident in LDS and every wave on its own
+    behind a single barrier.  Plain operands (the tuned 4096x4096x128 configuration is one of these) and a strided
+    A; sampled rows against the oracle, and no element of C left unwritten."""
     m, n, k = shape
     for layout, dist in (("N", "normal"), ("N", "int"), ("S", "int")):
         say(f"forced {name}:p{per_cu} {m}x{n}x{k} A:{layout} {dist}")
