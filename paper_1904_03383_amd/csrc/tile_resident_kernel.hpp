@@ -136,7 +136,8 @@ __global__ void __launch_bounds__(NC * 64) sgemm_resident_kernel(const GemmParam
         for (int j = 0; j < nch; ++j) {
             const int k_next = j + 1 < nch ? 64 * (j + 1) : 0;   // (after the last run: the first fragment of the next tile)
             // four steps of 4 * NQ groups of one load (for the step PD steps on) and 4 * RB independent MFMAs, in the
-            // order they are to issue, fenced group by group (see the row-panel kernel)
+            // order they are to issue, fenced group by group (see the row-panel kernel; with four waves per SIMD the load
+            // in front of its group is the faster place here: 36.1 us against 36.3 - 36.7 us with it in the middle)
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
 #pragma unroll
