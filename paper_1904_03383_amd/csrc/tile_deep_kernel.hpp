@@ -184,6 +184,31 @@ sgemm_tile_deep_kernel(const GemmParams p) {
             Ag += a_step;
             Bg += b_step;
         };
+        auto issue_a = [&](int stage) {
+            TG_POISON_DIRECT(stage * A_STAGE, NS * A_STAGE + stage * B_STAGE);   // (debug flavour only)
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i)
+                direct_load<A_EL>(byte_offset(Ag, a_off[i]), smem + stage * A_STAGE + (i * NWAVES + wave) * (64 * A_EL));
+            Ag += a_step;
+        };
+        auto issue_b = [&](int stage) {
+#pragma unroll
+            for (int i = 0; i < B_LD; ++i)
+                direct_load<B_EL>(byte_offset(Bg, b_off[i]), smem + NS * A_STAGE + stage * B_STAGE + (i * NWAVES + wave) * (64 * B_EL));
+            --to_issue;
+            Bg += b_step;
+        };
+        auto issue_one = [&](int stage, int j) {
+            if (j == 0) { TG_POISON_DIRECT(stage * A_STAGE, NS * A_STAGE + stage * B_STAGE); }
+            if (j < A_LD) {
+                direct_load<A_EL>(byte_offset(Ag, a_off[j]), smem + stage * A_STAGE + (j * NWAVES + wave) * (64 * A_EL));
+                if (j == A_LD - 1) Ag += a_step;
+            } else {
+                const int i = j - A_LD;
+                direct_load<B_EL>(byte_offset(Bg, b_off[i]), smem + NS * A_STAGE + stage * B_STAGE + (i * NWAVES + wave) * (64 * B_EL));
+                if (i == B_LD - 1) { Bg += b_step; --to_issue; }
+            }
+        };
         const bool deep = to_issue >= NS;           // the K range fills the ring
 #pragma unroll
         for (int st = 0; st < NS; ++st)
@@ -211,10 +236,27 @@ sgemm_tile_deep_kernel(const GemmParams p) {
             // ones, which do not depend on them
             // (measured at 1024^3, alternating in one process: 20.0 us this way, 20.4 us with the loads ahead of the
             // first MFMA, 21.7 us for the kernel that fetches fragments octet by octet)
-            mfma_range(cur, 0, 1);
-            if (more) issue(cur_stage);
+            // (and the loads themselves are spread: a vector-memory instruction holds the wave's issue for several cycles,
+            // and four or eight of them in a row let the MFMA pipe run dry.  K tiles of 32: A's loads behind the first MFMA,
+            // B's behind the second; K tiles of 64: one load behind each of the first eight.  Measured against all loads
+            // behind the first MFMA, alternating in one process, bit-identical: 1024^3 18.63 -> 18.19 us and 20.1 ->
+            // 18.5 us, 768^3 14.6 -> 14.3 us, 2048^3 with K tiles of 64 126.9 -> 122.4 us; one load per MFMA with K tiles
+            // of 32: no gain)
+            constexpr int LOAD_BLOCKS = BK == 32 ? 2 : N_LD;
+            if constexpr (BK == 32) {
+                mfma_range(cur, 0, 1);
+                if (more) issue_a(cur_stage);
+                mfma_range(cur, 1, 2);
+                if (more) issue_b(cur_stage);
+            } else {
+#pragma unroll
+                for (int j = 0; j < N_LD; ++j) {
+                    mfma_range(cur, j, j + 1);
+                    if (more) issue_one(cur_stage, j);
+                }
+            }
             read_tile(next, nxt);
-            mfma_range(cur, 1, 4 * NO);
+            mfma_range(cur, LOAD_BLOCKS, 4 * NO);
 #pragma unroll
             for (int i = 0; i < N_RD; i += 2) {
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads
