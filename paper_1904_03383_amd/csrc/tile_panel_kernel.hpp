@@ -32,6 +32,7 @@ constexpr int kPanelRows = 16;
 // (gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; all ones = not waited for)
 constexpr int panel_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 constexpr int kPanelStages = 3;
+constexpr unsigned kPanelCUs = 256;     // MI355X: 8 XCDs of 32 CUs (a grid up to this size gives every workgroup a CU of its own)
 
 // Workgroups are dealt to the eight XCDs in turn (workgroup w runs on XCD w % 8, each with an L2 of its own).  The
 // persistent row-panel forms want the workgroups that share a row panel of A on one XCD, so that a strided A crosses
@@ -108,6 +109,17 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         unsigned lane_bytes = 4u * (unsigned)lane * (unsigned)p.csa;   // (the host checks that a chunk spans < 2^30 elements)
         const int64_t step = (int64_t)kPanelChunk * p.csa;
         int gathered = 0;                        // chunks of the current tile asked for
+        // Pacing: once the pipeline is full, a producer rests after each row's loads, so that the loads of a chunk
+        // spread over about half of the time the compute waves spend on one (512 * CW * NQ * RB * NC cycles of MFMAs;
+        // s_sleep counts in units of 64) instead of leaving in one burst that the compute waves' own loads of B have to
+        // queue behind.  Only where the workgroup has its CU to itself (a grid of at most one workgroup per CU): with
+        // several resident their bursts interleave anyway.  Same process, bit-identical, A at stride 32: 4096x1024x1024
+        // 124.5 -> 114.6 us, 2048^3 209.9 -> 197.7 us, 1024^3 33.2 -> 32.4 us, 512^3 17.2 -> 16.9 us; plain operands
+        // unchanged; resting for the whole of a chunk's time instead of half costs the plain products 1 %.
+        constexpr int kPaceRaw = 4 * CW * NQ * RB * NC / ROWS_PER_PRODUCER;
+        constexpr int kPace = kPaceRaw < 127 ? kPaceRaw : 127;
+        const bool may_pace = kPace > 0 && gridDim.x <= kPanelCUs;
+        bool paced = false;
         auto gather = [&](int stage) {
 #pragma unroll
             for (int i = 0; i < ROWS_PER_PRODUCER; ++i) {
@@ -117,6 +129,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
                     direct_load<1>(byte_offset(row[i] + (int64_t)(64 * w) * p.csa, lane_bytes),
                                    smem + stage * kPanelStageFloats + r * kPanelPitch + 64 * w);
                 row[i] += step;
+                if (paced) __builtin_amdgcn_s_sleep(kPace);
             }
             if constexpr (WALK) {
                 if (++gathered == nch) {         // the next tile of the walk has the same rows of A: back to their start
@@ -136,6 +149,7 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         gather(0);
         if (chunks > 1) gather(1);
         int stage_free = 2;                      // where chunk j + 2 goes
+        paced = may_pace;
         for (int j = 0; j < chunks; ++j) {
             // chunk j has landed (the chunk after it may still be on its way)
             if (j + 1 < chunks) __builtin_amdgcn_s_waitcnt(panel_vmcnt(ROWS_PER_PRODUCER * CW));   // vmcnt(one chunk's loads)
