@@ -115,9 +115,13 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
         // queue behind.  Only where the workgroup has its CU to itself (a grid of at most one workgroup per CU): with
         // several resident their bursts interleave anyway.  Same process, bit-identical, A at stride 32: 4096x1024x1024
         // 124.5 -> 114.6 us, 2048^3 209.9 -> 197.7 us, 1024^3 33.2 -> 32.4 us, 512^3 17.2 -> 16.9 us; plain operands
-        // unchanged; resting for the whole of a chunk's time instead of half costs the plain products 1 %.
+        // unchanged; resting for the whole of a chunk's time instead of half costs the plain products 1 %, but where
+        // every element of A is a cache line of its own (stride >= 32) it is the better spread: another 0.3 - 2.5 %
+        // (2048^3 185.0 -> 181.9 us, 1024^3 at stride 64 38.7 -> 37.7 us, 1024^3 at stride 32 32.4 -> 32.1 us).
         constexpr int kPaceRaw = 4 * CW * NQ * RB * NC / ROWS_PER_PRODUCER;
         constexpr int kPace = kPaceRaw < 127 ? kPaceRaw : 127;
+        constexpr int kPaceFar = 2 * kPaceRaw < 127 ? 2 * kPaceRaw : 127;
+        const bool far = p.csa >= 32;            // every element a cache line of its own
         const bool may_pace = kPace > 0 && gridDim.x <= kPanelCUs;
         bool paced = false;
         auto gather = [&](int stage) {
@@ -129,7 +133,10 @@ __global__ void __launch_bounds__((NC + NP) * 64) sgemm_panel_kernel(const GemmP
                     direct_load<1>(byte_offset(row[i] + (int64_t)(64 * w) * p.csa, lane_bytes),
                                    smem + stage * kPanelStageFloats + r * kPanelPitch + 64 * w);
                 row[i] += step;
-                if (paced) __builtin_amdgcn_s_sleep(kPace);
+                if (paced) {
+                    if (far) __builtin_amdgcn_s_sleep(kPaceFar);
+                    else __builtin_amdgcn_s_sleep(kPace);
+                }
             }
             if constexpr (WALK) {
                 if (++gathered == nch) {         // the next tile of the walk has the same rows of A: back to their start
