@@ -610,6 +610,11 @@ double heuristic_seconds(const Problem &p, const Config &c) {
             const double t_chip = (double)p.m * p.k * line / 128.0 / 5e10;
             const double t_mfma = 2.0 * (double)p.m * p.n * p.k / (kNumCUs * 4.0 * kSimdFlops * 0.965);
             double t = launch + std::max(t_chip, t_cu) + t_mfma + 4.0 * (double)p.m * p.n / 20e12;
+            // (few rows: hardly anybody has fetched a line of B before the wave that needs it, and one or three steps of
+            // prefetch do not cover a miss.  256x16384x256 22.9 us on 32-row and 26.9 us on 16-row panels against 20.1 us
+            // on 64x64 tiles, 256x8192x448 21.5 against 17.0 us; from 512 rows on the panels are level or ahead:
+            // 512x16384x128 21.4 against 23.8 us, 512x8192x256 18.9 against 19.9 us)
+            if (p.m < 512) t *= 1.25;
             if (!resident_panel(ki)) t = (t + 1.0e-6) * (ki.two_level ? 1.01 : 1.0) + (strstr(ki.name, "_b3") ? 0.3e-6 : 0.0);
             else t = t * (ki.threads < 1024 ? 1.0 : 1.005) + (strstr(ki.name, "_b3") ? 0.1e-6 : 0.0);
             // (sixteen waves in one workgroup: on a par on most shapes, 8192x8192x64 97 us against 82 us; three steps of B
