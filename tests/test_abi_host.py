@@ -337,6 +337,32 @@ def test_candidates_are_valid_ordered_and_bounded(lib, shape):
     assert tg.get_config(batch, m, n, k) == cands[0][0]
 
 
+@pytest.mark.parametrize("shape,expect", [
+    # short K, plain operands, tiles that divide over 256 workgroups: the row panels with A resident in LDS
+    ((4096, 4096, 128), r"g32x(512|1024)x64_w32x64(_b3)?_res_ga:.*:p1$"),
+    ((2048, 8192, 256), r"g32x(512|1024)x64_w32x64(_b3)?_res_ga:"),
+    # ... but not below 512 rows (B's lines are then first touched by the wave that needs them) nor from k = 512 on
+    ((256, 16384, 256), r"[tdw]"),
+    ((4096, 4096, 512), r"[td]"),
+    # a single long-K product whose 32 x 512 panels fill every CU the same number of times: deep-chunk row panels
+    ((8192, 8192, 8192), r"g32x512x(128|256)_w32x64_acc2_b3_ga:s1"),
+    ((2048, 2048, 2048), r"g32x512x(128|256)_w32x64_acc2_b3_ga:s1"),
+    # ... with a partly empty last round the tile kernels keep the product (576 panels over 256 CUs)
+    ((3072, 3072, 3072), r"[td]"),
+    ((2048, 1024, 4096), r"[td]"),
+], ids=str)
+def test_untuned_choice_on_shapes_the_row_panels_were_measured_on(lib, shape, expect):
+    """The cost model's first choice for a few shapes on either side of the rules that hand plain products to the
+    row-panel kernels (each rule stands on same-process measurements quoted beside it in the cost model)."""
+    import re
+    m, n, k = shape
+    first = tg.candidates(1, m, n, k)[0][0]
+    assert re.match(expect, first), first
+    batch = tg.candidates(4, m, n, k)[0][0] if m * n * k <= 2048 ** 3 else None
+    if batch is not None and k >= 2048:
+        assert not batch.startswith("g"), batch          # on batches the tile kernels are level or ahead
+
+
 def test_lower_bound_reflects_tile_quantisation_and_wave_share(lib):
     by = {spec: (lb, model) for spec, lb, model in tg.candidates(1, 4096, 4096, 4096)}
     simd_flops = 64 * 2.4e9            # one SIMD: 64 flop per clock at 2.4 GHz; 1024 of them make the chip
